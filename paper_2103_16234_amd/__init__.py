@@ -1,0 +1,18 @@
+"""MI355X-native stride-1 forward direct convolution (NCHW fp32 / KCRS fp32).
+
+`inputs` (seeded synthetic tensors and layer shapes) is importable anywhere; the HIP
+binding is loaded on first use of `conv_fwd` and friends and fails loudly when the
+compiled library is missing.
+"""
+from . import inputs  # noqa: F401
+
+_BINDING_NAMES = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_set_stream", "conv_strerror",
+                  "ConvPlan", "ConvError", "load_library", "library_path", "build_library")
+
+
+def __getattr__(name):
+    if name in _BINDING_NAMES or name == "binding":
+        import importlib
+        mod = importlib.import_module(".binding", __name__)
+        return mod if name == "binding" else getattr(mod, name)
+    raise AttributeError(name)
