@@ -1,0 +1,125 @@
+/*
+ * convfwd: stride-1 forward convolution of a CNN layer on one MI355X (gfx950),
+ * computed directly on NCHW fp32 activations and KCRS fp32 filters.
+ *
+ * The operation (Section 2.1 of the paper: every output element is the dot
+ * product of one filter with a C x R x S sub-volume of the input, the
+ * sub-volume translated over X and Y; padding adds rows and columns around the
+ * input; Section 3: NCHW layout, X contiguous; Section 4: stride 1, fp32):
+ *
+ *   y[n,k,p,q] = sum_{c<C, r<R, s<S} xpad[n, c, p+r-pad_h, q+s-pad_w] * w[k,c,r,s]
+ *   xpad = x inside [0,H) x [0,W) and 0 outside
+ *   P = H + 2*pad_h - R + 1,   Q = W + 2*pad_w - S + 1
+ *
+ * The filter is not flipped, there is no bias, scaling or activation, and y is
+ * overwritten. All arithmetic is fp32 (fp32 FMA or full-precision fp32 MFMA,
+ * fp32 accumulation); no reduced-precision type is used anywhere.
+ *
+ * Layout: x is [N][C][H][W], w is [K][C][R][S], y is [N][K][P][Q], all dense
+ * and contiguous, W / S / Q fastest. Stride, dilation and groups are fixed to 1.
+ *
+ * Ownership: x, w and y are DEVICE pointers owned by the caller; the library
+ * never allocates, frees or keeps them and needs no workspace. x and w must not
+ * overlap y. Calls are asynchronous on the stream given to conv_set_stream
+ * (default: the null stream); the caller synchronises.
+ *
+ * Errors: every entry point returns 0 on success or a negative CONV_E_* code;
+ * nothing throws or aborts. Results are bitwise reproducible for equal inputs
+ * and equal plans (no atomics).
+ */
+#ifndef CONVFWD_H
+#define CONVFWD_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CONV_OK 0
+#define CONV_E_NULL (-1)      /* a required pointer is null */
+#define CONV_E_DIM (-2)       /* a dimension is not positive or a padding is negative */
+#define CONV_E_EMPTY (-3)     /* P <= 0 or Q <= 0 */
+#define CONV_E_OVERFLOW (-4)  /* a tensor has 2^31 or more elements (kernels index with 32 bits) */
+#define CONV_E_HIP (-5)       /* a HIP runtime call failed; conv_strerror gives its text */
+#define CONV_E_PLAN (-6)      /* a caller-supplied plan does not fit the shape or the kernels */
+
+/* Kernel families a plan can name. */
+#define CONV_KERNEL_GENERIC 0 /* one output per thread, fp32 FMA; any R, S, padding */
+#define CONV_KERNEL_TAP 1     /* LDS halo tile + filter block, fp32 MFMA over (channel, tap); R = S in {1,3,5} */
+#define CONV_KERNEL_POINTWISE 2 /* 1x1, pad 0: inputs streamed HBM -> registers -> fp32 MFMA, filters in LDS */
+
+/*
+ * How one layer is mapped onto the GPU. Filled by conv_fwd_plan; plain data.
+ * The reduction over (c, r, s) stays inside one work-group, so no plan ever
+ * needs a workspace (unlike the two-stage scheme of Section 3, whose first
+ * stage writes R*S partial matrices per input/filter pair).
+ */
+typedef struct conv_plan {
+    int kernel;          /* CONV_KERNEL_* */
+    int variant;         /* tile shape index inside the family (see conv_variant_info) */
+    int tile_k;          /* output channels per work-group */
+    int tile_pix;        /* output pixels per work-group, counted in flattened (n,p,q) order */
+    int chunk_c;         /* input channels staged in LDS per round */
+    int x_vec, w_vec;    /* dwords per global load of input rows / filter slices: 4, 2 or 1 */
+    int lds_rows;        /* input rows (of the zero-padded, vertically stacked images) held per channel */
+    int lds_pitch;       /* floats between consecutive rows of the LDS halo tile */
+    int lds_plane;       /* floats between consecutive channels of the LDS halo tile */
+    int grid;            /* work-groups */
+    int block;           /* threads per work-group */
+    int lds_bytes;       /* dynamic LDS per work-group */
+    int P, Q;            /* output height and width */
+    long long workspace_bytes; /* always 0 */
+    long long flops;     /* 2*N*K*P*Q*C*R*S */
+    long long bytes;     /* 4*(N*C*H*W + K*C*R*S + N*K*P*Q): compulsory HBM traffic */
+} conv_plan_t;
+
+/*
+ * y = conv(x, w). Plans the launch (as conv_fwd_plan does, then narrows the
+ * vector widths if x or w is not 16-byte aligned) and enqueues one kernel.
+ * x, w, y: device pointers (see the header comment). Returns CONV_OK or
+ * CONV_E_NULL / _DIM / _EMPTY / _OVERFLOW / _HIP.
+ */
+int conv_fwd(const float* x, const float* w, float* y,
+             int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w);
+
+/*
+ * Host-only: choose kernel family, tile shape, channel chunk, grid and LDS size
+ * for a shape (Section 3 discusses this choice as the number of thread blocks
+ * per filter row; Section 4.2 shows both too many and too few blocks lose).
+ * Touches no device. out: host pointer, fully written on success.
+ */
+int conv_fwd_plan(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
+                  conv_plan_t* out);
+
+/*
+ * As conv_fwd, with the mapping requested by the caller. Only plan->kernel,
+ * plan->variant, plan->tile_pix and plan->chunk_c are read as requests (0 in
+ * tile_pix / chunk_c means "choose"); every derived field is recomputed and
+ * checked, and CONV_E_PLAN is returned if the request cannot be honoured
+ * (family does not support R x S, tile exceeds the variant's capacity, LDS
+ * does not fit). If resolved is not null it receives the plan actually used.
+ */
+int conv_fwd_planned(const float* x, const float* w, float* y,
+                     int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
+                     const conv_plan_t* plan, conv_plan_t* resolved);
+
+/*
+ * Number of tile shapes of a kernel family (0 for an unknown family), and the
+ * capacity of one: output channels and output pixels per work-group and
+ * threads per work-group. Host-only. Returns CONV_E_PLAN for bad indices.
+ */
+int conv_variant_count(int kernel);
+int conv_variant_info(int kernel, int variant, int* tile_k, int* max_tile_pix, int* block);
+
+/*
+ * Stream used by later conv_fwd / conv_fwd_planned calls of the calling
+ * thread's process (a hipStream_t passed as void*; NULL = null stream).
+ */
+int conv_set_stream(void* hip_stream);
+
+/* Text for a CONV_E_* code; for CONV_E_HIP the text of the last HIP error seen. Never null. */
+const char* conv_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONVFWD_H */

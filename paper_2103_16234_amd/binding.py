@@ -1,0 +1,149 @@
+"""ctypes binding of libconvfwd.so: argument marshalling only.
+
+Every step of the convolution runs in the library's HIP kernels; torch is used for device
+memory and streams. There is no CPU or eager fallback: if the library is missing, loading
+raises and tells how to build it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libconvfwd.so")
+_lib = None
+
+CONV_KERNEL_GENERIC = 0
+CONV_KERNEL_TAP = 1
+CONV_KERNEL_POINTWISE = 2
+
+EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_variant_count", "conv_variant_info",
+           "conv_set_stream", "conv_strerror")
+
+
+class ConvPlan(ctypes.Structure):
+    """Mirror of conv_plan_t in include/convfwd.h."""
+    _fields_ = [(n, ctypes.c_int) for n in (
+        "kernel", "variant", "tile_k", "tile_pix", "chunk_c", "x_vec", "w_vec", "lds_rows", "lds_pitch",
+        "lds_plane", "grid", "block", "lds_bytes", "P", "Q")] + [
+        ("workspace_bytes", ctypes.c_longlong), ("flops", ctypes.c_longlong), ("bytes", ctypes.c_longlong)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class ConvError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"convfwd error {code}: {text}")
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def build_library(force: bool = False) -> str:
+    from . import build as _build
+    return _build.build(force=force)
+
+
+def load_library():
+    """Load libconvfwd.so (built in-tree by `python -m paper_2103_16234_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python -m paper_2103_16234_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    dims = [ci] * 9
+    lib.conv_fwd.argtypes = [vp, vp, vp] + dims
+    lib.conv_fwd_plan.argtypes = dims + [ctypes.POINTER(ConvPlan)]
+    lib.conv_fwd_planned.argtypes = [vp, vp, vp] + dims + [ctypes.POINTER(ConvPlan), ctypes.POINTER(ConvPlan)]
+    lib.conv_variant_count.argtypes = [ci]
+    lib.conv_variant_info.argtypes = [ci, ci] + [ctypes.POINTER(ci)] * 3
+    lib.conv_set_stream.argtypes = [vp]
+    lib.conv_strerror.argtypes = [ci]
+    lib.conv_strerror.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        if name != "conv_strerror":
+            getattr(lib, name).restype = ci
+    _lib = lib
+    return lib
+
+
+def conv_strerror(code: int) -> str:
+    return load_library().conv_strerror(code).decode()
+
+
+def _check(code: int):
+    if code != 0:
+        raise ConvError(code, conv_strerror(code))
+
+
+def conv_fwd_plan(N, C, H, W, K, R, S, pad_h, pad_w) -> ConvPlan:
+    plan = ConvPlan()
+    _check(load_library().conv_fwd_plan(N, C, H, W, K, R, S, pad_h, pad_w, ctypes.byref(plan)))
+    return plan
+
+
+def conv_variant_count(kernel: int) -> int:
+    return load_library().conv_variant_count(kernel)
+
+
+def conv_variant_info(kernel: int, variant: int):
+    tk, mp, bl = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(load_library().conv_variant_info(kernel, variant, ctypes.byref(tk), ctypes.byref(mp), ctypes.byref(bl)))
+    return tk.value, mp.value, bl.value
+
+
+def conv_set_stream(stream=None):
+    """Use a torch.cuda.Stream (or a raw hipStream_t integer, or None for the null stream)."""
+    handle = getattr(stream, "cuda_stream", stream)
+    _check(load_library().conv_set_stream(ctypes.c_void_p(handle or 0)))
+
+
+def _device_args(x, w, y, pad_h, pad_w):
+    import torch
+    for name, t in (("x", x), ("w", w)):
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+                and t.dim() == 4):
+            raise TypeError(f"{name} must be a contiguous 4-d float32 tensor on the GPU")
+    N, C, H, W = x.shape
+    K, Cw, R, S = w.shape
+    if Cw != C:
+        raise ValueError("x and w disagree on the number of channels")
+    P, Q = H + 2 * pad_h - R + 1, W + 2 * pad_w - S + 1
+    if y is None:
+        if P <= 0 or Q <= 0:
+            _check(-3)
+        y = torch.empty((N, K, P, Q), device=x.device, dtype=torch.float32)
+    elif not (y.is_cuda and y.dtype == torch.float32 and y.is_contiguous() and tuple(y.shape) == (N, K, P, Q)):
+        raise TypeError("y must be a contiguous float32 GPU tensor of shape [N,K,P,Q]")
+    return y, (N, C, H, W, K, R, S, pad_h, pad_w)
+
+
+def conv_fwd(x, w, pad_h: int, pad_w: int, y=None, use_current_stream: bool = True):
+    """y[N,K,P,Q] = stride-1 forward convolution of x[N,C,H,W] with w[K,C,R,S] (device tensors)."""
+    import torch
+    y, dims = _device_args(x, w, y, pad_h, pad_w)
+    lib = load_library()
+    if use_current_stream:
+        conv_set_stream(torch.cuda.current_stream(x.device))
+    _check(lib.conv_fwd(x.data_ptr(), w.data_ptr(), y.data_ptr(), *dims))
+    return y
+
+
+def conv_fwd_planned(x, w, pad_h: int, pad_w: int, kernel: int, variant: int = 0, tile_pix: int = 0,
+                     chunk_c: int = 0, y=None, use_current_stream: bool = True):
+    """As conv_fwd with a requested kernel family / tile shape; returns (y, resolved ConvPlan)."""
+    import torch
+    y, dims = _device_args(x, w, y, pad_h, pad_w)
+    lib = load_library()
+    if use_current_stream:
+        conv_set_stream(torch.cuda.current_stream(x.device))
+    req, res = ConvPlan(), ConvPlan()
+    req.kernel, req.variant, req.tile_pix, req.chunk_c = kernel, variant, tile_pix, chunk_c
+    _check(lib.conv_fwd_planned(x.data_ptr(), w.data_ptr(), y.data_ptr(), *dims, ctypes.byref(req), ctypes.byref(res)))
+    return y, res

@@ -1,0 +1,390 @@
+// C-ABI entry points, argument validation and the per-shape tile planner (host only).
+#include "../../include/convfwd.h"
+#include "conv_internal.h"
+
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <mutex>
+#include <numeric>
+#include <string>
+#include <vector>
+
+namespace convfwd {
+
+#define DECLARE_TAP(r, v) \
+    hipError_t launch_tap_##r##x##r##_v##v(int, int, int, int, hipStream_t, const KernelArgs&);
+#define DECLARE_TAP_ALL(r) DECLARE_TAP(r, 0) DECLARE_TAP(r, 1) DECLARE_TAP(r, 2) DECLARE_TAP(r, 3) DECLARE_TAP(r, 4)
+DECLARE_TAP_ALL(1)
+DECLARE_TAP_ALL(3)
+DECLARE_TAP_ALL(5)
+
+using TapLauncher = hipError_t (*)(int, int, int, int, hipStream_t, const KernelArgs&);
+#define TAP_ROW(r) {launch_tap_##r##x##r##_v0, launch_tap_##r##x##r##_v1, launch_tap_##r##x##r##_v2, \
+                    launch_tap_##r##x##r##_v3, launch_tap_##r##x##r##_v4}
+static const TapLauncher kTapLaunchers[3][kNumTapVariants] = {TAP_ROW(1), TAP_ROW(3), TAP_ROW(5)};
+static_assert(kNumTapVariants == 5, "update the launcher table");
+
+hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid, int lds_bytes,
+                      hipStream_t stream, const KernelArgs& a)
+{
+    if (rs_index < 0 || rs_index > 2 || variant < 0 || variant >= kNumTapVariants) return hipErrorInvalidValue;
+    return kTapLaunchers[rs_index][variant](x_vec, w_vec, grid, lds_bytes, stream, a);
+}
+
+namespace {
+
+constexpr int kNumCU = 256;              // MI355X: 8 XCDs x 32 CUs
+constexpr int kLdsBudget = 80 * 1024;    // per work-group: lets two work-groups share a CU's 160 KB
+constexpr int kMaxChunkC = 64;
+
+std::atomic<hipStream_t> g_stream{nullptr};
+thread_local std::string g_hip_error = "no HIP error recorded";
+
+struct Shape {
+    int N, C, H, W, K, R, S, pad_h, pad_w, P, Q;
+};
+
+int validate(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w, Shape* s)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || R <= 0 || S <= 0 || pad_h < 0 || pad_w < 0)
+        return CONV_E_DIM;
+    const int64_t P = (int64_t)H + 2 * (int64_t)pad_h - R + 1;
+    const int64_t Q = (int64_t)W + 2 * (int64_t)pad_w - S + 1;
+    if (P <= 0 || Q <= 0) return CONV_E_EMPTY;
+    const int64_t lim = (int64_t)1 << 31;
+    const int64_t nx = (int64_t)N * C * H * W;
+    const int64_t nw = (int64_t)K * C * R * S;
+    // guard the products step by step: the factors themselves can be near 2^31
+    if ((int64_t)N * C >= lim || (int64_t)H * W >= lim || nx >= lim || nx / ((int64_t)H * W) != (int64_t)N * C)
+        return CONV_E_OVERFLOW;
+    if ((int64_t)K * C >= lim || (int64_t)R * S >= lim || nw >= lim) return CONV_E_OVERFLOW;
+    if (P >= lim || Q >= lim || P * Q >= lim || (int64_t)N * K >= lim) return CONV_E_OVERFLOW;
+    const int64_t ny = (int64_t)N * K * (P * Q);
+    if (ny >= lim || ny / (P * Q) != (int64_t)N * K) return CONV_E_OVERFLOW;
+    if (((int64_t)H + 2 * (int64_t)pad_h) * N >= lim || (int64_t)W + 2 * (int64_t)pad_w >= lim) return CONV_E_OVERFLOW;
+    *s = Shape{N, C, H, W, K, R, S, pad_h, pad_w, (int)P, (int)Q};
+    return CONV_OK;
+}
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+int tap_rs_index(const Shape& s)
+{
+    if (s.R != s.S) return -1;
+    return s.R == 1 ? 0 : s.R == 3 ? 1 : s.R == 5 ? 2 : -1;
+}
+
+void base_args(const Shape& s, KernelArgs* a)
+{
+    std::memset(a, 0, sizeof(*a));
+    a->N = s.N; a->C = s.C; a->H = s.H; a->W = s.W; a->K = s.K; a->R = s.R; a->S = s.S;
+    a->pad_h = s.pad_h; a->pad_w = s.pad_w;
+    a->P = s.P; a->Q = s.Q; a->PQ = s.P * s.Q; a->HW = s.H * s.W; a->CRS = s.C * s.R * s.S;
+    a->Hp = s.H + 2 * s.pad_h;
+    a->total_pix = s.N * s.P * s.Q;
+}
+
+void fill_common(const Shape& s, conv_plan_t* p)
+{
+    p->P = s.P; p->Q = s.Q;
+    p->workspace_bytes = 0;
+    p->flops = 2LL * s.N * s.K * s.P * s.Q * s.C * s.R * s.S;
+    p->bytes = 4LL * ((int64_t)s.N * s.C * s.H * s.W + (int64_t)s.K * s.C * s.R * s.S + (int64_t)s.N * s.K * s.P * s.Q);
+}
+
+// Rows of the stacked zero-padded images (image n occupies rows n*Hp .. n*Hp+Hp-1) that the widest
+// pixel tile touches. The tile phase repeats every PQ / gcd(PQ, tile_pix) tiles.
+int max_halo_rows(const Shape& s, int tile_pix)
+{
+    const int64_t total = (int64_t)s.N * s.P * s.Q;
+    const int PQ = s.P * s.Q, Hp = s.H + 2 * s.pad_h;
+    const int64_t period = PQ / std::gcd(PQ, tile_pix);
+    int rows = 0;
+    int64_t g0 = 0;
+    for (int64_t i = 0; i <= period && g0 < total; ++i, g0 += tile_pix) {
+        const int64_t g1 = std::min<int64_t>(g0 + tile_pix, total) - 1;
+        const int64_t v0 = (g0 / PQ) * Hp + (g0 % PQ) / s.Q;
+        const int64_t v1 = (g1 / PQ) * Hp + (g1 % PQ) / s.Q + s.R - 1;
+        rows = std::max<int>(rows, (int)(v1 - v0 + 1));
+    }
+    return rows;
+}
+
+// Resolve a tap-family mapping. tile_pix / chunk_c of 0 mean "choose". Returns false if it cannot run.
+bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_cap, int w_cap,
+                 conv_plan_t* p, KernelArgs* a)
+{
+    const int rs_index = tap_rs_index(s);
+    if (rs_index < 0 || variant < 0 || variant >= kNumTapVariants) return false;
+    const TapVariant tv = kTapVariants[variant];
+    const int RS = s.R * s.S, TK = tv.tile_k(), BLOCK = tv.block();
+    const int64_t total64 = (int64_t)s.N * s.P * s.Q;
+    if (tile_pix == 0) tile_pix = (int)std::min<int64_t>(tv.max_pix(), total64);
+    if (tile_pix < 1 || tile_pix > tv.max_pix()) return false;
+    const int total = (int)total64;
+
+    int w_vec = (s.C % 4 == 0 && w_cap >= 4) ? 4 : 1;
+    int x_vec = s.W % 4 == 0 ? 4 : s.W % 2 == 0 ? 2 : 1;
+    x_vec = std::min(x_vec, x_cap);
+    if (w_vec == 1) x_vec = 1;  // only the (x_vec, 4) and (1, 1) loaders are built
+
+    const int col_shift = (x_vec - s.pad_w % x_vec) % x_vec;
+    const int pitch = round_up(s.W + 2 * s.pad_w + col_shift, x_vec);
+    const int rows = max_halo_rows(s, tile_pix);
+    // channel planes start 16 banks apart (mod 32): the four channels one B operand spans do not collide
+    const int plane = round_up(std::max(rows * pitch - 16, 0), 32) + 16;
+    const int row_vecs = s.W / x_vec;
+
+    auto fits = [&](int cc) {
+        const int64_t x_items = (int64_t)cc * rows * row_vecs;
+        const int64_t w_items = (int64_t)TK * cc * RS / w_vec;
+        const int64_t lds = 4LL * ((int64_t)cc * plane + (int64_t)TK * (cc * RS + 2));
+        return x_items <= (int64_t)kTapXSlots * BLOCK && w_items <= (int64_t)kTapWSlots * BLOCK && lds <= kLdsBudget &&
+               cc * RS < 65536 && (int64_t)cc * plane + rows * pitch < (1 << 20);
+    };
+    const int c_pad = round_up(s.C, 4);
+    if (chunk_c == 0) {
+        int cc = std::min(kMaxChunkC, c_pad);
+        while (cc >= 4 && !fits(cc)) cc -= 4;
+        if (cc < 4) return false;
+        const int n = ceil_div(s.C, cc);
+        chunk_c = std::min(cc, round_up(ceil_div(s.C, n), 4));  // even chunks, same count
+    }
+    if (chunk_c < 4 || chunk_c % 4 != 0 || chunk_c > std::max(c_pad, 4) || !fits(chunk_c)) return false;
+
+    base_args(s, a);
+    a->tile_pix = tile_pix;
+    a->ktiles = ceil_div(s.K, TK);
+    a->ptiles = ceil_div(total, tile_pix);
+    if ((int64_t)a->ktiles * a->ptiles >= ((int64_t)1 << 31)) return false;
+    a->chunk_c = chunk_c;
+    a->nchunks = ceil_div(s.C, chunk_c);
+    a->lds_rows = rows; a->lds_pitch = pitch; a->lds_plane = plane; a->col_shift = col_shift;
+    a->w_pitch = chunk_c * RS + 2;
+    a->x_items = chunk_c * rows * row_vecs;
+    a->w_items = TK * chunk_c * RS / w_vec;
+
+    std::memset(p, 0, sizeof(*p));
+    p->kernel = CONV_KERNEL_TAP; p->variant = variant;
+    p->tile_k = TK; p->tile_pix = tile_pix; p->chunk_c = chunk_c;
+    p->x_vec = x_vec; p->w_vec = w_vec;
+    p->lds_rows = rows; p->lds_pitch = pitch; p->lds_plane = plane;
+    p->grid = a->ktiles * a->ptiles; p->block = BLOCK;
+    p->lds_bytes = round_up(4 * (chunk_c * plane + TK * a->w_pitch), 16);
+    fill_common(s, p);
+    return true;
+}
+
+void resolve_generic(const Shape& s, conv_plan_t* p, KernelArgs* a)
+{
+    base_args(s, a);
+    std::memset(p, 0, sizeof(*p));
+    p->kernel = CONV_KERNEL_GENERIC;
+    p->block = 256;
+    const int64_t outputs = (int64_t)a->total_pix * s.K;
+    p->grid = (int)std::min<int64_t>((outputs + 255) / 256, (int64_t)kNumCU * 64);
+    p->tile_k = 1; p->tile_pix = 256; p->x_vec = 1; p->w_vec = 1;
+    fill_common(s, p);
+}
+
+// Relative time of a tap mapping: MFMA issue slots per SIMD over the busiest CU, plus staging overhead.
+double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv, int RS)
+{
+    const double waves_per_simd = tv.block() / 256.0;
+    const double rounds = std::ceil((double)p.grid / kNumCU);
+    const double mfma_slots = rounds * tv.MT * tv.NT * std::max(waves_per_simd, 0.25);
+    const double staged = (double)p.chunk_c * (a.lds_rows * a.lds_pitch + (double)p.tile_k * RS);
+    const double mfmas = (double)(tv.block() / 64) * tv.MT * tv.NT * (p.chunk_c / 4.0) * RS;
+    return mfma_slots * (1.0 + 2.0 * staged / (256.0 * mfmas));
+}
+
+// conv_fwd plans on every call; remember recent shapes so a launch costs a table lookup.
+struct CacheEntry {
+    Shape s;
+    int x_cap, w_cap;
+    conv_plan_t p;
+    KernelArgs a;
+};
+std::mutex g_cache_mutex;
+std::vector<CacheEntry> g_cache;
+constexpr size_t kCacheEntries = 64;
+
+bool same_shape(const Shape& a, const Shape& b) { return std::memcmp(&a, &b, sizeof(Shape)) == 0; }
+
+int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a);
+
+int plan_shape(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a)
+{
+    {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        for (const CacheEntry& e : g_cache)
+            if (same_shape(e.s, s) && e.x_cap == x_cap && e.w_cap == w_cap) {
+                *p = e.p; *a = e.a;
+                return CONV_OK;
+            }
+    }
+    const int rc = plan_shape_uncached(s, x_cap, w_cap, p, a);
+    if (rc == CONV_OK) {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        if (g_cache.size() >= kCacheEntries) g_cache.erase(g_cache.begin());
+        g_cache.push_back(CacheEntry{s, x_cap, w_cap, *p, *a});
+    }
+    return rc;
+}
+
+int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a)
+{
+    if (tap_rs_index(s) >= 0) {
+        bool found = false;
+        double best = 0;
+        const int PQ = s.P * s.Q;
+        const int64_t total = (int64_t)s.N * PQ;
+        for (int v = 0; v < kNumTapVariants; ++v) {
+            const TapVariant tv = kTapVariants[v];
+            const int cap = tv.max_pix();
+            // candidate pixel tiles: full capacity, an even split, whole images, whole rows
+            int cands[6];
+            int nc = 0;
+            cands[nc++] = (int)std::min<int64_t>(cap, total);
+            cands[nc++] = (int)((total + (total + cap - 1) / cap - 1) / ((total + cap - 1) / cap));
+            if (PQ <= cap) cands[nc++] = cap / PQ * PQ;
+            if (PQ > cap) {
+                const int parts = ceil_div(PQ, cap);
+                if (PQ % parts == 0) cands[nc++] = PQ / parts;
+                for (int d = parts; d <= std::min(PQ, parts + 8); ++d)
+                    if (PQ % d == 0) { cands[nc++] = PQ / d; break; }
+            }
+            if (s.Q <= cap) cands[nc++] = cap / s.Q * s.Q;
+            for (int i = 0; i < nc; ++i) {
+                conv_plan_t cp;
+                KernelArgs ca;
+                if (cands[i] < 1 || !resolve_tap(s, v, cands[i], 0, x_cap, w_cap, &cp, &ca)) continue;
+                const double c = tap_cost(cp, ca, tv, s.R * s.S);
+                if (!found || c < best * 0.999) {
+                    found = true; best = c; *p = cp; *a = ca;
+                }
+            }
+        }
+        if (found) return CONV_OK;
+    }
+    resolve_generic(s, p, a);
+    return CONV_OK;
+}
+
+int record_hip(hipError_t e)
+{
+    if (e == hipSuccess) return CONV_OK;
+    g_hip_error = std::string(hipGetErrorName(e)) + ": " + hipGetErrorString(e);
+    return CONV_E_HIP;
+}
+
+int launch(const conv_plan_t& p, KernelArgs& a, const Shape& s, const float* x, const float* w, float* y)
+{
+    a.x = x; a.w = w; a.y = y;
+    hipStream_t stream = g_stream.load();
+    if (p.kernel == CONV_KERNEL_TAP)
+        return record_hip(launch_tap(tap_rs_index(s), p.variant, p.x_vec, p.w_vec, p.grid, p.lds_bytes, stream, a));
+    if (p.kernel == CONV_KERNEL_GENERIC) return record_hip(launch_generic(p.grid, p.block, stream, a));
+    return CONV_E_PLAN;
+}
+
+void pointer_caps(const float* x, const float* w, int* x_cap, int* w_cap)
+{
+    const uintptr_t xa = reinterpret_cast<uintptr_t>(x), wa = reinterpret_cast<uintptr_t>(w);
+    *x_cap = xa % 16 == 0 ? 4 : xa % 8 == 0 ? 2 : 1;
+    *w_cap = wa % 16 == 0 ? 4 : 1;
+}
+
+}  // namespace
+}  // namespace convfwd
+
+using namespace convfwd;
+
+extern "C" int conv_fwd_plan(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w, conv_plan_t* out)
+{
+    if (!out) return CONV_E_NULL;
+    Shape s;
+    if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
+    KernelArgs a;
+    return plan_shape(s, 4, 4, out, &a);
+}
+
+extern "C" int conv_fwd(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,
+                        int pad_h, int pad_w)
+{
+    if (!x || !w || !y) return CONV_E_NULL;
+    Shape s;
+    if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
+    int x_cap, w_cap;
+    pointer_caps(x, w, &x_cap, &w_cap);
+    conv_plan_t p;
+    KernelArgs a;
+    if (int rc = plan_shape(s, x_cap, w_cap, &p, &a)) return rc;
+    return launch(p, a, s, x, w, y);
+}
+
+extern "C" int conv_fwd_planned(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R,
+                                int S, int pad_h, int pad_w, const conv_plan_t* plan, conv_plan_t* resolved)
+{
+    if (!x || !w || !y || !plan) return CONV_E_NULL;
+    Shape s;
+    if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
+    int x_cap, w_cap;
+    pointer_caps(x, w, &x_cap, &w_cap);
+    conv_plan_t p;
+    KernelArgs a;
+    if (plan->kernel == CONV_KERNEL_GENERIC) {
+        resolve_generic(s, &p, &a);
+    } else if (plan->kernel == CONV_KERNEL_TAP) {
+        if (plan->tile_pix < 0 || plan->chunk_c < 0) return CONV_E_PLAN;
+        if (!resolve_tap(s, plan->variant, plan->tile_pix, plan->chunk_c, x_cap, w_cap, &p, &a)) return CONV_E_PLAN;
+    } else {
+        return CONV_E_PLAN;
+    }
+    if (resolved) *resolved = p;
+    return launch(p, a, s, x, w, y);
+}
+
+extern "C" int conv_variant_count(int kernel)
+{
+    if (kernel == CONV_KERNEL_GENERIC) return 1;
+    if (kernel == CONV_KERNEL_TAP) return kNumTapVariants;
+    return 0;
+}
+
+extern "C" int conv_variant_info(int kernel, int variant, int* tile_k, int* max_tile_pix, int* block)
+{
+    if (variant < 0 || variant >= conv_variant_count(kernel)) return CONV_E_PLAN;
+    int tk = 1, mp = 256, bl = 256;
+    if (kernel == CONV_KERNEL_TAP) {
+        tk = kTapVariants[variant].tile_k(); mp = kTapVariants[variant].max_pix(); bl = kTapVariants[variant].block();
+    }
+    if (tile_k) *tile_k = tk;
+    if (max_tile_pix) *max_tile_pix = mp;
+    if (block) *block = bl;
+    return CONV_OK;
+}
+
+extern "C" int conv_set_stream(void* hip_stream)
+{
+    g_stream.store(reinterpret_cast<hipStream_t>(hip_stream));
+    return CONV_OK;
+}
+
+extern "C" const char* conv_strerror(int code)
+{
+    switch (code) {
+        case CONV_OK: return "ok";
+        case CONV_E_NULL: return "null pointer";
+        case CONV_E_DIM: return "dimension not positive or padding negative";
+        case CONV_E_EMPTY: return "empty output (P <= 0 or Q <= 0)";
+        case CONV_E_OVERFLOW: return "tensor has 2^31 or more elements";
+        case CONV_E_HIP: return g_hip_error.c_str();
+        case CONV_E_PLAN: return "plan does not fit the shape or the kernels";
+        default: return "unknown error code";
+    }
+}

@@ -1,0 +1,44 @@
+// Generic-family kernel: one output element per thread, plain fp32 FMA, any filter size and padding.
+// It is the fallback for shapes outside the specialised families and follows the definition of the
+// layer directly (Section 2.1): the dot product of one filter with one input sub-volume, padding
+// taps skipped. Lanes of a wave hold consecutive q, so input reads are coalesced along X (Section 3).
+#include "conv_internal.h"
+
+namespace convfwd {
+
+__global__ void __launch_bounds__(256) conv_generic(const KernelArgs a)
+{
+    const long long total = (long long)a.total_pix * a.K;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+        const int q = (int)(idx % a.Q);
+        long long t = idx / a.Q;
+        const int p = (int)(t % a.P);
+        t /= a.P;
+        const int k = (int)(t % a.K);
+        const int n = (int)(t / a.K);
+        const float* wk = a.w + k * a.CRS;
+        const float* xn = a.x + n * a.C * a.HW;
+        float acc = 0.f;
+        for (int c = 0; c < a.C; ++c) {
+            for (int r = 0; r < a.R; ++r) {
+                const int h = p + r - a.pad_h;
+                if (h < 0 || h >= a.H) continue;
+                for (int s = 0; s < a.S; ++s) {
+                    const int v = q + s - a.pad_w;
+                    if (v < 0 || v >= a.W) continue;
+                    acc = fmaf(xn[(c * a.H + h) * a.W + v], wk[(c * a.R + r) * a.S + s], acc);
+                }
+            }
+        }
+        a.y[idx] = acc;
+    }
+}
+
+hipError_t launch_generic(int grid, int block, hipStream_t stream, const KernelArgs& a)
+{
+    hipLaunchKernelGGL(conv_generic, dim3(grid), dim3(block), 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace convfwd

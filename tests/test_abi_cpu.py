@@ -1,0 +1,102 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, validates arguments before touching a device, and plans without a workspace."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2103_16234_amd import binding, inputs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.library_path()):
+        binding.build_library()
+    return binding.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "convfwd.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(conv_\w+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_plan_struct_matches_header():
+    header = open(os.path.join(ROOT, "include", "convfwd.h")).read()
+    body = re.search(r"typedef struct conv_plan \{(.*?)\} conv_plan_t;", header, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if not decl:
+            continue
+        names += [n.strip() for n in decl.split(None, 2 if decl.startswith("long long") else 1)[-1].split(",")]
+    assert names == [n for n, _ in binding.ConvPlan._fields_]
+
+
+def test_argument_errors_are_codes_not_crashes(lib):
+    plan = binding.ConvPlan()
+    ok = (1, 4, 8, 8, 4, 3, 3, 1, 1)
+    assert lib.conv_fwd_plan(*ok, ctypes.byref(plan)) == 0
+    assert lib.conv_fwd_plan(*ok, None) == -1
+    for i in range(7):                                  # a non-positive dimension
+        bad = list(ok)
+        bad[i] = 0
+        assert lib.conv_fwd_plan(*bad, ctypes.byref(plan)) == -2
+    assert lib.conv_fwd_plan(1, 4, 8, 8, 4, 3, 3, -1, 1, ctypes.byref(plan)) == -2
+    assert lib.conv_fwd_plan(1, 4, 2, 8, 4, 5, 5, 1, 2, ctypes.byref(plan)) == -3      # P = 0
+    assert lib.conv_fwd_plan(1 << 12, 1 << 10, 1 << 5, 1 << 5, 4, 1, 1, 0, 0, ctypes.byref(plan)) == -4
+    assert lib.conv_fwd_plan(1, 1 << 20, 1, 1, 1 << 11, 1, 1, 0, 0, ctypes.byref(plan)) == -4
+    # null device pointers and bad shapes are rejected before any HIP call
+    assert lib.conv_fwd(None, None, None, *ok) == -1
+    assert lib.conv_fwd(1 << 20, 1 << 20, None, *ok) == -1
+    assert lib.conv_fwd(1 << 20, 1 << 20, 1 << 20, 1, 4, 8, 8, 0, 3, 3, 1, 1) == -2
+    for code in (0, -1, -2, -3, -4, -5, -6, -99):
+        assert binding.conv_strerror(code)
+    with pytest.raises(binding.ConvError) as e:
+        binding.conv_fwd_plan(1, 4, 2, 8, 4, 5, 5, 1, 2)
+    assert e.value.code == -3
+
+
+def test_variant_tables(lib):
+    assert binding.conv_variant_count(binding.CONV_KERNEL_GENERIC) == 1
+    n = binding.conv_variant_count(binding.CONV_KERNEL_TAP)
+    assert n >= 3 and binding.conv_variant_count(77) == 0
+    for v in range(n):
+        tk, mp, bl = binding.conv_variant_info(binding.CONV_KERNEL_TAP, v)
+        assert tk % 16 == 0 and mp % 16 == 0 and bl % 64 == 0 and bl <= 1024
+    with pytest.raises(binding.ConvError):
+        binding.conv_variant_info(binding.CONV_KERNEL_TAP, n)
+
+
+@pytest.mark.parametrize("i", [1, 2, 3, 4, 5])
+def test_plans_of_the_benchmark_layers(i):
+    c = inputs.config(i)
+    p = binding.conv_fwd_plan(*c.dims)
+    assert p.workspace_bytes == 0
+    assert (p.P, p.Q) == (c.P, c.Q)
+    assert p.flops == c.flops and p.bytes == c.algorithmic_bytes
+    assert p.kernel != binding.CONV_KERNEL_GENERIC          # 1x1, 3x3 and 5x5 have specialised kernels
+    assert p.lds_bytes <= 160 * 1024 and p.grid >= 1 and p.block in (64, 128, 256, 512)
+    tiles_k = -(-c.K // p.tile_k)
+    tiles_p = -(-(c.N * c.P * c.Q) // p.tile_pix)
+    assert p.grid == tiles_k * tiles_p
+
+
+def test_plans_cover_odd_shapes():
+    shapes = [(1, 3, 7, 7, 5, 3, 3, 1, 1), (2, 5, 13, 13, 17, 5, 5, 2, 2), (1, 832, 7, 7, 32, 1, 1, 0, 0),
+              (3, 6, 9, 11, 4, 2, 3, 0, 1), (1, 4, 224, 224, 16, 3, 3, 1, 1), (1, 8, 5, 5, 8, 3, 3, 4, 4),
+              (1, 1, 1, 1, 1, 1, 1, 0, 0)]
+    for dims in shapes:
+        p = binding.conv_fwd_plan(*dims)
+        N, C, H, W, K, R, S, ph, pw = dims
+        assert p.P == H + 2 * ph - R + 1 and p.Q == W + 2 * pw - S + 1
+        assert p.workspace_bytes == 0 and p.lds_bytes <= 160 * 1024
+        if R != S or R not in (1, 3, 5):
+            assert p.kernel == binding.CONV_KERNEL_GENERIC

@@ -1,0 +1,213 @@
+"""Parity of the HIP path with the CPU oracle, through the C-ABI (needs an MI355X).
+
+Bar: |y_gpu - y_ref| <= 1e-5 * sum|x*w| + 1e-6 for every output element, the sum taken over the
+element's receptive field; exact equality where the inputs are small integers (all partial sums are
+then exact in fp32, so a dropped or duplicated tap cannot hide inside the tolerance).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2103_16234_amd import binding, inputs
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+TAP = binding.CONV_KERNEL_TAP
+GENERIC = binding.CONV_KERNEL_GENERIC
+
+_ref_cache = {}
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _reference(shape):
+    key = shape
+    if key not in _ref_cache:
+        x, w = inputs.make_inputs(shape)
+        y, ya = oracle.conv_ref(x, w, shape.pad_h, shape.pad_w)
+        if len(_ref_cache) > 8:
+            _ref_cache.clear()
+        _ref_cache[key] = (x, w, y, ya)
+    return _ref_cache[key]
+
+
+def _run(shape, kernel=None, variant=0, tile_pix=0, chunk_c=0, exact=False):
+    x, w, y_ref, ya_ref = _reference(shape)
+    xd = torch.from_numpy(x).cuda()
+    wd = torch.from_numpy(w).cuda()
+    yd = torch.full(shape.y_shape, float("nan"), device="cuda", dtype=torch.float32)   # every element must be written
+    _say(f"[case] {shape.name} dims={shape.dims} kernel={kernel} variant={variant} tile_pix={tile_pix} chunk_c={chunk_c}")
+    if kernel is None:
+        binding.conv_fwd(xd, wd, shape.pad_h, shape.pad_w, y=yd)
+        plan = binding.conv_fwd_plan(*shape.dims)
+    else:
+        _, plan = binding.conv_fwd_planned(xd, wd, shape.pad_h, shape.pad_w, kernel, variant, tile_pix, chunk_c, y=yd)
+    torch.cuda.synchronize()
+    y = yd.cpu().numpy().astype(np.float64)
+    assert not np.isnan(y).any(), "some outputs were never written"
+    if exact:
+        np.testing.assert_array_equal(y, y_ref)
+    ok, worst = oracle.within_tolerance(y, y_ref, ya_ref)
+    assert ok, f"worst (|diff|-1e-6)/(1e-5*sum|xw|) = {worst:.3g} with plan {plan.as_dict()}"
+    return plan, worst
+
+
+def S(name, *dims, x="u01", w="he", seed=1):
+    return inputs.ConvShape(name, *dims, x, w, 100 + seed, 200 + seed)
+
+
+# Small enough for the oracle in well under a second, large enough for several tiles and a ragged tail
+# in every dimension a kernel blocks over (K vs 16/32/64, pixels vs the tile, C vs the chunk of 4k).
+SMALL = [
+    S("s3x3_ragged", 2, 20, 9, 11, 37, 3, 3, 1, 1),
+    S("s3x3_even_w", 3, 12, 14, 14, 70, 3, 3, 1, 1),
+    S("s3x3_w_mult4", 2, 8, 10, 12, 16, 3, 3, 1, 1),
+    S("s3x3_odd_c", 1, 7, 13, 13, 18, 3, 3, 1, 1),          # C not a multiple of 4: scalar loaders
+    S("s3x3_pad0", 2, 16, 12, 10, 33, 3, 3, 0, 0),
+    S("s3x3_pad2", 1, 8, 6, 6, 20, 3, 3, 2, 2),            # wider padding than "same"
+    S("s5x5", 2, 12, 11, 12, 21, 5, 5, 2, 2),
+    S("s5x5_pad0", 1, 16, 9, 9, 40, 5, 5, 0, 0),
+    S("s1x1", 3, 40, 7, 8, 50, 1, 1, 0, 0),
+    S("s1x1_pad1", 2, 12, 5, 6, 17, 1, 1, 1, 1),            # zero frame around the output
+    S("s3x3_tiny_map", 5, 24, 3, 3, 19, 3, 3, 1, 1),        # several images per pixel tile
+    S("s3x3_1pix", 4, 8, 1, 1, 9, 3, 3, 1, 1),              # 1x1 maps: every tap but the centre is padding
+    S("s3x3_wide", 1, 4, 4, 70, 8, 3, 3, 1, 1),             # rows longer than a pixel tile
+    S("s3x3_single", 1, 1, 5, 5, 1, 3, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("shape", SMALL, ids=lambda s: s.name)
+def test_default_plan_matches_oracle(shape):
+    _run(shape)
+
+
+@pytest.mark.parametrize("shape", SMALL, ids=lambda s: s.name)
+def test_generic_kernel_matches_oracle(shape):
+    _run(shape, kernel=GENERIC)
+
+
+@pytest.mark.parametrize("variant", range(5))
+@pytest.mark.parametrize("shape", SMALL, ids=lambda s: s.name)
+def test_every_tap_variant_matches_oracle(shape, variant):
+    if variant >= binding.conv_variant_count(TAP):
+        pytest.skip("no such variant")
+    _run(shape, kernel=TAP, variant=variant)
+
+
+@pytest.mark.parametrize("tile_pix,chunk_c", [(1, 4), (17, 4), (33, 8), (50, 0), (64, 12)])
+def test_odd_tile_requests(tile_pix, chunk_c):
+    shape = S("s3x3_tiles", 2, 20, 9, 11, 37, 3, 3, 1, 1)
+    for variant in range(binding.conv_variant_count(TAP)):
+        _run(shape, kernel=TAP, variant=variant, tile_pix=tile_pix, chunk_c=chunk_c)
+
+
+NONSQUARE = [
+    S("g2x3", 2, 5, 8, 9, 7, 2, 3, 1, 0),
+    S("g7x7", 1, 3, 12, 12, 6, 7, 7, 3, 3),
+    S("g1x5", 2, 4, 6, 10, 5, 1, 5, 0, 2),
+    S("g4x4_pad5", 1, 2, 3, 3, 3, 4, 4, 5, 5),               # windows that lie wholly in the padding give exact zeros
+]
+
+
+@pytest.mark.parametrize("shape", NONSQUARE, ids=lambda s: s.name)
+def test_other_filter_sizes_use_the_generic_kernel(shape):
+    plan, _ = _run(shape)
+    assert plan.kernel == GENERIC
+
+
+@pytest.mark.parametrize("dims", [(2, 12, 9, 10, 35, 3, 3, 1, 1), (1, 16, 8, 8, 20, 5, 5, 2, 2),
+                                  (2, 24, 6, 7, 18, 1, 1, 0, 0), (1, 6, 7, 7, 5, 3, 3, 1, 1)])
+def test_integer_inputs_are_exact(dims):
+    shape = inputs.ConvShape("ints", *dims, "int", "int", 31, 32)
+    _run(shape, exact=True)
+    _run(shape, kernel=GENERIC, exact=True)
+    if dims[5] == dims[6] and dims[5] in (1, 3, 5):
+        for variant in range(binding.conv_variant_count(TAP)):
+            _run(shape, kernel=TAP, variant=variant, exact=True)
+
+
+def test_identity_filter_copies_input_bitwise():
+    x = inputs.uniform_pm1(5, 2 * 24 * 6 * 7).reshape(2, 24, 6, 7)
+    w = np.eye(24, dtype=np.float32).reshape(24, 24, 1, 1)
+    y = binding.conv_fwd(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), 0, 0)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(y.cpu().numpy(), x)
+
+
+def test_all_padding_windows_are_exact_zero():
+    shape = S("zeros", 1, 4, 2, 2, 16, 3, 3, 4, 4)
+    x, w = inputs.make_inputs(shape)
+    y = binding.conv_fwd(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), 4, 4).cpu().numpy()
+    assert y.shape == (1, 16, 8, 8)
+    assert not y[:, :, :2, :].any() and not y[:, :, -2:, :].any() and not y[:, :, :, :2].any()
+    _run(shape)
+
+
+def test_results_are_bitwise_reproducible():
+    shape = S("repro", 2, 32, 14, 14, 48, 3, 3, 1, 1)
+    x, w = inputs.make_inputs(shape)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    y1 = binding.conv_fwd(xd, wd, 1, 1).clone()
+    y2 = binding.conv_fwd(xd, wd, 1, 1)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
+
+
+def test_misaligned_pointers_fall_back_to_narrow_loads():
+    shape = S("misaligned", 2, 8, 10, 12, 16, 3, 3, 1, 1)
+    x, w, y_ref, ya_ref = _reference(shape)
+    for off in (1, 2):
+        xbuf = torch.zeros(x.size + 4, device="cuda")
+        wbuf = torch.zeros(w.size + 4, device="cuda")
+        xd = xbuf[off:off + x.size].view(x.shape)
+        wd = wbuf[off:off + w.size].view(w.shape)
+        xd.copy_(torch.from_numpy(x))
+        wd.copy_(torch.from_numpy(w))
+        _say(f"[case] misaligned by {off} floats")
+        y = binding.conv_fwd(xd, wd, 1, 1)
+        torch.cuda.synchronize()
+        ok, worst = oracle.within_tolerance(y.cpu().numpy(), y_ref, ya_ref)
+        assert ok, worst
+
+
+def test_runs_on_the_callers_stream():
+    shape = S("stream", 1, 16, 14, 14, 16, 3, 3, 1, 1)
+    x, w, y_ref, ya_ref = _reference(shape)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+        y = binding.conv_fwd(xd, wd, 1, 1)
+    st.synchronize()
+    assert oracle.within_tolerance(y.cpu().numpy(), y_ref, ya_ref)[0]
+    binding.conv_set_stream(None)
+
+
+def test_bad_plan_requests_are_refused():
+    shape = S("badplan", 1, 8, 6, 6, 8, 3, 3, 1, 1)
+    x, w = inputs.make_inputs(shape)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    for kw in (dict(kernel=TAP, variant=99), dict(kernel=TAP, variant=0, tile_pix=10 ** 6),
+               dict(kernel=TAP, variant=0, chunk_c=6), dict(kernel=42)):
+        with pytest.raises(binding.ConvError) as e:
+            binding.conv_fwd_planned(xd, wd, 1, 1, **kw)
+        assert e.value.code == -6
+    shape = S("badplan2", 1, 8, 6, 6, 8, 2, 2, 0, 0)
+    x, w = inputs.make_inputs(shape)
+    with pytest.raises(binding.ConvError):
+        binding.conv_fwd_planned(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), 0, 0, kernel=TAP)
+
+
+@pytest.mark.parametrize("i", [1, 2, 3, 4, 5])
+def test_benchmark_layers_full_size(i):
+    """The five benchmark layers at full size, in the launch configuration the benchmark times
+    (conv_fwd with its own plan), every output element against the oracle."""
+    shape = inputs.config(i)
+    plan, worst = _run(shape)
+    _say(f"[result] {shape.name}: worst tolerance ratio {worst:.3g}, plan {plan.as_dict()}")
+    _ref_cache.clear()
