@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the stride-1 forward convolution on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I] [--no-layers] [--no-cpu]
+
+A step is one conv_fwd call (plan, halo/filter staging, MAC loop, store: the whole hot path) on one
+batch of seeded synthetic input that already sits in HBM. The step rotates through enough
+(x, w, y) buffer sets to exceed the 256 MB Infinity Cache, so the HBM figures are not cache hits.
+Prints ONE JSON line: the headline layer at top level (`config.workload`), plus `layers` with the same
+measurement for all five benchmark layers, `roofline` for the headline layer's kernel and
+`cpu_baseline` (the CPU oracle timed on this host on a bounded sample of the same layer).
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+PEAK_FP32_TFLOPS = 157.3   # MI355X dense fp32 (vector packed and matrix), published
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
+# Which roofline binds each layer (arithmetic intensity against the 19.7 FLOP/B machine balance; the 1x1
+# layer sits near the balance point and is treated as HBM-bound, the tiny first layer is launch-bound).
+BOUND = {1: "hbm", 2: "hbm", 3: "mfma", 4: "mfma", 5: "mfma"}
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured.
+TRAFFIC_BYTES = {1: None, 2: None, 3: None, 4: None, 5: None}
+
+
+def _fail(msg: str, code: int = 2):
+    print(msg, file=sys.stderr)
+    sys.exit(code)
+
+
+class Layer:
+    """One benchmark layer with rotating device buffers."""
+
+    def __init__(self, index, torch, binding, inputs, min_bytes=600e6, max_sets=2048):
+        self.index = index
+        self.shape = inputs.config(index)
+        self.torch = torch
+        self.lib = binding.load_library()
+        x, w = inputs.make_inputs(self.shape)
+        self.x_host, self.w_host = x, w
+        per_set = self.shape.algorithmic_bytes
+        self.sets = int(min(max_sets, max(2, -(-int(min_bytes) // per_set))))
+        xd = torch.from_numpy(x).cuda()
+        wd = torch.from_numpy(w).cuda()
+        self.x = xd.unsqueeze(0).repeat(self.sets, 1, 1, 1, 1)
+        self.w = wd.unsqueeze(0).repeat(self.sets, 1, 1, 1, 1)
+        self.y = torch.empty((self.sets,) + self.shape.y_shape, device="cuda", dtype=torch.float32)
+        self.args = [(ctypes.c_void_p(self.x[i].data_ptr()), ctypes.c_void_p(self.w[i].data_ptr()),
+                      ctypes.c_void_p(self.y[i].data_ptr())) for i in range(self.sets)]
+        self.dims = tuple(self.shape.dims)
+        self.plan = binding.conv_fwd_plan(*self.dims)
+        self.calls = 0
+
+    def step(self):
+        xa, wa, ya = self.args[self.calls % self.sets]
+        self.calls += 1
+        rc = self.lib.conv_fwd(xa, wa, ya, *self.dims)
+        if rc != 0:
+            raise RuntimeError(f"conv_fwd failed with code {rc}")
+
+    def measure(self, steps, warmup):
+        """Wall clock and HIP-event time over exactly `steps` launches (after `warmup` untimed ones)."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record()
+        for _ in range(steps):
+            self.step()
+        ev1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        event_ms = ev0.elapsed_time(ev1) / steps
+        return wall_ms, event_ms
+
+    def report(self, wall_ms, event_ms, steps):
+        s = self.shape
+        t = event_ms * 1e-3
+        gflops = s.flops / t / 1e9
+        gbs = s.algorithmic_bytes / t / 1e9
+        bound = BOUND[self.index]
+        return {
+            "layer": s.name, "dims": {"N": s.N, "C": s.C, "H": s.H, "W": s.W, "K": s.K, "R": s.R, "S": s.S,
+                                      "pad": s.pad_h},
+            "steps": steps, "ms_per_step_wall": wall_ms, "kernel_us": event_ms * 1e3,
+            "gflops": gflops, "gbs": gbs,
+            "frac_fp32_peak": gflops / (PEAK_FP32_TFLOPS * 1e3), "frac_hbm_peak": gbs / PEAK_HBM_GBS,
+            "bound": bound, "buffer_sets": self.sets,
+            "plan": {k: getattr(self.plan, k) for k in ("kernel", "variant", "tile_k", "tile_pix", "chunk_c",
+                                                         "x_vec", "w_vec", "grid", "block", "lds_bytes")},
+        }
+
+    def roofline(self, event_ms):
+        s = self.shape
+        t = event_ms * 1e-3
+        bound = BOUND[self.index]
+        if bound == "hbm":
+            achieved, peak, unit = s.algorithmic_bytes / t / 1e9, PEAK_HBM_GBS, "GB/s"
+        else:
+            achieved, peak, unit = s.flops / t / 1e12, PEAK_FP32_TFLOPS, "TFLOP/s"
+        return {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+                "traffic": TRAFFIC_BYTES[self.index], "kernel": "conv_tap_mfma" if self.plan.kernel == 1 else
+                ("conv_pointwise_mfma" if self.plan.kernel == 2 else "conv_generic"),
+                "kernel_us": event_ms * 1e3, "algorithmic_bytes": s.algorithmic_bytes, "algorithmic_flops": s.flops}
+
+    def parity_sample(self, oracle, npts=512):
+        """Spot check of the timed configuration against the oracle on random output elements."""
+        torch = self.torch
+        s = self.shape
+        rng = np.random.default_rng(7)
+        coords = np.stack([rng.integers(0, d, npts) for d in s.y_shape], axis=1).astype(np.int32)
+        self.calls = 0
+        self.step()
+        torch.cuda.synchronize()
+        y = self.y[0].cpu().numpy()
+        y_ref, ya_ref = oracle.conv_ref_points(self.x_host, self.w_host, s.pad_h, s.pad_w, coords)
+        ok, worst = oracle.within_tolerance(y[tuple(coords.T)], y_ref, ya_ref)
+        return {"points": npts, "ok": ok, "worst_ratio": worst}
+
+
+def cpu_baseline(oracle, inputs, index, budget_macs=4e9):
+    """The oracle as it stands, on this host's cores, on the whole layer or on its first images."""
+    s = inputs.config(index)
+    x, w = inputs.make_inputs(s)
+    macs_per_image = s.flops / 2 / s.N
+    n = int(max(1, min(s.N, budget_macs // macs_per_image)))
+    cores = min(os.cpu_count() or 1, 16)
+    oracle.conv_ref(x[:1, :, :4, :4], w[:1], s.pad_h, s.pad_w, nthreads=1)   # load the library
+    reps = int(max(1, min(20, 2e9 // (macs_per_image * n))))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        oracle.conv_ref(x[:n], w, s.pad_h, s.pad_w, nthreads=cores)
+    dt = (time.perf_counter() - t0) / reps
+    return {"value": 2 * macs_per_image * n / dt / 1e9, "unit": "GFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"{s.name}: images 0..{n - 1} of {s.N}, all {s.K} filters, {reps} pass(es), {dt:.3f} s per pass"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed launches of the headline layer (0 = auto)")
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="headline layer, 1..5 (default 2: the 1x1 layer)")
+    ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ns = ap.parse_args()
+    if ns.gpus != 1:
+        _fail("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+    if not 1 <= ns.config <= 5:
+        _fail("bench.py: --config must be 1..5")
+
+    import torch
+    if not torch.cuda.is_available():
+        _fail("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    import oracle
+    from paper_2103_16234_amd import binding, inputs
+
+    binding.load_library()
+    binding.conv_set_stream(torch.cuda.current_stream())
+
+    def auto_steps(layer):
+        _, ev = layer.measure(5, 3)
+        return int(max(50, min(5000, 0.25 / max(ev * 1e-3, 1e-7))))
+
+    head = Layer(ns.config, torch, binding, inputs)
+    steps = ns.steps or auto_steps(head)
+    wall_ms, event_ms = head.measure(steps, ns.warmup)
+    parity = head.parity_sample(oracle)
+    s = head.shape
+    out = {
+        "metric": "effective GFLOP/s per conv layer + % of FP32 peak or HBM GB/s roofline",
+        "value": s.flops / (wall_ms * 1e-3) / 1e9, "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": steps, "warmup": ns.warmup, "ms_per_step": wall_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{s.name}: N={s.N} C={s.C} H=W={s.H} K={s.K} R=S={s.R} pad={s.pad_h} stride 1, "
+                               f"NCHW fp32, {head.sets} rotating buffer sets",
+                   "gbs": s.algorithmic_bytes / (wall_ms * 1e-3) / 1e9},
+        "roofline": head.roofline(event_ms),
+        "parity": parity,
+    }
+    del head
+    torch.cuda.empty_cache()
+    if not ns.no_layers:
+        layers = []
+        for i in range(1, 6):
+            layer = Layer(i, torch, binding, inputs)
+            k = auto_steps(layer)
+            w_ms, e_ms = layer.measure(k, ns.warmup)
+            rec = layer.report(w_ms, e_ms, k)
+            rec["parity"] = layer.parity_sample(oracle, 256)
+            layers.append(rec)
+            del layer
+            torch.cuda.empty_cache()
+        out["layers"] = layers
+    if not ns.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(oracle, inputs, ns.config)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
