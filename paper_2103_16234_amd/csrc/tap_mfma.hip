@@ -51,6 +51,19 @@ template <> struct Vec<1> {
     __device__ void store8(float* p) const { *p = v; }
 };
 
+// Scheduling directive for the code since the previous barrier: issue the matrix instructions in
+// order and slip (up to) two address computations and two LDS reads in front of each, then fence so nothing moves across.
+template <int N_MFMA> __device__ __forceinline__ void interleave_reads_with_mfma()
+{
+#pragma unroll
+    for (int i = 0; i < N_MFMA; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // VALU (addresses of the reads)
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // DS read
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 template <int R, int S, int MT, int NT, int WK, int WP, int VX, int VW>
 __global__ void __launch_bounds__(64 * WK * WP) conv_tap_mfma(const KernelArgs a)
 {
@@ -108,7 +121,7 @@ __global__ void __launch_bounds__(64 * WK * WP) conv_tap_mfma(const KernelArgs a
         const int pq = gc - n * a.PQ;
         const int p = pq / a.Q;
         const int q = pq - p * a.Q;
-        xb[t] = kq * a.lds_plane + (n * a.Hp + p - V0) * a.lds_pitch + q + a.col_shift;
+        xb[t] = 4 * (kq * a.lds_plane + (n * a.Hp + p - V0) * a.lds_pitch + q + a.col_shift);  // bytes
         yb[t] = valid ? n * a.K * a.PQ + pq : -1;
     }
 
@@ -192,7 +205,45 @@ __global__ void __launch_bounds__(64 * WK * WP) conv_tap_mfma(const KernelArgs a
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[m][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int arow = (wk * MT * 16 + j) * a.w_pitch + kq * RS;
+    const int arow = 4 * (xs_floats + (wk * MT * 16 + j) * a.w_pitch + kq * RS);  // bytes from the LDS base
+
+    // A pipeline unit is RU filter rows of one 4-channel group: UT taps, UT*MT*NT matrix instructions.
+    constexpr int RU = (MT * NT >= 6) ? 1 : R;
+    constexpr int UNITS = R / RU;
+    constexpr int UT = RU * S;
+    struct Operands {
+        float a[UT][MT];
+        float b[UT][NT];
+    };
+    auto load_unit = [&](Operands& o, int u) {
+        const int cs = u / UNITS;
+        const int r0 = (u - cs * UNITS) * RU;
+        const char* base = reinterpret_cast<const char*>(xs);
+        const int woff = 4 * (cs * 4 * RS + r0 * S);                         // wave-uniform byte offsets
+        const int xoff = 4 * (cs * 4 * a.lds_plane + r0 * a.lds_pitch);
+#pragma unroll
+        for (int rr = 0; rr < RU; ++rr)
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    o.a[rr * S + s][m] = *reinterpret_cast<const float*>(
+                        base + (arow + woff + 4 * (m * 16 * a.w_pitch + rr * S + s)));
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    o.b[rr * S + s][t] = *reinterpret_cast<const float*>(
+                        base + (xb[t] + xoff + 4 * (rr * a.lds_pitch + s)));
+            }
+    };
+    auto mfma_unit = [&](const Operands& o) {
+#pragma unroll
+        for (int i = 0; i < UT; ++i)
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(o.a[i][m], o.b[i][t], acc[m][t], 0, 0, 0);
+    };
 
     load_chunk(0);
     __syncthreads();  // zero fill complete before any data lands
@@ -204,27 +255,22 @@ __global__ void __launch_bounds__(64 * WK * WP) conv_tap_mfma(const KernelArgs a
         const bool more = ch + 1 < a.nchunks;
         if (more) load_chunk(c0 + a.chunk_c);
 
+        // a3, software pipelined: the LDS reads of unit u+1 are issued before the MFMAs of unit u, so
+        // a wave that has its SIMD to itself never waits on LDS latency between matrix instructions.
         const int groups = (min(a.chunk_c, a.C - c0) + 3) >> 2;
-        for (int cs = 0; cs < groups; ++cs) {
-            const float* wsp = ws + arow + cs * 4 * RS;
-            const float* xsp = xs + cs * 4 * a.lds_plane;
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-#pragma unroll
-                for (int s = 0; s < S; ++s) {
-                    float av[MT], bv[NT];
-#pragma unroll
-                    for (int m = 0; m < MT; ++m) av[m] = wsp[m * 16 * a.w_pitch + r * S + s];
-#pragma unroll
-                    for (int t = 0; t < NT; ++t) bv[t] = xsp[xb[t] + r * a.lds_pitch + s];
-#pragma unroll
-                    for (int m = 0; m < MT; ++m)
-#pragma unroll
-                        for (int t = 0; t < NT; ++t)
-                            acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[m], bv[t], acc[m][t], 0, 0, 0);
-                }
-            }
+        const int units = groups * UNITS;
+        Operands o0, o1;
+        load_unit(o0, 0);
+        int u = 0;
+        for (; u + 2 <= units; u += 2) {
+            load_unit(o1, u + 1);
+            mfma_unit(o0);
+            interleave_reads_with_mfma<UT * MT * NT>();
+            load_unit(o0, min(u + 2, units - 1));
+            mfma_unit(o1);
+            interleave_reads_with_mfma<UT * MT * NT>();
         }
+        if (u < units) mfma_unit(o0);
 
         if (more) {
             __syncthreads();  // every wave has finished reading this chunk
