@@ -23,6 +23,8 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
+COMMON += os.environ.get("CONVFWD_EXTRA_HIPCC_FLAGS", "").split()
+
 TAP_SIZES = (1, 3, 5)
 
 

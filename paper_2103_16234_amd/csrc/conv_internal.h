@@ -29,26 +29,42 @@ struct KernelArgs {
     int w_items;     // vector loads per chunk for the filter block
 };
 
-// Tile shapes of the tap family. A work-group holds WK x WP waves; a wave owns
-// MT x NT MFMA tiles of 16 output channels x 16 pixels.
+// Tile shapes of the tap family. A work-group holds WK x WP x WC waves; a wave owns MT x NT MFMA
+// tiles of 16 output channels x 16 pixels. The WC waves that share a tile position split the channel
+// groups of every chunk between them and add their partial tiles through LDS at the end.
 struct TapVariant {
-    int MT, NT, WK, WP;
+    int MT, NT, WK, WP, WC;
+    int occ;     // waves per SIMD the kernel is compiled for (bounds its registers)
+    int xslots;  // halo-tile vector loads a thread may hold in flight
+    int wslots;  // filter-block vector loads a thread may hold in flight
+    bool dbuf;   // two copies of the LDS staging area (one barrier per chunk, stores hidden in the MAC loop)
     constexpr int tile_k() const { return 16 * MT * WK; }
     constexpr int max_pix() const { return 16 * NT * WP; }
-    constexpr int block() const { return 64 * WK * WP; }
+    constexpr int block() const { return 64 * WK * WP * WC; }
+    // LDS floats the cross-wave reduction needs (first round of the tree is the widest)
+    constexpr int reduce_floats() const { return WC > 1 ? (WC / 2) * WK * WP * MT * NT * 256 : 0; }
+    // LDS bytes a work-group may take so that as many work-groups as the registers allow share a CU
+    constexpr int lds_limit() const { return 160 * 1024 / (occ * 256 / block() > 0 ? occ * 256 / block() : 1); }
 };
-
-constexpr int kTapXSlots = 8;   // halo-tile vector loads a thread may hold in flight
-constexpr int kTapWSlots = 12;  // filter-block vector loads a thread may hold in flight
 
 constexpr TapVariant kTapVariants[] = {
-    {1, 13, 4, 1},  // 0: 64 ch x 208 px  - one 14x14 image (196 px) per work-group
-    {1, 7, 4, 1},   // 1: 64 ch x 112 px
-    {1, 1, 1, 4},   // 2: 16 ch x  64 px  - small layers: one MFMA tile per wave
-    {2, 4, 2, 2},   // 3: 64 ch x 128 px  - 2x4 tiles per wave, fewest LDS reads per MFMA
-    {1, 2, 2, 2},   // 4: 32 ch x  64 px
+    {1, 13, 4, 1, 1, 1, 8, 12, false},  // 0: 64 ch x 208 px, waves split K
+    {1, 7, 4, 1, 1, 1, 8, 12, false},   // 1: 64 ch x 112 px, waves split K
+    {1, 1, 1, 4, 1, 2, 6, 8, false},    // 2: 16 ch x  64 px, one MFMA tile per wave
+    {2, 4, 2, 2, 1, 1, 8, 12, false},   // 3: 64 ch x 128 px, 2x4 tiles per wave
+    {1, 2, 2, 2, 1, 2, 6, 8, false},    // 4: 32 ch x  64 px
+    {1, 7, 4, 1, 1, 2, 6, 8, false},    // 5: 64 ch x 112 px, two work-groups per CU
+    {4, 13, 1, 1, 4, 1, 7, 9, false},   // 6: 64 ch x 208 px (a 14x14 image), every wave owns the whole tile for 1/4 of the channels
+    {4, 7, 1, 1, 4, 1, 8, 12, false},   // 7: 64 ch x 112 px, same scheme
+    {2, 2, 1, 1, 4, 2, 4, 6, false},    // 8: 32 ch x  32 px, same scheme, for layers with few outputs
+    {2, 13, 2, 1, 4, 2, 4, 5, true},    // 9: 64 ch x 208 px, 8 waves: 2 along K x 4 channel shares, two per SIMD
+    {2, 7, 2, 1, 4, 2, 4, 6, true},     // 10: 64 ch x 112 px, same scheme
+    {1, 13, 4, 1, 1, 1, 8, 12, true},   // 11: as 0 with double-buffered staging
+    {1, 13, 4, 1, 2, 2, 4, 5, true},    // 12: 64 ch x 208 px, 8 waves: 4 along K x 2 channel shares, two per SIMD
+    {1, 7, 4, 1, 2, 2, 4, 6, true},     // 13: 64 ch x 112 px, same scheme
 };
 constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
+#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13)
 
 // rs_index: 0 -> 1x1, 1 -> 3x3, 2 -> 5x5. Returns hipSuccess or the launch error.
 hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid, int lds_bytes,

@@ -14,18 +14,18 @@
 
 namespace convfwd {
 
-#define DECLARE_TAP(r, v) \
-    hipError_t launch_tap_##r##x##r##_v##v(int, int, int, int, hipStream_t, const KernelArgs&);
-#define DECLARE_TAP_ALL(r) DECLARE_TAP(r, 0) DECLARE_TAP(r, 1) DECLARE_TAP(r, 2) DECLARE_TAP(r, 3) DECLARE_TAP(r, 4)
-DECLARE_TAP_ALL(1)
-DECLARE_TAP_ALL(3)
-DECLARE_TAP_ALL(5)
-
 using TapLauncher = hipError_t (*)(int, int, int, int, hipStream_t, const KernelArgs&);
-#define TAP_ROW(r) {launch_tap_##r##x##r##_v0, launch_tap_##r##x##r##_v1, launch_tap_##r##x##r##_v2, \
-                    launch_tap_##r##x##r##_v3, launch_tap_##r##x##r##_v4}
-static const TapLauncher kTapLaunchers[3][kNumTapVariants] = {TAP_ROW(1), TAP_ROW(3), TAP_ROW(5)};
-static_assert(kNumTapVariants == 5, "update the launcher table");
+#define DECLARE_TAP1(v) hipError_t launch_tap_1x1_v##v(int, int, int, int, hipStream_t, const KernelArgs&);
+#define DECLARE_TAP3(v) hipError_t launch_tap_3x3_v##v(int, int, int, int, hipStream_t, const KernelArgs&);
+#define DECLARE_TAP5(v) hipError_t launch_tap_5x5_v##v(int, int, int, int, hipStream_t, const KernelArgs&);
+TAP_VARIANT_LIST(DECLARE_TAP1)
+TAP_VARIANT_LIST(DECLARE_TAP3)
+TAP_VARIANT_LIST(DECLARE_TAP5)
+#define ENTRY_TAP1(v) launch_tap_1x1_v##v,
+#define ENTRY_TAP3(v) launch_tap_3x3_v##v,
+#define ENTRY_TAP5(v) launch_tap_5x5_v##v,
+static const TapLauncher kTapLaunchers[3][kNumTapVariants] = {
+    {TAP_VARIANT_LIST(ENTRY_TAP1)}, {TAP_VARIANT_LIST(ENTRY_TAP3)}, {TAP_VARIANT_LIST(ENTRY_TAP5)}};
 
 hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid, int lds_bytes,
                       hipStream_t stream, const KernelArgs& a)
@@ -37,7 +37,7 @@ hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid,
 namespace {
 
 constexpr int kNumCU = 256;              // MI355X: 8 XCDs x 32 CUs
-constexpr int kLdsBudget = 80 * 1024;    // per work-group: lets two work-groups share a CU's 160 KB
+constexpr int kLdsMax = 160 * 1024;      // LDS of one CU
 constexpr int kMaxChunkC = 64;
 
 std::atomic<hipStream_t> g_stream{nullptr};
@@ -142,19 +142,21 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     auto fits = [&](int cc) {
         const int64_t x_items = (int64_t)cc * rows * row_vecs;
         const int64_t w_items = (int64_t)TK * cc * RS / w_vec;
-        const int64_t lds = 4LL * ((int64_t)cc * plane + (int64_t)TK * (cc * RS + 2));
-        return x_items <= (int64_t)kTapXSlots * BLOCK && w_items <= (int64_t)kTapWSlots * BLOCK && lds <= kLdsBudget &&
+        const int64_t lds = (tv.dbuf ? 2 : 1) * 4LL * (((int64_t)cc * plane + (int64_t)TK * (cc * RS + 2) + 3) / 4 * 4);
+        if (cc < 4 * tv.WC) return false;  // every channel-splitting wave needs a group it may read
+        return x_items <= (int64_t)tv.xslots * BLOCK && w_items <= (int64_t)tv.wslots * BLOCK && lds <= tv.lds_limit() &&
                cc * RS < 65536 && (int64_t)cc * plane + rows * pitch < (1 << 20);
     };
-    const int c_pad = round_up(s.C, 4);
+    const int gran = 4 * tv.WC;  // channel-splitting waves take whole 4-channel groups in turn
+    const int c_pad = round_up(s.C, gran);
     if (chunk_c == 0) {
-        int cc = std::min(kMaxChunkC, c_pad);
-        while (cc >= 4 && !fits(cc)) cc -= 4;
-        if (cc < 4) return false;
+        int cc = std::min(kMaxChunkC / gran * gran, c_pad);
+        while (cc >= gran && !fits(cc)) cc -= gran;
+        if (cc < gran) return false;
         const int n = ceil_div(s.C, cc);
-        chunk_c = std::min(cc, round_up(ceil_div(s.C, n), 4));  // even chunks, same count
+        chunk_c = std::min(cc, round_up(ceil_div(s.C, n), gran));  // even chunks, same count
     }
-    if (chunk_c < 4 || chunk_c % 4 != 0 || chunk_c > std::max(c_pad, 4) || !fits(chunk_c)) return false;
+    if (chunk_c < 4 || chunk_c % 4 != 0 || chunk_c > c_pad || !fits(chunk_c)) return false;
 
     base_args(s, a);
     a->tile_pix = tile_pix;
@@ -174,7 +176,8 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     p->x_vec = x_vec; p->w_vec = w_vec;
     p->lds_rows = rows; p->lds_pitch = pitch; p->lds_plane = plane;
     p->grid = a->ktiles * a->ptiles; p->block = BLOCK;
-    p->lds_bytes = round_up(4 * (chunk_c * plane + TK * a->w_pitch), 16);
+    p->lds_bytes = 4 * std::max((tv.dbuf ? 2 : 1) * round_up(chunk_c * plane + TK * a->w_pitch, 4), tv.reduce_floats());
+    if (p->lds_bytes > kLdsMax) return false;
     fill_common(s, p);
     return true;
 }

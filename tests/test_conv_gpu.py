@@ -92,19 +92,31 @@ def test_generic_kernel_matches_oracle(shape):
     _run(shape, kernel=GENERIC)
 
 
-@pytest.mark.parametrize("variant", range(5))
+@pytest.mark.parametrize("variant", range(16))
 @pytest.mark.parametrize("shape", SMALL, ids=lambda s: s.name)
 def test_every_tap_variant_matches_oracle(shape, variant):
     if variant >= binding.conv_variant_count(TAP):
         pytest.skip("no such variant")
-    _run(shape, kernel=TAP, variant=variant)
+    try:
+        _run(shape, kernel=TAP, variant=variant)
+    except binding.ConvError as e:
+        # a tile shape may not fit a layer (too few channels for its channel-splitting waves, LDS):
+        # the library must say so instead of running it
+        assert e.code == -6
 
 
 @pytest.mark.parametrize("tile_pix,chunk_c", [(1, 4), (17, 4), (33, 8), (50, 0), (64, 12)])
 def test_odd_tile_requests(tile_pix, chunk_c):
     shape = S("s3x3_tiles", 2, 20, 9, 11, 37, 3, 3, 1, 1)
+    ran = 0
     for variant in range(binding.conv_variant_count(TAP)):
-        _run(shape, kernel=TAP, variant=variant, tile_pix=tile_pix, chunk_c=chunk_c)
+        _, cap, _ = binding.conv_variant_info(TAP, variant)
+        try:
+            _run(shape, kernel=TAP, variant=variant, tile_pix=min(tile_pix, cap), chunk_c=chunk_c)
+            ran += 1
+        except binding.ConvError as e:
+            assert e.code == -6
+    assert ran >= 5
 
 
 NONSQUARE = [
@@ -129,7 +141,10 @@ def test_integer_inputs_are_exact(dims):
     _run(shape, kernel=GENERIC, exact=True)
     if dims[5] == dims[6] and dims[5] in (1, 3, 5):
         for variant in range(binding.conv_variant_count(TAP)):
-            _run(shape, kernel=TAP, variant=variant, exact=True)
+            try:
+                _run(shape, kernel=TAP, variant=variant, exact=True)
+            except binding.ConvError as e:
+                assert e.code == -6
 
 
 def test_identity_filter_copies_input_bitwise():
