@@ -93,10 +93,11 @@ int conv_fwd_plan(int N, int C, int H, int W, int K, int R, int S, int pad_h, in
 /*
  * As conv_fwd, with the mapping requested by the caller. Only plan->kernel,
  * plan->variant, plan->tile_pix and plan->chunk_c are read as requests (0 in
- * tile_pix / chunk_c means "choose"); every derived field is recomputed and
- * checked, and CONV_E_PLAN is returned if the request cannot be honoured
- * (family does not support R x S, tile exceeds the variant's capacity, LDS
- * does not fit). If resolved is not null it receives the plan actually used.
+ * tile_pix means "the variant's capacity"; chunk_c is fixed by the variant and
+ * may be left 0); every derived field is recomputed and checked, and
+ * CONV_E_PLAN is returned if the request cannot be honoured (family does not
+ * support R x S, tile exceeds the variant's capacity, staging does not fit
+ * the variant's registers or LDS). If resolved is not null it receives the plan actually used.
  */
 int conv_fwd_planned(const float* x, const float* w, float* y,
                      int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,

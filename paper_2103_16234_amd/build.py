@@ -20,7 +20,7 @@ LIB = os.path.join(HERE, "libconvfwd.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -packed-fp32-ops is switched off on purpose: packed fp32 forms are not used on this target pool.
-COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Wall", "-Wno-unused-function",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 COMMON += os.environ.get("CONVFWD_EXTRA_HIPCC_FLAGS", "").split()

@@ -19,49 +19,67 @@ struct KernelArgs {
     int tile_pix;    // output pixels per work-group
     int ktiles;      // work-groups along K
     int ptiles;      // work-groups along the flattened pixels
-    int chunk_c;     // channels per LDS round (multiple of 4)
-    int nchunks;
+    int nchunks;     // channel chunks (the chunk size is a property of the tile shape)
     // LDS halo tile of the tap family
     int lds_rows, lds_pitch, lds_plane;
     int col_shift;   // LDS column of padded column 0 (keeps vector stores aligned)
-    int w_pitch;     // floats per output channel in the LDS filter block
     int x_items;     // vector loads per chunk for the halo tile
-    int w_items;     // vector loads per chunk for the filter block
 };
 
+// Taps per software-pipeline unit of the tap kernel: the shortest of {1, S, R*S} that keeps at least
+// 24 matrix instructions between an LDS read and its use, stepped down again if two operand sets
+// would not fit ~96 registers (~64 with two waves per SIMD).
+constexpr int tap_unit_taps(int S, int RS, int MT, int NT, int occ)
+{
+    const int cand[3] = {1, S, RS};
+    int pick = 2;
+    for (int i = 2; i >= 0; --i)
+        if (cand[i] * MT * NT >= 24) pick = i;
+    while (pick > 0 && 2 * cand[pick] * (MT + NT) > (occ > 1 ? 64 : 96)) --pick;
+    return cand[pick];
+}
+
 // Tile shapes of the tap family. A work-group holds WK x WP x WC waves; a wave owns MT x NT MFMA
-// tiles of 16 output channels x 16 pixels. The WC waves that share a tile position split the channel
-// groups of every chunk between them and add their partial tiles through LDS at the end.
+// tiles of 16 output channels x 16 pixels. A chunk is 4*WC*GPC input channels: the WC waves that share
+// a tile position take the chunk's 4-channel groups in turn (GPC each) and add their partial tiles
+// through LDS at the end.
 struct TapVariant {
-    int MT, NT, WK, WP, WC;
+    int MT, NT, WK, WP, WC, GPC;
     int occ;     // waves per SIMD the kernel is compiled for (bounds its registers)
-    int xslots;  // halo-tile vector loads a thread may hold in flight
-    int wslots;  // filter-block vector loads a thread may hold in flight
-    bool dbuf;   // two copies of the LDS staging area (one barrier per chunk, stores hidden in the MAC loop)
+    int xslots;  // dwordx4 halo-tile loads a thread keeps in flight (x2 / x4 as many when rows force dwordx2 / dword)
     constexpr int tile_k() const { return 16 * MT * WK; }
     constexpr int max_pix() const { return 16 * NT * WP; }
     constexpr int block() const { return 64 * WK * WP * WC; }
-    // LDS floats the cross-wave reduction needs (first round of the tree is the widest)
+    constexpr int chunk_c() const { return 4 * WC * GPC; }
+    // filter-block loads per thread and chunk, and whether that many registers are reasonable
+    constexpr int wslots(int RS, int w_vec) const { return (tile_k() * chunk_c() * RS / w_vec + block() - 1) / block(); }
+    constexpr bool supports(int RS) const { return tile_k() * chunk_c() * RS <= (occ > 1 ? 40 : 64) * block(); }
+    // LDS floats of one staging copy for a halo plane of `plane` floats (with the 256-float dump)
+    constexpr int staging_floats(int RS, int plane) const
+    {
+        return ((chunk_c() * plane + tile_k() * (chunk_c() * RS + 2) + 3) & ~3) + 256;
+    }
+    // LDS floats the cross-wave reduction needs (the first round of the tree is the widest)
     constexpr int reduce_floats() const { return WC > 1 ? (WC / 2) * WK * WP * MT * NT * 256 : 0; }
     // LDS bytes a work-group may take so that as many work-groups as the registers allow share a CU
     constexpr int lds_limit() const { return 160 * 1024 / (occ * 256 / block() > 0 ? occ * 256 / block() : 1); }
 };
 
 constexpr TapVariant kTapVariants[] = {
-    {1, 13, 4, 1, 1, 1, 8, 12, false},  // 0: 64 ch x 208 px, waves split K
-    {1, 7, 4, 1, 1, 1, 8, 12, false},   // 1: 64 ch x 112 px, waves split K
-    {1, 1, 1, 4, 1, 2, 6, 8, false},    // 2: 16 ch x  64 px, one MFMA tile per wave
-    {2, 4, 2, 2, 1, 1, 8, 12, false},   // 3: 64 ch x 128 px, 2x4 tiles per wave
-    {1, 2, 2, 2, 1, 2, 6, 8, false},    // 4: 32 ch x  64 px
-    {1, 7, 4, 1, 1, 2, 6, 8, false},    // 5: 64 ch x 112 px, two work-groups per CU
-    {4, 13, 1, 1, 4, 1, 7, 9, false},   // 6: 64 ch x 208 px (a 14x14 image), every wave owns the whole tile for 1/4 of the channels
-    {4, 7, 1, 1, 4, 1, 8, 12, false},   // 7: 64 ch x 112 px, same scheme
-    {2, 2, 1, 1, 4, 2, 4, 6, false},    // 8: 32 ch x  32 px, same scheme, for layers with few outputs
-    {2, 13, 2, 1, 4, 2, 4, 5, true},    // 9: 64 ch x 208 px, 8 waves: 2 along K x 4 channel shares, two per SIMD
-    {2, 7, 2, 1, 4, 2, 4, 6, true},     // 10: 64 ch x 112 px, same scheme
-    {1, 13, 4, 1, 1, 1, 8, 12, true},   // 11: as 0 with double-buffered staging
-    {1, 13, 4, 1, 2, 2, 4, 5, true},    // 12: 64 ch x 208 px, 8 waves: 4 along K x 2 channel shares, two per SIMD
-    {1, 7, 4, 1, 2, 2, 4, 6, true},     // 13: 64 ch x 112 px, same scheme
+    {1, 13, 4, 1, 1, 4, 1, 8},  //  0: 64 ch x 208 px, waves split K, 16-channel chunks
+    {1, 7, 4, 1, 1, 4, 1, 8},   //  1: 64 ch x 112 px
+    {1, 1, 1, 4, 1, 2, 2, 4},   //  2: 16 ch x  64 px, one MFMA tile per wave, 8-channel chunks
+    {2, 4, 2, 2, 1, 4, 1, 8},   //  3: 64 ch x 128 px, 2x4 tiles per wave
+    {1, 2, 2, 2, 1, 2, 2, 4},   //  4: 32 ch x  64 px, 8-channel chunks
+    {4, 13, 1, 1, 4, 1, 1, 4},  //  5: 64 ch x 208 px (a 14x14 image): every wave owns the whole tile for 1/4 of the channels
+    {4, 7, 1, 1, 4, 1, 1, 4},   //  6: 64 ch x 112 px, same scheme
+    {2, 13, 2, 1, 4, 1, 2, 2},  //  7: 64 ch x 208 px, 8 waves (2 along K x 4 channel shares), two per SIMD
+    {2, 7, 2, 1, 4, 1, 2, 2},   //  8: 64 ch x 112 px, same scheme
+    {2, 2, 1, 1, 4, 1, 2, 4},   //  9: 32 ch x  32 px, 4 channel shares, for layers with few outputs
+    {1, 13, 4, 1, 2, 2, 2, 2},  // 10: 64 ch x 208 px, 8 waves (4 along K x 2 channel shares), two per SIMD
+    {1, 7, 4, 1, 2, 2, 2, 2},   // 11: 64 ch x 112 px, same scheme
+    {1, 7, 4, 1, 1, 2, 1, 8},   // 12: 64 ch x 112 px, 8-channel chunks (large filters)
+    {2, 7, 2, 1, 2, 1, 1, 8},   // 13: 64 ch x 112 px, 2 channel shares, 8-channel chunks (large filters)
 };
 constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
 #define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13)

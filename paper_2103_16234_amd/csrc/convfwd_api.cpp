@@ -38,7 +38,6 @@ namespace {
 
 constexpr int kNumCU = 256;              // MI355X: 8 XCDs x 32 CUs
 constexpr int kLdsMax = 160 * 1024;      // LDS of one CU
-constexpr int kMaxChunkC = 64;
 
 std::atomic<hipStream_t> g_stream{nullptr};
 thread_local std::string g_hip_error = "no HIP error recorded";
@@ -139,45 +138,33 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     const int plane = round_up(std::max(rows * pitch - 16, 0), 32) + 16;
     const int row_vecs = s.W / x_vec;
 
-    auto fits = [&](int cc) {
-        const int64_t x_items = (int64_t)cc * rows * row_vecs;
-        const int64_t w_items = (int64_t)TK * cc * RS / w_vec;
-        const int64_t lds = (tv.dbuf ? 2 : 1) * 4LL * (((int64_t)cc * plane + (int64_t)TK * (cc * RS + 2) + 3) / 4 * 4);
-        if (cc < 4 * tv.WC) return false;  // every channel-splitting wave needs a group it may read
-        return x_items <= (int64_t)tv.xslots * BLOCK && w_items <= (int64_t)tv.wslots * BLOCK && lds <= tv.lds_limit() &&
-               cc * RS < 65536 && (int64_t)cc * plane + rows * pitch < (1 << 20);
-    };
-    const int gran = 4 * tv.WC;  // channel-splitting waves take whole 4-channel groups in turn
-    const int c_pad = round_up(s.C, gran);
-    if (chunk_c == 0) {
-        int cc = std::min(kMaxChunkC / gran * gran, c_pad);
-        while (cc >= gran && !fits(cc)) cc -= gran;
-        if (cc < gran) return false;
-        const int n = ceil_div(s.C, cc);
-        chunk_c = std::min(cc, round_up(ceil_div(s.C, n), gran));  // even chunks, same count
-    }
-    if (chunk_c < 4 || chunk_c % 4 != 0 || chunk_c > c_pad || !fits(chunk_c)) return false;
+    // The chunk is a property of the tile shape; a caller may only name that size.
+    const int cc = tv.chunk_c();
+    if (chunk_c != 0 && chunk_c != cc) return false;
+    chunk_c = cc;
+    if (!tv.supports(RS)) return false;  // the filter block would not fit the variant's registers
+    const int64_t x_floats = (int64_t)cc * rows * s.W;
+    if (x_floats > (int64_t)tv.xslots * 4 * BLOCK) return false;
+    const int64_t copy_floats = tv.staging_floats(RS, plane);
+    const int64_t lds = 4 * std::max<int64_t>(2 * copy_floats, tv.reduce_floats());
+    if (lds > tv.lds_limit() || lds > kLdsMax || copy_floats >= (1 << 16)) return false;
 
     base_args(s, a);
     a->tile_pix = tile_pix;
     a->ktiles = ceil_div(s.K, TK);
     a->ptiles = ceil_div(total, tile_pix);
     if ((int64_t)a->ktiles * a->ptiles >= ((int64_t)1 << 31)) return false;
-    a->chunk_c = chunk_c;
-    a->nchunks = ceil_div(s.C, chunk_c);
+    a->nchunks = ceil_div(s.C, cc);
     a->lds_rows = rows; a->lds_pitch = pitch; a->lds_plane = plane; a->col_shift = col_shift;
-    a->w_pitch = chunk_c * RS + 2;
-    a->x_items = chunk_c * rows * row_vecs;
-    a->w_items = TK * chunk_c * RS / w_vec;
+    a->x_items = cc * rows * row_vecs;
 
     std::memset(p, 0, sizeof(*p));
     p->kernel = CONV_KERNEL_TAP; p->variant = variant;
-    p->tile_k = TK; p->tile_pix = tile_pix; p->chunk_c = chunk_c;
+    p->tile_k = TK; p->tile_pix = tile_pix; p->chunk_c = cc;
     p->x_vec = x_vec; p->w_vec = w_vec;
     p->lds_rows = rows; p->lds_pitch = pitch; p->lds_plane = plane;
     p->grid = a->ktiles * a->ptiles; p->block = BLOCK;
-    p->lds_bytes = 4 * std::max((tv.dbuf ? 2 : 1) * round_up(chunk_c * plane + TK * a->w_pitch, 4), tv.reduce_floats());
-    if (p->lds_bytes > kLdsMax) return false;
+    p->lds_bytes = (int)lds;
     fill_common(s, p);
     return true;
 }

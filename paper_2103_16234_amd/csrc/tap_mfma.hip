@@ -2,23 +2,36 @@
 // reduced over (channel, tap) with full-precision fp32 MFMA (v_mfma_f32_16x16x4_f32).
 //
 // One work-group owns TK output channels x tile_pix output pixels, the pixels counted in
-// flattened (n, p, q) order, and loops over the input channels in chunks:
+// flattened (n, p, q) order, and walks the input channels in chunks of CC = 4*WC*GPC:
 //   a1  halo tile: the rows of the zero-padded, vertically stacked images that the pixel range
-//       touches are copied HBM -> registers -> LDS with dwordx4 (dwordx2 / dword when the row
-//       length forbids) loads; padding cells are zeroed once and never written again;
-//   a2  filter block: w[k0..k0+TK, c0..c0+chunk_c, :, :] is chunk_c*R*S contiguous floats per
-//       output channel and is copied the same way;
-//   a3  for every (4-channel group, r, s): A = filters [16 k x 4 c], B = inputs [4 c x 16 px] read
-//       from the halo tile at the tap's offset, acc += A*B on the matrix cores; each input element
-//       in LDS is reused by the R*S taps and by all TK channels, each filter element by all pixels
-//       (the two reuse levels of Section 3);
-//   a4  accumulators -> y in NCHW, no second pass and no workspace (the per-tap partial matrices
-//       of the two-stage scheme of Section 3 never leave the registers).
-// The next chunk's global loads are issued before the current chunk's MFMA loop and written to
-// LDS after it, so HBM/L2 latency overlaps the arithmetic.
+//       touches go HBM -> registers -> LDS with dwordx4 loads (dwordx2 / dword when the row length
+//       forbids); padding cells are zeroed once and never written again;
+//   a2  filter block: w[k0..k0+TK, c0..c0+CC, :, :] is CC*R*S contiguous floats per output channel
+//       and takes the same path;
+//   a3  for every (4-channel group, r, s): A = filters [16 k x 4 c], B = inputs [4 c x 16 px] read from
+//       the halo tile at the tap's offset, acc += A*B on the matrix cores. Each input element in LDS
+//       is reused by the R*S taps and by all TK channels, each filter element by all pixels (the two
+//       reuse levels of Section 3);
+//   a4  accumulators -> y in NCHW: no second pass and no workspace (the per-tap partial matrices of
+//       the two-stage scheme of Section 3 never leave the registers).
+//
+// What shapes the code (measured on gfx950): a wave's matrix instructions issue back to back only if
+// little else sits between them. One or two independent LDS reads / address adds per MFMA are free;
+// bursts of scalar arithmetic, of global loads (the CU's address path takes 64 B/clk and the issuing
+// wave stalls) or of LDS stores are not. Hence
+//   * the MAC loop of one chunk is fully unrolled with every tap offset a compile-time immediate, and
+//     the LDS reads of unit u+1 are interleaved with the MFMAs of unit u (software pipeline);
+//   * the staging area exists twice. While chunk ch is read from copy ch&1, each thread drips its
+//     staging slots through the chunk: slot k is written (data of chunk ch+1, loaded one chunk ago,
+//     so HBM latency is long gone) to the other copy and at once reloaded with chunk ch+2. No
+//     bursts, one barrier per chunk;
+//   * waves can split the channels of a chunk (WC) and each own a larger tile, which cuts the LDS
+//     reads per MFMA; their partial tiles are added through LDS in a fixed order at the end.
 //
 // Compiled once per (filter size, tile shape): TAP_R, TAP_S, TAP_VARIANT come from the build.
 #include "conv_internal.h"
+
+#include <utility>
 
 namespace convfwd {
 
@@ -29,9 +42,10 @@ template <int V> struct Vec;
 template <> struct Vec<4> {
     f32x4 v;
     __device__ void load(const float* p) { v = *reinterpret_cast<const f32x4*>(p); }
-    __device__ void zero() { v = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    __device__ void keep_if(bool c) { v = c ? v : f32x4{0.f, 0.f, 0.f, 0.f}; }
     __device__ void store16(float* p) const { *reinterpret_cast<f32x4*>(p) = v; }
-    __device__ void store8(float* p) const {
+    __device__ void store8(float* p) const
+    {
         *reinterpret_cast<f32x2*>(p) = f32x2{v.x, v.y};
         *reinterpret_cast<f32x2*>(p + 2) = f32x2{v.z, v.w};
     }
@@ -39,68 +53,66 @@ template <> struct Vec<4> {
 template <> struct Vec<2> {
     f32x2 v;
     __device__ void load(const float* p) { v = *reinterpret_cast<const f32x2*>(p); }
-    __device__ void zero() { v = f32x2{0.f, 0.f}; }
+    __device__ void keep_if(bool c) { v = c ? v : f32x2{0.f, 0.f}; }
     __device__ void store16(float* p) const { *reinterpret_cast<f32x2*>(p) = v; }
     __device__ void store8(float* p) const { *reinterpret_cast<f32x2*>(p) = v; }
 };
 template <> struct Vec<1> {
     float v;
     __device__ void load(const float* p) { v = *p; }
-    __device__ void zero() { v = 0.f; }
+    __device__ void keep_if(bool c) { v = c ? v : 0.f; }
     __device__ void store16(float* p) const { *p = v; }
     __device__ void store8(float* p) const { *p = v; }
 };
 
-// Taps per pipeline unit: the shortest of {1, S, R*S} that keeps at least 24 matrix instructions
-// between a read and its use, stepped down again if two operand sets would not fit ~96 registers (~64 with two waves per SIMD).
-constexpr int unit_taps(int S, int RS, int MT, int NT, int OCC)
-{
-    const int cand[3] = {1, S, RS};
-    int pick = 2;
-    for (int i = 2; i >= 0; --i)
-        if (cand[i] * MT * NT >= 24) pick = i;
-    while (pick > 0 && 2 * cand[pick] * (MT + NT) > (OCC > 1 ? 64 : 96)) --pick;
-    return cand[pick];
-}
+template <int N> using IntC = std::integral_constant<int, N>;
 
-// Scheduling directive for the code since the previous barrier: issue the matrix instructions in
-// order and slip (up to) two address computations and two LDS reads in front of each, then fence so nothing moves across.
-template <int N_MFMA> __device__ __forceinline__ void interleave_reads_with_mfma()
+// Scheduling directive for the straight-line code since the previous fence: issue the matrix
+// instructions in order and slip in front of each a few address adds, up to two LDS reads, one LDS
+// store and one global load; then fence so nothing moves across.
+template <int N_MFMA> __device__ __forceinline__ void interleave_with_mfma()
 {
 #pragma unroll
     for (int i = 0; i < N_MFMA; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // VALU (addresses of the reads)
+        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // VALU
         __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // DS read
+        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // DS write
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
     }
     __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int R, int S, int MT, int NT, int WK, int WP, int WC, int OCC, int XS, int WS, bool DB, int VX, int VW>
+template <int R, int S, int MT, int NT, int WK, int WP, int WC, int GPC, int OCC, int XS, int WS, int VX, int VW>
 __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const KernelArgs a)
 {
     static_assert(WC == 1 || WC == 2 || WC == 4, "the cross-wave reduction is a binary tree");
     constexpr int BLOCK = 64 * WK * WP * WC;
     constexpr int RS = R * S;
     constexpr int TK = 16 * MT * WK;
+    constexpr int CC = 4 * WC * GPC;     // channels per chunk
+    constexpr int WPITCH = CC * RS + 2;  // floats per output channel in the LDS filter block
+    constexpr int UT = tap_unit_taps(S, RS, MT, NT, OCC);
+    constexpr int UNITS = RS / UT;       // pipeline units per 4-channel group
+    constexpr int U = GPC * UNITS;       // pipeline units per chunk (per wave)
+    constexpr int TS = XS + WS;          // staging slots per thread
 
     extern __shared__ f32x4 smem4[];
-    float* const xs = reinterpret_cast<float*>(smem4);
-    const int xs_floats = a.chunk_c * a.lds_plane;
-    float* const ws = xs + xs_floats;
-    const int ws_floats = TK * a.w_pitch;
-    // With DB the staging area exists twice: chunk ch is read from copy ch&1 while chunk ch+1 is
-    // written to the other copy in the middle of the MAC loop, and one barrier per chunk suffices.
-    const int buf_floats = (xs_floats + ws_floats + 3) & ~3;
+    float* const lds = reinterpret_cast<float*>(smem4);
+    // One staging copy: halo tile [CC][plane], filter block [TK][WPITCH], then a 64 x 16 B dump that
+    // absorbs the stores of slots a thread does not own.
+    const int xs_floats = CC * a.lds_plane;
+    const int dump_off = (xs_floats + TK * WPITCH + 3) & ~3;
+    const int buf_floats = dump_off + 256;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps wk/wp/wc in SGPRs
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: wk, wp, wc live in SGPRs
     const int j = lane & 15;   // pixel column of B / D, output-channel row of A
     const int kq = lane >> 4;  // channel within the 4-channel group (A, B); row group of D
     const int wk = wave % WK;
     const int wp = (wave / WK) % WP;
-    const int wc = wave / (WK * WP);  // which share of the channel groups this wave reduces
+    const int wc = wave / (WK * WP);  // this wave reduces the chunk's channel groups wc + WC*gi
 
     // Work-groups are dealt round-robin to the 8 XCDs; renumber them so that each XCD (one L2)
     // gets a contiguous run of tiles: neighbours share the pixel tile and walk the K tiles.
@@ -118,15 +130,13 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     const int n0 = g0 / a.PQ;
     const int V0 = n0 * a.Hp + (g0 - n0 * a.PQ) / a.Q;  // first stacked padded row held in LDS
 
-    // Zero the whole LDS allocation once: padding cells, rows past the batch and output
-    // channels past K then stay zero for the whole kernel.
-    {
-        const int n4 = (DB ? 2 : 1) * (buf_floats >> 2);
-        for (int i = tid; i < n4; i += BLOCK) smem4[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+    // Zero both staging copies once: padding cells, rows past the batch and output channels past K
+    // then stay zero for the whole kernel.
+    for (int i = tid; i < (2 * buf_floats) >> 2; i += BLOCK) smem4[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // Per-lane pixel table: byte offset in LDS of the origin of the pixel's window (lanes past the
-    // end of the tile read the tile's last pixel and are masked at the store).
+    // Per-lane pixel table: byte offset inside a staging copy of the origin of the pixel's window, for
+    // this lane's channel of this wave's first group (lanes past the end of the tile read the tile's
+    // last pixel and are masked at the store).
     int xb[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
@@ -135,11 +145,14 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         const int pq = gc - n * a.PQ;
         const int p = pq / a.Q;
         const int q = pq - p * a.Q;
-        xb[t] = 4 * (kq * a.lds_plane + (n * a.Hp + p - V0) * a.lds_pitch + q + a.col_shift);
+        xb[t] = 4 * ((4 * wc + kq) * a.lds_plane + (n * a.Hp + p - V0) * a.lds_pitch + q + a.col_shift);
     }
+    const int arow = 4 * (xs_floats + (wk * MT * 16 + j) * WPITCH + (4 * wc + kq) * RS);
 
-    // Halo-tile load slots: global offset (channel 0 of the chunk) and packed LDS offset | channel<<20.
-    int xg[XS], xl[XS];
+    // Staging slots. xg / wg: offset in floats from the chunk's first channel in x / w; xl / wl: float
+    // offset inside a staging copy in the low 16 bits, the slot's channel (x) or element offset in the
+    // chunk's filter slice (w) above. Slots the thread does not own read element 0 and write the dump.
+    unsigned xg[XS], xl[XS], wg[WS], wl[WS];
     {
         const int XV = a.W / VX;
         const int per_c = a.lds_rows * XV;
@@ -147,7 +160,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         for (int i = 0; i < XS; ++i) {
             const int e = tid + i * BLOCK;
             xg[i] = 0;
-            xl[i] = -1;
+            xl[i] = dump_off + lane * 4;
             if (e < a.x_items) {
                 const int c_l = e / per_c;
                 const int rem = e - c_l * per_c;
@@ -158,23 +171,23 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
                 const int h = v - n * a.Hp - a.pad_h;
                 if (n < a.N && h >= 0 && h < a.H) {
                     xg[i] = ((n * a.C + c_l) * a.H + h) * a.W + cv * VX;
-                    xl[i] = (c_l * a.lds_plane + row * a.lds_pitch + a.col_shift + a.pad_w + cv * VX) | (c_l << 20);
+                    xl[i] = (c_l * a.lds_plane + row * a.lds_pitch + a.col_shift + a.pad_w + cv * VX) | (c_l << 16);
                 }
             }
         }
-    }
-    // Filter-block load slots: (local output channel << 16) | element offset inside the chunk's slice.
-    int wpk[WS];
-    {
-        const int WV = a.chunk_c * RS / VW;
+        constexpr int WV = CC * RS / VW;
 #pragma unroll
         for (int i = 0; i < WS; ++i) {
             const int e = tid + i * BLOCK;
-            wpk[i] = -1;
-            if (e < a.w_items) {
+            wg[i] = 0;
+            wl[i] = dump_off + lane * 4;
+            if (e < TK * WV) {
                 const int kl = e / WV;
                 const int ev = (e - kl * WV) * VW;
-                if (k0 + kl < a.K) wpk[i] = (kl << 16) | ev;
+                if (k0 + kl < a.K) {
+                    wg[i] = kl * a.CRS + ev;
+                    wl[i] = (xs_floats + kl * WPITCH + ev) | (ev << 16);
+                }
             }
         }
     }
@@ -182,34 +195,28 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     Vec<VX> xv[XS];
     Vec<VW> wv[WS];
 
-    auto load_chunk = [&](int c0) {
-        const float* xc = a.x + c0 * a.HW;
-#pragma unroll
-        for (int i = 0; i < XS; ++i) {
-            xv[i].zero();
-            if (xl[i] >= 0 && c0 + (xl[i] >> 20) < a.C) xv[i].load(xc + static_cast<unsigned>(xg[i]));
-        }
-        const int valid_len = min(a.chunk_c, a.C - c0) * RS;
-        const float* wc = a.w + k0 * a.CRS + c0 * RS;
-#pragma unroll
-        for (int i = 0; i < WS; ++i) {
-            wv[i].zero();
-            if (wpk[i] >= 0) {
-                const int kl = wpk[i] >> 16, ev = wpk[i] & 0xffff;
-                if (ev < valid_len) wv[i].load(wc + static_cast<unsigned>(kl * a.CRS + ev));
-            }
+    // One slot of the staging pipeline: slot k < XS is a halo-tile slot, the others filter slots.
+    auto slot_load = [&](auto kc, int c0) {
+        constexpr int k = decltype(kc)::value;
+        if constexpr (k < XS) xv[k].load(a.x + c0 * a.HW + xg[k]);
+        else wv[k - XS].load(a.w + k0 * a.CRS + c0 * RS + wg[k - XS]);
+    };
+    // c0: first channel of the chunk the slot's data belongs to; channels past C are stored as zeros.
+    auto slot_store = [&](auto kc, int c0, int dst_floats) {
+        constexpr int k = decltype(kc)::value;
+        if constexpr (k < XS) {
+            Vec<VX> t = xv[k];
+            t.keep_if(c0 + static_cast<int>(xl[k] >> 16) < a.C);
+            t.store16(lds + dst_floats + (xl[k] & 0xffff));
+        } else {
+            Vec<VW> t = wv[k - XS];
+            t.keep_if(static_cast<int>(wl[k - XS] >> 16) < (a.C - c0) * RS);
+            t.store8(lds + dst_floats + (wl[k - XS] & 0xffff));  // rows are 8-byte aligned (pitch = 2 mod 4)
         }
     };
-    auto store_chunk = [&](int buf_off) {
-#pragma unroll
-        for (int i = 0; i < XS; ++i)
-            if (xl[i] >= 0) xv[i].store16(xs + buf_off + (xl[i] & 0xfffff));
-#pragma unroll
-        for (int i = 0; i < WS; ++i)
-            if (wpk[i] >= 0) {
-                const int kl = wpk[i] >> 16, ev = wpk[i] & 0xffff;
-                wv[i].store8(ws + buf_off + kl * a.w_pitch + ev);  // rows are 8-byte aligned (pitch = 2 mod 4)
-            }
+    auto for_each_slot = [&](auto&& f) {
+        [&]<int... Ks>(std::integer_sequence<int, Ks...>) { (f(IntC<Ks>{}), ...); }
+        (std::make_integer_sequence<int, TS>{});
     };
 
     f32x4 acc[MT][NT];
@@ -218,111 +225,84 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[m][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int arow = 4 * (xs_floats + (wk * MT * 16 + j) * a.w_pitch + kq * RS);  // bytes from the LDS base
+    // Prologue: chunk 0 goes straight into copy 0, chunk 1 waits in the registers.
+    const int last_c0 = (a.nchunks - 1) * CC;
+    for_each_slot([&](auto kc) { slot_load(kc, 0); });
+    __syncthreads();  // zero fill complete before any data lands
+    for_each_slot([&](auto kc) { slot_store(kc, 0, 0); });
+    for_each_slot([&](auto kc) { slot_load(kc, min(CC, last_c0)); });
+    __syncthreads();
 
-    // A pipeline unit is UT consecutive taps of one 4-channel group (UT*MT*NT matrix instructions):
-    // one tap when the wave owns many tiles, a filter row, or the whole filter when it owns few.
-    constexpr int UT = unit_taps(S, RS, MT, NT, OCC);
-    constexpr int UNITS = RS / UT;
     struct Operands {
         float a[UT][MT];
         float b[UT][NT];
     };
-    int cur_bytes = 0;  // byte offset of the staging copy being read
-    auto load_unit = [&](Operands& o, int u) {
-        const int gi = u / UNITS;
-        const int cs = wc + WC * gi;  // waves with different wc take the channel groups round-robin
-        const int tap0 = (u - gi * UNITS) * UT;
-        const int r0 = tap0 / S, s0 = tap0 - r0 * S;  // s0 is 0 unless the unit is a single tap
-        const char* base = reinterpret_cast<const char*>(xs) + cur_bytes;
-        const int woff = 4 * (cs * 4 * RS + tap0);  // wave-uniform byte offsets
-        const int xoff = 4 * (cs * 4 * a.lds_plane + r0 * a.lds_pitch + s0);
-#pragma unroll
-        for (int i = 0; i < UT; ++i) {
-            const int rr = i / S, s = i - rr * S;
-#pragma unroll
-            for (int m = 0; m < MT; ++m)
-                o.a[i][m] = *reinterpret_cast<const float*>(base + (arow + woff + 4 * (m * 16 * a.w_pitch + i)));
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-                o.b[i][t] = *reinterpret_cast<const float*>(base + (xb[t] + xoff + 4 * (rr * a.lds_pitch + s)));
-        }
-    };
-    auto mfma_unit = [&](const Operands& o) {
-#pragma unroll
-        for (int i = 0; i < UT; ++i)
-#pragma unroll
-            for (int m = 0; m < MT; ++m)
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-                    acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(o.a[i][m], o.b[i][t], acc[m][t], 0, 0, 0);
-    };
-
-    load_chunk(0);
-    __syncthreads();  // zero fill complete before any data lands
-    store_chunk(0);
-    __syncthreads();
-
-    // A wave stalls while it issues its burst of global loads (the CU's address path takes them at
-    // 64 B/clk) or LDS stores, and its own matrix instructions do not overlap that. Waves that share
-    // a SIMD therefore do both at different points of their MAC loops: one of the two always has
-    // matrix work to issue.
-    const int stagger = (wave >> 2) & 1;
+    const char* const lds_bytes = reinterpret_cast<const char*>(lds);
 
     for (int ch = 0; ch < a.nchunks; ++ch) {
-        const int c0 = ch * a.chunk_c;
-#ifdef EXP_NO_RELOAD
-        const bool more = false;
-#else
-        const bool more = ch + 1 < a.nchunks;
-#endif
-        const int next_off = DB ? ((ch + 1) & 1) * buf_floats : 0;
-        cur_bytes = DB ? (ch & 1) * buf_floats * 4 : 0;
-        // a3, software pipelined: the LDS reads of unit u+1 are issued before the MFMAs of unit u. A
-        // wave's own loads and address arithmetic do not overlap its matrix instructions, a second wave
-        // on the SIMD does; hence few reads per MFMA and, where registers allow, two waves per SIMD.
-        const int groups = (min(a.chunk_c, a.C - c0) + 3) >> 2;
-        const int units = groups > wc ? (groups - wc + WC - 1) / WC * UNITS : 0;
-        const int store_at = DB && more ? ((units * (2 + stagger)) >> 2) & ~1 : -1;
-        const int load_at = DB && units >= 8 ? 2 * stagger : 0;
-        bool stored = false;
-        if (more && load_at == 0) load_chunk(c0 + a.chunk_c);
-        Operands o0, o1;
-        load_unit(o0, 0);  // in bounds even when this wave has no group in a ragged last chunk
-        int u = 0;
-        for (; u + 2 <= units; u += 2) {
-            if (more && load_at != 0 && u == load_at) load_chunk(c0 + a.chunk_c);
-            if (u == store_at) {
-                store_chunk(next_off);
-                stored = true;
-            }
-#ifdef EXP_NO_LDS_READ
-            if (u == 0) load_unit(o1, u + 1);
-            mfma_unit(o0);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_unit(o1);
-            __builtin_amdgcn_sched_barrier(0);
-#else
-            load_unit(o1, u + 1);
-            mfma_unit(o0);
-            interleave_reads_with_mfma<UT * MT * NT>();
-            load_unit(o0, min(u + 2, units - 1));
-            mfma_unit(o1);
-            interleave_reads_with_mfma<UT * MT * NT>();
-#endif
-        }
-        if (u < units) mfma_unit(o0);
+        const int cur_bytes = (ch & 1) * buf_floats * 4;
+        const int nxt_floats = ((ch + 1) & 1) * buf_floats;
+        const int c0_regs = min((ch + 1) * CC, last_c0);  // chunk whose data the staging registers hold
+        const int c0_load = min((ch + 2) * CC, last_c0);  // chunk to fetch next (the last one again at the end)
 
-        if (more) {
-            if (DB) {
-                if (!stored) store_chunk(next_off);
-                __syncthreads();  // all waves are done reading this copy and writing the other
-            } else {
-                __syncthreads();  // every wave has finished reading this chunk
-                store_chunk(0);
-                __syncthreads();
+        const char* const a_base = lds_bytes + cur_bytes + arow;
+        int xa[NT];  // B addresses of the filter row being read
+        Operands o0, o1;
+
+        // Operands of unit ui: taps tap0 .. tap0+UT-1 of this wave's group gi of the chunk.
+        auto load_unit = [&](Operands& o, auto uic) {
+            constexpr int ui = decltype(uic)::value;
+            constexpr int gi = ui / UNITS;
+            constexpr int tap0 = (ui % UNITS) * UT;
+            constexpr int r0 = tap0 / S, s0 = tap0 % S;
+            if constexpr (s0 == 0) {
+                const int row_off = cur_bytes + 16 * gi * WC * a.lds_plane + 4 * r0 * a.lds_pitch;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) xa[t] = xb[t] + row_off;
             }
-        }
+#pragma unroll
+            for (int i = 0; i < UT; ++i) {
+                const int rr = i / S, s = s0 + i - rr * S;
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    o.a[i][m] = *reinterpret_cast<const float*>(
+                        a_base + 4 * (gi * WC * 4 * RS + tap0 + i + m * 16 * WPITCH));
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    o.b[i][t] = *reinterpret_cast<const float*>(lds_bytes + (xa[t] + 4 * (rr * a.lds_pitch + s)));
+            }
+        };
+        auto mfma_unit = [&](const Operands& o) {
+#pragma unroll
+            for (int i = 0; i < UT; ++i)
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(o.a[i][m], o.b[i][t], acc[m][t], 0, 0, 0);
+        };
+        // Unit ui: read the operands of unit ui+1, move this unit's share of the staging slots
+        // (write chunk ch+1 to the other copy, refill with chunk ch+2), multiply.
+        auto unit = [&](auto uic) {
+            constexpr int ui = decltype(uic)::value;
+            Operands& cur = (ui & 1) ? o1 : o0;
+            Operands& nxt = (ui & 1) ? o0 : o1;
+            if constexpr (ui + 1 < U) load_unit(nxt, IntC<ui + 1>{});
+            for_each_slot([&](auto kc) {
+                if constexpr (decltype(kc)::value * U / TS == ui) {
+                    slot_store(kc, c0_regs, nxt_floats);
+                    slot_load(kc, c0_load);
+                }
+            });
+            mfma_unit(cur);
+            interleave_with_mfma<UT * MT * NT>();
+        };
+
+        load_unit(o0, IntC<0>{});
+        [&]<int... UIs>(std::integer_sequence<int, UIs...>) { (unit(IntC<UIs>{}), ...); }
+        (std::make_integer_sequence<int, U>{});
+
+        __syncthreads();  // every wave is done reading this copy and writing the other
     }
 
     // Waves that split the channels add their partial tiles through LDS, as a binary tree in a fixed
@@ -330,7 +310,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     if constexpr (WC > 1) {
 #pragma unroll
         for (int stride = WC / 2; stride >= 1; stride /= 2) {
-            __syncthreads();  // the staging buffers (first pass) or the previous round's partials are dead
+            if (stride != WC / 2) __syncthreads();  // the previous round's partials are dead
             const int slot = ((wc - stride) * WP + wp) * WK + wk;
             f32x4* const part = smem4 + slot * (MT * NT * 64) + lane;
             if (wc >= stride && wc < 2 * stride) {
@@ -377,7 +357,12 @@ using KernFn = void (*)(const KernelArgs);
 template <int VX, int VW> static KernFn instance()
 {
     constexpr TapVariant tv = kTapVariants[TAP_VARIANT];
-    return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.occ, tv.xslots, tv.wslots, tv.dbuf, VX, VW>;
+    if constexpr (!tv.supports(TAP_R * TAP_S)) {
+        return nullptr;  // the filter block of this filter size does not fit the variant's registers
+    } else {
+        return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, tv.occ, tv.xslots * 4 / VX,
+                             tv.wslots(TAP_R * TAP_S, VW), VX, VW>;
+    }
 }
 
 // One exported launcher per translation unit, named by filter size and tile shape.
