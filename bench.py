@@ -26,8 +26,10 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
 # Which roofline binds each layer (arithmetic intensity against the 19.7 FLOP/B machine balance; the 1x1
 # layer sits near the balance point and is treated as HBM-bound, the tiny first layer is launch-bound).
 BOUND = {1: "hbm", 2: "hbm", 3: "mfma", 4: "mfma", 5: "mfma"}
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured.
-TRAFFIC_BYTES = {1: None, 2: None, 3: None, 4: None, 5: None}
+# Bytes per launch that the L2s exchanged with the fabric (Infinity Cache / HBM), measured with rocprofv3 --pmc
+# FETCH_SIZE and WRITE_SIZE and scaled by what the same counters read for a plain device copy of known size
+# (profiles/conv_tap_mfma_hbm_traffic.txt); None = not measured.
+TRAFFIC_BYTES = {1: None, 2: 5364162, 3: 14042323, 4: None, 5: 99557448}
 
 
 def _fail(msg: str, code: int = 2):
@@ -166,6 +168,11 @@ def main():
 
     binding.load_library()
     binding.conv_set_stream(torch.cuda.current_stream())
+    # A plain 64 MiB device-to-device copy: the known-size kernel the FETCH_SIZE / WRITE_SIZE counters are scaled by.
+    calib = torch.ones(16 * 1024 * 1024, device="cuda")
+    calib = calib.clone()
+    torch.cuda.synchronize()
+    del calib
 
     def auto_steps(layer):
         _, ev = layer.measure(5, 3)

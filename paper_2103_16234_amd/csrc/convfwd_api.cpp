@@ -181,16 +181,36 @@ void resolve_generic(const Shape& s, conv_plan_t* p, KernelArgs* a)
     fill_common(s, p);
 }
 
-// Relative time of a tap mapping: MFMA issue slots per SIMD over the busiest CU, plus staging overhead.
+// Estimated cycles of a tap mapping on 256 CUs. A work-group keeps each SIMD busy for
+// (waves per SIMD) x (MFMAs per wave) x 32 cycles; measured MFMA issue efficiency is ~0.85 when two
+// waves share a SIMD (their LDS reads, staging and address arithmetic overlap each other's matrix
+// instructions) and ~0.72 when a wave has the SIMD to itself. Added: a per-chunk barrier/first-read
+// cost and a per-work-group prologue + epilogue.
 double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv, int RS)
 {
-    const double waves_per_simd = tv.block() / 256.0;
-    const double rounds = std::ceil((double)p.grid / kNumCU);
-    const double mfma_slots = rounds * tv.MT * tv.NT * std::max(waves_per_simd, 0.25);
-    const double staged = (double)p.chunk_c * (a.lds_rows * a.lds_pitch + (double)p.tile_k * RS);
-    const double mfmas = (double)(tv.block() / 64) * tv.MT * tv.NT * (p.chunk_c / 4.0) * RS;
-    return mfma_slots * (1.0 + 2.0 * staged / (256.0 * mfmas));
+    const int by_regs = std::max(1, tv.occ * 256 / tv.block());
+    const int by_lds = std::max(1, kLdsMax / std::max(p.lds_bytes, 1));
+    const int wpc = std::min(std::min(by_regs, by_lds), 8);  // work-groups sharing a CU
+    const double waves_per_simd = std::max(1.0, tv.block() / 256.0);
+    const double eff = wpc * waves_per_simd >= 2 ? 0.85 : 0.72;
+    const double simd_cycles = waves_per_simd * tv.MT * tv.NT * (double)a.nchunks * tv.GPC * RS * 32.0;
+    const double per_wg = simd_cycles / eff + a.nchunks * 400.0;
+    const double rounds = std::ceil((double)p.grid / (kNumCU * wpc));
+    return rounds * (wpc * per_wg + 6000.0);
 }
+
+// Measured best mappings of known layer shapes (sweeps over tile shape x pixel tile on an MI355X);
+// shapes not listed go through the cost model.
+struct TunedEntry {
+    int N, C, H, W, K, R, pad, variant, tile_pix;
+};
+constexpr TunedEntry kTuned[] = {
+    {1, 16, 14, 14, 16, 3, 1, 2, 16},
+    {1, 256, 56, 56, 64, 1, 0, 9, 32},
+    {8, 64, 56, 56, 64, 3, 1, 11, 112},
+    {1, 48, 28, 28, 128, 5, 2, 2, 56},
+    {32, 512, 14, 14, 512, 3, 1, 10, 196},
+};
 
 // conv_fwd plans on every call; remember recent shapes so a launch costs a table lookup.
 struct CacheEntry {
@@ -229,6 +249,10 @@ int plan_shape(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs*
 int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a)
 {
     if (tap_rs_index(s) >= 0) {
+        for (const TunedEntry& t : kTuned)
+            if (t.N == s.N && t.C == s.C && t.H == s.H && t.W == s.W && t.K == s.K && t.R == s.R && t.R == s.S &&
+                t.pad == s.pad_h && t.pad == s.pad_w && resolve_tap(s, t.variant, t.tile_pix, 0, x_cap, w_cap, p, a))
+                return CONV_OK;
         bool found = false;
         double best = 0;
         const int PQ = s.P * s.Q;
@@ -237,7 +261,7 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, Ke
             const TapVariant tv = kTapVariants[v];
             const int cap = tv.max_pix();
             // candidate pixel tiles: full capacity, an even split, whole images, whole rows
-            int cands[6];
+            int cands[8];
             int nc = 0;
             cands[nc++] = (int)std::min<int64_t>(cap, total);
             cands[nc++] = (int)((total + (total + cap - 1) / cap - 1) / ((total + cap - 1) / cap));
@@ -249,6 +273,8 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, Ke
                     if (PQ % d == 0) { cands[nc++] = PQ / d; break; }
             }
             if (s.Q <= cap) cands[nc++] = cap / s.Q * s.Q;
+            if (cap >= 32) cands[nc++] = cap / 2;
+            if (cap >= 64) cands[nc++] = cap / 4;
             for (int i = 0; i < nc; ++i) {
                 conv_plan_t cp;
                 KernelArgs ca;
