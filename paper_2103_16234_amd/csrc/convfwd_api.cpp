@@ -169,6 +169,48 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     return true;
 }
 
+// Pointwise family: 1x1 filters, no padding, planes and channel runs that dwordx4 can walk.
+bool pointwise_ok(const Shape& s, int x_cap, int w_cap, int y_cap)
+{
+    return s.R == 1 && s.S == 1 && s.pad_h == 0 && s.pad_w == 0 && (s.H * s.W) % 4 == 0 && s.C % 4 == 0 &&
+           x_cap >= 4 && w_cap >= 4 && y_cap >= 4;
+}
+
+bool resolve_pointwise(const Shape& s, int variant, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
+{
+    if (!pointwise_ok(s, x_cap, w_cap, y_cap) || variant < 0 || variant >= kNumPointwiseVariants) return false;
+    const PointwiseVariant pv = kPointwiseVariants[variant];
+    base_args(s, a);
+    a->tile_pix = 64;
+    a->ktiles = ceil_div(s.K, pv.tile_k());
+    a->ptiles = ceil_div(s.H * s.W, 64);  // per image
+    const int64_t grid = (int64_t)a->ktiles * a->ptiles * s.N;
+    if (grid >= ((int64_t)1 << 31)) return false;
+    a->nchunks = ceil_div(s.C, 16);
+    std::memset(p, 0, sizeof(*p));
+    p->kernel = CONV_KERNEL_POINTWISE; p->variant = variant;
+    p->tile_k = pv.tile_k(); p->tile_pix = 64; p->chunk_c = 16 * pv.WC;
+    p->x_vec = 4; p->w_vec = 4;
+    p->grid = (int)grid; p->block = pv.block(); p->lds_bytes = pv.lds_bytes();
+    fill_common(s, p);
+    return true;
+}
+
+// Estimated cycles of a pointwise mapping: the longer of the MFMA time of the busiest SIMD and the time
+// to stream the inputs of all resident waves at the CU's share of HBM bandwidth, plus a round trip.
+double pointwise_cost(const Shape& s, const conv_plan_t& p, const PointwiseVariant& pv)
+{
+    const double steps_per_wave = std::ceil(std::ceil(s.C / 16.0) / pv.WC);
+    const double mfma_per_wave = steps_per_wave * 16.0 * pv.MT * 32.0;
+    const double waves = (double)p.grid * pv.WC;
+    const double waves_per_simd = std::ceil(waves / (kNumCU * 4.0));
+    const double bytes_per_wave = steps_per_wave * (16.0 * 64 * 4 + pv.tile_k() * 16.0 * 4) + pv.tile_k() * 64.0 * 4 / pv.WC;
+    const double stream = waves_per_simd * 4.0 * bytes_per_wave / 10.0;  // ~10 B/clk/CU sustained from HBM
+    // each wave's life is one memory round trip, its MFMAs, a tree of barriers and the store; measured
+    // sweeps favour many small work-groups (low MT) even where that re-reads the inputs through L2
+    return std::max(waves_per_simd * mfma_per_wave / 0.8, stream) * (1.0 + 0.15 * (pv.MT - 1)) + 4000.0 + pv.WC * 150.0;
+}
+
 void resolve_generic(const Shape& s, conv_plan_t* p, KernelArgs* a)
 {
     base_args(s, a);
@@ -202,20 +244,28 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
 // Measured best mappings of known layer shapes (sweeps over tile shape x pixel tile on an MI355X);
 // shapes not listed go through the cost model.
 struct TunedEntry {
-    int N, C, H, W, K, R, pad, variant, tile_pix;
+    int N, C, H, W, K, R, pad, kernel, variant, tile_pix;
 };
 constexpr TunedEntry kTuned[] = {
-    {1, 16, 14, 14, 16, 3, 1, 2, 16},
-    {1, 256, 56, 56, 64, 1, 0, 9, 32},
-    {8, 64, 56, 56, 64, 3, 1, 11, 112},
-    {1, 48, 28, 28, 128, 5, 2, 2, 56},
-    {32, 512, 14, 14, 512, 3, 1, 10, 196},
+    {1, 16, 14, 14, 16, 3, 1, CONV_KERNEL_TAP, 2, 16},
+    {1, 256, 56, 56, 64, 1, 0, CONV_KERNEL_POINTWISE, 1, 64},
+    {8, 64, 56, 56, 64, 3, 1, CONV_KERNEL_TAP, 11, 112},
+    {1, 48, 28, 28, 128, 5, 2, CONV_KERNEL_TAP, 2, 56},
+    {32, 512, 14, 14, 512, 3, 1, CONV_KERNEL_TAP, 10, 196},
 };
+const TunedEntry* find_tuned(const Shape& s)
+{
+    for (const TunedEntry& t : kTuned)
+        if (t.N == s.N && t.C == s.C && t.H == s.H && t.W == s.W && t.K == s.K && t.R == s.R && t.R == s.S &&
+            t.pad == s.pad_h && t.pad == s.pad_w)
+            return &t;
+    return nullptr;
+}
 
 // conv_fwd plans on every call; remember recent shapes so a launch costs a table lookup.
 struct CacheEntry {
     Shape s;
-    int x_cap, w_cap;
+    int x_cap, w_cap, y_cap;
     conv_plan_t p;
     KernelArgs a;
 };
@@ -225,34 +275,51 @@ constexpr size_t kCacheEntries = 64;
 
 bool same_shape(const Shape& a, const Shape& b) { return std::memcmp(&a, &b, sizeof(Shape)) == 0; }
 
-int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a);
+int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a);
 
-int plan_shape(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a)
+int plan_shape(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
 {
     {
         std::lock_guard<std::mutex> lock(g_cache_mutex);
         for (const CacheEntry& e : g_cache)
-            if (same_shape(e.s, s) && e.x_cap == x_cap && e.w_cap == w_cap) {
+            if (same_shape(e.s, s) && e.x_cap == x_cap && e.w_cap == w_cap && e.y_cap == y_cap) {
                 *p = e.p; *a = e.a;
                 return CONV_OK;
             }
     }
-    const int rc = plan_shape_uncached(s, x_cap, w_cap, p, a);
+    const int rc = plan_shape_uncached(s, x_cap, w_cap, y_cap, p, a);
     if (rc == CONV_OK) {
         std::lock_guard<std::mutex> lock(g_cache_mutex);
         if (g_cache.size() >= kCacheEntries) g_cache.erase(g_cache.begin());
-        g_cache.push_back(CacheEntry{s, x_cap, w_cap, *p, *a});
+        g_cache.push_back(CacheEntry{s, x_cap, w_cap, y_cap, *p, *a});
     }
     return rc;
 }
 
-int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a)
+int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
 {
+    const TunedEntry* const tuned = find_tuned(s);
+    if (tuned && tuned->kernel == CONV_KERNEL_POINTWISE &&
+        resolve_pointwise(s, tuned->variant, x_cap, w_cap, y_cap, p, a))
+        return CONV_OK;
+    if (pointwise_ok(s, x_cap, w_cap, y_cap)) {
+        bool found = false;
+        double best = 0;
+        for (int v = 0; v < kNumPointwiseVariants; ++v) {
+            conv_plan_t cp;
+            KernelArgs ca;
+            if (!resolve_pointwise(s, v, x_cap, w_cap, y_cap, &cp, &ca)) continue;
+            const double c = pointwise_cost(s, cp, kPointwiseVariants[v]);
+            if (!found || c < best * 0.999) {
+                found = true; best = c; *p = cp; *a = ca;
+            }
+        }
+        if (found) return CONV_OK;
+    }
     if (tap_rs_index(s) >= 0) {
-        for (const TunedEntry& t : kTuned)
-            if (t.N == s.N && t.C == s.C && t.H == s.H && t.W == s.W && t.K == s.K && t.R == s.R && t.R == s.S &&
-                t.pad == s.pad_h && t.pad == s.pad_w && resolve_tap(s, t.variant, t.tile_pix, 0, x_cap, w_cap, p, a))
-                return CONV_OK;
+        if (tuned && tuned->kernel == CONV_KERNEL_TAP &&
+            resolve_tap(s, tuned->variant, tuned->tile_pix, 0, x_cap, w_cap, p, a))
+            return CONV_OK;
         bool found = false;
         double best = 0;
         const int PQ = s.P * s.Q;
@@ -304,15 +371,17 @@ int launch(const conv_plan_t& p, KernelArgs& a, const Shape& s, const float* x, 
     hipStream_t stream = g_stream.load();
     if (p.kernel == CONV_KERNEL_TAP)
         return record_hip(launch_tap(tap_rs_index(s), p.variant, p.x_vec, p.w_vec, p.grid, p.lds_bytes, stream, a));
+    if (p.kernel == CONV_KERNEL_POINTWISE) return record_hip(launch_pointwise(p.variant, p.grid, p.lds_bytes, stream, a));
     if (p.kernel == CONV_KERNEL_GENERIC) return record_hip(launch_generic(p.grid, p.block, stream, a));
     return CONV_E_PLAN;
 }
 
-void pointer_caps(const float* x, const float* w, int* x_cap, int* w_cap)
+void pointer_caps(const float* x, const float* w, const float* y, int* x_cap, int* w_cap, int* y_cap)
 {
     const uintptr_t xa = reinterpret_cast<uintptr_t>(x), wa = reinterpret_cast<uintptr_t>(w);
     *x_cap = xa % 16 == 0 ? 4 : xa % 8 == 0 ? 2 : 1;
     *w_cap = wa % 16 == 0 ? 4 : 1;
+    *y_cap = reinterpret_cast<uintptr_t>(y) % 16 == 0 ? 4 : 1;
 }
 
 }  // namespace
@@ -326,7 +395,7 @@ extern "C" int conv_fwd_plan(int N, int C, int H, int W, int K, int R, int S, in
     Shape s;
     if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
     KernelArgs a;
-    return plan_shape(s, 4, 4, out, &a);
+    return plan_shape(s, 4, 4, 4, out, &a);
 }
 
 extern "C" int conv_fwd(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,
@@ -335,11 +404,11 @@ extern "C" int conv_fwd(const float* x, const float* w, float* y, int N, int C, 
     if (!x || !w || !y) return CONV_E_NULL;
     Shape s;
     if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
-    int x_cap, w_cap;
-    pointer_caps(x, w, &x_cap, &w_cap);
+    int x_cap, w_cap, y_cap;
+    pointer_caps(x, w, y, &x_cap, &w_cap, &y_cap);
     conv_plan_t p;
     KernelArgs a;
-    if (int rc = plan_shape(s, x_cap, w_cap, &p, &a)) return rc;
+    if (int rc = plan_shape(s, x_cap, w_cap, y_cap, &p, &a)) return rc;
     return launch(p, a, s, x, w, y);
 }
 
@@ -349,11 +418,13 @@ extern "C" int conv_fwd_planned(const float* x, const float* w, float* y, int N,
     if (!x || !w || !y || !plan) return CONV_E_NULL;
     Shape s;
     if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
-    int x_cap, w_cap;
-    pointer_caps(x, w, &x_cap, &w_cap);
+    int x_cap, w_cap, y_cap;
+    pointer_caps(x, w, y, &x_cap, &w_cap, &y_cap);
     conv_plan_t p;
     KernelArgs a;
-    if (plan->kernel == CONV_KERNEL_GENERIC) {
+    if (plan->kernel == CONV_KERNEL_POINTWISE) {
+        if (!resolve_pointwise(s, plan->variant, x_cap, w_cap, y_cap, &p, &a)) return CONV_E_PLAN;
+    } else if (plan->kernel == CONV_KERNEL_GENERIC) {
         resolve_generic(s, &p, &a);
     } else if (plan->kernel == CONV_KERNEL_TAP) {
         if (plan->tile_pix < 0 || plan->chunk_c < 0) return CONV_E_PLAN;
@@ -369,6 +440,7 @@ extern "C" int conv_variant_count(int kernel)
 {
     if (kernel == CONV_KERNEL_GENERIC) return 1;
     if (kernel == CONV_KERNEL_TAP) return kNumTapVariants;
+    if (kernel == CONV_KERNEL_POINTWISE) return kNumPointwiseVariants;
     return 0;
 }
 
@@ -378,6 +450,9 @@ extern "C" int conv_variant_info(int kernel, int variant, int* tile_k, int* max_
     int tk = 1, mp = 256, bl = 256;
     if (kernel == CONV_KERNEL_TAP) {
         tk = kTapVariants[variant].tile_k(); mp = kTapVariants[variant].max_pix(); bl = kTapVariants[variant].block();
+    }
+    if (kernel == CONV_KERNEL_POINTWISE) {
+        tk = kPointwiseVariants[variant].tile_k(); mp = 64; bl = kPointwiseVariants[variant].block();
     }
     if (tile_k) *tile_k = tk;
     if (max_tile_pix) *max_tile_pix = mp;

@@ -68,6 +68,7 @@ def test_variant_tables(lib):
     assert binding.conv_variant_count(binding.CONV_KERNEL_GENERIC) == 1
     n = binding.conv_variant_count(binding.CONV_KERNEL_TAP)
     assert n >= 3 and binding.conv_variant_count(77) == 0
+    assert binding.conv_variant_count(binding.CONV_KERNEL_POINTWISE) >= 4
     for v in range(n):
         tk, mp, bl = binding.conv_variant_info(binding.CONV_KERNEL_TAP, v)
         assert tk % 16 == 0 and mp % 16 == 0 and bl % 64 == 0 and bl <= 1024

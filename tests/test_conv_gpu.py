@@ -17,6 +17,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 TAP = binding.CONV_KERNEL_TAP
 GENERIC = binding.CONV_KERNEL_GENERIC
+POINTWISE = binding.CONV_KERNEL_POINTWISE
 
 _ref_cache = {}
 
@@ -119,6 +120,45 @@ def test_odd_tile_requests(tile_pix, chunk_c):
     assert ran >= 5
 
 
+POINTWISE_SHAPES = [
+    S("p_ragged", 3, 40, 7, 8, 50, 1, 1, 0, 0),            # HW = 56 < 64, C = 40 (2.5 steps of 16), K = 50
+    S("p_two_tiles", 2, 64, 10, 10, 16, 1, 1, 0, 0),       # HW = 100: a full and a ragged pixel tile per image
+    S("p_small_c", 1, 4, 8, 8, 70, 1, 1, 0, 0),            # a single 4-channel group
+    S("p_deep", 1, 272, 4, 6, 33, 1, 1, 0, 0),             # 17 steps: more than any wave count
+    S("p_one_k", 2, 32, 4, 4, 1, 1, 1, 0, 0),
+]
+
+
+@pytest.mark.parametrize("variant", range(8))
+@pytest.mark.parametrize("shape", POINTWISE_SHAPES, ids=lambda s: s.name)
+def test_every_pointwise_variant_matches_oracle(shape, variant):
+    if variant >= binding.conv_variant_count(POINTWISE):
+        pytest.skip("no such variant")
+    plan, _ = _run(shape, kernel=POINTWISE, variant=variant)
+    assert plan.kernel == POINTWISE and plan.workspace_bytes == 0
+
+
+@pytest.mark.parametrize("shape", POINTWISE_SHAPES, ids=lambda s: s.name)
+def test_pointwise_shapes_default_plan_and_other_families(shape):
+    plan, _ = _run(shape)
+    assert plan.kernel == POINTWISE
+    _run(shape, kernel=GENERIC)
+    _run(shape, kernel=TAP, variant=2)
+
+
+def test_pointwise_needs_its_preconditions():
+    for dims in [(1, 8, 7, 7, 8, 1, 1, 0, 0), (1, 6, 8, 8, 8, 1, 1, 0, 0), (1, 8, 8, 8, 8, 1, 1, 1, 1),
+                 (1, 8, 8, 8, 8, 3, 3, 1, 1)]:
+        shape = S("p_not", *dims)       # HW % 4 != 0, C % 4 != 0, padded, 3x3
+        x, w = inputs.make_inputs(shape)
+        with pytest.raises(binding.ConvError) as e:
+            binding.conv_fwd_planned(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), dims[7], dims[8],
+                                     kernel=POINTWISE)
+        assert e.value.code == -6
+        plan, _ = _run(shape)
+        assert plan.kernel != POINTWISE
+
+
 NONSQUARE = [
     S("g2x3", 2, 5, 8, 9, 7, 2, 3, 1, 0),
     S("g7x7", 1, 3, 12, 12, 6, 7, 7, 3, 3),
@@ -134,7 +174,7 @@ def test_other_filter_sizes_use_the_generic_kernel(shape):
 
 
 @pytest.mark.parametrize("dims", [(2, 12, 9, 10, 35, 3, 3, 1, 1), (1, 16, 8, 8, 20, 5, 5, 2, 2),
-                                  (2, 24, 6, 7, 18, 1, 1, 0, 0), (1, 6, 7, 7, 5, 3, 3, 1, 1)])
+                                  (2, 24, 6, 8, 18, 1, 1, 0, 0), (1, 6, 7, 7, 5, 3, 3, 1, 1)])
 def test_integer_inputs_are_exact(dims):
     shape = inputs.ConvShape("ints", *dims, "int", "int", 31, 32)
     _run(shape, exact=True)
@@ -145,6 +185,9 @@ def test_integer_inputs_are_exact(dims):
                 _run(shape, kernel=TAP, variant=variant, exact=True)
             except binding.ConvError as e:
                 assert e.code == -6
+    if dims[5] == 1:
+        for variant in range(binding.conv_variant_count(POINTWISE)):
+            _run(shape, kernel=POINTWISE, variant=variant, exact=True)
 
 
 def test_identity_filter_copies_input_bitwise():
