@@ -28,8 +28,8 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
 BOUND = {1: "hbm", 2: "hbm", 3: "mfma", 4: "mfma", 5: "mfma"}
 # Bytes per launch that the L2s exchanged with the fabric (Infinity Cache / HBM), measured with rocprofv3 --pmc
 # FETCH_SIZE and WRITE_SIZE and scaled by what the same counters read for a plain device copy of known size
-# (profiles/conv_tap_mfma_hbm_traffic.txt); None = not measured.
-TRAFFIC_BYTES = {1: None, 2: 5364162, 3: 14042323, 4: None, 5: 99557448}
+# (profiles/conv_kernels_hbm_traffic.txt); None = not measured.
+TRAFFIC_BYTES = {1: None, 2: 4826536, 3: 14211512, 4: None, 5: 101480994}
 
 
 def _fail(msg: str, code: int = 2):
