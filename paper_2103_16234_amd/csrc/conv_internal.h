@@ -5,6 +5,29 @@
 
 namespace convfwd {
 
+// Division by a launch-time constant as multiply-high, subtract, shift (round-up method of Granlund and
+// Montgomery: exact for every 32-bit unsigned dividend). The host fills it, the kernels only use div().
+struct FastDiv {
+    unsigned mul, sh1, sh2;
+#if defined(__HIPCC__)
+    __device__ __forceinline__ unsigned div(unsigned n) const
+    {
+        const unsigned t = __umulhi(mul, n);
+        return (t + ((n - t) >> sh1)) >> sh2;
+    }
+#endif
+};
+inline FastDiv make_fastdiv(unsigned d)
+{
+    unsigned l = 0;
+    while ((1ull << l) < d) ++l;  // ceil(log2 d)
+    FastDiv f;
+    f.mul = (unsigned)(((1ull << 32) * ((1ull << l) - d)) / d + 1);
+    f.sh1 = l < 1 ? l : 1;
+    f.sh2 = l > 0 ? l - 1 : 0;
+    return f;
+}
+
 // Everything a kernel needs; passed by value. All offsets are in floats and fit 32 bits
 // (the host rejects tensors of 2^31 or more elements).
 struct KernelArgs {
@@ -24,6 +47,8 @@ struct KernelArgs {
     int lds_rows, lds_pitch, lds_plane;
     int col_shift;   // LDS column of padded column 0 (keeps vector stores aligned)
     int x_items;     // vector loads per chunk for the halo tile
+    // dividers for the index arithmetic of the prologue
+    FastDiv div_ktiles, div_ptiles, div_PQ, div_Q, div_Hp, div_row_vecs, div_slot_c;
 };
 
 // Taps per software-pipeline unit of the tap kernel: the shortest of {1, S, R*S} that keeps at least
@@ -57,7 +82,7 @@ struct TapVariant {
     // LDS floats of one staging copy for a halo plane of `plane` floats (with the 256-float dump)
     constexpr int staging_floats(int RS, int plane) const
     {
-        return ((chunk_c() * plane + tile_k() * (chunk_c() * RS + 2) + 3) & ~3) + 256;
+        return ((chunk_c() * plane + tile_k() * (chunk_c() * RS + 4) + 3) & ~3) + 256;
     }
     // LDS floats the cross-wave reduction needs (the first round of the tree is the widest)
     constexpr int reduce_floats() const { return WC > 1 ? (WC / 2) * WK * WP * MT * NT * 256 : 0; }

@@ -157,6 +157,9 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     a->nchunks = ceil_div(s.C, cc);
     a->lds_rows = rows; a->lds_pitch = pitch; a->lds_plane = plane; a->col_shift = col_shift;
     a->x_items = cc * rows * row_vecs;
+    a->div_ktiles = make_fastdiv(a->ktiles); a->div_ptiles = make_fastdiv(a->ptiles);
+    a->div_PQ = make_fastdiv(a->PQ); a->div_Q = make_fastdiv(s.Q); a->div_Hp = make_fastdiv(a->Hp);
+    a->div_row_vecs = make_fastdiv(row_vecs); a->div_slot_c = make_fastdiv(rows * row_vecs);
 
     std::memset(p, 0, sizeof(*p));
     p->kernel = CONV_KERNEL_TAP; p->variant = variant;
@@ -187,6 +190,7 @@ bool resolve_pointwise(const Shape& s, int variant, int x_cap, int w_cap, int y_
     const int64_t grid = (int64_t)a->ktiles * a->ptiles * s.N;
     if (grid >= ((int64_t)1 << 31)) return false;
     a->nchunks = ceil_div(s.C, 16);
+    a->div_ktiles = make_fastdiv(a->ktiles); a->div_ptiles = make_fastdiv(a->ptiles);
     std::memset(p, 0, sizeof(*p));
     p->kernel = CONV_KERNEL_POINTWISE; p->variant = variant;
     p->tile_k = pv.tile_k(); p->tile_pix = 64; p->chunk_c = 16 * pv.WC;

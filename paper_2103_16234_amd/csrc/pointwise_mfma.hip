@@ -36,10 +36,10 @@ __global__ void __launch_bounds__(64 * WC) conv_pointwise_mfma(const KernelArgs 
         const int per = nb >> 3, rem = nb & 7, xcd = b & 7;
         L = xcd * per + (xcd < rem ? xcd : rem) + (b >> 3);
     }
-    const int ktile = L % a.ktiles;
-    const int rest = L / a.ktiles;
-    const int pt = rest % a.ptiles;
-    const int n = rest / a.ptiles;
+    const int rest = a.div_ktiles.div(L);
+    const int ktile = L - rest * a.ktiles;
+    const int n = a.div_ptiles.div(rest);
+    const int pt = rest - n * a.ptiles;
     const int k0 = ktile * (16 * MT);
     const int px = pt * 64 + 4 * j;
     const bool pvalid = px < a.HW;  // HW is a multiple of 4: the lane's four pixels are valid together

@@ -91,7 +91,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     constexpr int RS = R * S;
     constexpr int TK = 16 * MT * WK;
     constexpr int CC = 4 * WC * GPC;     // channels per chunk
-    constexpr int WPITCH = CC * RS + 2;  // floats per output channel in the LDS filter block
+    constexpr int WPITCH = CC * RS + 4;  // floats per output channel in the LDS filter block (rows stay 16-byte aligned)
     constexpr int UT = tap_unit_taps(S, RS, MT, NT, OCC);
     constexpr int UNITS = RS / UT;       // pipeline units per 4-channel group
     constexpr int U = GPC * UNITS;       // pipeline units per chunk (per wave)
@@ -122,32 +122,13 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         const int per = nb >> 3, rem = nb & 7, xcd = b & 7;
         L = xcd * per + (xcd < rem ? xcd : rem) + (b >> 3);
     }
-    const int ptile = L / a.ktiles;
+    const int ptile = a.div_ktiles.div(L);
     const int ktile = L - ptile * a.ktiles;
     const int k0 = ktile * TK;
     const int g0 = ptile * a.tile_pix;
     const int g_end = min(g0 + a.tile_pix, a.total_pix);
-    const int n0 = g0 / a.PQ;
-    const int V0 = n0 * a.Hp + (g0 - n0 * a.PQ) / a.Q;  // first stacked padded row held in LDS
-
-    // Zero both staging copies once: padding cells, rows past the batch and output channels past K
-    // then stay zero for the whole kernel.
-    for (int i = tid; i < (2 * buf_floats) >> 2; i += BLOCK) smem4[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // Per-lane pixel table: byte offset inside a staging copy of the origin of the pixel's window, for
-    // this lane's channel of this wave's first group (lanes past the end of the tile read the tile's
-    // last pixel and are masked at the store).
-    int xb[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int gc = min(g0 + (wp * NT + t) * 16 + j, g_end - 1);
-        const int n = gc / a.PQ;
-        const int pq = gc - n * a.PQ;
-        const int p = pq / a.Q;
-        const int q = pq - p * a.Q;
-        xb[t] = 4 * ((4 * wc + kq) * a.lds_plane + (n * a.Hp + p - V0) * a.lds_pitch + q + a.col_shift);
-    }
-    const int arow = 4 * (xs_floats + (wk * MT * 16 + j) * WPITCH + (4 * wc + kq) * RS);
+    const int n0 = a.div_PQ.div(g0);
+    const int V0 = n0 * a.Hp + a.div_Q.div(g0 - n0 * a.PQ);  // first stacked padded row held in LDS
 
     // Staging slots. xg / wg: offset in floats from the chunk's first channel in x / w; xl / wl: float
     // offset inside a staging copy in the low 16 bits, the slot's channel (x) or element offset in the
@@ -162,12 +143,12 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
             xg[i] = 0;
             xl[i] = dump_off + lane * 4;
             if (e < a.x_items) {
-                const int c_l = e / per_c;
+                const int c_l = a.div_slot_c.div(e);
                 const int rem = e - c_l * per_c;
-                const int row = rem / XV;
+                const int row = a.div_row_vecs.div(rem);
                 const int cv = rem - row * XV;
                 const int v = V0 + row;
-                const int n = v / a.Hp;
+                const int n = a.div_Hp.div(v);
                 const int h = v - n * a.Hp - a.pad_h;
                 if (n < a.N && h >= 0 && h < a.H) {
                     xg[i] = ((n * a.C + c_l) * a.H + h) * a.W + cv * VX;
@@ -211,7 +192,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         } else {
             Vec<VW> t = wv[k - XS];
             t.keep_if(static_cast<int>(wl[k - XS] >> 16) < (a.C - c0) * RS);
-            t.store8(lds + dst_floats + (wl[k - XS] & 0xffff));  // rows are 8-byte aligned (pitch = 2 mod 4)
+            t.store16(lds + dst_floats + (wl[k - XS] & 0xffff));
         }
     };
     auto for_each_slot = [&](auto&& f) {
@@ -225,9 +206,28 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[m][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // Prologue: chunk 0 goes straight into copy 0, chunk 1 waits in the registers.
+    // Prologue: chunk 0 goes straight into copy 0, chunk 1 waits in the registers. While the first
+    // loads are in flight, zero both staging copies (padding cells, rows past the batch and output
+    // channels past K then stay zero for the whole kernel) and build the per-lane pixel table.
     const int last_c0 = (a.nchunks - 1) * CC;
     for_each_slot([&](auto kc) { slot_load(kc, 0); });
+    for (int i = tid; i < (2 * buf_floats) >> 2; i += BLOCK) smem4[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // Per-lane pixel table: byte offset inside a staging copy of the origin of the pixel's window, for
+    // this lane's channel of this wave's first group (lanes past the end of the tile read the tile's
+    // last pixel and are masked at the store).
+    int xb[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int gc = min(g0 + (wp * NT + t) * 16 + j, g_end - 1);
+        const int n = a.div_PQ.div(gc);
+        const int pq = gc - n * a.PQ;
+        const int p = a.div_Q.div(pq);
+        const int q = pq - p * a.Q;
+        xb[t] = 4 * ((4 * wc + kq) * a.lds_plane + (n * a.Hp + p - V0) * a.lds_pitch + q + a.col_shift);
+    }
+    const int arow = 4 * (xs_floats + (wk * MT * 16 + j) * WPITCH + (4 * wc + kq) * RS);
+
     __syncthreads();  // zero fill complete before any data lands
     for_each_slot([&](auto kc) { slot_store(kc, 0, 0); });
     for_each_slot([&](auto kc) { slot_load(kc, min(CC, last_c0)); });
@@ -339,7 +339,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         for (int t = 0; t < NT; ++t) {
             const int g = g0 + (wp * NT + t) * 16 + j;
             if (g >= g_end) continue;
-            const int n = g / a.PQ;
+            const int n = a.div_PQ.div(g);
             const int yb = n * a.K * a.PQ + (g - n * a.PQ);
 #pragma unroll
             for (int v = 0; v < 4; ++v)
