@@ -109,18 +109,21 @@ constexpr TapVariant kTapVariants[] = {
 constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
 #define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13)
 
-// Tile shapes of the pointwise (1x1, no padding) family: a work-group is WC waves that share
-// 16*MT output channels x 64 pixels of one image and split the input channels.
+// Tile shapes of the pointwise (1x1, no padding) family: a work-group is WC x WP waves on 16*MT output
+// channels x WP*64 contiguous pixels of one image; the WC shares split the input channels.
 struct PointwiseVariant {
-    int MT, WC;
+    int MT, WC, WP;
     constexpr int tile_k() const { return 16 * MT; }
-    constexpr int block() const { return 64 * WC; }
-    constexpr int lds_bytes() const { return WC > 1 ? (WC / 2) * MT * 4 * 1024 : 0; }
+    constexpr int tile_pix() const { return 64 * WP; }
+    constexpr int block() const { return 64 * WC * WP; }
+    constexpr int lds_bytes() const { return WC > 1 ? (WC / 2) * WP * MT * 4 * 1024 : 0; }
 };
 constexpr PointwiseVariant kPointwiseVariants[] = {
-    {1, 4}, {1, 8}, {2, 4}, {2, 8}, {4, 4}, {4, 8}, {1, 16}, {2, 16},
+    {1, 4, 1}, {1, 8, 1}, {2, 4, 1}, {2, 8, 1}, {4, 4, 1}, {4, 8, 1}, {1, 16, 1}, {2, 16, 1},  // 0-7: channel shares only
+    {1, 1, 4}, {2, 1, 4}, {4, 1, 4}, {2, 1, 2}, {2, 2, 2}, {4, 2, 2},                          // 8-13: streaming shapes
 };
 constexpr int kNumPointwiseVariants = sizeof(kPointwiseVariants) / sizeof(kPointwiseVariants[0]);
+#define POINTWISE_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13)
 hipError_t launch_pointwise(int variant, int grid, int lds_bytes, hipStream_t stream, const KernelArgs& a);
 
 // rs_index: 0 -> 1x1, 1 -> 3x3, 2 -> 5x5. Returns hipSuccess or the launch error.

@@ -184,35 +184,36 @@ bool resolve_pointwise(const Shape& s, int variant, int x_cap, int w_cap, int y_
     if (!pointwise_ok(s, x_cap, w_cap, y_cap) || variant < 0 || variant >= kNumPointwiseVariants) return false;
     const PointwiseVariant pv = kPointwiseVariants[variant];
     base_args(s, a);
-    a->tile_pix = 64;
+    a->tile_pix = pv.tile_pix();
     a->ktiles = ceil_div(s.K, pv.tile_k());
-    a->ptiles = ceil_div(s.H * s.W, 64);  // per image
+    a->ptiles = ceil_div(s.H * s.W, pv.tile_pix());  // per image
     const int64_t grid = (int64_t)a->ktiles * a->ptiles * s.N;
     if (grid >= ((int64_t)1 << 31)) return false;
     a->nchunks = ceil_div(s.C, 16);
     a->div_ktiles = make_fastdiv(a->ktiles); a->div_ptiles = make_fastdiv(a->ptiles);
     std::memset(p, 0, sizeof(*p));
     p->kernel = CONV_KERNEL_POINTWISE; p->variant = variant;
-    p->tile_k = pv.tile_k(); p->tile_pix = 64; p->chunk_c = 16 * pv.WC;
+    p->tile_k = pv.tile_k(); p->tile_pix = pv.tile_pix(); p->chunk_c = 16 * pv.WC;
     p->x_vec = 4; p->w_vec = 4;
     p->grid = (int)grid; p->block = pv.block(); p->lds_bytes = pv.lds_bytes();
     fill_common(s, p);
     return true;
 }
 
-// Estimated cycles of a pointwise mapping: the longer of the MFMA time of the busiest SIMD and the time
-// to stream the inputs of all resident waves at the CU's share of HBM bandwidth, plus a round trip.
-double pointwise_cost(const Shape& s, const conv_plan_t& p, const PointwiseVariant& pv)
+// Choice of the pointwise tile shape, from sweeps: with plenty of work, 32 channels x 64 pixels per
+// work-group and four channel shares (inputs are re-read through L2 by the second channel tile, which
+// costs less than fewer, longer-lived waves); for small layers 16 channels per work-group and as many
+// channel shares as it takes to put ~4 waves on every SIMD's queue.
+int pick_pointwise(const Shape& s)
 {
-    const double steps_per_wave = std::ceil(std::ceil(s.C / 16.0) / pv.WC);
-    const double mfma_per_wave = steps_per_wave * 16.0 * pv.MT * 32.0;
-    const double waves = (double)p.grid * pv.WC;
-    const double waves_per_simd = std::ceil(waves / (kNumCU * 4.0));
-    const double bytes_per_wave = steps_per_wave * (16.0 * 64 * 4 + pv.tile_k() * 16.0 * 4) + pv.tile_k() * 64.0 * 4 / pv.WC;
-    const double stream = waves_per_simd * 4.0 * bytes_per_wave / 10.0;  // ~10 B/clk/CU sustained from HBM
-    // each wave's life is one memory round trip, its MFMAs, a tree of barriers and the store; measured
-    // sweeps favour many small work-groups (low MT) even where that re-reads the inputs through L2
-    return std::max(waves_per_simd * mfma_per_wave / 0.8, stream) * (1.0 + 0.15 * (pv.MT - 1)) + 4000.0 + pv.WC * 150.0;
+    const int64_t pix_tiles = (int64_t)s.N * ceil_div(s.H * s.W, 64);
+    const int64_t waves_v2 = pix_tiles * ceil_div(s.K, 32) * 4;
+    if (waves_v2 >= 4096) return 2;  // {MT 2, WC 4}
+    const int64_t groups = pix_tiles * ceil_div(s.K, 16);
+    const int steps = ceil_div(s.C, 16);
+    if (groups * 4 >= 1024 || steps <= 8) return 0;   // {1, 4}
+    if (groups * 8 >= 1024 || steps <= 16) return 1;  // {1, 8}
+    return 6;                                          // {1, 16}
 }
 
 void resolve_generic(const Shape& s, conv_plan_t* p, KernelArgs* a)
@@ -306,20 +307,8 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_pl
     if (tuned && tuned->kernel == CONV_KERNEL_POINTWISE &&
         resolve_pointwise(s, tuned->variant, x_cap, w_cap, y_cap, p, a))
         return CONV_OK;
-    if (pointwise_ok(s, x_cap, w_cap, y_cap)) {
-        bool found = false;
-        double best = 0;
-        for (int v = 0; v < kNumPointwiseVariants; ++v) {
-            conv_plan_t cp;
-            KernelArgs ca;
-            if (!resolve_pointwise(s, v, x_cap, w_cap, y_cap, &cp, &ca)) continue;
-            const double c = pointwise_cost(s, cp, kPointwiseVariants[v]);
-            if (!found || c < best * 0.999) {
-                found = true; best = c; *p = cp; *a = ca;
-            }
-        }
-        if (found) return CONV_OK;
-    }
+    if (pointwise_ok(s, x_cap, w_cap, y_cap) && resolve_pointwise(s, pick_pointwise(s), x_cap, w_cap, y_cap, p, a))
+        return CONV_OK;
     if (tap_rs_index(s) >= 0) {
         if (tuned && tuned->kernel == CONV_KERNEL_TAP &&
             resolve_tap(s, tuned->variant, tuned->tile_pix, 0, x_cap, w_cap, p, a))
@@ -456,7 +445,7 @@ extern "C" int conv_variant_info(int kernel, int variant, int* tile_k, int* max_
         tk = kTapVariants[variant].tile_k(); mp = kTapVariants[variant].max_pix(); bl = kTapVariants[variant].block();
     }
     if (kernel == CONV_KERNEL_POINTWISE) {
-        tk = kPointwiseVariants[variant].tile_k(); mp = 64; bl = kPointwiseVariants[variant].block();
+        tk = kPointwiseVariants[variant].tile_k(); mp = kPointwiseVariants[variant].tile_pix(); bl = kPointwiseVariants[variant].block();
     }
     if (tile_k) *tile_k = tk;
     if (max_tile_pix) *max_tile_pix = mp;

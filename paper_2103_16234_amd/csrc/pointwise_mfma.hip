@@ -7,25 +7,34 @@
 // load of four consecutive input channels of one filter is the A operand of four successive MFMA steps
 // (the channel <-> step assignment is a free permutation of the reduction as long as A and B agree).
 // Outputs leave as dwordx4 stores of four consecutive pixels. Both tensors are read exactly once per
-// work-group column; all loads of a wave are in flight together (one HBM round trip for small layers).
+// work-group column; two 16-channel steps of loads per wave are in flight at any time.
 //
-// A work-group is WC waves that share 16*MT output channels x 64 pixels of one image and split the
-// input channels in steps of 16; their partial tiles are added through LDS in a fixed tree order.
+// A work-group is WC x WP waves on 16*MT output channels x WP*64 contiguous pixels of one image: the WP
+// waves of a channel share take neighbouring 64-pixel runs (longer contiguous reads per channel row),
+// the WC shares split the input channels in steps of 16 and add their partial tiles through LDS in a
+// fixed tree order.
 #include "conv_internal.h"
+
+#include <utility>
 
 namespace convfwd {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <int MT, int WC, int PD>
-__global__ void __launch_bounds__(64 * WC) conv_pointwise_mfma(const KernelArgs a)
+// MASK: some (wave, step) pair needs its filters zeroed: C is not a multiple of 16, or the steps do
+// not divide evenly into pairs per wave. Loads are never predicated (addresses are clamped to valid
+// elements instead), so the compiler keeps all of them in flight; masking happens just before the MFMAs.
+template <int MT, int WC, int WP, bool MASK>
+__global__ void __launch_bounds__(64 * WC * WP) conv_pointwise_mfma(const KernelArgs a)
 {
     static_assert((WC & (WC - 1)) == 0, "the cross-wave reduction is a binary tree");
     extern __shared__ f32x4 smem4[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wc = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wp = wave % WP;  // which 64-pixel run of the work-group's WP*64 contiguous pixels
+    const int wc = wave / WP;  // which share of the input channels
     const int j = lane & 15;
     const int kq = lane >> 4;
 
@@ -41,36 +50,31 @@ __global__ void __launch_bounds__(64 * WC) conv_pointwise_mfma(const KernelArgs 
     const int n = a.div_ptiles.div(rest);
     const int pt = rest - n * a.ptiles;
     const int k0 = ktile * (16 * MT);
-    const int px = pt * 64 + 4 * j;
+    const int px = (pt * WP + wp) * 64 + 4 * j;
     const bool pvalid = px < a.HW;  // HW is a multiple of 4: the lane's four pixels are valid together
 
-    const float* const xlane = a.x + n * a.C * a.HW + px;
+    const float* const xlane = a.x + n * a.C * a.HW + min(px, a.HW - 4);
     const float* wlane[MT];
-    bool kvalid[MT];
 #pragma unroll
-    for (int m = 0; m < MT; ++m) {
-        const int k = k0 + 16 * m + j;
-        kvalid[m] = k < a.K;
-        wlane[m] = a.w + (kvalid[m] ? k : 0) * a.C + 4 * kq;
-    }
+    for (int m = 0; m < MT; ++m) wlane[m] = a.w + min(k0 + 16 * m + j, a.K - 1) * a.C;
 
-    const int nsteps = (a.C + 15) >> 4;                         // steps of 16 input channels
-    const int mine = nsteps > wc ? (nsteps - wc + WC - 1) / WC : 0;  // this wave takes steps wc, wc+WC, ...
+    // Steps of 16 input channels; wave wc takes steps wc, wc+WC, ...; every wave runs the same even
+    // number of steps (steps past the end are dummies with zeroed filters).
+    const int nsteps = (a.C + 15) >> 4;
+    const int mine = (((nsteps + WC - 1) / WC) + 1) & ~1;
 
-    f32x4 xr[PD][4];
-    f32x4 wr[PD][MT];
-    auto load_step = [&](int slot, int i) {
-        const int c = 16 * (wc + WC * i) + 4 * kq;  // this lane's four channels of the step: c .. c+3
+    f32x4 xr[2][4];
+    f32x4 wr[2][MT];
+    bool keep[2];
+    auto load_step = [&](auto slotc, int i) {
+        constexpr int slot = decltype(slotc)::value;
+        const int c_true = 16 * (wc + WC * i) + 4 * kq;  // this lane's four channels of the step
+        const int c = MASK ? min(c_true, a.C - 4) : c_true;
+        keep[slot] = c_true < a.C;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            xr[slot][e] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (pvalid && c + e < a.C) xr[slot][e] = *reinterpret_cast<const f32x4*>(xlane + (c + e) * a.HW);
-        }
+        for (int e = 0; e < 4; ++e) xr[slot][e] = *reinterpret_cast<const f32x4*>(xlane + (c + e) * a.HW);
 #pragma unroll
-        for (int m = 0; m < MT; ++m) {
-            wr[slot][m] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (kvalid[m] && c < a.C) wr[slot][m] = *reinterpret_cast<const f32x4*>(wlane[m] + (c - 4 * kq));
-        }
+        for (int m = 0; m < MT; ++m) wr[slot][m] = *reinterpret_cast<const f32x4*>(wlane[m] + c);
     };
 
     f32x4 acc[MT][4];
@@ -79,34 +83,37 @@ __global__ void __launch_bounds__(64 * WC) conv_pointwise_mfma(const KernelArgs 
 #pragma unroll
         for (int t = 0; t < 4; ++t) acc[m][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto mfma_step = [&](int slot) {
+    auto mfma_step = [&](auto slotc) {
+        constexpr int slot = decltype(slotc)::value;
+        f32x4 wv[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) wv[m] = (!MASK || keep[slot]) ? wr[slot][m] : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int e = 0; e < 4; ++e)
 #pragma unroll
             for (int m = 0; m < MT; ++m)
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
-                    acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr[slot][m][e], xr[slot][e][t], acc[m][t], 0, 0, 0);
+                    acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[m][e], xr[slot][e][t], acc[m][t], 0, 0, 0);
     };
 
-#pragma unroll
-    for (int s = 0; s < PD; ++s)
-        if (s < mine) load_step(s, s);
-    for (int i = 0; i < mine; i += PD) {
-#pragma unroll
-        for (int s = 0; s < PD; ++s) {
-            if (i + s < mine) {
-                mfma_step(s);
-                if (i + s + PD < mine) load_step(s, i + s + PD);
-            }
-        }
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    load_step(S0{}, 0);
+    load_step(S1{}, 1);
+    for (int i = 0; i < mine; i += 2) {
+        const bool more = i + 2 < mine;
+        mfma_step(S0{});
+        if (more) load_step(S0{}, i + 2);
+        mfma_step(S1{});
+        if (more) load_step(S1{}, i + 3);
     }
 
     if constexpr (WC > 1) {
 #pragma unroll
         for (int stride = WC / 2; stride >= 1; stride /= 2) {
             if (stride != WC / 2) __syncthreads();
-            f32x4* const part = smem4 + (wc - stride) * (MT * 4 * 64) + lane;
+            f32x4* const part = smem4 + ((wc - stride) * WP + wp) * (MT * 4 * 64) + lane;
             if (wc >= stride && wc < 2 * stride) {
 #pragma unroll
                 for (int m = 0; m < MT; ++m)
@@ -115,7 +122,7 @@ __global__ void __launch_bounds__(64 * WC) conv_pointwise_mfma(const KernelArgs 
             }
             __syncthreads();
             if (wc < stride) {
-                const f32x4* const other = part + stride * (MT * 4 * 64);
+                const f32x4* const other = part + stride * (WP * MT * 4 * 64);
 #pragma unroll
                 for (int m = 0; m < MT; ++m)
 #pragma unroll
@@ -140,20 +147,24 @@ __global__ void __launch_bounds__(64 * WC) conv_pointwise_mfma(const KernelArgs 
 
 using KernFn = void (*)(const KernelArgs);
 
-template <int V> static KernFn pointwise_instance()
+template <int V, bool MASK> static KernFn pointwise_instance()
 {
     constexpr PointwiseVariant pv = kPointwiseVariants[V];
-    return conv_pointwise_mfma<pv.MT, pv.WC, (pv.WC * pv.MT >= 32 ? 2 : 4)>;  // 1024 threads leave 128 registers
+    return conv_pointwise_mfma<pv.MT, pv.WC, pv.WP, MASK>;
 }
 
 hipError_t launch_pointwise(int variant, int grid, int lds_bytes, hipStream_t stream, const KernelArgs& a)
 {
-    static_assert(kNumPointwiseVariants == 8, "update the table below");
-    static const KernFn table[kNumPointwiseVariants] = {
-        pointwise_instance<0>(), pointwise_instance<1>(), pointwise_instance<2>(), pointwise_instance<3>(),
-        pointwise_instance<4>(), pointwise_instance<5>(), pointwise_instance<6>(), pointwise_instance<7>()};
+#define PW_PLAIN(v) pointwise_instance<v, false>(),
+#define PW_MASKED(v) pointwise_instance<v, true>(),
+    static const KernFn plain[kNumPointwiseVariants] = {POINTWISE_VARIANT_LIST(PW_PLAIN)};
+    static const KernFn masked[kNumPointwiseVariants] = {POINTWISE_VARIANT_LIST(PW_MASKED)};
     if (variant < 0 || variant >= kNumPointwiseVariants) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(table[variant], dim3(grid), dim3(kPointwiseVariants[variant].block()), lds_bytes, stream, a);
+    // no masking needed when every wave gets an even number of whole 16-channel steps
+    const int WC = kPointwiseVariants[variant].WC;
+    const bool mask = a.C % (32 * WC) != 0;
+    hipLaunchKernelGGL((mask ? masked : plain)[variant], dim3(grid), dim3(kPointwiseVariants[variant].block()), lds_bytes,
+                       stream, a);
     return hipGetLastError();
 }
 

@@ -126,10 +126,11 @@ POINTWISE_SHAPES = [
     S("p_small_c", 1, 4, 8, 8, 70, 1, 1, 0, 0),            # a single 4-channel group
     S("p_deep", 1, 272, 4, 6, 33, 1, 1, 0, 0),             # 17 steps: more than any wave count
     S("p_one_k", 2, 32, 4, 4, 1, 1, 1, 0, 0),
+    S("p_wide_tiles", 2, 48, 12, 25, 20, 1, 1, 0, 0),      # HW = 300: full and ragged 256- and 128-pixel work-groups
 ]
 
 
-@pytest.mark.parametrize("variant", range(8))
+@pytest.mark.parametrize("variant", range(16))
 @pytest.mark.parametrize("shape", POINTWISE_SHAPES, ids=lambda s: s.name)
 def test_every_pointwise_variant_matches_oracle(shape, variant):
     if variant >= binding.conv_variant_count(POINTWISE):
