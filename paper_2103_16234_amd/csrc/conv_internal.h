@@ -117,6 +117,7 @@ struct PointwiseVariant {
     constexpr int tile_pix() const { return 64 * WP; }
     constexpr int block() const { return 64 * WC * WP; }
     constexpr int lds_bytes() const { return WC > 1 ? (WC / 2) * WP * MT * 4 * 1024 : 0; }
+    constexpr int depth() const { return MT == 1 && WC == 16 ? 4 : 2; }  // 16-channel steps in flight per wave
 };
 constexpr PointwiseVariant kPointwiseVariants[] = {
     {1, 4, 1}, {1, 8, 1}, {2, 4, 1}, {2, 8, 1}, {4, 4, 1}, {4, 8, 1}, {1, 16, 1}, {2, 16, 1},  // 0-7: channel shares only
@@ -124,7 +125,7 @@ constexpr PointwiseVariant kPointwiseVariants[] = {
 };
 constexpr int kNumPointwiseVariants = sizeof(kPointwiseVariants) / sizeof(kPointwiseVariants[0]);
 #define POINTWISE_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13)
-hipError_t launch_pointwise(int variant, int grid, int lds_bytes, hipStream_t stream, const KernelArgs& a);
+hipError_t launch_pointwise(int variant, int x_vec, int grid, int lds_bytes, hipStream_t stream, const KernelArgs& a);
 
 // rs_index: 0 -> 1x1, 1 -> 3x3, 2 -> 5x5. Returns hipSuccess or the launch error.
 hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid, int lds_bytes,

@@ -172,11 +172,16 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     return true;
 }
 
-// Pointwise family: 1x1 filters, no padding, planes and channel runs that dwordx4 can walk.
+// Pointwise family: 1x1 filters, no padding, filter rows that dwordx4 can walk. Pixels move as dwordx4
+// when H*W is a multiple of 4 and x, y are 16-byte aligned, as single dwords otherwise.
 bool pointwise_ok(const Shape& s, int x_cap, int w_cap, int y_cap)
 {
-    return s.R == 1 && s.S == 1 && s.pad_h == 0 && s.pad_w == 0 && (s.H * s.W) % 4 == 0 && s.C % 4 == 0 &&
-           x_cap >= 4 && w_cap >= 4 && y_cap >= 4;
+    (void)x_cap; (void)y_cap;
+    return s.R == 1 && s.S == 1 && s.pad_h == 0 && s.pad_w == 0 && s.C % 4 == 0 && w_cap >= 4;
+}
+int pointwise_x_vec(const Shape& s, int x_cap, int y_cap)
+{
+    return ((s.H * s.W) % 4 == 0 && x_cap >= 4 && y_cap >= 4) ? 4 : 1;
 }
 
 bool resolve_pointwise(const Shape& s, int variant, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
@@ -194,7 +199,7 @@ bool resolve_pointwise(const Shape& s, int variant, int x_cap, int w_cap, int y_
     std::memset(p, 0, sizeof(*p));
     p->kernel = CONV_KERNEL_POINTWISE; p->variant = variant;
     p->tile_k = pv.tile_k(); p->tile_pix = pv.tile_pix(); p->chunk_c = 16 * pv.WC;
-    p->x_vec = 4; p->w_vec = 4;
+    p->x_vec = pointwise_x_vec(s, x_cap, y_cap); p->w_vec = 4;
     p->grid = (int)grid; p->block = pv.block(); p->lds_bytes = pv.lds_bytes();
     fill_common(s, p);
     return true;
@@ -364,7 +369,7 @@ int launch(const conv_plan_t& p, KernelArgs& a, const Shape& s, const float* x, 
     hipStream_t stream = g_stream.load();
     if (p.kernel == CONV_KERNEL_TAP)
         return record_hip(launch_tap(tap_rs_index(s), p.variant, p.x_vec, p.w_vec, p.grid, p.lds_bytes, stream, a));
-    if (p.kernel == CONV_KERNEL_POINTWISE) return record_hip(launch_pointwise(p.variant, p.grid, p.lds_bytes, stream, a));
+    if (p.kernel == CONV_KERNEL_POINTWISE) return record_hip(launch_pointwise(p.variant, p.x_vec, p.grid, p.lds_bytes, stream, a));
     if (p.kernel == CONV_KERNEL_GENERIC) return record_hip(launch_generic(p.grid, p.block, stream, a));
     return CONV_E_PLAN;
 }

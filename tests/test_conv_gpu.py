@@ -127,6 +127,8 @@ POINTWISE_SHAPES = [
     S("p_deep", 1, 272, 4, 6, 33, 1, 1, 0, 0),             # 17 steps: more than any wave count
     S("p_one_k", 2, 32, 4, 4, 1, 1, 1, 0, 0),
     S("p_wide_tiles", 2, 48, 12, 25, 20, 1, 1, 0, 0),      # HW = 300: full and ragged 256- and 128-pixel work-groups
+    S("p_7x7", 2, 36, 7, 7, 24, 1, 1, 0, 0),               # HW = 49: pixels move as single dwords
+    S("p_13x13", 1, 20, 13, 13, 40, 1, 1, 0, 0),           # HW = 169: three pixel tiles, the last one ragged
 ]
 
 
@@ -148,9 +150,8 @@ def test_pointwise_shapes_default_plan_and_other_families(shape):
 
 
 def test_pointwise_needs_its_preconditions():
-    for dims in [(1, 8, 7, 7, 8, 1, 1, 0, 0), (1, 6, 8, 8, 8, 1, 1, 0, 0), (1, 8, 8, 8, 8, 1, 1, 1, 1),
-                 (1, 8, 8, 8, 8, 3, 3, 1, 1)]:
-        shape = S("p_not", *dims)       # HW % 4 != 0, C % 4 != 0, padded, 3x3
+    for dims in [(1, 6, 8, 8, 8, 1, 1, 0, 0), (1, 8, 8, 8, 8, 1, 1, 1, 1), (1, 8, 8, 8, 8, 3, 3, 1, 1)]:
+        shape = S("p_not", *dims)       # C % 4 != 0, padded, 3x3
         x, w = inputs.make_inputs(shape)
         with pytest.raises(binding.ConvError) as e:
             binding.conv_fwd_planned(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), dims[7], dims[8],
