@@ -79,6 +79,8 @@ struct TapVariant {
     // filter-block loads per thread and chunk, and whether that many registers are reasonable
     constexpr int wslots(int RS, int w_vec) const { return (tile_k() * chunk_c() * RS / w_vec + block() - 1) / block(); }
     constexpr bool supports(int RS) const { return tile_k() * chunk_c() * RS <= (occ > 1 ? 40 : 64) * block(); }
+    // the all-dword loaders (C not a multiple of 4) need a table entry per float staged: small shapes only
+    constexpr bool supports_scalar(int RS) const { return supports(RS) && xslots * 4 + tile_k() * chunk_c() * RS / block() <= 48; }
     // LDS floats of one staging copy for a halo plane of `plane` floats (with the 256-float dump)
     constexpr int staging_floats(int RS, int plane) const
     {
@@ -96,18 +98,16 @@ constexpr TapVariant kTapVariants[] = {
     {1, 1, 1, 4, 1, 2, 2, 4},   //  2: 16 ch x  64 px, one MFMA tile per wave, 8-channel chunks
     {2, 4, 2, 2, 1, 4, 1, 8},   //  3: 64 ch x 128 px, 2x4 tiles per wave
     {1, 2, 2, 2, 1, 2, 2, 4},   //  4: 32 ch x  64 px, 8-channel chunks
-    {4, 13, 1, 1, 4, 1, 1, 4},  //  5: 64 ch x 208 px (a 14x14 image): every wave owns the whole tile for 1/4 of the channels
-    {4, 7, 1, 1, 4, 1, 1, 4},   //  6: 64 ch x 112 px, same scheme
-    {2, 13, 2, 1, 4, 1, 2, 2},  //  7: 64 ch x 208 px, 8 waves (2 along K x 4 channel shares), two per SIMD
-    {2, 7, 2, 1, 4, 1, 2, 2},   //  8: 64 ch x 112 px, same scheme
-    {2, 2, 1, 1, 4, 1, 2, 4},   //  9: 32 ch x  32 px, 4 channel shares, for layers with few outputs
-    {1, 13, 4, 1, 2, 2, 2, 2},  // 10: 64 ch x 208 px, 8 waves (4 along K x 2 channel shares), two per SIMD
-    {1, 7, 4, 1, 2, 2, 2, 2},   // 11: 64 ch x 112 px, same scheme
-    {1, 7, 4, 1, 1, 2, 1, 8},   // 12: 64 ch x 112 px, 8-channel chunks (large filters)
-    {2, 7, 2, 1, 2, 1, 1, 8},   // 13: 64 ch x 112 px, 2 channel shares, 8-channel chunks (large filters)
+    {2, 2, 1, 1, 4, 1, 2, 4},   //  5: 32 ch x  32 px, 4 channel shares, for layers with few outputs
+    {1, 13, 4, 1, 2, 2, 2, 2},  //  6: 64 ch x 208 px (a 14x14 image), 8 waves (4 along K x 2 channel shares), two per SIMD
+    {1, 7, 4, 1, 2, 2, 2, 2},   //  7: 64 ch x 112 px, same scheme
+    {1, 7, 4, 1, 1, 2, 1, 8},   //  8: 64 ch x 112 px, 8-channel chunks (large filters)
+    {2, 7, 2, 1, 2, 1, 1, 8},   //  9: 64 ch x 112 px, 2 channel shares, 8-channel chunks (large filters)
+    {1, 1, 1, 1, 4, 1, 2, 4},   // 10: 16 ch x  16 px, 4 channel shares: many small work-groups for tiny layers
+    {1, 2, 1, 1, 4, 1, 2, 4},   // 11: 16 ch x  32 px, 4 channel shares
 };
 constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
-#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13)
+#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11)
 
 // Tile shapes of the pointwise (1x1, no padding) family: a work-group is WC x WP waves on 16*MT output
 // channels x WP*64 contiguous pixels of one image; the WC shares split the input channels.

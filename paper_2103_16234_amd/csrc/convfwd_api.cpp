@@ -142,7 +142,7 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     const int cc = tv.chunk_c();
     if (chunk_c != 0 && chunk_c != cc) return false;
     chunk_c = cc;
-    if (!tv.supports(RS)) return false;  // the filter block would not fit the variant's registers
+    if (!tv.supports(RS) || (w_vec == 1 && !tv.supports_scalar(RS))) return false;  // staging would not fit the registers
     const int64_t x_floats = (int64_t)cc * rows * s.W;
     if (x_floats > (int64_t)tv.xslots * 4 * BLOCK) return false;
     const int64_t copy_floats = tv.staging_floats(RS, plane);
@@ -259,9 +259,9 @@ struct TunedEntry {
 constexpr TunedEntry kTuned[] = {
     {1, 16, 14, 14, 16, 3, 1, CONV_KERNEL_TAP, 2, 16},
     {1, 256, 56, 56, 64, 1, 0, CONV_KERNEL_POINTWISE, 1, 64},
-    {8, 64, 56, 56, 64, 3, 1, CONV_KERNEL_TAP, 11, 112},
-    {1, 48, 28, 28, 128, 5, 2, CONV_KERNEL_TAP, 2, 56},
-    {32, 512, 14, 14, 512, 3, 1, CONV_KERNEL_TAP, 10, 196},
+    {8, 64, 56, 56, 64, 3, 1, CONV_KERNEL_TAP, 7, 112},
+    {1, 48, 28, 28, 128, 5, 2, CONV_KERNEL_TAP, 11, 28},
+    {32, 512, 14, 14, 512, 3, 1, CONV_KERNEL_TAP, 6, 196},
 };
 const TunedEntry* find_tuned(const Shape& s)
 {
