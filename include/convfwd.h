@@ -41,6 +41,7 @@ extern "C" {
 #define CONV_E_OVERFLOW (-4)  /* a tensor has 2^31 or more elements (kernels index with 32 bits) */
 #define CONV_E_HIP (-5)       /* a HIP runtime call failed; conv_strerror gives its text */
 #define CONV_E_PLAN (-6)      /* a caller-supplied plan does not fit the shape or the kernels */
+#define CONV_E_WORKSPACE (-7) /* the workspace given to conv_fwd_two_stage is too small */
 
 /* Kernel families a plan can name. */
 #define CONV_KERNEL_GENERIC 0 /* one output per thread, fp32 FMA; any R, S, padding */
@@ -102,6 +103,21 @@ int conv_fwd_plan(int N, int C, int H, int W, int K, int R, int S, int pad_h, in
 int conv_fwd_planned(const float* x, const float* w, float* y,
                      int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
                      const conv_plan_t* plan, conv_plan_t* resolved);
+
+/*
+ * The paper's own two-stage scheme (Section 3), opt-in and outside the planner, for comparison with the
+ * fused kernels: stage 1 computes, per filter tap (r,s), the channel-reduced matrix
+ * T[r,s][n,k,p,q] = sum_c w[k,c,r,s] * xpad[n,c,p+r-pad_h,q+s-pad_w] into the workspace (one work-group
+ * per filter row staged in LDS, one dot product per thread), stage 2 adds the R*S matrices into y; a 1x1
+ * filter needs no second stage and no workspace. workspace: device pointer to at least
+ * conv_two_stage_workspace_bytes(...) bytes, owned by the caller, contents undefined afterwards (may be
+ * null when that size is 0). Two kernels are enqueued on the library's stream. Returns CONV_OK,
+ * CONV_E_NULL / _DIM / _EMPTY / _OVERFLOW / _HIP, CONV_E_WORKSPACE if workspace_bytes is too small, or
+ * CONV_E_PLAN if C exceeds 16384 (a filter row must fit LDS) or the workspace would pass 2^31 elements.
+ */
+long long conv_two_stage_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w);
+int conv_fwd_two_stage(const float* x, const float* w, float* y, float* workspace, long long workspace_bytes,
+                       int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w);
 
 /*
  * Number of tile shapes of a kernel family (0 for an unknown family), and the

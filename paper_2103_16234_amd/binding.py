@@ -17,8 +17,8 @@ CONV_KERNEL_GENERIC = 0
 CONV_KERNEL_TAP = 1
 CONV_KERNEL_POINTWISE = 2
 
-EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_variant_count", "conv_variant_info",
-           "conv_set_stream", "conv_strerror")
+EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_two_stage_workspace_bytes", "conv_fwd_two_stage",
+           "conv_variant_count", "conv_variant_info", "conv_set_stream", "conv_strerror")
 
 
 class ConvPlan(ctypes.Structure):
@@ -61,13 +61,16 @@ def load_library():
     lib.conv_fwd.argtypes = [vp, vp, vp] + dims
     lib.conv_fwd_plan.argtypes = dims + [ctypes.POINTER(ConvPlan)]
     lib.conv_fwd_planned.argtypes = [vp, vp, vp] + dims + [ctypes.POINTER(ConvPlan), ctypes.POINTER(ConvPlan)]
+    lib.conv_two_stage_workspace_bytes.argtypes = dims
+    lib.conv_two_stage_workspace_bytes.restype = ctypes.c_longlong
+    lib.conv_fwd_two_stage.argtypes = [vp, vp, vp, vp, ctypes.c_longlong] + dims
     lib.conv_variant_count.argtypes = [ci]
     lib.conv_variant_info.argtypes = [ci, ci] + [ctypes.POINTER(ci)] * 3
     lib.conv_set_stream.argtypes = [vp]
     lib.conv_strerror.argtypes = [ci]
     lib.conv_strerror.restype = ctypes.c_char_p
     for name in EXPORTS:
-        if name != "conv_strerror":
+        if name not in ("conv_strerror", "conv_two_stage_workspace_bytes"):
             getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -147,3 +150,26 @@ def conv_fwd_planned(x, w, pad_h: int, pad_w: int, kernel: int, variant: int = 0
     req.kernel, req.variant, req.tile_pix, req.chunk_c = kernel, variant, tile_pix, chunk_c
     _check(lib.conv_fwd_planned(x.data_ptr(), w.data_ptr(), y.data_ptr(), *dims, ctypes.byref(req), ctypes.byref(res)))
     return y, res
+
+
+def conv_two_stage_workspace_bytes(N, C, H, W, K, R, S, pad_h, pad_w) -> int:
+    n = load_library().conv_two_stage_workspace_bytes(N, C, H, W, K, R, S, pad_h, pad_w)
+    if n < 0:
+        _check(int(n))
+    return int(n)
+
+
+def conv_fwd_two_stage(x, w, pad_h: int, pad_w: int, workspace=None, y=None, use_current_stream: bool = True):
+    """The paper's two-stage scheme (opt-in): y = conv(x, w) through an explicit workspace tensor."""
+    import torch
+    y, dims = _device_args(x, w, y, pad_h, pad_w)
+    lib = load_library()
+    need = conv_two_stage_workspace_bytes(*dims)
+    if workspace is None and need:
+        workspace = torch.empty(need // 4, device=x.device, dtype=torch.float32)
+    if use_current_stream:
+        conv_set_stream(torch.cuda.current_stream(x.device))
+    ws_ptr = workspace.data_ptr() if workspace is not None else 0
+    ws_bytes = workspace.numel() * 4 if workspace is not None else 0
+    _check(lib.conv_fwd_two_stage(x.data_ptr(), w.data_ptr(), y.data_ptr(), ws_ptr, ws_bytes, *dims))
+    return y

@@ -38,7 +38,8 @@ def _jobs():
     """(object path, source path, extra flags) for every translation unit."""
     jobs = [(os.path.join(OBJ, "convfwd_api.o"), os.path.join(CSRC, "convfwd_api.cpp"), ["-x", "hip"]),
             (os.path.join(OBJ, "generic.o"), os.path.join(CSRC, "generic.hip"), []),
-            (os.path.join(OBJ, "pointwise.o"), os.path.join(CSRC, "pointwise_mfma.hip"), [])]
+            (os.path.join(OBJ, "pointwise.o"), os.path.join(CSRC, "pointwise_mfma.hip"), []),
+            (os.path.join(OBJ, "two_stage.o"), os.path.join(CSRC, "two_stage.hip"), [])]
     jobs = [j for j in jobs if os.path.exists(j[1])]
     for r in TAP_SIZES:
         for v in range(_num_tap_variants()):

@@ -5,6 +5,8 @@
 
 namespace convfwd {
 
+constexpr int kMaxDevices = 16;  // per-device launch state is kept for this many GPUs of one process
+
 // Division by a launch-time constant as multiply-high, subtract, shift (round-up method of Granlund and
 // Montgomery: exact for every 32-bit unsigned dividend). The host fills it, the kernels only use div().
 struct FastDiv {
@@ -131,5 +133,7 @@ hipError_t launch_pointwise(int variant, int x_vec, int grid, int lds_bytes, hip
 hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid, int lds_bytes,
                       hipStream_t stream, const KernelArgs& a);
 hipError_t launch_generic(int grid, int block, hipStream_t stream, const KernelArgs& a);
+// temp: R*S*N*K*P*Q floats (unused for 1x1 filters)
+hipError_t launch_two_stage(hipStream_t stream, const KernelArgs& a, float* temp);
 
 }  // namespace convfwd

@@ -434,6 +434,30 @@ extern "C" int conv_fwd_planned(const float* x, const float* w, float* y, int N,
     return launch(p, a, s, x, w, y);
 }
 
+extern "C" long long conv_two_stage_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w)
+{
+    Shape s;
+    if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
+    if (R * S == 1) return 0;
+    return 4LL * R * S * N * K * s.P * s.Q;
+}
+
+extern "C" int conv_fwd_two_stage(const float* x, const float* w, float* y, float* workspace, long long workspace_bytes,
+                                  int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w)
+{
+    if (!x || !w || !y) return CONV_E_NULL;
+    Shape s;
+    if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
+    const long long need = conv_two_stage_workspace_bytes(N, C, H, W, K, R, S, pad_h, pad_w);
+    if (need / 4 >= (1LL << 31) || C > 16384) return CONV_E_PLAN;
+    if (need > 0 && !workspace) return CONV_E_NULL;
+    if (workspace_bytes < need) return CONV_E_WORKSPACE;
+    KernelArgs a;
+    base_args(s, &a);
+    a.x = x; a.w = w; a.y = y;
+    return record_hip(launch_two_stage(g_stream.load(), a, workspace));
+}
+
 extern "C" int conv_variant_count(int kernel)
 {
     if (kernel == CONV_KERNEL_GENERIC) return 1;
@@ -474,6 +498,7 @@ extern "C" const char* conv_strerror(int code)
         case CONV_E_OVERFLOW: return "tensor has 2^31 or more elements";
         case CONV_E_HIP: return g_hip_error.c_str();
         case CONV_E_PLAN: return "plan does not fit the shape or the kernels";
+        case CONV_E_WORKSPACE: return "workspace too small";
         default: return "unknown error code";
     }
 }

@@ -31,6 +31,7 @@
 // Compiled once per (filter size, tile shape): TAP_R, TAP_S, TAP_VARIANT come from the build.
 #include "conv_internal.h"
 
+#include <atomic>
 #include <utility>
 
 namespace convfwd {
@@ -372,16 +373,24 @@ hipError_t TAP_CAT(TAP_R, TAP_S, TAP_VARIANT)(int x_vec, int w_vec, int grid, in
                                               const KernelArgs& a)
 {
     KernFn fn = nullptr;
+    int mode = -1;
     if (w_vec == 4) {
         fn = x_vec == 4 ? instance<4, 4>() : x_vec == 2 ? instance<2, 4>() : x_vec == 1 ? instance<1, 4>() : nullptr;
+        mode = x_vec == 4 ? 0 : x_vec == 2 ? 1 : 2;
     } else if (w_vec == 1 && x_vec == 1) {
         fn = instance<1, 1>();
+        mode = 3;
     }
     if (!fn) return hipErrorInvalidValue;
-    if (lds_bytes > 48 * 1024) {
+    // Kernels may use all 160 KB of a CU's LDS; the runtime wants to be told once per kernel (and device).
+    static std::atomic<int> lds_allowed[4][kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
+    if (lds_bytes > 48 * 1024 && lds_allowed[mode][dev].load(std::memory_order_acquire) < lds_bytes) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
+        lds_allowed[mode][dev].store(160 * 1024, std::memory_order_release);
     }
     constexpr TapVariant tv = kTapVariants[TAP_VARIANT];
     hipLaunchKernelGGL(fn, dim3(grid), dim3(tv.block()), lds_bytes, stream, a);

@@ -57,7 +57,14 @@ def test_argument_errors_are_codes_not_crashes(lib):
     assert lib.conv_fwd(None, None, None, *ok) == -1
     assert lib.conv_fwd(1 << 20, 1 << 20, None, *ok) == -1
     assert lib.conv_fwd(1 << 20, 1 << 20, 1 << 20, 1, 4, 8, 8, 0, 3, 3, 1, 1) == -2
-    for code in (0, -1, -2, -3, -4, -5, -6, -99):
+    assert lib.conv_two_stage_workspace_bytes(2, 4, 8, 8, 3, 3, 3, 1, 1) == 4 * 9 * 2 * 3 * 8 * 8
+    assert lib.conv_two_stage_workspace_bytes(2, 4, 8, 8, 3, 1, 1, 0, 0) == 0
+    assert lib.conv_two_stage_workspace_bytes(2, 4, 2, 8, 3, 5, 5, 1, 2) == -3
+    assert lib.conv_fwd_two_stage(None, None, None, None, 0, *ok) == -1
+    assert lib.conv_fwd_two_stage(1 << 20, 1 << 20, 1 << 20, None, 0, *ok) == -1      # workspace needed but null
+    assert lib.conv_fwd_two_stage(1 << 20, 1 << 20, 1 << 20, 1 << 20, 16, *ok) == -7   # too small
+    assert lib.conv_fwd_two_stage(1 << 20, 1 << 20, 1 << 20, 1 << 20, 1 << 40, 1, 20000, 8, 8, 4, 3, 3, 1, 1) == -6
+    for code in (0, -1, -2, -3, -4, -5, -6, -7, -99):
         assert binding.conv_strerror(code)
     with pytest.raises(binding.ConvError) as e:
         binding.conv_fwd_plan(1, 4, 2, 8, 4, 5, 5, 1, 2)

@@ -161,6 +161,39 @@ def test_pointwise_needs_its_preconditions():
         assert plan.kernel != POINTWISE
 
 
+@pytest.mark.parametrize("shape", SMALL + POINTWISE_SHAPES[:3], ids=lambda s: s.name)
+def test_two_stage_scheme_matches_oracle(shape):
+    """The paper's own two-stage method (Section 3), opt-in with an explicit workspace."""
+    x, w, y_ref, ya_ref = _reference(shape)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    need = binding.conv_two_stage_workspace_bytes(*shape.dims)
+    assert need == (0 if shape.R * shape.S == 1 else 4 * shape.R * shape.S * int(np.prod(shape.y_shape)))
+    yd = torch.full(shape.y_shape, float("nan"), device="cuda")
+    _say(f"[case] two-stage {shape.name} dims={shape.dims} workspace={need}")
+    binding.conv_fwd_two_stage(xd, wd, shape.pad_h, shape.pad_w, y=yd)
+    torch.cuda.synchronize()
+    ok, worst = oracle.within_tolerance(yd.cpu().numpy(), y_ref, ya_ref)
+    assert ok, worst
+    if need:
+        small = torch.empty(need // 4 - 1, device="cuda")
+        with pytest.raises(binding.ConvError) as e:
+            binding.conv_fwd_two_stage(xd, wd, shape.pad_h, shape.pad_w, workspace=small, y=yd)
+        assert e.value.code == -7
+
+
+def test_two_stage_scheme_other_filter_sizes_and_exactness():
+    for shape in list(NONSQUARE):
+        x, w, y_ref, ya_ref = _reference(shape)
+        y = binding.conv_fwd_two_stage(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), shape.pad_h, shape.pad_w)
+        torch.cuda.synchronize()
+        assert oracle.within_tolerance(y.cpu().numpy(), y_ref, ya_ref)[0]
+    shape = inputs.ConvShape("ints2", 2, 12, 9, 10, 35, 3, 3, 1, 1, "int", "int", 31, 32)
+    x, w, y_ref, _ = _reference(shape)
+    y = binding.conv_fwd_two_stage(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), 1, 1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(y.cpu().numpy().astype(np.float64), y_ref)
+
+
 NONSQUARE = [
     S("g2x3", 2, 5, 8, 9, 7, 2, 3, 1, 0),
     S("g7x7", 1, 3, 12, 12, 6, 7, 7, 3, 3),
