@@ -146,6 +146,62 @@ def cpu_baseline(oracle, inputs, index, budget_macs=4e9):
             "sample": f"{s.name}: images 0..{n - 1} of {s.N}, all {s.K} filters, {reps} pass(es), {dt:.3f} s per pass"}
 
 
+# The shapes whose kernel times the paper prints (Tables 3-5: H - N - filter - K - C), with its own stage-1 (+ stage-2)
+# time and the best vendor-library time on its GPU (NVIDIA V100, CUDA 9.2), in microseconds: context, not targets.
+PAPER_SHAPES = (
+    ("1x1 A", (1, 832, 7, 7, 256, 1, 1, 0, 0), 58.56, 107.29),
+    ("1x1 B", (1, 256, 14, 14, 1024, 1, 1, 0, 0), 73.86, 45.23),
+    ("1x1 C", (1, 64, 27, 27, 256, 1, 1, 0, 0), 22.53, 19.20),
+    ("3x3 A", (1, 192, 7, 7, 384, 3, 3, 1, 1), 57.79, 105.63),
+    ("3x3 B", (1, 384, 13, 13, 384, 3, 3, 1, 1), 466.68, 232.35),
+    ("5x5 A", (1, 48, 7, 7, 128, 5, 5, 2, 2), 22.50, 74.80),
+    ("5x5 B", (8, 48, 7, 7, 128, 5, 5, 2, 2), 116.60, 76.58),
+)
+
+
+def paper_shapes(torch, binding, inputs, oracle):
+    """Fused kernels (conv_fwd) against the paper's own two-stage scheme (conv_fwd_two_stage) on the paper's shapes."""
+    lib = binding.load_library()
+    rows = []
+    for label, dims, paper_us, vendor_us in PAPER_SHAPES:
+        shape = inputs.ConvShape(label, *dims, "u01", "he", 77, 78)
+        x, w = inputs.make_inputs(shape)
+        sets = 64
+        xd = torch.from_numpy(x).cuda().unsqueeze(0).repeat(sets, 1, 1, 1, 1)
+        wd = torch.from_numpy(w).cuda().unsqueeze(0).repeat(sets, 1, 1, 1, 1)
+        yd = torch.empty((sets,) + shape.y_shape, device="cuda")
+        need = binding.conv_two_stage_workspace_bytes(*dims)
+        ws = torch.empty(max(need // 4, 1), device="cuda")
+
+        def fused(i):
+            return lib.conv_fwd(xd[i].data_ptr(), wd[i].data_ptr(), yd[i].data_ptr(), *dims)
+
+        def staged(i):
+            return lib.conv_fwd_two_stage(xd[i].data_ptr(), wd[i].data_ptr(), yd[i].data_ptr(), ws.data_ptr(), need, *dims)
+
+        rec = {"shape": label, "dims": dict(zip("N C H W K R S pad_h pad_w".split(), dims)),
+               "paper_two_stage_us_v100": paper_us, "paper_best_vendor_us_v100": vendor_us}
+        y_ref, ya_ref = oracle.conv_ref(x, w, shape.pad_h, shape.pad_w)
+        for name, fn in (("fused_us", fused), ("two_stage_us", staged)):
+            for i in range(10):
+                assert fn(i % sets) == 0
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(500):
+                fn(i % sets)
+            e1.record()
+            torch.cuda.synchronize()
+            rec[name] = e0.elapsed_time(e1) / 500 * 1e3
+            assert fn(0) == 0
+            torch.cuda.synchronize()
+            rec[name.replace("_us", "_parity_ok")] = oracle.within_tolerance(yd[0].cpu().numpy(), y_ref, ya_ref)[0]
+        plan = binding.conv_fwd_plan(*dims)
+        rec["fused_plan"] = {"kernel": plan.kernel, "variant": plan.variant, "grid": plan.grid, "block": plan.block}
+        rows.append(rec)
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -154,6 +210,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="headline layer, 1..5 (default 2: the 1x1 layer)")
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--paper-shapes", action="store_true",
+                    help="also time the fused kernels and the paper's two-stage scheme on the shapes the paper profiles")
     ns = ap.parse_args()
     if ns.gpus != 1:
         _fail("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -208,6 +266,8 @@ def main():
             del layer
             torch.cuda.empty_cache()
         out["layers"] = layers
+    if ns.paper_shapes:
+        out["paper_shapes"] = paper_shapes(torch, binding, inputs, oracle)
     if not ns.no_cpu:
         out["cpu_baseline"] = cpu_baseline(oracle, inputs, ns.config)
     print(json.dumps(out))
