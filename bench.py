@@ -41,8 +41,8 @@ class Layer:
     """One benchmark layer with rotating device buffers."""
 
     def __init__(self, index, torch, binding, inputs, min_bytes=600e6, max_sets=2048):
-        self.index = index
-        self.shape = inputs.config(index)
+        self.index = index if isinstance(index, int) else None   # a benchmark layer number, or a shape record
+        self.shape = inputs.config(index) if isinstance(index, int) else index
         self.torch = torch
         self.lib = binding.load_library()
         x, w = inputs.make_inputs(self.shape)
@@ -89,7 +89,7 @@ class Layer:
         t = event_ms * 1e-3
         gflops = s.flops / t / 1e9
         gbs = s.algorithmic_bytes / t / 1e9
-        bound = BOUND[self.index]
+        bound = self.bound()
         return {
             "layer": s.name, "dims": {"N": s.N, "C": s.C, "H": s.H, "W": s.W, "K": s.K, "R": s.R, "S": s.S,
                                       "pad": s.pad_h},
@@ -101,16 +101,23 @@ class Layer:
                                                          "x_vec", "w_vec", "grid", "block", "lds_bytes")},
         }
 
+    def bound(self):
+        """The benchmark layers carry their stated bound; any other shape takes the slower of its two roofline times."""
+        if self.index is not None:
+            return BOUND[self.index]
+        s = self.shape
+        return "hbm" if s.algorithmic_bytes / PEAK_HBM_GBS / 1e9 > s.flops / PEAK_FP32_TFLOPS / 1e12 else "mfma"
+
     def roofline(self, event_ms):
         s = self.shape
         t = event_ms * 1e-3
-        bound = BOUND[self.index]
+        bound = self.bound()
         if bound == "hbm":
             achieved, peak, unit = s.algorithmic_bytes / t / 1e9, PEAK_HBM_GBS, "GB/s"
         else:
             achieved, peak, unit = s.flops / t / 1e12, PEAK_FP32_TFLOPS, "TFLOP/s"
         return {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
-                "traffic": TRAFFIC_BYTES[self.index], "kernel": "conv_tap_mfma" if self.plan.kernel == 1 else
+                "traffic": TRAFFIC_BYTES.get(self.index), "kernel": "conv_tap_mfma" if self.plan.kernel == 1 else
                 ("conv_pointwise_mfma" if self.plan.kernel == 2 else "conv_generic"),
                 "kernel_us": event_ms * 1e3, "algorithmic_bytes": s.algorithmic_bytes, "algorithmic_flops": s.flops}
 
@@ -202,6 +209,29 @@ def paper_shapes(torch, binding, inputs, oracle):
     return rows
 
 
+def sweep(torch, binding, inputs, oracle, only=None):
+    """Second workload: every shape of the synthetic sweep grid, timed like the layers and spot-checked against the oracle."""
+    rows = []
+    for shape in inputs.sweep_shapes():
+        if only and only not in shape.name:
+            continue
+        layer = Layer(shape, torch, binding, inputs, min_bytes=600e6, max_sets=256)
+        _, ev = layer.measure(3, 2)
+        k = int(max(10, min(1000, 0.05 / max(ev * 1e-3, 1e-7))))
+        w_ms, e_ms = layer.measure(k, 3)
+        roof = layer.roofline(e_ms)
+        par = layer.parity_sample(oracle, 128)
+        p = layer.plan
+        rows.append({"shape": shape.name, "kernel_us": e_ms * 1e3, "tflops": shape.flops / e_ms / 1e9,
+                     "gbs": shape.algorithmic_bytes / e_ms / 1e6, "bound": roof["bound"], "frac": roof["frac"],
+                     "plan": [p.kernel, p.variant, p.tile_pix, p.grid, p.block], "parity_ok": par["ok"]})
+        print(f"sweep {shape.name}: {e_ms * 1e3:.1f} us {roof['bound']} {roof['frac']:.3f} parity {par['ok']}",
+              file=sys.stderr, flush=True)
+        del layer
+        torch.cuda.empty_cache()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -212,6 +242,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--paper-shapes", action="store_true",
                     help="also time the fused kernels and the paper's two-stage scheme on the shapes the paper profiles")
+    ap.add_argument("--sweep", nargs="?", const="", default=None, metavar="SUBSTR",
+                    help="also run the synthetic shape sweep (optionally only shapes whose name contains SUBSTR)")
     ns = ap.parse_args()
     if ns.gpus != 1:
         _fail("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -268,6 +300,8 @@ def main():
         out["layers"] = layers
     if ns.paper_shapes:
         out["paper_shapes"] = paper_shapes(torch, binding, inputs, oracle)
+    if ns.sweep is not None:
+        out["sweep"] = sweep(torch, binding, inputs, oracle, ns.sweep)
     if not ns.no_cpu:
         out["cpu_baseline"] = cpu_baseline(oracle, inputs, ns.config)
     print(json.dumps(out))

@@ -46,7 +46,8 @@ extern "C" {
 /* Kernel families a plan can name. */
 #define CONV_KERNEL_GENERIC 0 /* one output per thread, fp32 FMA; any R, S, padding */
 #define CONV_KERNEL_TAP 1     /* LDS halo tile + filter block, fp32 MFMA over (channel, tap); R = S in {1,3,5} */
-#define CONV_KERNEL_POINTWISE 2 /* 1x1, pad 0: inputs streamed HBM -> registers -> fp32 MFMA, filters in LDS */
+#define CONV_KERNEL_POINTWISE 2 /* 1x1, pad 0: inputs and filters streamed HBM -> registers -> fp32 MFMA, waves split C */
+#define CONV_KERNEL_PANEL 3   /* 1x1, pad 0, batched: filters of a channel tile resident in LDS, waves stream pixel tiles */
 
 /*
  * How one layer is mapped onto the GPU. Filled by conv_fwd_plan; plain data.
@@ -58,7 +59,8 @@ typedef struct conv_plan {
     int kernel;          /* CONV_KERNEL_* */
     int variant;         /* tile shape index inside the family (see conv_variant_info) */
     int tile_k;          /* output channels per work-group */
-    int tile_pix;        /* output pixels per work-group, counted in flattened (n,p,q) order */
+    int tile_pix;        /* output pixels per work-group, counted in flattened (n,p,q) order
+                            (CONV_KERNEL_PANEL: work-groups per channel tile, each wave streaming 64-pixel tiles) */
     int chunk_c;         /* input channels staged in LDS per round */
     int x_vec, w_vec;    /* dwords per global load of input rows / filter slices: 4, 2 or 1 */
     int lds_rows;        /* input rows (of the zero-padded, vertically stacked images) held per channel */

@@ -16,6 +16,7 @@ _lib = None
 CONV_KERNEL_GENERIC = 0
 CONV_KERNEL_TAP = 1
 CONV_KERNEL_POINTWISE = 2
+CONV_KERNEL_PANEL = 3
 
 EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_two_stage_workspace_bytes", "conv_fwd_two_stage",
            "conv_variant_count", "conv_variant_info", "conv_set_stream", "conv_strerror")

@@ -39,6 +39,7 @@ def _jobs():
     jobs = [(os.path.join(OBJ, "convfwd_api.o"), os.path.join(CSRC, "convfwd_api.cpp"), ["-x", "hip"]),
             (os.path.join(OBJ, "generic.o"), os.path.join(CSRC, "generic.hip"), []),
             (os.path.join(OBJ, "pointwise.o"), os.path.join(CSRC, "pointwise_mfma.hip"), []),
+            (os.path.join(OBJ, "pointwise_panel.o"), os.path.join(CSRC, "pointwise_panel.hip"), []),
             (os.path.join(OBJ, "two_stage.o"), os.path.join(CSRC, "two_stage.hip"), [])]
     jobs = [j for j in jobs if os.path.exists(j[1])]
     for r in TAP_SIZES:

@@ -129,6 +129,23 @@ constexpr int kNumPointwiseVariants = sizeof(kPointwiseVariants) / sizeof(kPoint
 #define POINTWISE_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13)
 hipError_t launch_pointwise(int variant, int x_vec, int grid, int lds_bytes, hipStream_t stream, const KernelArgs& a);
 
+// Panel shapes of the pointwise family (batched 1x1 layers): a work-group of NW waves keeps the filters
+// of 16*MT output channels in LDS and every wave streams 64-pixel tiles past them with PD 16-channel
+// steps of input loads in flight. KernelArgs carry: ktiles, ptiles = work-groups per channel tile,
+// nchunks = steps (C rounded up to 16*PD, over 16), x_items = 64-pixel tiles in all, lds_pitch = floats per
+// panel row, div_ktiles, div_PQ, div_row_vecs (by 4 * nchunks).
+struct PanelVariant {
+    int MT, NW, PD;
+    constexpr int tile_k() const { return 16 * MT; }
+    constexpr int block() const { return 64 * NW; }
+};
+constexpr PanelVariant kPanelVariants[] = {
+    {4, 8, 4}, {2, 8, 4}, {1, 8, 4}, {4, 4, 4}, {2, 4, 4}, {1, 4, 4},
+};
+constexpr int kNumPanelVariants = sizeof(kPanelVariants) / sizeof(kPanelVariants[0]);
+#define PANEL_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5)
+hipError_t launch_panel(int variant, int x_vec, int grid, int lds_bytes, hipStream_t stream, const KernelArgs& a);
+
 // rs_index: 0 -> 1x1, 1 -> 3x3, 2 -> 5x5. Returns hipSuccess or the launch error.
 hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid, int lds_bytes,
                       hipStream_t stream, const KernelArgs& a);

@@ -205,6 +205,54 @@ bool resolve_pointwise(const Shape& s, int variant, int x_cap, int w_cap, int y_
     return true;
 }
 
+// Panel kernel of the pointwise family: the filters of a channel tile must fit LDS whole. tile_pix > 0
+// requests that many work-groups per channel tile (0 = choose).
+bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
+{
+    if (!pointwise_ok(s, x_cap, w_cap, y_cap) || variant < 0 || variant >= kNumPanelVariants) return false;
+    const PanelVariant pv = kPanelVariants[variant];
+    const int steps = round_up(s.C, 16 * pv.PD) / 16;
+    const int pitch = 16 * steps + 4;
+    const int64_t lds = (int64_t)pv.tile_k() * pitch * 4;
+    if (lds > kLdsMax) return false;
+    base_args(s, a);
+    const int tiles = ceil_div(a->total_pix, 64);
+    if (a->total_pix < 4 || a->total_pix > (1 << 30)) return false;  // tile * 64 + lane offsets stay far inside 32 bits
+    a->ktiles = ceil_div(s.K, pv.tile_k());
+    int groups = groups_req;
+    const int most = ceil_div(tiles, pv.NW);  // one tile per wave
+    if (groups <= 0) {
+        // as many work-groups as stay resident together (two waves per SIMD, LDS permitting), then the
+        // fewest that still finish in the same number of tile rounds
+        const int per_cu = std::max(1, std::min((int)(kLdsMax / lds), 8 / pv.NW));
+        const int target = std::max(1, kNumCU * per_cu / a->ktiles);
+        if (target >= most) {
+            groups = most;
+        } else {
+            const int rounds = ceil_div(tiles, target * pv.NW);
+            groups = ceil_div(tiles, rounds * pv.NW);
+        }
+    }
+    groups = std::min(groups, most);
+    if ((int64_t)groups * a->ktiles >= ((int64_t)1 << 31)) return false;
+    a->ptiles = groups;
+    a->tile_pix = 64;
+    a->nchunks = steps;
+    a->x_items = tiles;
+    a->lds_pitch = pitch;
+    a->div_ktiles = make_fastdiv(a->ktiles);
+    a->div_PQ = make_fastdiv(a->HW);
+    a->div_row_vecs = make_fastdiv(4 * steps);
+    std::memset(p, 0, sizeof(*p));
+    p->kernel = CONV_KERNEL_PANEL; p->variant = variant;
+    p->tile_k = pv.tile_k(); p->tile_pix = groups; p->chunk_c = 16 * pv.PD;
+    p->x_vec = pointwise_x_vec(s, x_cap, y_cap); p->w_vec = 4;
+    p->lds_pitch = pitch;
+    p->grid = groups * a->ktiles; p->block = pv.block(); p->lds_bytes = (int)lds;
+    fill_common(s, p);
+    return true;
+}
+
 // Choice of the pointwise tile shape, from sweeps: with plenty of work, 32 channels x 64 pixels per
 // work-group and four channel shares (inputs are re-read through L2 by the second channel tile, which
 // costs less than fewer, longer-lived waves); for small layers 16 channels per work-group and as many
@@ -370,6 +418,7 @@ int launch(const conv_plan_t& p, KernelArgs& a, const Shape& s, const float* x, 
     if (p.kernel == CONV_KERNEL_TAP)
         return record_hip(launch_tap(tap_rs_index(s), p.variant, p.x_vec, p.w_vec, p.grid, p.lds_bytes, stream, a));
     if (p.kernel == CONV_KERNEL_POINTWISE) return record_hip(launch_pointwise(p.variant, p.x_vec, p.grid, p.lds_bytes, stream, a));
+    if (p.kernel == CONV_KERNEL_PANEL) return record_hip(launch_panel(p.variant, p.x_vec, p.grid, p.lds_bytes, stream, a));
     if (p.kernel == CONV_KERNEL_GENERIC) return record_hip(launch_generic(p.grid, p.block, stream, a));
     return CONV_E_PLAN;
 }
@@ -422,6 +471,8 @@ extern "C" int conv_fwd_planned(const float* x, const float* w, float* y, int N,
     KernelArgs a;
     if (plan->kernel == CONV_KERNEL_POINTWISE) {
         if (!resolve_pointwise(s, plan->variant, x_cap, w_cap, y_cap, &p, &a)) return CONV_E_PLAN;
+    } else if (plan->kernel == CONV_KERNEL_PANEL) {
+        if (plan->tile_pix < 0 || !resolve_panel(s, plan->variant, plan->tile_pix, x_cap, w_cap, y_cap, &p, &a)) return CONV_E_PLAN;
     } else if (plan->kernel == CONV_KERNEL_GENERIC) {
         resolve_generic(s, &p, &a);
     } else if (plan->kernel == CONV_KERNEL_TAP) {
@@ -463,6 +514,7 @@ extern "C" int conv_variant_count(int kernel)
     if (kernel == CONV_KERNEL_GENERIC) return 1;
     if (kernel == CONV_KERNEL_TAP) return kNumTapVariants;
     if (kernel == CONV_KERNEL_POINTWISE) return kNumPointwiseVariants;
+    if (kernel == CONV_KERNEL_PANEL) return kNumPanelVariants;
     return 0;
 }
 
@@ -475,6 +527,9 @@ extern "C" int conv_variant_info(int kernel, int variant, int* tile_k, int* max_
     }
     if (kernel == CONV_KERNEL_POINTWISE) {
         tk = kPointwiseVariants[variant].tile_k(); mp = kPointwiseVariants[variant].tile_pix(); bl = kPointwiseVariants[variant].block();
+    }
+    if (kernel == CONV_KERNEL_PANEL) {
+        tk = kPanelVariants[variant].tile_k(); mp = 64 * kPanelVariants[variant].NW; bl = kPanelVariants[variant].block();
     }
     if (tile_k) *tile_k = tk;
     if (max_tile_pix) *max_tile_pix = mp;

@@ -1,0 +1,221 @@
+// Panel kernel of the pointwise family: 1x1 filters without padding on batched layers. For such a layer
+// the whole batch is one matrix product y[K x N*HW] = w[K x C] * x[C x N*HW] per image block (Section 3, last
+// paragraph: with a 1x1 filter the first stage already yields the output). A work-group keeps the filters
+// of its 16*MT output channels - a panel of 16*MT x C floats - in LDS for its whole life and its waves
+// stream 64-pixel tiles of the flattened (n, pixel) axis past it:
+//   x: HBM -> registers (dwordx4 of four consecutive pixels = B operands of four MFMA tiles), PD steps of
+//      16 channels in flight per wave, the stream of loads running on across tile boundaries;
+//   w: LDS -> registers (one 16-byte read per 16 x 16 filter tile and step = A operands of four MFMAs);
+//   y: registers -> HBM as dwordx4 of four consecutive pixels.
+// Filter rows reach LDS through fully coalesced loads once per work-group instead of once per wave and
+// step, which is what bounds the register-streaming kernel on deep layers (sixteen 64-byte row pieces per
+// load instruction keep the vector cache busy four times longer than the same bytes read contiguously).
+// Channels beyond C are zero in the panel, so the steps that pad C to a multiple of 16*PD need no masking:
+// their inputs are read from clamped (valid) addresses and multiplied by zero.
+#include "conv_internal.h"
+
+#include <atomic>
+#include <utility>
+
+namespace convfwd {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// VEC = 4: H*W is a multiple of 4 and x, y are 16-byte aligned; a lane's four pixels 4j..4j+3 of a tile
+// lie in one image and move as one dwordx4. VEC = 1: pixel t of lane j is 16t + j and moves as a dword.
+// CLAMP: C is not a multiple of 16*PD, channel indices of the padding steps are clamped per lane.
+template <int MT, int NW, int PD, int VEC, bool CLAMP>
+__global__ void __launch_bounds__(64 * NW) conv_pointwise_panel(const KernelArgs a)
+{
+    extern __shared__ f32x4 smem4[];
+    float* const panel = reinterpret_cast<float*>(smem4);
+    constexpr int NTHREADS = 64 * NW;
+    constexpr int NP = VEC == 4 ? 1 : 4;  // pixel base pointers per lane
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j = lane & 15;
+    const int kq = lane >> 4;
+
+    // XCD-aware renumbering: work-groups that stream the same pixel tiles past different filter panels
+    // sit on one L2.
+    int L;
+    {
+        const int nb = gridDim.x, b = blockIdx.x;
+        const int per = nb >> 3, rem = nb & 7, xcd = b & 7;
+        L = xcd * per + (xcd < rem ? xcd : rem) + (b >> 3);
+    }
+    const int g = a.div_ktiles.div(L);
+    const int k0 = (L - g * a.ktiles) * (16 * MT);
+
+    const int nsteps = a.nchunks;   // 16-channel steps, a multiple of PD
+    const int T = a.x_items;        // 64-pixel tiles of the flattened (n, pixel) axis
+    const int stride = a.ptiles * NW;
+    const int t0 = g * NW + wave;
+    const int pitch = a.lds_pitch;
+
+    // Base pointers of this lane's pixels of tile t (channel 0 of their image, plus the lane's channel
+    // quarter when channel indices need no clamping).
+    auto lane_ptrs = [&](int t, const float* (&xp)[NP]) {
+        const int tt = min(t, T - 1);
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int px = VEC == 4 ? min(tt * 64 + 4 * j, a.total_pix - 4) : min(tt * 64 + 16 * i + j, a.total_pix - 1);
+            const int n = a.div_PQ.div(px);
+            const int p = px - n * a.HW;
+            xp[i] = a.x + ((size_t)n * a.C + (CLAMP ? 0 : 4 * kq)) * a.HW + p;
+        }
+    };
+
+    f32x4 xr[PD][4];
+    auto load_step = [&](auto slotc, const float* (&xp)[NP], int s) {
+        constexpr int slot = decltype(slotc)::value;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const size_t off = CLAMP ? (size_t)min(16 * s + 4 * kq + e, a.C - 1) * a.HW : (size_t)(16 * s + e) * a.HW;
+            if constexpr (VEC == 4) {
+                xr[slot][e] = *reinterpret_cast<const f32x4*>(xp[0] + off);
+            } else {
+                xr[slot][e] = f32x4{xp[0][off], xp[1][off], xp[2][off], xp[3][off]};
+            }
+        }
+    };
+    auto for_each_slot = [&](auto&& f) {
+        [&]<int... Ss>(std::integer_sequence<int, Ss...>) { (f(std::integral_constant<int, Ss>{}), ...); }
+        (std::make_integer_sequence<int, PD>{});
+    };
+
+    const float* cur[NP];
+    const float* nxt[NP];
+    lane_ptrs(t0, cur);
+    // the first input steps are requested before the panel is fetched, so both latencies overlap
+    for_each_slot([&](auto sc) { load_step(sc, cur, decltype(sc)::value); });
+
+    {
+        const int rowv = nsteps * 4;  // dwordx4 per panel row
+        const int total = 16 * MT * rowv;
+        for (int base = 0; base < total; base += 8 * NTHREADS) {
+            f32x4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * NTHREADS + tid;
+                const int r = a.div_row_vecs.div(idx);
+                const int c = 4 * (idx - r * rowv);
+                const bool real = idx < total && c < a.C;
+                v[u] = *reinterpret_cast<const f32x4*>(a.w + (real ? min(k0 + r, a.K - 1) * a.C + c : 0));
+                if (!real) v[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * NTHREADS + tid;
+                const int r = a.div_row_vecs.div(idx);
+                const int c = 4 * (idx - r * rowv);
+                if (idx < total) *reinterpret_cast<f32x4*>(panel + r * pitch + c) = v[u];
+            }
+        }
+    }
+    __syncthreads();
+
+    f32x4 acc[MT][4];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[m][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // lane (j, kq) reads channels 16s + 4kq .. +3 of filter 16m + j: the A operands of the four MFMAs
+    // that consume the lane's four input loads of step s
+    const float* const arow = panel + j * pitch + 4 * kq;
+    f32x4 wv[2][MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) wv[0][m] = *reinterpret_cast<const f32x4*>(arow + 16 * m * pitch);
+
+    for (int ct = t0; ct < T; ct += stride) {
+        lane_ptrs(ct + stride, nxt);
+        for (int it = 0; it < nsteps; it += PD) {
+            const bool last = it + PD >= nsteps;  // the loads issued in this round belong to the next tile
+            const int ls = last ? 0 : it + PD;
+            if (last) {
+#pragma unroll
+                for (int i = 0; i < NP; ++i) cur[i] = nxt[i];
+            }
+            for_each_slot([&](auto sc) {
+                constexpr int slot = decltype(sc)::value;
+                constexpr int wb = slot & 1;
+                int sn = it + slot + 1;
+                if (sn == nsteps) sn = 0;
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    wv[wb ^ 1][m] = *reinterpret_cast<const f32x4*>(arow + 16 * m * pitch + 16 * sn);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int m = 0; m < MT; ++m)
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[wb][m][e], xr[slot][e][t], acc[m][t], 0, 0, 0);
+                load_step(sc, cur, ls + slot);
+            });
+        }
+
+        // lane (j, kq) holds output channels 16m + 4kq + v for its four pixels of tile ct
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int px = VEC == 4 ? ct * 64 + 4 * j : ct * 64 + 16 * i + j;
+            if (px < a.total_pix) {
+                const int n = a.div_PQ.div(px);
+                const int p = px - n * a.HW;
+                float* const yl = a.y + ((size_t)n * a.K + k0 + 4 * kq) * a.HW + p;
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        if (k0 + 16 * m + 4 * kq + v >= a.K) continue;
+                        float* const dst = yl + (size_t)(16 * m + v) * a.HW;
+                        if constexpr (VEC == 4) {
+                            *reinterpret_cast<f32x4*>(dst) = f32x4{acc[m][0][v], acc[m][1][v], acc[m][2][v], acc[m][3][v]};
+                        } else {
+                            *dst = acc[m][i][v];
+                        }
+                    }
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[m][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+}
+
+using KernFn = void (*)(const KernelArgs);
+
+template <int V, int VEC, bool CLAMP> static KernFn panel_instance()
+{
+    constexpr PanelVariant pv = kPanelVariants[V];
+    return conv_pointwise_panel<pv.MT, pv.NW, pv.PD, VEC, CLAMP>;
+}
+
+hipError_t launch_panel(int variant, int x_vec, int grid, int lds_bytes, hipStream_t stream, const KernelArgs& a)
+{
+#define PANEL_ROW(v) {panel_instance<v, 4, false>(), panel_instance<v, 4, true>(), panel_instance<v, 1, false>(), panel_instance<v, 1, true>()},
+    static const KernFn table[kNumPanelVariants][4] = {PANEL_VARIANT_LIST(PANEL_ROW)};
+    static std::atomic<int> lds_ready[kNumPanelVariants][4][kMaxDevices] = {};
+    if (variant < 0 || variant >= kNumPanelVariants) return hipErrorInvalidValue;
+    const PanelVariant pv = kPanelVariants[variant];
+    const bool clamp = a.C % (16 * pv.PD) != 0;
+    const int mode = (x_vec == 4 ? 0 : 2) + (clamp ? 1 : 0);
+    const KernFn fn = table[variant][mode];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!lds_ready[variant][mode][dev].load(std::memory_order_acquire)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        lds_ready[variant][mode][dev].store(1, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(pv.block()), lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace convfwd

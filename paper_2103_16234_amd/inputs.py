@@ -164,3 +164,34 @@ CONFIGS = (
 def config(i: int) -> ConvShape:
     """Benchmark layer i, 1-based as the layers are numbered in the reports."""
     return CONFIGS[i - 1]
+
+
+# Second workload: a product grid of synthetic layer shapes inside the ranges of the evaluation sweep (Section 4,
+# Table 1: batch 1..256, square maps 7..224, 16..2048 filters, 1x1 / 3x3 / 5x5 filters with "same" padding). It is
+# a grid over those ranges, not any network's layer list; channel counts shrink as maps grow, as they do in CNNs.
+_SWEEP_BATCHES = (1, 8, 32, 128)
+_SWEEP_CHANNELS = {   # map size -> (C, K) pairs, per filter size
+    1: {7: ((512, 512), (832, 256), (1024, 2048)), 13: ((256, 384), (384, 384)), 14: ((256, 256), (512, 512), (256, 1024)),
+        27: ((64, 256), (96, 256)), 28: ((128, 128), (192, 256), (512, 128)), 56: ((64, 64), (256, 64), (64, 256)),
+        112: ((32, 64), (64, 128))},
+    3: {7: ((512, 512), (192, 384)), 13: ((256, 384), (384, 384)), 14: ((256, 256), (512, 512)),
+        27: ((64, 192), (96, 256)), 28: ((128, 128), (128, 256)), 56: ((64, 64), (64, 192)),
+        112: ((32, 64), (64, 128)), 224: ((3, 64), (16, 16), (64, 64))},
+    5: {7: ((48, 128), (32, 128)), 13: ((32, 96), (48, 128)), 14: ((16, 48), (32, 96)), 27: ((48, 128), (96, 256)),
+        28: ((16, 32), (32, 96), (48, 128))},
+}
+
+
+def sweep_shapes(max_elems: int = 1 << 25):
+    """The shapes of the sweep workload whose x and y both hold at most max_elems elements."""
+    out = []
+    for f in (1, 3, 5):
+        for hw in sorted(_SWEEP_CHANNELS[f]):
+            for (c, k) in _SWEEP_CHANNELS[f][hw]:
+                for n in _SWEEP_BATCHES:
+                    if n * c * hw * hw > max_elems or n * k * hw * hw > max_elems:
+                        continue
+                    i = len(out)
+                    out.append(ConvShape(f"sweep_{f}x{f}_n{n}_c{c}_{hw}_k{k}", n, c, hw, hw, k, f, f, f // 2, f // 2,
+                                         "u01", "he", 3000 + i, 4000 + i))
+    return out

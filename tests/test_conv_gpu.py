@@ -18,6 +18,7 @@ torch = pytest.importorskip("torch")
 TAP = binding.CONV_KERNEL_TAP
 GENERIC = binding.CONV_KERNEL_GENERIC
 POINTWISE = binding.CONV_KERNEL_POINTWISE
+PANEL = binding.CONV_KERNEL_PANEL
 
 _ref_cache = {}
 
@@ -141,10 +142,37 @@ def test_every_pointwise_variant_matches_oracle(shape, variant):
     assert plan.kernel == POINTWISE and plan.workspace_bytes == 0
 
 
+PANEL_SHAPES = POINTWISE_SHAPES + [
+    S("p_batch", 37, 24, 6, 6, 70, 1, 1, 0, 0),            # 1332 pixels = 20.8 tiles that span images; K = 64 + 6
+    S("p_batch_7x7", 9, 20, 7, 7, 35, 1, 1, 0, 0),         # dword pixels, 441 of them; C = 20 pads to 64
+    S("p_batch_deep", 5, 132, 8, 8, 18, 1, 1, 0, 0),       # 9 steps pad to 12: clamped channel indices
+    S("p_batch_c64", 6, 64, 8, 10, 64, 1, 1, 0, 0),        # nothing ragged: the unclamped, unmasked instance
+]
+
+
+@pytest.mark.parametrize("groups", [0, 1, 2])
+@pytest.mark.parametrize("variant", range(8))
+@pytest.mark.parametrize("shape", PANEL_SHAPES, ids=lambda s: s.name)
+def test_every_panel_variant_matches_oracle(shape, variant, groups):
+    """Filter panel resident in LDS, waves streaming pixel tiles; few work-groups make every wave loop over tiles."""
+    if variant >= binding.conv_variant_count(PANEL):
+        pytest.skip("no such variant")
+    plan, _ = _run(shape, kernel=PANEL, variant=variant, tile_pix=groups)
+    assert plan.kernel == PANEL and plan.workspace_bytes == 0
+
+
+def test_panel_needs_filters_that_fit_lds():
+    shape = S("p_too_deep", 1, 4096, 2, 2, 64, 1, 1, 0, 0)   # 64 x 4096 floats = 1 MB of filters per channel tile
+    x, w = inputs.make_inputs(shape)
+    with pytest.raises(binding.ConvError) as e:
+        binding.conv_fwd_planned(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), 0, 0, kernel=PANEL, variant=0)
+    assert e.value.code == -6
+
+
 @pytest.mark.parametrize("shape", POINTWISE_SHAPES, ids=lambda s: s.name)
 def test_pointwise_shapes_default_plan_and_other_families(shape):
     plan, _ = _run(shape)
-    assert plan.kernel == POINTWISE
+    assert plan.kernel in (POINTWISE, PANEL)
     _run(shape, kernel=GENERIC)
     _run(shape, kernel=TAP, variant=2)
 
