@@ -218,6 +218,9 @@ bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w
     base_args(s, a);
     const int tiles = ceil_div(a->total_pix, 64);
     if (a->total_pix < 4 || a->total_pix > (1 << 30)) return false;  // tile * 64 + lane offsets stay far inside 32 bits
+    // the kernel addresses inputs as a 64-bit tile base plus 32-bit byte offsets that cover every image a
+    // 64-pixel tile touches and all (padded) channels
+    if ((int64_t)(64 / a->HW + 3) * (s.C + 64) * a->HW * 4 >= ((int64_t)1 << 32)) return false;
     a->ktiles = ceil_div(s.K, pv.tile_k());
     int groups = groups_req;
     const int most = ceil_div(tiles, pv.NW);  // one tile per wave

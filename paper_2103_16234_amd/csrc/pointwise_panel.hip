@@ -55,42 +55,62 @@ __global__ void __launch_bounds__(64 * NW) conv_pointwise_panel(const KernelArgs
     const int t0 = g * NW + wave;
     const int pitch = a.lds_pitch;
 
-    // Base pointers of this lane's pixels of tile t (channel 0 of their image, plus the lane's channel
-    // quarter when channel indices need no clamping).
-    auto lane_ptrs = [&](int t, const float* (&xp)[NP]) {
+    // Addresses of the input loads are a uniform 64-bit base per tile (channel 0 of the image that holds
+    // the tile's first pixel) plus 32-bit byte offsets per lane: the lane's pixels relative to that image
+    // (a tile of small maps spans several images) and a running channel offset that is the same for all lanes.
+    struct TileAddr {
+        const char* base;
+        unsigned voff[NP];
+    };
+    const unsigned hw4 = 4u * (unsigned)a.HW;
+    auto tile_addr = [&](int t, TileAddr& ta) {
         const int tt = min(t, T - 1);
+        const int n0 = a.div_PQ.div(tt * 64);
+        ta.base = reinterpret_cast<const char*>(a.x) + (size_t)n0 * a.C * a.HW * 4;
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
             const int px = VEC == 4 ? min(tt * 64 + 4 * j, a.total_pix - 4) : min(tt * 64 + 16 * i + j, a.total_pix - 1);
             const int n = a.div_PQ.div(px);
             const int p = px - n * a.HW;
-            xp[i] = a.x + ((size_t)n * a.C + (CLAMP ? 0 : 4 * kq)) * a.HW + p;
+            ta.voff[i] = 4u * (unsigned)((n - n0) * a.C * a.HW + p + (CLAMP ? 0 : 4 * kq * a.HW));
         }
     };
 
     f32x4 xr[PD][4];
-    auto load_step = [&](auto slotc, const float* (&xp)[NP], int s) {
+    // one of the four input loads of a step: channel 16s + 4kq + e for the lane's four pixels;
+    // soff = 4 * (16s + e) * HW bytes
+    auto load_one = [&](auto slotc, auto ec, const TileAddr& ta, int s, unsigned soff) {
         constexpr int slot = decltype(slotc)::value;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const size_t off = CLAMP ? (size_t)min(16 * s + 4 * kq + e, a.C - 1) * a.HW : (size_t)(16 * s + e) * a.HW;
-            if constexpr (VEC == 4) {
-                xr[slot][e] = *reinterpret_cast<const f32x4*>(xp[0] + off);
-            } else {
-                xr[slot][e] = f32x4{xp[0][off], xp[1][off], xp[2][off], xp[3][off]};
-            }
+        constexpr int e = decltype(ec)::value;
+        const unsigned coff = CLAMP ? (unsigned)min(16 * s + 4 * kq + e, a.C - 1) * hw4 : soff;
+        if constexpr (VEC == 4) {
+            xr[slot][e] = *reinterpret_cast<const f32x4*>(ta.base + (ta.voff[0] + coff));
+        } else {
+            xr[slot][e] = f32x4{*reinterpret_cast<const float*>(ta.base + (ta.voff[0] + coff)),
+                                *reinterpret_cast<const float*>(ta.base + (ta.voff[1] + coff)),
+                                *reinterpret_cast<const float*>(ta.base + (ta.voff[2] + coff)),
+                                *reinterpret_cast<const float*>(ta.base + (ta.voff[3] + coff))};
         }
+    };
+    auto for_each_e = [&](auto&& f) {
+        [&]<int... Es>(std::integer_sequence<int, Es...>) { (f(std::integral_constant<int, Es>{}), ...); }
+        (std::make_integer_sequence<int, 4>{});
     };
     auto for_each_slot = [&](auto&& f) {
         [&]<int... Ss>(std::integer_sequence<int, Ss...>) { (f(std::integral_constant<int, Ss>{}), ...); }
         (std::make_integer_sequence<int, PD>{});
     };
 
-    const float* cur[NP];
-    const float* nxt[NP];
-    lane_ptrs(t0, cur);
-    // the first input steps are requested before the panel is fetched, so both latencies overlap
-    for_each_slot([&](auto sc) { load_step(sc, cur, decltype(sc)::value); });
+    TileAddr cur, nxt;
+    tile_addr(t0, cur);
+    // The first input steps are requested before the panel is fetched, so both latencies overlap. They are
+    // issued in the order the loop issues and consumes them (the counter of outstanding loads is in order).
+    for_each_slot([&](auto sc) {
+        for_each_e([&](auto ec) {
+            load_one(sc, ec, cur, decltype(sc)::value, (16u * decltype(sc)::value + decltype(ec)::value) * hw4);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    });
 
     {
         const int rowv = nsteps * 4;  // dwordx4 per panel row
@@ -115,6 +135,9 @@ __global__ void __launch_bounds__(64 * NW) conv_pointwise_panel(const KernelArgs
             }
         }
     }
+    // Every load so far is complete on every path before the main loop starts: the loop's own waits then
+    // only have to track the loop's loads (vmcnt = 0, other counters untouched).
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
 
     f32x4 acc[MT][4];
@@ -130,55 +153,63 @@ __global__ void __launch_bounds__(64 * NW) conv_pointwise_panel(const KernelArgs
 #pragma unroll
     for (int m = 0; m < MT; ++m) wv[0][m] = *reinterpret_cast<const f32x4*>(arow + 16 * m * pitch);
 
-    for (int ct = t0; ct < T; ct += stride) {
-        lane_ptrs(ct + stride, nxt);
-        for (int it = 0; it < nsteps; it += PD) {
-            const bool last = it + PD >= nsteps;  // the loads issued in this round belong to the next tile
-            const int ls = last ? 0 : it + PD;
-            if (last) {
+    // One round = PD steps: matrix instructions on the registers loaded PD steps ago, each register
+    // reloaded (for step ls + slot of the load cursor's tile) right after its last use.
+    auto round = [&](int it) {
+        const bool last = it + PD >= nsteps;  // the loads issued in this round belong to the next tile
+        const int ls = last ? 0 : it + PD;
+        if (last) cur = nxt;
+        for_each_slot([&](auto sc) {
+            constexpr int slot = decltype(sc)::value;
+            constexpr int wb = slot & 1;
+            int sn = it + slot + 1;
+            if (sn == nsteps) sn = 0;
 #pragma unroll
-                for (int i = 0; i < NP; ++i) cur[i] = nxt[i];
-            }
-            for_each_slot([&](auto sc) {
-                constexpr int slot = decltype(sc)::value;
-                constexpr int wb = slot & 1;
-                int sn = it + slot + 1;
-                if (sn == nsteps) sn = 0;
+            for (int m = 0; m < MT; ++m)
+                wv[wb ^ 1][m] = *reinterpret_cast<const f32x4*>(arow + 16 * m * pitch + 16 * sn);
+            const unsigned soff = 16u * (unsigned)(ls + slot) * hw4;
+            // nothing moves across the barriers: every load keeps PD - 1 steps of distance to its use
+            for_each_e([&](auto ec) {
+                constexpr int e = decltype(ec)::value;
 #pragma unroll
                 for (int m = 0; m < MT; ++m)
-                    wv[wb ^ 1][m] = *reinterpret_cast<const f32x4*>(arow + 16 * m * pitch + 16 * sn);
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int m = 0; m < MT; ++m)
-#pragma unroll
-                        for (int t = 0; t < 4; ++t)
-                            acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[wb][m][e], xr[slot][e][t], acc[m][t], 0, 0, 0);
-                load_step(sc, cur, ls + slot);
+                    for (int t = 0; t < 4; ++t)
+                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[wb][m][e], xr[slot][e][t], acc[m][t], 0, 0, 0);
+                load_one(sc, ec, cur, ls + slot, soff + e * hw4);
+                __builtin_amdgcn_sched_barrier(0);
             });
-        }
+        });
+    };
 
-        // lane (j, kq) holds output channels 16m + 4kq + v for its four pixels of tile ct
+    for (int ct = t0; ct < T; ct += stride) {
+        tile_addr(ct + stride, nxt);
+        // The first round of a tile is a copy of its own: it runs right after the previous tile's stores,
+        // which share the in-order counter of outstanding memory operations with the loads, and its waits
+        // can allow for them instead of draining the load stream.
+        round(0);
+        for (int it = PD; it < nsteps; it += PD) round(it);
+
+        // Lane (j, kq) holds output channels 16m + 4kq + v for its four pixels of tile ct. Stores are
+        // unconditional: lanes past the last pixel and rows past the last channel were computed from
+        // clamped (duplicated) inputs and filters, so they rewrite the owner's value bit for bit.
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
-            const int px = VEC == 4 ? ct * 64 + 4 * j : ct * 64 + 16 * i + j;
-            if (px < a.total_pix) {
-                const int n = a.div_PQ.div(px);
-                const int p = px - n * a.HW;
-                float* const yl = a.y + ((size_t)n * a.K + k0 + 4 * kq) * a.HW + p;
+            const int px = VEC == 4 ? min(ct * 64 + 4 * j, a.total_pix - 4) : min(ct * 64 + 16 * i + j, a.total_pix - 1);
+            const int n = a.div_PQ.div(px);
+            const int p = px - n * a.HW;
+            float* const yl = a.y + (size_t)n * a.K * a.HW + p;
 #pragma unroll
-                for (int m = 0; m < MT; ++m)
+            for (int m = 0; m < MT; ++m)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        if (k0 + 16 * m + 4 * kq + v >= a.K) continue;
-                        float* const dst = yl + (size_t)(16 * m + v) * a.HW;
-                        if constexpr (VEC == 4) {
-                            *reinterpret_cast<f32x4*>(dst) = f32x4{acc[m][0][v], acc[m][1][v], acc[m][2][v], acc[m][3][v]};
-                        } else {
-                            *dst = acc[m][i][v];
-                        }
+                for (int v = 0; v < 4; ++v) {
+                    float* const dst = yl + (size_t)min(k0 + 16 * m + 4 * kq + v, a.K - 1) * a.HW;
+                    if constexpr (VEC == 4) {
+                        *reinterpret_cast<f32x4*>(dst) = f32x4{acc[m][0][v], acc[m][1][v], acc[m][2][v], acc[m][3][v]};
+                    } else {
+                        *dst = acc[m][i][v];
                     }
-            }
+                }
         }
 #pragma unroll
         for (int m = 0; m < MT; ++m)
