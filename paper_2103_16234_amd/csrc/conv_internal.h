@@ -141,9 +141,10 @@ struct PanelVariant {
 };
 constexpr PanelVariant kPanelVariants[] = {
     {4, 8, 4}, {2, 8, 4}, {1, 8, 4}, {4, 4, 4}, {2, 4, 4}, {1, 4, 4},
+    {4, 4, 2}, {2, 4, 2}, {2, 8, 2},  // two steps in flight: layers with 32 (mod 64) or fewer channels
 };
 constexpr int kNumPanelVariants = sizeof(kPanelVariants) / sizeof(kPanelVariants[0]);
-#define PANEL_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5)
+#define PANEL_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8)
 hipError_t launch_panel(int variant, int x_vec, int grid, int lds_bytes, hipStream_t stream, const KernelArgs& a);
 
 // rs_index: 0 -> 1x1, 1 -> 3x3, 2 -> 5x5. Returns hipSuccess or the launch error.

@@ -272,6 +272,23 @@ int pick_pointwise(const Shape& s)
     return 6;                                          // {1, 16}
 }
 
+// Panel kernel or not, from sweeps over batched 1x1 layers: it wins once there are about 700 units of
+// (64-pixel tile) x (32 output channels) - roughly one per SIMD with some to spare - and loses below, where
+// splitting the channels over the waves of a work-group fills the chip better. 32 channels per panel and two
+// steps in flight is the best or within 3 % of it almost everywhere; maps whose pixels move as single dwords
+// do better with 64 channels per panel (half as many input load instructions per output).
+int pick_panel(const Shape& s, int x_cap, int y_cap)
+{
+    const int64_t tiles = ((int64_t)s.N * s.H * s.W + 63) / 64;
+    if (tiles * ceil_div(s.K, 32) < 704) return -1;
+    const bool dwords = pointwise_x_vec(s, x_cap, y_cap) == 1;
+    const int c64 = round_up(s.C, 32);
+    if (dwords && s.K >= 64 && tiles * ceil_div(s.K, 64) >= 704 && 64 * (c64 + 4) * 4 <= kLdsMax) return 6;  // {4, 4, 2}
+    if (32 * (c64 + 4) * 4 <= kLdsMax) return 7;                                                                // {2, 4, 2}
+    if (16 * (round_up(s.C, 64) + 4) * 4 <= kLdsMax) return 5;                                                  // {1, 4, 4}
+    return -1;
+}
+
 void resolve_generic(const Shape& s, conv_plan_t* p, KernelArgs* a)
 {
     base_args(s, a);
@@ -363,8 +380,11 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_pl
     if (tuned && tuned->kernel == CONV_KERNEL_POINTWISE &&
         resolve_pointwise(s, tuned->variant, x_cap, w_cap, y_cap, p, a))
         return CONV_OK;
-    if (pointwise_ok(s, x_cap, w_cap, y_cap) && resolve_pointwise(s, pick_pointwise(s), x_cap, w_cap, y_cap, p, a))
-        return CONV_OK;
+    if (pointwise_ok(s, x_cap, w_cap, y_cap)) {
+        const int pv = pick_panel(s, x_cap, y_cap);
+        if (pv >= 0 && resolve_panel(s, pv, 0, x_cap, w_cap, y_cap, p, a)) return CONV_OK;
+        if (resolve_pointwise(s, pick_pointwise(s), x_cap, w_cap, y_cap, p, a)) return CONV_OK;
+    }
     if (tap_rs_index(s) >= 0) {
         if (tuned && tuned->kernel == CONV_KERNEL_TAP &&
             resolve_tap(s, tuned->variant, tuned->tile_pix, 0, x_cap, w_cap, p, a))

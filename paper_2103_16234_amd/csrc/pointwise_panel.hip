@@ -52,7 +52,10 @@ __global__ void __launch_bounds__(64 * NW) conv_pointwise_panel(const KernelArgs
     const int nsteps = a.nchunks;   // 16-channel steps, a multiple of PD
     const int T = a.x_items;        // 64-pixel tiles of the flattened (n, pixel) axis
     const int stride = a.ptiles * NW;
-    const int t0 = g * NW + wave;
+    // Wave numbering along the tile axis: waves w and w + 4 of a work-group share a SIMD, and low numbers
+    // get the extra tile when the tiles do not divide evenly, so the second half of an 8-wave work-group
+    // counts down from the top: every SIMD then carries one "long" and one "short" wave.
+    const int t0 = NW == 8 ? (wave < 4 ? g * 4 + wave : stride - 1 - (g * 4 + wave - 4)) : g * NW + wave;
     const int pitch = a.lds_pitch;
 
     // Addresses of the input loads are a uniform 64-bit base per tile (channel 0 of the image that holds

@@ -151,7 +151,7 @@ PANEL_SHAPES = POINTWISE_SHAPES + [
 
 
 @pytest.mark.parametrize("groups", [0, 1, 2])
-@pytest.mark.parametrize("variant", range(8))
+@pytest.mark.parametrize("variant", range(12))
 @pytest.mark.parametrize("shape", PANEL_SHAPES, ids=lambda s: s.name)
 def test_every_panel_variant_matches_oracle(shape, variant, groups):
     """Filter panel resident in LDS, waves streaming pixel tiles; few work-groups make every wave loop over tiles."""
