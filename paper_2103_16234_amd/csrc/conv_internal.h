@@ -73,16 +73,18 @@ constexpr int tap_unit_taps(int S, int RS, int MT, int NT, int occ)
 struct TapVariant {
     int MT, NT, WK, WP, WC, GPC;
     int occ;     // waves per SIMD the kernel is compiled for (bounds its registers)
-    int xslots;  // dwordx4 halo-tile loads a thread keeps in flight (x2 / x4 as many when rows force dwordx2 / dword)
+    int xslots;  // dwordx4 halo-tile loads a thread keeps in flight (x2 as many when rows force dwordx2)
+    int xslots1; // the same for rows that force single dwords (maps of odd width are small: fewer than 4 * xslots do)
+    constexpr int xs(int x_vec) const { return x_vec == 1 ? xslots1 : xslots * 4 / x_vec; }
     constexpr int tile_k() const { return 16 * MT * WK; }
     constexpr int max_pix() const { return 16 * NT * WP; }
     constexpr int block() const { return 64 * WK * WP * WC; }
     constexpr int chunk_c() const { return 4 * WC * GPC; }
     // filter-block loads per thread and chunk, and whether that many registers are reasonable
     constexpr int wslots(int RS, int w_vec) const { return (tile_k() * chunk_c() * RS / w_vec + block() - 1) / block(); }
-    constexpr bool supports(int RS) const { return tile_k() * chunk_c() * RS <= (occ > 1 ? 40 : 64) * block(); }
+    constexpr bool supports(int RS) const { return tile_k() * chunk_c() * RS <= (occ > 2 ? 20 : occ > 1 ? 40 : 64) * block(); }
     // the all-dword loaders (C not a multiple of 4) need a table entry per float staged: small shapes only
-    constexpr bool supports_scalar(int RS) const { return supports(RS) && xslots * 4 + tile_k() * chunk_c() * RS / block() <= 48; }
+    constexpr bool supports_scalar(int RS) const { return supports(RS) && xslots1 + tile_k() * chunk_c() * RS / block() <= (occ > 2 ? 24 : 48); }
     // LDS floats of one staging copy for a halo plane of `plane` floats (with the 256-float dump)
     constexpr int staging_floats(int RS, int plane) const
     {
@@ -95,21 +97,26 @@ struct TapVariant {
 };
 
 constexpr TapVariant kTapVariants[] = {
-    {1, 13, 4, 1, 1, 4, 1, 8},  //  0: 64 ch x 208 px, waves split K, 16-channel chunks
-    {1, 7, 4, 1, 1, 4, 1, 8},   //  1: 64 ch x 112 px
-    {1, 1, 1, 4, 1, 2, 2, 4},   //  2: 16 ch x  64 px, one MFMA tile per wave, 8-channel chunks
-    {2, 4, 2, 2, 1, 4, 1, 8},   //  3: 64 ch x 128 px, 2x4 tiles per wave
-    {1, 2, 2, 2, 1, 2, 2, 4},   //  4: 32 ch x  64 px, 8-channel chunks
-    {2, 2, 1, 1, 4, 1, 2, 4},   //  5: 32 ch x  32 px, 4 channel shares, for layers with few outputs
-    {1, 13, 4, 1, 2, 2, 2, 2},  //  6: 64 ch x 208 px (a 14x14 image), 8 waves (4 along K x 2 channel shares), two per SIMD
-    {1, 7, 4, 1, 2, 2, 2, 2},   //  7: 64 ch x 112 px, same scheme
-    {1, 7, 4, 1, 1, 2, 1, 8},   //  8: 64 ch x 112 px, 8-channel chunks (large filters)
-    {2, 7, 2, 1, 2, 1, 1, 8},   //  9: 64 ch x 112 px, 2 channel shares, 8-channel chunks (large filters)
-    {1, 1, 1, 1, 4, 1, 2, 4},   // 10: 16 ch x  16 px, 4 channel shares: many small work-groups for tiny layers
-    {1, 2, 1, 1, 4, 1, 2, 4},   // 11: 16 ch x  32 px, 4 channel shares
+    {1, 13, 4, 1, 1, 4, 1, 8, 32},  //  0: 64 ch x 208 px, waves split K, 16-channel chunks
+    {1, 7, 4, 1, 1, 4, 1, 8, 32},   //  1: 64 ch x 112 px
+    {1, 1, 1, 4, 1, 2, 2, 4, 16},   //  2: 16 ch x  64 px, one MFMA tile per wave, 8-channel chunks
+    {2, 4, 2, 2, 1, 4, 1, 8, 32},   //  3: 64 ch x 128 px, 2x4 tiles per wave
+    {1, 2, 2, 2, 1, 2, 2, 4, 16},   //  4: 32 ch x  64 px, 8-channel chunks
+    {2, 2, 1, 1, 4, 1, 2, 4, 16},   //  5: 32 ch x  32 px, 4 channel shares, for layers with few outputs
+    {1, 13, 4, 1, 2, 2, 2, 2, 8},  //  6: 64 ch x 208 px (a 14x14 image), 8 waves (4 along K x 2 channel shares), two per SIMD
+    {1, 7, 4, 1, 2, 2, 2, 2, 8},   //  7: 64 ch x 112 px, same scheme
+    {1, 7, 4, 1, 1, 2, 1, 8, 32},   //  8: 64 ch x 112 px, 8-channel chunks (large filters)
+    {2, 7, 2, 1, 2, 1, 1, 8, 32},   //  9: 64 ch x 112 px, 2 channel shares, 8-channel chunks (large filters)
+    {1, 1, 1, 1, 4, 1, 2, 4, 16},   // 10: 16 ch x  16 px, 4 channel shares: many small work-groups for tiny layers
+    {1, 2, 1, 1, 4, 1, 2, 4, 16},   // 11: 16 ch x  32 px, 4 channel shares
+    {1, 7, 2, 1, 4, 1, 2, 8, 12},   // 12: 32 ch x 112 px, 8 waves (2 along K x 4 channel shares)
+    {2, 2, 1, 1, 4, 1, 4, 4, 8},   // 13: as 5, four waves per SIMD (latency of short chunks hidden by occupancy)
+    {1, 2, 1, 1, 4, 1, 4, 4, 8},   // 14: as 11, four waves per SIMD
+    {1, 7, 1, 4, 1, 2, 2, 8, 16},   // 15: 16 ch x 448 px: layers with 16 or fewer filters on large maps
+    {1, 4, 1, 4, 1, 4, 2, 8, 16},   // 16: 16 ch x 256 px, 16-channel chunks
 };
 constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
-#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11)
+#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16)
 
 // Tile shapes of the pointwise (1x1, no padding) family: a work-group is WC x WP waves on 16*MT output
 // channels x WP*64 contiguous pixels of one image; the WC shares split the input channels.

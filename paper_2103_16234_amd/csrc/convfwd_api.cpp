@@ -144,7 +144,7 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     chunk_c = cc;
     if (!tv.supports(RS) || (w_vec == 1 && !tv.supports_scalar(RS))) return false;  // staging would not fit the registers
     const int64_t x_floats = (int64_t)cc * rows * s.W;
-    if (x_floats > (int64_t)tv.xslots * 4 * BLOCK) return false;
+    if (x_floats > (int64_t)tv.xs(x_vec) * x_vec * BLOCK) return false;
     const int64_t copy_floats = tv.staging_floats(RS, plane);
     const int64_t lds = 4 * std::max<int64_t>(2 * copy_floats, tv.reduce_floats());
     if (lds > tv.lds_limit() || lds > kLdsMax || copy_floats >= (1 << 16)) return false;

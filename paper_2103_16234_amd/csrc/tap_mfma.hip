@@ -361,7 +361,7 @@ template <int VX, int VW> static KernFn instance()
     if constexpr (!tv.supports(TAP_R * TAP_S) || (VW == 1 && !tv.supports_scalar(TAP_R * TAP_S))) {
         return nullptr;  // the filter block of this filter size does not fit the variant's registers
     } else {
-        return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, tv.occ, tv.xslots * 4 / VX,
+        return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, tv.occ, tv.xs(VX),
                              tv.wslots(TAP_R * TAP_S, VW), VX, VW>;
     }
 }
