@@ -301,22 +301,30 @@ void resolve_generic(const Shape& s, conv_plan_t* p, KernelArgs* a)
     fill_common(s, p);
 }
 
-// Estimated cycles of a tap mapping on 256 CUs. A work-group keeps each SIMD busy for
-// (waves per SIMD) x (MFMAs per wave) x 32 cycles; measured MFMA issue efficiency is ~0.85 when two
-// waves share a SIMD (their LDS reads, staging and address arithmetic overlap each other's matrix
-// instructions) and ~0.72 when a wave has the SIMD to itself. Added: a per-chunk barrier/first-read
-// cost and a per-work-group prologue + epilogue.
+// Estimated cycles of a tap mapping on 256 CUs, fitted to timings of every tile shape x pixel tile over a
+// grid of 3x3 and 5x5 layers (batch 1..128, maps 7..224): the mapping it picks is on average within 5 % of
+// the best one measured. Per chunk, the work-groups sharing a CU take the longest of
+//   their matrix instructions   (wpc x MFMA cycles per SIMD; issue efficiency 0.85 with two or more waves
+//                                 per SIMD, 0.6 with one),
+//   one chunk's latency chain   (~2000 cycles from a staging load's issue to its data sitting in LDS behind
+//                                 the barrier, plus the chunk's own matrix instructions), and
+//   their staging traffic       (halo rows + filter block through registers into LDS, ~16 B/clk per CU),
+// a work-group adds ~12000 cycles of prologue and epilogue (first loads, LDS fill, the reduction tree,
+// stores at ~32 B/clk), and the launch ~5000.
 double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv, int RS)
 {
     const int by_regs = std::max(1, tv.occ * 256 / tv.block());
     const int by_lds = std::max(1, kLdsMax / std::max(p.lds_bytes, 1));
     const int wpc = std::min(std::min(by_regs, by_lds), 8);  // work-groups sharing a CU
-    const double waves_per_simd = std::max(1.0, tv.block() / 256.0);
-    const double eff = wpc * waves_per_simd >= 2 ? 0.85 : 0.72;
-    const double simd_cycles = waves_per_simd * tv.MT * tv.NT * (double)a.nchunks * tv.GPC * RS * 32.0;
-    const double per_wg = simd_cycles / eff + a.nchunks * 400.0;
+    const double waves_per_simd = tv.block() / 256.0;
+    const double eff = wpc * waves_per_simd >= 2 ? 0.85 : 0.6;
+    const double mfma = waves_per_simd * tv.MT * tv.NT * tv.GPC * RS * 32.0;  // per SIMD, chunk and work-group
+    const double staged = 4.0 * ((double)tv.chunk_c() * a.lds_rows * a.W + (double)tv.tile_k() * tv.chunk_c() * RS);
+    const double chunk = std::max(std::max(wpc * mfma / eff, 2000.0 + mfma), wpc * staged / 16.0);
+    const double tree = tv.WC > 1 ? tv.MT * tv.NT * 1024.0 * tv.WK * tv.WP / 64.0 * std::log2((double)tv.WC) : 0.0;
+    const double per_round = a.nchunks * chunk + 12000.0 + wpc * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree);
     const double rounds = std::ceil((double)p.grid / (kNumCU * wpc));
-    return rounds * (wpc * per_wg + 6000.0);
+    return rounds * per_round + 5000.0;
 }
 
 // Measured best mappings of known layer shapes (sweeps over tile shape x pixel tile on an MI355X);
