@@ -83,8 +83,13 @@ struct TapVariant {
     // filter-block loads per thread and chunk, and whether that many registers are reasonable
     constexpr int wslots(int RS, int w_vec) const { return (tile_k() * chunk_c() * RS / w_vec + block() - 1) / block(); }
     constexpr bool supports(int RS) const { return tile_k() * chunk_c() * RS <= (occ > 2 ? 20 : occ > 1 ? 40 : 64) * block(); }
-    // the all-dword loaders (C not a multiple of 4) need a table entry per float staged: small shapes only
-    constexpr bool supports_scalar(int RS) const { return supports(RS) && xslots1 + tile_k() * chunk_c() * RS / block() <= (occ > 2 ? 24 : 48); }
+    // Filters whose rows dwordx4 cannot walk (C not a multiple of 4) are staged dword by dword, with inputs
+    // as dwordx4 (maps whose width is a multiple of 4: first layers) or dwords: a table entry per dword
+    // staged, so small filter blocks only.
+    constexpr bool supports_scalar(int RS, int x_vec = 1) const
+    {
+        return supports(RS) && xs(x_vec) + tile_k() * chunk_c() * RS / block() <= (occ > 2 ? 24 : 48);
+    }
     // LDS floats of one staging copy for a halo plane of `plane` floats (with the 256-float dump)
     constexpr int staging_floats(int RS, int plane) const
     {
@@ -110,10 +115,10 @@ constexpr TapVariant kTapVariants[] = {
     {1, 1, 1, 1, 4, 1, 2, 4, 16},   // 10: 16 ch x  16 px, 4 channel shares: many small work-groups for tiny layers
     {1, 2, 1, 1, 4, 1, 2, 4, 16},   // 11: 16 ch x  32 px, 4 channel shares
     {1, 7, 2, 1, 4, 1, 2, 8, 12},   // 12: 32 ch x 112 px, 8 waves (2 along K x 4 channel shares)
-    {2, 2, 1, 1, 4, 1, 4, 4, 8},   // 13: as 5, four waves per SIMD (latency of short chunks hidden by occupancy)
-    {1, 2, 1, 1, 4, 1, 4, 4, 8},   // 14: as 11, four waves per SIMD
-    {1, 7, 1, 4, 1, 2, 2, 8, 16},   // 15: 16 ch x 448 px: layers with 16 or fewer filters on large maps
-    {1, 4, 1, 4, 1, 4, 2, 8, 16},   // 16: 16 ch x 256 px, 16-channel chunks
+    {1, 2, 1, 1, 4, 1, 4, 4, 8},   // 13: as 11 with four waves per SIMD: the latency of short chunks is hidden by occupancy
+    {1, 7, 1, 4, 1, 2, 2, 8, 16},   // 14: 16 ch x 448 px: layers with 16 or fewer filters on large maps
+    {1, 4, 1, 4, 1, 4, 2, 8, 16},   // 15: 16 ch x 256 px, 16-channel chunks
+    {1, 7, 1, 4, 1, 1, 2, 8, 16},   // 16: 16 ch x 448 px, 4-channel chunks: first layers (3 input channels)
 };
 constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
 #define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16)

@@ -129,7 +129,7 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     int w_vec = (s.C % 4 == 0 && w_cap >= 4) ? 4 : 1;
     int x_vec = s.W % 4 == 0 ? 4 : s.W % 2 == 0 ? 2 : 1;
     x_vec = std::min(x_vec, x_cap);
-    if (w_vec == 1) x_vec = 1;  // only the (x_vec, 4) and (1, 1) loaders are built
+    if (w_vec == 1 && x_vec != 4) x_vec = 1;  // the loaders built: (4, 4), (2, 4), (1, 4), (4, 1), (1, 1)
 
     const int col_shift = (x_vec - s.pad_w % x_vec) % x_vec;
     const int pitch = round_up(s.W + 2 * s.pad_w + col_shift, x_vec);
@@ -142,7 +142,7 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     const int cc = tv.chunk_c();
     if (chunk_c != 0 && chunk_c != cc) return false;
     chunk_c = cc;
-    if (!tv.supports(RS) || (w_vec == 1 && !tv.supports_scalar(RS))) return false;  // staging would not fit the registers
+    if (!tv.supports(RS) || (w_vec == 1 && !tv.supports_scalar(RS, x_vec))) return false;  // staging would not fit the registers
     const int64_t x_floats = (int64_t)cc * rows * s.W;
     if (x_floats > (int64_t)tv.xs(x_vec) * x_vec * BLOCK) return false;
     const int64_t copy_floats = tv.staging_floats(RS, plane);

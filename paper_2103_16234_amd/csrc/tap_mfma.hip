@@ -178,10 +178,24 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     Vec<VW> wv[WS];
 
     // One slot of the staging pipeline: slot k < XS is a halo-tile slot, the others filter slots.
+    // When C is not a multiple of the chunk, the last chunk's slots past channel C - 1 read the last valid
+    // channel (x) or the last VW floats of the filter row (w) instead of running past the tensors; what
+    // they fetch is replaced by zeros at the store.
+    const bool ragged = a.C % CC != 0;
     auto slot_load = [&](auto kc, int c0) {
         constexpr int k = decltype(kc)::value;
-        if constexpr (k < XS) xv[k].load(a.x + c0 * a.HW + xg[k]);
-        else wv[k - XS].load(a.w + k0 * a.CRS + c0 * RS + wg[k - XS]);
+        if constexpr (k < XS) {
+            int cb = c0;
+            if (ragged) cb = min(c0, a.C - 1 - static_cast<int>(xl[k] >> 16));
+            xv[k].load(a.x + cb * a.HW + xg[k]);
+        } else {
+            unsigned off = c0 * RS + wg[k - XS];
+            if (ragged) {
+                const unsigned ev = wl[k - XS] >> 16;
+                off = wg[k - XS] - ev + min(c0 * RS + ev, static_cast<unsigned>(a.CRS - VW));
+            }
+            wv[k - XS].load(a.w + k0 * a.CRS + off);
+        }
     };
     // c0: first channel of the chunk the slot's data belongs to; channels past C are stored as zeros.
     auto slot_store = [&](auto kc, int c0, int dst_floats) {
@@ -358,7 +372,7 @@ using KernFn = void (*)(const KernelArgs);
 template <int VX, int VW> static KernFn instance()
 {
     constexpr TapVariant tv = kTapVariants[TAP_VARIANT];
-    if constexpr (!tv.supports(TAP_R * TAP_S) || (VW == 1 && !tv.supports_scalar(TAP_R * TAP_S))) {
+    if constexpr (!tv.supports(TAP_R * TAP_S) || (VW == 1 && !tv.supports_scalar(TAP_R * TAP_S, VX))) {
         return nullptr;  // the filter block of this filter size does not fit the variant's registers
     } else {
         return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, tv.occ, tv.xs(VX),
@@ -380,10 +394,13 @@ hipError_t TAP_CAT(TAP_R, TAP_S, TAP_VARIANT)(int x_vec, int w_vec, int grid, in
     } else if (w_vec == 1 && x_vec == 1) {
         fn = instance<1, 1>();
         mode = 3;
+    } else if (w_vec == 1 && x_vec == 4) {
+        fn = instance<4, 1>();
+        mode = 4;
     }
     if (!fn) return hipErrorInvalidValue;
     // Kernels may use all 160 KB of a CU's LDS; the runtime wants to be told once per kernel (and device).
-    static std::atomic<int> lds_allowed[4][kMaxDevices] = {};
+    static std::atomic<int> lds_allowed[5][kMaxDevices] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
     if (lds_bytes > 48 * 1024 && lds_allowed[mode][dev].load(std::memory_order_acquire) < lds_bytes) {

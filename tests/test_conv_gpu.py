@@ -81,6 +81,8 @@ SMALL = [
     S("s3x3_1pix", 4, 8, 1, 1, 9, 3, 3, 1, 1),              # 1x1 maps: every tap but the centre is padding
     S("s3x3_wide", 1, 4, 4, 70, 8, 3, 3, 1, 1),             # rows longer than a pixel tile
     S("s3x3_single", 1, 1, 5, 5, 1, 3, 3, 1, 1),
+    S("s3x3_c3_w8", 2, 3, 6, 8, 20, 3, 3, 1, 1),            # first-layer like: dwordx4 input rows, dword filter rows
+    S("s5x5_c6_w12", 1, 6, 9, 12, 18, 5, 5, 2, 2),
 ]
 
 
