@@ -178,23 +178,27 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     Vec<VW> wv[WS];
 
     // One slot of the staging pipeline: slot k < XS is a halo-tile slot, the others filter slots.
-    // When C is not a multiple of the chunk, the last chunk's slots past channel C - 1 read the last valid
-    // channel (x) or the last VW floats of the filter row (w) instead of running past the tensors; what
-    // they fetch is replaced by zeros at the store.
-    const bool ragged = a.C % CC != 0;
     auto slot_load = [&](auto kc, int c0) {
         constexpr int k = decltype(kc)::value;
-        if constexpr (k < XS) {
-            int cb = c0;
-            if (ragged) cb = min(c0, a.C - 1 - static_cast<int>(xl[k] >> 16));
-            xv[k].load(a.x + cb * a.HW + xg[k]);
-        } else {
-            unsigned off = c0 * RS + wg[k - XS];
-            if (ragged) {
-                const unsigned ev = wl[k - XS] >> 16;
-                off = wg[k - XS] - ev + min(c0 * RS + ev, static_cast<unsigned>(a.CRS - VW));
-            }
-            wv[k - XS].load(a.w + k0 * a.CRS + off);
+        if constexpr (k < XS) xv[k].load(a.x + c0 * a.HW + xg[k]);
+        else wv[k - XS].load(a.w + k0 * a.CRS + c0 * RS + wg[k - XS]);
+    };
+    // When C is not a multiple of the chunk, the last chunk's slots past channel C - 1 would read past the
+    // tensors. Before the first load of the last chunk (no other chunk is loaded after it) their table
+    // entries are moved back to the last valid channel (x) or the last VW floats of the filter row (w);
+    // what they fetch is replaced by zeros at the store anyway.
+    const int last_c0 = (a.nchunks - 1) * CC;
+    const bool ragged = a.C % CC != 0;
+    auto retarget_last_chunk = [&]() {
+#pragma unroll
+        for (int i = 0; i < XS; ++i) {
+            const int over = last_c0 + static_cast<int>(xl[i] >> 16) - (a.C - 1);
+            if (over > 0) xg[i] -= over * a.HW;
+        }
+#pragma unroll
+        for (int i = 0; i < WS; ++i) {
+            const int over = last_c0 * RS + static_cast<int>(wl[i] >> 16) - (a.CRS - VW);
+            if (over > 0) wg[i] -= over;
         }
     };
     // c0: first channel of the chunk the slot's data belongs to; channels past C are stored as zeros.
@@ -224,7 +228,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     // Prologue: chunk 0 goes straight into copy 0, chunk 1 waits in the registers. While the first
     // loads are in flight, zero both staging copies (padding cells, rows past the batch and output
     // channels past K then stay zero for the whole kernel) and build the per-lane pixel table.
-    const int last_c0 = (a.nchunks - 1) * CC;
+    if (ragged && a.nchunks == 1) retarget_last_chunk();
     for_each_slot([&](auto kc) { slot_load(kc, 0); });
     for (int i = tid; i < (2 * buf_floats) >> 2; i += BLOCK) smem4[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -245,6 +249,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
 
     __syncthreads();  // zero fill complete before any data lands
     for_each_slot([&](auto kc) { slot_store(kc, 0, 0); });
+    if (ragged && a.nchunks == 2) retarget_last_chunk();
     for_each_slot([&](auto kc) { slot_load(kc, min(CC, last_c0)); });
     __syncthreads();
 
@@ -259,6 +264,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         const int nxt_floats = ((ch + 1) & 1) * buf_floats;
         const int c0_regs = min((ch + 1) * CC, last_c0);  // chunk whose data the staging registers hold
         const int c0_load = min((ch + 2) * CC, last_c0);  // chunk to fetch next (the last one again at the end)
+        if (ragged && ch + 3 == a.nchunks) retarget_last_chunk();
 
         const char* const a_base = lds_bytes + cur_bytes + arow;
         int xa[NT];  // B addresses of the filter row being read
