@@ -107,6 +107,20 @@ int conv_fwd_planned(const float* x, const float* w, float* y,
                      const conv_plan_t* plan, conv_plan_t* resolved);
 
 /*
+ * The layer with its fused epilogue: y = act(conv(x, w) + bias[k]). Section 2.1: the weighted sums of a
+ * convolutional layer are usually passed through a non-linear function such as ReLU; the per-filter
+ * constant is what CNN layers add before it (the paper does not mention one: pass null to leave it out).
+ * bias: device pointer to K floats, or null. relu: nonzero applies max(., 0) to every output. The epilogue
+ * runs in the store path of the same single kernel (after the cross-wave reduction where waves split C);
+ * no second pass over y and no workspace. plan: null plans as conv_fwd does, otherwise a request as in
+ * conv_fwd_planned. resolved (may be null) receives the plan used. x, w, y as for conv_fwd; y is overwritten.
+ * Returns CONV_OK or the error codes of conv_fwd / conv_fwd_planned.
+ */
+int conv_fwd_bias_relu(const float* x, const float* w, const float* bias, float* y,
+                       int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
+                       int relu, const conv_plan_t* plan, conv_plan_t* resolved);
+
+/*
  * The paper's own two-stage scheme (Section 3), opt-in and outside the planner, for comparison with the
  * fused kernels: stage 1 computes, per filter tap (r,s), the channel-reduced matrix
  * T[r,s][n,k,p,q] = sum_c w[k,c,r,s] * xpad[n,c,p+r-pad_h,q+s-pad_w] into the workspace (one work-group
@@ -130,7 +144,7 @@ int conv_variant_count(int kernel);
 int conv_variant_info(int kernel, int variant, int* tile_k, int* max_tile_pix, int* block);
 
 /*
- * Stream used by later conv_fwd / conv_fwd_planned calls of the calling
+ * Stream used by later conv_fwd / conv_fwd_planned / conv_fwd_bias_relu / conv_fwd_two_stage calls of the calling
  * thread's process (a hipStream_t passed as void*; NULL = null stream).
  */
 int conv_set_stream(void* hip_stream);

@@ -3,4 +3,5 @@
 Nothing in the product package imports this; it is called by the tests, the
 smoke check and the benchmark's CPU-baseline leg.
 """
-from .conv_ref import conv_ref, conv_ref_points, conv_ref_counted, within_tolerance, build  # noqa: F401
+from .conv_ref import (conv_ref, conv_ref_points, conv_ref_counted, conv_bias_relu_ref, within_tolerance,  # noqa: F401
+                       build)

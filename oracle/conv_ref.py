@@ -105,6 +105,23 @@ def conv_ref_counted(x, w, pad_h: int, pad_w: int):
     return y, xt, wt, int(macs.value)
 
 
+def conv_bias_relu_ref(x, w, bias, pad_h: int, pad_w: int, relu: bool, nthreads: int = 0):
+    """The layer with its epilogue (Section 2.1: the weighted sums are usually passed through a non-linear
+    function such as ReLU): conv_ref, plus bias[k] on every output of channel k (None: no bias), then
+    max(., 0) if relu. Returns (y, yabs) in fp64 with yabs = sum |x*w| + |bias[k]|, the magnitude the
+    tolerance rule scales with."""
+    y, ya = conv_ref(x, w, pad_h, pad_w, nthreads=nthreads)
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float64).reshape(1, -1, 1, 1)
+        if b.shape[1] != y.shape[1]:
+            raise ValueError("bias needs one value per filter")
+        y = y + b
+        ya = ya + np.abs(b)
+    if relu:
+        y = np.maximum(y, 0.0)
+    return y, ya
+
+
 def within_tolerance(y_test, y_ref, yabs_ref, rel: float = 1e-5, abs_: float = 1e-6):
     """The acceptance rule: |y_test - y_ref| <= rel * sum|x*w| + abs_, elementwise.
 

@@ -18,7 +18,8 @@ CONV_KERNEL_TAP = 1
 CONV_KERNEL_POINTWISE = 2
 CONV_KERNEL_PANEL = 3
 
-EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_two_stage_workspace_bytes", "conv_fwd_two_stage",
+EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_two_stage_workspace_bytes",
+           "conv_fwd_two_stage",
            "conv_variant_count", "conv_variant_info", "conv_set_stream", "conv_strerror")
 
 
@@ -62,6 +63,7 @@ def load_library():
     lib.conv_fwd.argtypes = [vp, vp, vp] + dims
     lib.conv_fwd_plan.argtypes = dims + [ctypes.POINTER(ConvPlan)]
     lib.conv_fwd_planned.argtypes = [vp, vp, vp] + dims + [ctypes.POINTER(ConvPlan), ctypes.POINTER(ConvPlan)]
+    lib.conv_fwd_bias_relu.argtypes = [vp, vp, vp, vp] + dims + [ci, ctypes.POINTER(ConvPlan), ctypes.POINTER(ConvPlan)]
     lib.conv_two_stage_workspace_bytes.argtypes = dims
     lib.conv_two_stage_workspace_bytes.restype = ctypes.c_longlong
     lib.conv_fwd_two_stage.argtypes = [vp, vp, vp, vp, ctypes.c_longlong] + dims
@@ -150,6 +152,28 @@ def conv_fwd_planned(x, w, pad_h: int, pad_w: int, kernel: int, variant: int = 0
     req, res = ConvPlan(), ConvPlan()
     req.kernel, req.variant, req.tile_pix, req.chunk_c = kernel, variant, tile_pix, chunk_c
     _check(lib.conv_fwd_planned(x.data_ptr(), w.data_ptr(), y.data_ptr(), *dims, ctypes.byref(req), ctypes.byref(res)))
+    return y, res
+
+
+def conv_fwd_bias_relu(x, w, bias, pad_h: int, pad_w: int, relu: bool, kernel=None, variant: int = 0, tile_pix: int = 0,
+                       y=None, use_current_stream: bool = True):
+    """y = act(conv(x, w) + bias) in one kernel; bias may be None. kernel=None plans as conv_fwd does. Returns (y, plan)."""
+    import torch
+    y, dims = _device_args(x, w, y, pad_h, pad_w)
+    if bias is not None and (not bias.is_cuda or bias.dtype != torch.float32 or not bias.is_contiguous()
+                             or bias.numel() != w.shape[0]):
+        raise ValueError("bias must be a contiguous fp32 device tensor of K elements")
+    lib = load_library()
+    if use_current_stream:
+        conv_set_stream(torch.cuda.current_stream(x.device))
+    res = ConvPlan()
+    req = None
+    if kernel is not None:
+        req = ConvPlan()
+        req.kernel, req.variant, req.tile_pix = kernel, variant, tile_pix
+    _check(lib.conv_fwd_bias_relu(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None, y.data_ptr(),
+                                  *dims, int(bool(relu)), ctypes.byref(req) if req is not None else None,
+                                  ctypes.byref(res)))
     return y, res
 
 

@@ -30,12 +30,20 @@ inline FastDiv make_fastdiv(unsigned d)
     return f;
 }
 
+#if defined(__HIPCC__)
+// Fused epilogue (Section 2.1: the weighted sums of a layer are usually passed through a non-linear function
+// such as ReLU): bias of the output channel, then the optional clamp at zero.
+__device__ __forceinline__ float finish_output(float v, float b, int relu) { v += b; return relu ? fmaxf(v, 0.f) : v; }
+#endif
+
 // Everything a kernel needs; passed by value. All offsets are in floats and fit 32 bits
 // (the host rejects tensors of 2^31 or more elements).
 struct KernelArgs {
     const float* x;
     const float* w;
     float* y;
+    const float* bias;  // K floats added to every output of a channel before the optional ReLU; null: none
+    int relu;           // nonzero: outputs are max(., 0)
     int N, C, H, W, K, R, S, pad_h, pad_w;
     int P, Q, PQ, HW, CRS;
     int Hp;          // H + 2*pad_h: rows of one zero-padded image

@@ -442,9 +442,10 @@ int record_hip(hipError_t e)
     return CONV_E_HIP;
 }
 
-int launch(const conv_plan_t& p, KernelArgs& a, const Shape& s, const float* x, const float* w, float* y)
+int launch(const conv_plan_t& p, KernelArgs& a, const Shape& s, const float* x, const float* w, float* y,
+           const float* bias = nullptr, int relu = 0)
 {
-    a.x = x; a.w = w; a.y = y;
+    a.x = x; a.w = w; a.y = y; a.bias = bias; a.relu = relu;
     hipStream_t stream = g_stream.load();
     if (p.kernel == CONV_KERNEL_TAP)
         return record_hip(launch_tap(tap_rs_index(s), p.variant, p.x_vec, p.w_vec, p.grid, p.lds_bytes, stream, a));
@@ -490,17 +491,21 @@ extern "C" int conv_fwd(const float* x, const float* w, float* y, int N, int C, 
     return launch(p, a, s, x, w, y);
 }
 
-extern "C" int conv_fwd_planned(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R,
-                                int S, int pad_h, int pad_w, const conv_plan_t* plan, conv_plan_t* resolved)
+// Shared by conv_fwd_planned and conv_fwd_bias_relu: resolve the requested mapping (or plan, when none is
+// requested) and enqueue the kernel.
+static int run_planned(const float* x, const float* w, const float* bias, float* y, int N, int C, int H, int W, int K,
+                       int R, int S, int pad_h, int pad_w, int relu, const conv_plan_t* plan, conv_plan_t* resolved)
 {
-    if (!x || !w || !y || !plan) return CONV_E_NULL;
+    if (!x || !w || !y) return CONV_E_NULL;
     Shape s;
     if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
     int x_cap, w_cap, y_cap;
     pointer_caps(x, w, y, &x_cap, &w_cap, &y_cap);
     conv_plan_t p;
     KernelArgs a;
-    if (plan->kernel == CONV_KERNEL_POINTWISE) {
+    if (!plan) {
+        if (int rc = plan_shape(s, x_cap, w_cap, y_cap, &p, &a)) return rc;
+    } else if (plan->kernel == CONV_KERNEL_POINTWISE) {
         if (!resolve_pointwise(s, plan->variant, x_cap, w_cap, y_cap, &p, &a)) return CONV_E_PLAN;
     } else if (plan->kernel == CONV_KERNEL_PANEL) {
         if (plan->tile_pix < 0 || !resolve_panel(s, plan->variant, plan->tile_pix, x_cap, w_cap, y_cap, &p, &a)) return CONV_E_PLAN;
@@ -513,7 +518,21 @@ extern "C" int conv_fwd_planned(const float* x, const float* w, float* y, int N,
         return CONV_E_PLAN;
     }
     if (resolved) *resolved = p;
-    return launch(p, a, s, x, w, y);
+    return launch(p, a, s, x, w, y, bias, relu);
+}
+
+extern "C" int conv_fwd_planned(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R,
+                                int S, int pad_h, int pad_w, const conv_plan_t* plan, conv_plan_t* resolved)
+{
+    if (!plan) return CONV_E_NULL;
+    return run_planned(x, w, nullptr, y, N, C, H, W, K, R, S, pad_h, pad_w, 0, plan, resolved);
+}
+
+extern "C" int conv_fwd_bias_relu(const float* x, const float* w, const float* bias, float* y, int N, int C, int H, int W,
+                                  int K, int R, int S, int pad_h, int pad_w, int relu, const conv_plan_t* plan,
+                                  conv_plan_t* resolved)
+{
+    return run_planned(x, w, bias, y, N, C, H, W, K, R, S, pad_h, pad_w, relu != 0, plan, resolved);
 }
 
 extern "C" long long conv_two_stage_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w)

@@ -31,7 +31,7 @@ __global__ void __launch_bounds__(256) conv_generic(const KernelArgs a)
                 }
             }
         }
-        a.y[idx] = acc;
+        a.y[idx] = finish_output(acc, a.bias ? a.bias[k] : 0.f, a.relu);
     }
 }
 

@@ -159,12 +159,15 @@ __global__ void __launch_bounds__(64 * WC * WP) conv_pointwise_mfma(const Kernel
         for (int v = 0; v < 4; ++v) {
             const int k = k0 + 16 * m + 4 * kq + v;
             if (k >= a.K) continue;
+            const float bk = a.bias ? a.bias[k] : 0.f;
             if constexpr (VEC == 4) {
-                *reinterpret_cast<f32x4*>(ylane + k * a.HW) = f32x4{acc[m][0][v], acc[m][1][v], acc[m][2][v], acc[m][3][v]};
+                *reinterpret_cast<f32x4*>(ylane + k * a.HW) =
+                    f32x4{finish_output(acc[m][0][v], bk, a.relu), finish_output(acc[m][1][v], bk, a.relu),
+                          finish_output(acc[m][2][v], bk, a.relu), finish_output(acc[m][3][v], bk, a.relu)};
             } else {
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
-                    if (px + PSTEP * t < a.HW) ylane[k * a.HW + PSTEP * t] = acc[m][t][v];
+                    if (px + PSTEP * t < a.HW) ylane[k * a.HW + PSTEP * t] = finish_output(acc[m][t][v], bk, a.relu);
             }
         }
 }

@@ -206,11 +206,15 @@ __global__ void __launch_bounds__(64 * NW) conv_pointwise_panel(const KernelArgs
             for (int m = 0; m < MT; ++m)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    float* const dst = yl + (size_t)min(k0 + 16 * m + 4 * kq + v, a.K - 1) * a.HW;
+                    const int k = min(k0 + 16 * m + 4 * kq + v, a.K - 1);
+                    float* const dst = yl + (size_t)k * a.HW;
+                    const float bk = a.bias ? a.bias[k] : 0.f;
                     if constexpr (VEC == 4) {
-                        *reinterpret_cast<f32x4*>(dst) = f32x4{acc[m][0][v], acc[m][1][v], acc[m][2][v], acc[m][3][v]};
+                        *reinterpret_cast<f32x4*>(dst) =
+                            f32x4{finish_output(acc[m][0][v], bk, a.relu), finish_output(acc[m][1][v], bk, a.relu),
+                                  finish_output(acc[m][2][v], bk, a.relu), finish_output(acc[m][3][v], bk, a.relu)};
                     } else {
-                        *dst = acc[m][i][v];
+                        *dst = finish_output(acc[m][i][v], bk, a.relu);
                     }
                 }
         }

@@ -356,6 +356,9 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
         const int kbase = k0 + (wk * MT + m) * 16 + 4 * kq;
+        float bk[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) bk[v] = a.bias ? a.bias[min(kbase + v, a.K - 1)] : 0.f;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const int g = g0 + (wp * NT + t) * 16 + j;
@@ -364,7 +367,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
             const int yb = n * a.K * a.PQ + (g - n * a.PQ);
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                if (kbase + v < a.K) a.y[yb + (kbase + v) * a.PQ] = acc[m][t][v];
+                if (kbase + v < a.K) a.y[yb + (kbase + v) * a.PQ] = finish_output(acc[m][t][v], bk[v], a.relu);
         }
     }
 }

@@ -232,6 +232,49 @@ NONSQUARE = [
 ]
 
 
+EPILOGUE_CASES = [   # (shape, kernel family or None for the default plan, variant, tile_pix)
+    (SMALL[0], None, 0, 0), (SMALL[0], GENERIC, 0, 0), (SMALL[0], TAP, 2, 0), (SMALL[0], TAP, 5, 0), (SMALL[0], TAP, 12, 0),
+    (SMALL[6], TAP, 4, 0), (SMALL[6], TAP, 2, 0), (SMALL[3], TAP, 2, 0), (SMALL[1], TAP, 10, 0),
+    (POINTWISE_SHAPES[0], POINTWISE, 0, 0), (POINTWISE_SHAPES[0], POINTWISE, 9, 0), (POINTWISE_SHAPES[6], POINTWISE, 2, 0),
+    (PANEL_SHAPES[8], PANEL, 7, 1), (PANEL_SHAPES[9], PANEL, 6, 2), (PANEL_SHAPES[10], PANEL, 3, 0), (PANEL_SHAPES[0], PANEL, 1, 0),
+    (NONSQUARE[0], None, 0, 0),
+]
+
+
+@pytest.mark.parametrize("with_bias,relu", [(False, True), (True, False), (True, True)])
+@pytest.mark.parametrize("case", EPILOGUE_CASES, ids=lambda c: f"{c[0].name}-k{c[1]}v{c[2]}")
+def test_fused_bias_relu_matches_oracle(case, with_bias, relu):
+    """y = act(conv + bias) in the store path of the same kernel (Section 2.1), every kernel family."""
+    shape, kernel, variant, tile_pix = case
+    x, w = inputs.make_inputs(shape)
+    b = inputs.uniform_pm1(900 + shape.K, shape.K) * np.float32(0.5) if with_bias else None
+    y_ref, ya_ref = oracle.conv_bias_relu_ref(x, w, b, shape.pad_h, shape.pad_w, relu)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    bd = torch.from_numpy(b).cuda() if with_bias else None
+    yd = torch.full(shape.y_shape, float("nan"), device="cuda")
+    _say(f"[case] bias_relu {shape.name} dims={shape.dims} kernel={kernel} variant={variant} bias={with_bias} relu={relu}")
+    _, plan = binding.conv_fwd_bias_relu(xd, wd, bd, shape.pad_h, shape.pad_w, relu, kernel, variant, tile_pix, y=yd)
+    torch.cuda.synchronize()
+    if kernel is not None:
+        assert plan.kernel == kernel
+    y = yd.cpu().numpy().astype(np.float64)
+    assert not np.isnan(y).any()
+    ok, worst = oracle.within_tolerance(y, y_ref, ya_ref)
+    assert ok, worst
+    if relu:
+        assert (y >= 0).all() and (y == 0).any() and (y > 0).any()
+
+
+def test_fused_epilogue_integer_inputs_are_exact():
+    shape = inputs.ConvShape("ints_b", 2, 12, 9, 10, 35, 3, 3, 1, 1, "int", "int", 31, 32)
+    x, w = inputs.make_inputs(shape)
+    b = inputs.small_ints(77, shape.K, -20, 20)
+    y_ref, _ = oracle.conv_bias_relu_ref(x, w, b, 1, 1, True)
+    y, _ = binding.conv_fwd_bias_relu(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(b).cuda(), 1, 1, True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(y.cpu().numpy().astype(np.float64), y_ref)
+
+
 @pytest.mark.parametrize("shape", NONSQUARE, ids=lambda s: s.name)
 def test_other_filter_sizes_use_the_generic_kernel(shape):
     plan, _ = _run(shape)

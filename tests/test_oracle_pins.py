@@ -37,7 +37,46 @@ def _read_golden(path):
     return x, w, ph, pw, y, ya
 
 
-@pytest.mark.parametrize("path", sorted(glob.glob(os.path.join(GOLDEN, "*.txt"))), ids=os.path.basename)
+def _plain_cases():
+    return [p for p in sorted(glob.glob(os.path.join(GOLDEN, "*.txt"))) if not os.path.basename(p).startswith("bias_relu")]
+
+
+def test_hand_worked_epilogue_case():
+    """Bias and ReLU after the convolution (Section 2.1), against values worked by hand."""
+    path = os.path.join(GOLDEN, "bias_relu_c2k2_1x2.txt")
+    x, w, ph, pw, y, ya = _read_golden(path)
+    rec = {}
+    for line in open(path):
+        if line.startswith(("bias", "relu")):
+            key, *vals = line.split()
+            rec[key] = [float(v) for v in vals]
+    got, got_abs = oracle.conv_bias_relu_ref(x, w, np.array(rec["bias"], dtype=np.float32), ph, pw, bool(rec["relu"][0]))
+    np.testing.assert_array_equal(got, y)
+    np.testing.assert_array_equal(got_abs, ya)
+
+
+def test_epilogue_properties_and_library_routine():
+    torch = pytest.importorskip("torch")
+    x, w = _rand((2, 5, 6, 7), 61), _rand((4, 5, 3, 3), 62)
+    b = _rand((4,), 63)
+    plain, plain_abs = oracle.conv_ref(x, w, 1, 1)
+    y0, a0 = oracle.conv_bias_relu_ref(x, w, None, 1, 1, False)            # no bias, no ReLU: the convolution itself
+    np.testing.assert_array_equal(y0, plain)
+    np.testing.assert_array_equal(a0, plain_abs)
+    yb, ab = oracle.conv_bias_relu_ref(x, w, b, 1, 1, False)
+    np.testing.assert_array_equal(yb, plain + b.astype(np.float64).reshape(1, 4, 1, 1))   # bias lands on its own channel
+    np.testing.assert_array_equal(ab, plain_abs + np.abs(b.astype(np.float64)).reshape(1, 4, 1, 1))
+    yr, _ = oracle.conv_bias_relu_ref(x, w, b, 1, 1, True)
+    assert (yr >= 0).all() and (yr[yb > 0] == yb[yb > 0]).all() and (yr[yb <= 0] == 0).all()
+    assert (yb < 0).any() and (yb > 0).any()                                 # the case exercises both branches
+    zero, _ = oracle.conv_bias_relu_ref(x, np.zeros_like(w), b, 1, 1, True)  # closed form: ReLU(bias) everywhere
+    np.testing.assert_array_equal(zero, np.broadcast_to(np.maximum(b.astype(np.float64), 0).reshape(1, 4, 1, 1), zero.shape))
+    t = torch.nn.functional.relu(torch.nn.functional.conv2d(
+        torch.from_numpy(x).double(), torch.from_numpy(w).double(), torch.from_numpy(b).double(), padding=1)).numpy()
+    np.testing.assert_allclose(yr, t, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("path", _plain_cases(), ids=os.path.basename)
 def test_hand_worked_cases(path):
     x, w, ph, pw, y, ya = _read_golden(path)
     for nthreads in (1, 3):
