@@ -127,9 +127,11 @@ constexpr TapVariant kTapVariants[] = {
     {1, 7, 1, 4, 1, 2, 2, 8, 16},   // 14: 16 ch x 448 px: layers with 16 or fewer filters on large maps
     {1, 4, 1, 4, 1, 4, 2, 8, 16},   // 15: 16 ch x 256 px, 16-channel chunks
     {1, 7, 1, 4, 1, 1, 2, 8, 16},   // 16: 16 ch x 448 px, 4-channel chunks: first layers (3 input channels)
+    {1, 1, 1, 1, 16, 1, 4, 2, 8},   // 17: 16 ch x  16 px, 16 channel shares (64-channel chunks): deep N=1 layers on tiny maps
+    {1, 2, 1, 1, 8, 1, 2, 4, 16},   // 18: 16 ch x  32 px, 8 channel shares (32-channel chunks)
 };
 constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
-#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16)
+#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18)
 
 // Tile shapes of the pointwise (1x1, no padding) family: a work-group is WC x WP waves on 16*MT output
 // channels x WP*64 contiguous pixels of one image; the WC shares split the input channels.
@@ -160,7 +162,7 @@ struct PanelVariant {
     constexpr int block() const { return 64 * NW; }
 };
 constexpr PanelVariant kPanelVariants[] = {
-    {4, 8, 4}, {2, 8, 4}, {1, 8, 4}, {4, 4, 4}, {2, 4, 4}, {1, 4, 4},
+    {4, 8, 2}, {2, 8, 4}, {1, 8, 4}, {4, 4, 4}, {2, 4, 4}, {1, 4, 4},
     {4, 4, 2}, {2, 4, 2}, {2, 8, 2},  // two steps in flight: layers with 32 (mod 64) or fewer channels
 };
 constexpr int kNumPanelVariants = sizeof(kPanelVariants) / sizeof(kPanelVariants[0]);

@@ -306,11 +306,11 @@ void resolve_generic(const Shape& s, conv_plan_t* p, KernelArgs* a)
 // the best one measured. Per chunk, the work-groups sharing a CU take the longest of
 //   their matrix instructions   (wpc x MFMA cycles per SIMD; issue efficiency 0.85 with two or more waves
 //                                 per SIMD, 0.6 with one),
-//   one chunk's latency chain   (~2000 cycles from a staging load's issue to its data sitting in LDS behind
+//   one chunk's latency chain   (~2500 cycles from a staging load's issue to its data sitting in LDS behind
 //                                 the barrier, plus the chunk's own matrix instructions), and
 //   their staging traffic       (halo rows + filter block through registers into LDS, ~16 B/clk per CU),
 // a work-group adds ~12000 cycles of prologue and epilogue (first loads, LDS fill, the reduction tree,
-// stores at ~32 B/clk), and the launch ~5000.
+// stores at ~32 B/clk), the launch ~5000 and the dispatcher ~24 per work-group.
 double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv, int RS)
 {
     const int by_regs = std::max(1, tv.occ * 256 / tv.block());
@@ -320,11 +320,11 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
     const double eff = wpc * waves_per_simd >= 2 ? 0.85 : 0.6;
     const double mfma = waves_per_simd * tv.MT * tv.NT * tv.GPC * RS * 32.0;  // per SIMD, chunk and work-group
     const double staged = 4.0 * ((double)tv.chunk_c() * a.lds_rows * a.W + (double)tv.tile_k() * tv.chunk_c() * RS);
-    const double chunk = std::max(std::max(wpc * mfma / eff, 2000.0 + mfma), wpc * staged / 16.0);
+    const double chunk = std::max(std::max(wpc * mfma / eff, 2500.0 + mfma), wpc * staged / 16.0);
     const double tree = tv.WC > 1 ? tv.MT * tv.NT * 1024.0 * tv.WK * tv.WP / 64.0 * std::log2((double)tv.WC) : 0.0;
     const double per_round = a.nchunks * chunk + 12000.0 + wpc * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree);
     const double rounds = std::ceil((double)p.grid / (kNumCU * wpc));
-    return rounds * per_round + 5000.0;
+    return rounds * per_round + 5000.0 + 24.0 * p.grid;  // ... and ~24 cycles of dispatch per work-group
 }
 
 // Measured best mappings of known layer shapes (sweeps over tile shape x pixel tile on an MI355X);

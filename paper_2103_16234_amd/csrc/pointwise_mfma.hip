@@ -152,6 +152,14 @@ __global__ void __launch_bounds__(64 * WC * WP) conv_pointwise_mfma(const Kernel
 
     // lane (j, kq) holds output channels 4*kq + v of tile m for pixels 4j .. 4j+3 (one per pixel tile)
     if (!pvalid) return;
+    // the epilogue's per-channel constants are fetched first and waited for once: a load between the stores
+    // would make every later store wait for the earlier ones (one in-order counter for loads and stores)
+    float bias_k[MT][4];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) bias_k[m][v] = a.bias ? a.bias[min(k0 + 16 * m + 4 * kq + v, a.K - 1)] : 0.f;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     float* const ylane = a.y + n * a.K * a.HW + px;
 #pragma unroll
     for (int m = 0; m < MT; ++m)
@@ -159,7 +167,7 @@ __global__ void __launch_bounds__(64 * WC * WP) conv_pointwise_mfma(const Kernel
         for (int v = 0; v < 4; ++v) {
             const int k = k0 + 16 * m + 4 * kq + v;
             if (k >= a.K) continue;
-            const float bk = a.bias ? a.bias[k] : 0.f;
+            const float bk = bias_k[m][v];
             if constexpr (VEC == 4) {
                 *reinterpret_cast<f32x4*>(ylane + k * a.HW) =
                     f32x4{finish_output(acc[m][0][v], bk, a.relu), finish_output(acc[m][1][v], bk, a.relu),

@@ -138,6 +138,14 @@ __global__ void __launch_bounds__(64 * NW) conv_pointwise_panel(const KernelArgs
             }
         }
     }
+    // The epilogue's per-channel constants live in registers for the kernel's whole life: a load inside the
+    // tile loop would sit behind the prefetched inputs in the in-order counter and drain them at every tile.
+    float bk[MT][4];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) bk[m][v] = a.bias ? a.bias[min(k0 + 16 * m + 4 * kq + v, a.K - 1)] : 0.f;
+
     // Every load so far is complete on every path before the main loop starts: the loop's own waits then
     // only have to track the loop's loads (vmcnt = 0, other counters untouched).
     __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -206,15 +214,14 @@ __global__ void __launch_bounds__(64 * NW) conv_pointwise_panel(const KernelArgs
             for (int m = 0; m < MT; ++m)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int k = min(k0 + 16 * m + 4 * kq + v, a.K - 1);
-                    float* const dst = yl + (size_t)k * a.HW;
-                    const float bk = a.bias ? a.bias[k] : 0.f;
+                    float* const dst = yl + (size_t)min(k0 + 16 * m + 4 * kq + v, a.K - 1) * a.HW;
+                    const float b = bk[m][v];
                     if constexpr (VEC == 4) {
                         *reinterpret_cast<f32x4*>(dst) =
-                            f32x4{finish_output(acc[m][0][v], bk, a.relu), finish_output(acc[m][1][v], bk, a.relu),
-                                  finish_output(acc[m][2][v], bk, a.relu), finish_output(acc[m][3][v], bk, a.relu)};
+                            f32x4{finish_output(acc[m][0][v], b, a.relu), finish_output(acc[m][1][v], b, a.relu),
+                                  finish_output(acc[m][2][v], b, a.relu), finish_output(acc[m][3][v], b, a.relu)};
                     } else {
-                        *dst = finish_output(acc[m][i][v], bk, a.relu);
+                        *dst = finish_output(acc[m][i][v], b, a.relu);
                     }
                 }
         }

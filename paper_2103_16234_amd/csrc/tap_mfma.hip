@@ -87,7 +87,7 @@ template <int N_MFMA> __device__ __forceinline__ void interleave_with_mfma()
 template <int R, int S, int MT, int NT, int WK, int WP, int WC, int GPC, int OCC, int XS, int WS, int VX, int VW>
 __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const KernelArgs a)
 {
-    static_assert(WC == 1 || WC == 2 || WC == 4, "the cross-wave reduction is a binary tree");
+    static_assert(WC >= 1 && WC <= 16 && (WC & (WC - 1)) == 0, "the cross-wave reduction is a binary tree");
     constexpr int BLOCK = 64 * WK * WP * WC;
     constexpr int RS = R * S;
     constexpr int TK = 16 * MT * WK;
@@ -352,13 +352,19 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         if (wc != 0) return;
     }
 
-    // a4: lane (j, kq) holds output channels 4*kq..4*kq+3 of each tile for pixel j.
+    // a4: lane (j, kq) holds output channels 4*kq..4*kq+3 of each tile for pixel j. The epilogue's
+    // per-channel constants are fetched first and waited for once, so that no store has to wait for a load
+    // that sits behind earlier stores in the in-order memory counter.
+    float bk[MT][4];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            bk[m][v] = a.bias ? a.bias[min(k0 + (wk * MT + m) * 16 + 4 * kq + v, a.K - 1)] : 0.f;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
         const int kbase = k0 + (wk * MT + m) * 16 + 4 * kq;
-        float bk[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) bk[v] = a.bias ? a.bias[min(kbase + v, a.K - 1)] : 0.f;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const int g = g0 + (wp * NT + t) * 16 + j;
@@ -367,7 +373,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
             const int yb = n * a.K * a.PQ + (g - n * a.PQ);
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                if (kbase + v < a.K) a.y[yb + (kbase + v) * a.PQ] = finish_output(acc[m][t][v], bk[v], a.relu);
+                if (kbase + v < a.K) a.y[yb + (kbase + v) * a.PQ] = finish_output(acc[m][t][v], bk[m][v], a.relu);
         }
     }
 }
