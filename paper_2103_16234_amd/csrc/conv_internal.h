@@ -90,7 +90,11 @@ struct TapVariant {
     constexpr int chunk_c() const { return 4 * WC * GPC; }
     // filter-block loads per thread and chunk, and whether that many registers are reasonable
     constexpr int wslots(int RS, int w_vec) const { return (tile_k() * chunk_c() * RS / w_vec + block() - 1) / block(); }
-    constexpr bool supports(int RS) const { return tile_k() * chunk_c() * RS <= (occ > 2 ? 20 : occ > 1 ? 40 : 64) * block(); }
+    // (eight or more channel shares never paid off on 5x5 filters in the sweeps: the filter block per chunk gets too large)
+    constexpr bool supports(int RS) const
+    {
+        return tile_k() * chunk_c() * RS <= (occ > 2 ? 20 : occ > 1 ? 40 : 64) * block() && (WC < 8 || RS <= 9);
+    }
     // Filters whose rows dwordx4 cannot walk (C not a multiple of 4) are staged dword by dword, with inputs
     // as dwordx4 (maps whose width is a multiple of 4: first layers) or dwords: a table entry per dword
     // staged, so small filter blocks only.
@@ -129,9 +133,11 @@ constexpr TapVariant kTapVariants[] = {
     {1, 7, 1, 4, 1, 1, 2, 8, 16},   // 16: 16 ch x 448 px, 4-channel chunks: first layers (3 input channels)
     {1, 1, 1, 1, 16, 1, 4, 2, 8},   // 17: 16 ch x  16 px, 16 channel shares (64-channel chunks): deep N=1 layers on tiny maps
     {1, 2, 1, 1, 8, 1, 2, 4, 16},   // 18: 16 ch x  32 px, 8 channel shares (32-channel chunks)
+    {1, 7, 2, 1, 4, 2, 2, 8, 12},   // 19: as 12 with 32-channel chunks: half as many barriers per layer
+    {1, 2, 1, 1, 4, 2, 2, 4, 16},   // 20: as 11 with 32-channel chunks
 };
 constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
-#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18)
+#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18) X(19) X(20)
 
 // Tile shapes of the pointwise (1x1, no padding) family: a work-group is WC x WP waves on 16*MT output
 // channels x WP*64 contiguous pixels of one image; the WC shares split the input channels.

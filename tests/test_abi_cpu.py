@@ -108,3 +108,44 @@ def test_plans_cover_odd_shapes():
         assert p.workspace_bytes == 0 and p.lds_bytes <= 160 * 1024
         if R != S or R not in (1, 3, 5):
             assert p.kernel == binding.CONV_KERNEL_GENERIC
+
+
+def test_plans_of_the_sweep_grid_are_well_formed():
+    """Host-only planner over the 169 synthetic layers: every plan is a launch the kernels accept."""
+    tap, pw, panel = binding.CONV_KERNEL_TAP, binding.CONV_KERNEL_POINTWISE, binding.CONV_KERNEL_PANEL
+    families = set()
+    for s in inputs.sweep_shapes():
+        p = binding.conv_fwd_plan(*s.dims)
+        families.add(p.kernel)
+        assert p.workspace_bytes == 0 and (p.P, p.Q) == (s.P, s.Q)
+        assert p.flops == s.flops and p.bytes == s.algorithmic_bytes
+        assert 1 <= p.grid < 2 ** 31 and p.block in (64, 128, 256, 512, 1024) and 0 <= p.lds_bytes <= 160 * 1024
+        assert p.kernel in (tap, pw, panel)                      # every sweep layer has a specialised kernel
+        assert 0 <= p.variant < binding.conv_variant_count(p.kernel)
+        tile_k, cap, block = binding.conv_variant_info(p.kernel, p.variant)
+        assert p.block == block and p.tile_k == tile_k
+        total = s.N * s.P * s.Q
+        if p.kernel == tap:
+            assert 1 <= p.tile_pix <= cap
+            assert p.grid == -(-s.K // p.tile_k) * -(-total // p.tile_pix)
+            assert p.chunk_c % 4 == 0 and p.x_vec in (1, 2, 4) and p.w_vec in (1, 4)
+            assert s.W % p.x_vec == 0 and (p.w_vec == 1 or s.C % 4 == 0)
+        elif p.kernel == pw:
+            assert s.R == 1 and s.pad_h == 0 and s.C % 4 == 0
+            assert p.grid == -(-s.K // p.tile_k) * s.N * -(-(s.H * s.W) // p.tile_pix)
+        else:
+            assert s.R == 1 and s.pad_h == 0 and s.C % 4 == 0
+            groups = p.tile_pix                                  # work-groups per channel tile
+            assert p.grid == -(-s.K // p.tile_k) * groups
+            assert 1 <= groups * (block // 64) <= -(-total // 64) + block // 64   # no more waves than 64-pixel tiles (+ one work-group)
+            assert p.lds_bytes >= 4 * p.tile_k * s.C                 # the whole filter panel of a channel tile
+    assert families == {tap, pw, panel}
+
+
+def test_panel_plans_follow_the_batch():
+    """The panel kernel takes over from the register-streaming kernel once a 1x1 layer has enough tiles."""
+    small = binding.conv_fwd_plan(1, 256, 56, 56, 64, 1, 1, 0, 0)
+    big = binding.conv_fwd_plan(32, 256, 56, 56, 64, 1, 1, 0, 0)
+    assert small.kernel == binding.CONV_KERNEL_POINTWISE and big.kernel == binding.CONV_KERNEL_PANEL
+    deep = binding.conv_fwd_plan(128, 4096, 7, 7, 64, 1, 1, 0, 0)      # 16 x 4096 floats of filters do not fit LDS
+    assert deep.kernel != binding.CONV_KERNEL_PANEL
