@@ -225,16 +225,40 @@ bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w
     int groups = groups_req;
     const int most = ceil_div(tiles, pv.NW);  // one tile per wave
     if (groups <= 0) {
-        // as many work-groups as stay resident together (two waves per SIMD, LDS permitting), then the
-        // fewest that still finish in the same number of tile rounds
+        // Work-groups are dealt round-robin to the 256 CUs and the longest CU decides. Candidates: grids of
+        // 1..8 work-groups per CU (measured: 400 work-groups of 3.9 tiles per wave take 130 us where 512 of
+        // 3.06 take 118 - the 144 CUs that get a second work-group finish last), and one tile per wave.
+        // Cost of a candidate, in units of one tile of one wave: the busiest CU's tiles per SIMD (over 0.85
+        // if a SIMD only ever holds one wave) plus its panel loads (~32 B/clk).
         const int per_cu = std::max(1, std::min((int)(kLdsMax / lds), 8 / pv.NW));
-        const int target = std::max(1, kNumCU * per_cu / a->ktiles);
-        if (target >= most) {
-            groups = most;
-        } else {
-            const int rounds = ceil_div(tiles, target * pv.NW);
-            groups = ceil_div(tiles, rounds * pv.NW);
+        const double tile_cycles = steps * 16.0 * pv.MT * 32.0;
+        double best = 0;
+        auto consider = [&](int g) {
+            g = std::max(1, std::min(g, most));
+            const int64_t wgs = (int64_t)g * a->ktiles;
+            if (wgs >= ((int64_t)1 << 20)) return;  // (the loop below is per work-group)
+            const int stride = g * pv.NW;
+            std::vector<int> load(kNumCU, 0), count(kNumCU, 0);
+            for (int64_t L = 0; L < wgs; ++L) {
+                const int first_wave = (int)(L / a->ktiles) * pv.NW;
+                const int per_wave = first_wave < tiles ? ceil_div(tiles - first_wave, stride) : 0;
+                load[L % kNumCU] += per_wave * (pv.NW / 4);
+                count[L % kNumCU] += 1;
+            }
+            const int busiest = *std::max_element(load.begin(), load.end());
+            const int most_wgs = *std::max_element(count.begin(), count.end());
+            const double waves_per_simd = std::min<double>(per_cu, most_wgs) * pv.NW / 4.0;
+            const double cost = busiest / (waves_per_simd >= 2 ? 1.0 : 0.85) + most_wgs * (lds / 32.0) / tile_cycles;
+            if (groups <= 0 || cost < best * 0.999) { groups = g; best = cost; }
+        };
+        for (int m = 1; m <= 8; ++m) {
+            const int g = std::max(1, std::min(ceil_div(kNumCU * m, a->ktiles), most));
+            // first the fewest work-groups that need no more tiles per wave than g does (ties keep the first)
+            consider(ceil_div(tiles, ceil_div(tiles, g * pv.NW) * pv.NW));
+            consider(kNumCU * m / a->ktiles);
+            consider(g);
         }
+        consider(most);
     }
     groups = std::min(groups, most);
     if ((int64_t)groups * a->ktiles >= ((int64_t)1 << 31)) return false;
