@@ -377,3 +377,39 @@ def test_benchmark_layers_full_size(i):
     plan, worst = _run(shape)
     _say(f"[result] {shape.name}: worst tolerance ratio {worst:.3g}, plan {plan.as_dict()}")
     _ref_cache.clear()
+
+
+def test_conv_fwd_replays_from_a_hip_graph():
+    """conv_fwd enqueues one kernel and nothing else, so it can be captured; every replay (with eager launches and
+    synchronisations in between) must reproduce the eager result bit for bit."""
+    shapes = [SMALL[0], POINTWISE_SHAPES[0], PANEL_SHAPES[8]]
+    tensors = []
+    for s in shapes:
+        x, w = inputs.make_inputs(s)
+        xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+        eager = binding.conv_fwd(xd, wd, s.pad_h, s.pad_w)
+        tensors.append((s, xd, wd, eager, torch.zeros_like(eager)))
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up on the capture stream (plans, kernel attributes)
+        for s, xd, wd, _, out in tensors:
+            binding.conv_fwd(xd, wd, s.pad_h, s.pad_w, y=out)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for s, xd, wd, _, out in tensors:
+            binding.conv_fwd(xd, wd, s.pad_h, s.pad_w, y=out)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for _, _, _, _, out in tensors:
+            out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        _say(f"[case] graph replay {rep}")
+        graph.replay()
+        torch.cuda.synchronize()
+        for s, xd, wd, eager, out in tensors:
+            assert torch.equal(out, eager), s.name
+            again = binding.conv_fwd(xd, wd, s.pad_h, s.pad_w)     # eager work between replays
+            torch.cuda.synchronize()
+            assert torch.equal(again, eager)
