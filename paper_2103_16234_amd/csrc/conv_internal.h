@@ -161,7 +161,8 @@ hipError_t launch_pointwise(int variant, int x_vec, int grid, int lds_bytes, hip
 // of 16*MT output channels in LDS and every wave streams 64-pixel tiles past them with PD 16-channel
 // steps of input loads in flight. KernelArgs carry: ktiles, ptiles = work-groups per channel tile,
 // nchunks = steps (C rounded up to 16*PD, over 16), x_items = 64-pixel tiles in all, lds_pitch = floats per
-// panel row, div_ktiles, div_PQ, div_row_vecs (by 4 * nchunks).
+// panel row, div_ktiles, div_PQ, div_row_vecs (by 4 * nchunks); col_shift = pixel mode (launch_panel's pix); with
+// tiles per image: tile_pix = tiles per image and div_ptiles divides by it.
 struct PanelVariant {
     int MT, NW, PD;
     constexpr int tile_k() const { return 16 * MT; }
@@ -173,7 +174,7 @@ constexpr PanelVariant kPanelVariants[] = {
 };
 constexpr int kNumPanelVariants = sizeof(kPanelVariants) / sizeof(kPanelVariants[0]);
 #define PANEL_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8)
-hipError_t launch_panel(int variant, int x_vec, int grid, int lds_bytes, hipStream_t stream, const KernelArgs& a);
+hipError_t launch_panel(int variant, int pix, int grid, int lds_bytes, hipStream_t stream, const KernelArgs& a);
 
 // rs_index: 0 -> 1x1, 1 -> 3x3, 2 -> 5x5. Returns hipSuccess or the launch error.
 hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid, int lds_bytes,

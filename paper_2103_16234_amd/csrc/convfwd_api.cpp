@@ -205,6 +205,17 @@ bool resolve_pointwise(const Shape& s, int variant, int x_cap, int w_cap, int y_
     return true;
 }
 
+// Pixel mode of the panel kernel: 0 = aligned dwordx4 over flattened tiles when H*W is a multiple of 4 and x, y are
+// 16-byte aligned; otherwise 2 = dword-aligned dwordx4 over tiles cut per image if that wastes at most 6 % of the
+// tiles' pixels (27x27: 729 of 768; measured 5-11 % faster than dwords there, but 25 % slower on 13x13 maps, which
+// fill 169 of 192), else 1 = single dwords over flattened tiles.
+int panel_pixel_mode(const Shape& s, int x_cap, int y_cap)
+{
+    if (pointwise_x_vec(s, x_cap, y_cap) == 4) return 0;
+    const int hw = s.H * s.W;
+    return (hw >= 4 && ceil_div(hw, 64) * 64 * 100 <= hw * 106) ? 2 : 1;
+}
+
 // Panel kernel of the pointwise family: the filters of a channel tile must fit LDS whole. tile_pix > 0
 // requests that many work-groups per channel tile (0 = choose).
 bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
@@ -216,8 +227,11 @@ bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w
     const int64_t lds = (int64_t)pv.tile_k() * pitch * 4;
     if (lds > kLdsMax) return false;
     base_args(s, a);
-    const int tiles = ceil_div(a->total_pix, 64);
     if (a->total_pix < 4 || a->total_pix > (1 << 30)) return false;  // tile * 64 + lane offsets stay far inside 32 bits
+    const int per_image = ceil_div(a->HW, 64);
+    const int pix = panel_pixel_mode(s, x_cap, y_cap);
+    const int tiles = pix == 2 ? s.N * per_image : ceil_div(a->total_pix, 64);
+    if ((int64_t)s.N * per_image >= (1 << 30)) return false;
     // the kernel addresses inputs as a 64-bit tile base plus 32-bit byte offsets that cover every image a
     // 64-pixel tile touches and all (padded) channels
     if ((int64_t)(64 / a->HW + 3) * (s.C + 64) * a->HW * 4 >= ((int64_t)1 << 32)) return false;
@@ -263,7 +277,9 @@ bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w
     groups = std::min(groups, most);
     if ((int64_t)groups * a->ktiles >= ((int64_t)1 << 31)) return false;
     a->ptiles = groups;
-    a->tile_pix = 64;
+    a->tile_pix = pix == 2 ? per_image : 64;
+    a->div_ptiles = make_fastdiv(per_image);
+    a->col_shift = pix;
     a->nchunks = steps;
     a->x_items = tiles;
     a->lds_pitch = pitch;
@@ -273,7 +289,7 @@ bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w
     std::memset(p, 0, sizeof(*p));
     p->kernel = CONV_KERNEL_PANEL; p->variant = variant;
     p->tile_k = pv.tile_k(); p->tile_pix = groups; p->chunk_c = 16 * pv.PD;
-    p->x_vec = pointwise_x_vec(s, x_cap, y_cap); p->w_vec = 4;
+    p->x_vec = pix == 1 ? 1 : 4; p->w_vec = 4;
     p->lds_pitch = pitch;
     p->grid = groups * a->ktiles; p->block = pv.block(); p->lds_bytes = (int)lds;
     fill_common(s, p);
@@ -305,7 +321,7 @@ int pick_panel(const Shape& s, int x_cap, int y_cap)
 {
     const int64_t tiles = ((int64_t)s.N * s.H * s.W + 63) / 64;
     if (tiles * ceil_div(s.K, 32) < 704) return -1;
-    const bool dwords = pointwise_x_vec(s, x_cap, y_cap) == 1;
+    const bool dwords = panel_pixel_mode(s, x_cap, y_cap) == 1;
     const int c64 = round_up(s.C, 32);
     if (dwords && s.K >= 64 && tiles * ceil_div(s.K, 64) >= 704 && 64 * (c64 + 4) * 4 <= kLdsMax) return 6;  // {4, 4, 2}
     if (32 * (c64 + 4) * 4 <= kLdsMax) return 7;                                                                // {2, 4, 2}
@@ -474,7 +490,7 @@ int launch(const conv_plan_t& p, KernelArgs& a, const Shape& s, const float* x, 
     if (p.kernel == CONV_KERNEL_TAP)
         return record_hip(launch_tap(tap_rs_index(s), p.variant, p.x_vec, p.w_vec, p.grid, p.lds_bytes, stream, a));
     if (p.kernel == CONV_KERNEL_POINTWISE) return record_hip(launch_pointwise(p.variant, p.x_vec, p.grid, p.lds_bytes, stream, a));
-    if (p.kernel == CONV_KERNEL_PANEL) return record_hip(launch_panel(p.variant, p.x_vec, p.grid, p.lds_bytes, stream, a));
+    if (p.kernel == CONV_KERNEL_PANEL) return record_hip(launch_panel(p.variant, a.col_shift, p.grid, p.lds_bytes, stream, a));
     if (p.kernel == CONV_KERNEL_GENERIC) return record_hip(launch_generic(p.grid, p.block, stream, a));
     return CONV_E_PLAN;
 }

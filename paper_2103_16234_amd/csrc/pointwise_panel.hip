@@ -21,16 +21,26 @@ namespace convfwd {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// VEC = 4: H*W is a multiple of 4 and x, y are 16-byte aligned; a lane's four pixels 4j..4j+3 of a tile
-// lie in one image and move as one dwordx4. VEC = 1: pixel t of lane j is 16t + j and moves as a dword.
+// How the 64 pixels of a tile map to memory (PIX):
+//   kFlatVec    H*W is a multiple of 4 and x, y are 16-byte aligned: tiles cut the flattened (n, pixel) axis, a
+//               lane's four pixels 4j..4j+3 lie in one image and move as one aligned dwordx4;
+//   kFlatDword  any H*W: same tiles, pixel t of lane j is 16t + j and moves as a dword (tiny maps, where tiles
+//               per image would waste too much);
+//   kImageVec   H*W not a multiple of 4 (13x13, 27x27 maps) or pointers only dword-aligned: tiles cut each
+//               image on its own, the lane's four pixels move as one dwordx4 at a dword-aligned address (the
+//               hardware runs in unaligned-access mode; the vector type below tells the compiler), and the
+//               lanes past an image's last pixel are moved back onto its last four pixels.
 // CLAMP: C is not a multiple of 16*PD, channel indices of the padding steps are clamped per lane.
-template <int MT, int NW, int PD, int VEC, bool CLAMP>
+enum { kFlatVec = 0, kFlatDword = 1, kImageVec = 2 };
+typedef f32x4 f32x4_u __attribute__((aligned(4)));
+
+template <int MT, int NW, int PD, int PIX, bool CLAMP>
 __global__ void __launch_bounds__(64 * NW) conv_pointwise_panel(const KernelArgs a)
 {
     extern __shared__ f32x4 smem4[];
     float* const panel = reinterpret_cast<float*>(smem4);
     constexpr int NTHREADS = 64 * NW;
-    constexpr int NP = VEC == 4 ? 1 : 4;  // pixel base pointers per lane
+    constexpr int NP = PIX == kFlatDword ? 4 : 1;  // pixel base pointers per lane
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -66,15 +76,25 @@ __global__ void __launch_bounds__(64 * NW) conv_pointwise_panel(const KernelArgs
         unsigned voff[NP];
     };
     const unsigned hw4 = 4u * (unsigned)a.HW;
+    // first pixel of the lane's i-th pixel group of tile t, as (image, pixel in the image)
+    auto lane_pixel = [&](int t, int i, int& n, int& p) {
+        if constexpr (PIX == kImageVec) {
+            n = a.div_ptiles.div(t);  // a.tile_pix = tiles per image
+            p = min((t - n * a.tile_pix) * 64 + 4 * j, a.HW - 4);
+        } else {
+            const int px = PIX == kFlatVec ? min(t * 64 + 4 * j, a.total_pix - 4) : min(t * 64 + 16 * i + j, a.total_pix - 1);
+            n = a.div_PQ.div(px);
+            p = px - n * a.HW;
+        }
+    };
     auto tile_addr = [&](int t, TileAddr& ta) {
         const int tt = min(t, T - 1);
-        const int n0 = a.div_PQ.div(tt * 64);
+        const int n0 = PIX == kImageVec ? a.div_ptiles.div(tt) : a.div_PQ.div(tt * 64);
         ta.base = reinterpret_cast<const char*>(a.x) + (size_t)n0 * a.C * a.HW * 4;
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
-            const int px = VEC == 4 ? min(tt * 64 + 4 * j, a.total_pix - 4) : min(tt * 64 + 16 * i + j, a.total_pix - 1);
-            const int n = a.div_PQ.div(px);
-            const int p = px - n * a.HW;
+            int n, p;
+            lane_pixel(tt, i, n, p);
             ta.voff[i] = 4u * (unsigned)((n - n0) * a.C * a.HW + p + (CLAMP ? 0 : 4 * kq * a.HW));
         }
     };
@@ -86,8 +106,10 @@ __global__ void __launch_bounds__(64 * NW) conv_pointwise_panel(const KernelArgs
         constexpr int slot = decltype(slotc)::value;
         constexpr int e = decltype(ec)::value;
         const unsigned coff = CLAMP ? (unsigned)min(16 * s + 4 * kq + e, a.C - 1) * hw4 : soff;
-        if constexpr (VEC == 4) {
+        if constexpr (PIX == kFlatVec) {
             xr[slot][e] = *reinterpret_cast<const f32x4*>(ta.base + (ta.voff[0] + coff));
+        } else if constexpr (PIX == kImageVec) {
+            xr[slot][e] = *reinterpret_cast<const f32x4_u*>(ta.base + (ta.voff[0] + coff));
         } else {
             xr[slot][e] = f32x4{*reinterpret_cast<const float*>(ta.base + (ta.voff[0] + coff)),
                                 *reinterpret_cast<const float*>(ta.base + (ta.voff[1] + coff)),
@@ -206,9 +228,8 @@ __global__ void __launch_bounds__(64 * NW) conv_pointwise_panel(const KernelArgs
         // clamped (duplicated) inputs and filters, so they rewrite the owner's value bit for bit.
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
-            const int px = VEC == 4 ? min(ct * 64 + 4 * j, a.total_pix - 4) : min(ct * 64 + 16 * i + j, a.total_pix - 1);
-            const int n = a.div_PQ.div(px);
-            const int p = px - n * a.HW;
+            int n, p;
+            lane_pixel(ct, i, n, p);
             float* const yl = a.y + (size_t)n * a.K * a.HW + p;
 #pragma unroll
             for (int m = 0; m < MT; ++m)
@@ -216,10 +237,11 @@ __global__ void __launch_bounds__(64 * NW) conv_pointwise_panel(const KernelArgs
                 for (int v = 0; v < 4; ++v) {
                     float* const dst = yl + (size_t)min(k0 + 16 * m + 4 * kq + v, a.K - 1) * a.HW;
                     const float b = bk[m][v];
-                    if constexpr (VEC == 4) {
-                        *reinterpret_cast<f32x4*>(dst) =
-                            f32x4{finish_output(acc[m][0][v], b, a.relu), finish_output(acc[m][1][v], b, a.relu),
-                                  finish_output(acc[m][2][v], b, a.relu), finish_output(acc[m][3][v], b, a.relu)};
+                    if constexpr (PIX != kFlatDword) {
+                        const f32x4 out{finish_output(acc[m][0][v], b, a.relu), finish_output(acc[m][1][v], b, a.relu),
+                                        finish_output(acc[m][2][v], b, a.relu), finish_output(acc[m][3][v], b, a.relu)};
+                        if constexpr (PIX == kFlatVec) *reinterpret_cast<f32x4*>(dst) = out;
+                        else *reinterpret_cast<f32x4_u*>(dst) = out;
                     } else {
                         *dst = finish_output(acc[m][i][v], b, a.relu);
                     }
@@ -234,21 +256,26 @@ __global__ void __launch_bounds__(64 * NW) conv_pointwise_panel(const KernelArgs
 
 using KernFn = void (*)(const KernelArgs);
 
-template <int V, int VEC, bool CLAMP> static KernFn panel_instance()
+template <int V, int PIX, bool CLAMP> static KernFn panel_instance()
 {
     constexpr PanelVariant pv = kPanelVariants[V];
-    return conv_pointwise_panel<pv.MT, pv.NW, pv.PD, VEC, CLAMP>;
+    return conv_pointwise_panel<pv.MT, pv.NW, pv.PD, PIX, CLAMP>;
 }
 
-hipError_t launch_panel(int variant, int x_vec, int grid, int lds_bytes, hipStream_t stream, const KernelArgs& a)
+// pix: 0 flattened tiles / aligned dwordx4, 1 flattened tiles / dwords, 2 tiles per image / dword-aligned dwordx4
+hipError_t launch_panel(int variant, int pix, int grid, int lds_bytes, hipStream_t stream, const KernelArgs& a)
 {
-#define PANEL_ROW(v) {panel_instance<v, 4, false>(), panel_instance<v, 4, true>(), panel_instance<v, 1, false>(), panel_instance<v, 1, true>()},
-    static const KernFn table[kNumPanelVariants][4] = {PANEL_VARIANT_LIST(PANEL_ROW)};
-    static std::atomic<int> lds_ready[kNumPanelVariants][4][kMaxDevices] = {};
+#define PANEL_ROW(v)                                                                                        \
+    {panel_instance<v, kFlatVec, false>(),   panel_instance<v, kFlatVec, true>(),                           \
+     panel_instance<v, kFlatDword, false>(), panel_instance<v, kFlatDword, true>(),                         \
+     panel_instance<v, kImageVec, false>(),  panel_instance<v, kImageVec, true>()},
+    static const KernFn table[kNumPanelVariants][6] = {PANEL_VARIANT_LIST(PANEL_ROW)};
+    static std::atomic<int> lds_ready[kNumPanelVariants][6][kMaxDevices] = {};
+    if (pix < 0 || pix > 2) return hipErrorInvalidValue;
     if (variant < 0 || variant >= kNumPanelVariants) return hipErrorInvalidValue;
     const PanelVariant pv = kPanelVariants[variant];
     const bool clamp = a.C % (16 * pv.PD) != 0;
-    const int mode = (x_vec == 4 ? 0 : 2) + (clamp ? 1 : 0);
+    const int mode = 2 * pix + (clamp ? 1 : 0);
     const KernFn fn = table[variant][mode];
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);

@@ -137,7 +137,8 @@ def test_plans_of_the_sweep_grid_are_well_formed():
             assert s.R == 1 and s.pad_h == 0 and s.C % 4 == 0
             groups = p.tile_pix                                  # work-groups per channel tile
             assert p.grid == -(-s.K // p.tile_k) * groups
-            assert 1 <= groups * (block // 64) <= -(-total // 64) + block // 64   # no more waves than 64-pixel tiles (+ one work-group)
+            tiles = s.N * -(-(s.H * s.W) // 64)                      # at most: tiles cut per image
+            assert 1 <= groups * (block // 64) <= tiles + block // 64   # no more waves than 64-pixel tiles (+ one work-group)
             assert p.lds_bytes >= 4 * p.tile_k * s.C                 # the whole filter panel of a channel tile
     assert families == {tap, pw, panel}
 

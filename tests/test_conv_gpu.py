@@ -149,6 +149,9 @@ PANEL_SHAPES = POINTWISE_SHAPES + [
     S("p_batch_7x7", 9, 20, 7, 7, 35, 1, 1, 0, 0),         # dword pixels, 441 of them; C = 20 pads to 64
     S("p_batch_deep", 5, 132, 8, 8, 18, 1, 1, 0, 0),       # 9 steps pad to 12: clamped channel indices
     S("p_batch_c64", 6, 64, 8, 10, 64, 1, 1, 0, 0),        # nothing ragged: the unclamped, unmasked instance
+    S("p_batch_13x13", 7, 24, 13, 13, 40, 1, 1, 0, 0),     # 169 pixels: dwords over flattened tiles
+    S("p_batch_27x27", 3, 16, 27, 27, 33, 1, 1, 0, 0),     # 729 pixels: twelve tiles per image (dword-aligned dwordx4), the last with 25 pixels
+    S("p_batch_11x23", 4, 20, 11, 23, 19, 1, 1, 0, 0),     # 253 pixels: four tiles per image, 3 pixels short
 ]
 
 
@@ -340,6 +343,27 @@ def test_misaligned_pointers_fall_back_to_narrow_loads():
         torch.cuda.synchronize()
         ok, worst = oracle.within_tolerance(y.cpu().numpy(), y_ref, ya_ref)
         assert ok, worst
+
+
+def test_panel_kernel_with_dword_aligned_tensors():
+    """x and y that are only 4-byte aligned: the panel kernel moves pixels as dwordx4 at dword-aligned addresses."""
+    shape = S("p_misaligned", 3, 32, 10, 25, 40, 1, 1, 0, 0)      # 250 pixels: four tiles per image, 6 pixels short
+    x, w, y_ref, ya_ref = _reference(shape)
+    ny = int(np.prod(shape.y_shape))
+    for off in (1, 3):
+        xbuf = torch.zeros(x.size + 4, device="cuda")
+        ybuf = torch.full((ny + 8,), float("nan"), device="cuda")
+        xd = xbuf[off:off + x.size].view(x.shape)
+        yd = ybuf[off:off + ny].view(shape.y_shape)
+        xd.copy_(torch.from_numpy(x))
+        _say(f"[case] panel kernel, x and y misaligned by {off} floats")
+        _, plan = binding.conv_fwd_planned(xd, torch.from_numpy(w).cuda(), 0, 0, PANEL, 7, 0, y=yd)
+        torch.cuda.synchronize()
+        assert plan.kernel == PANEL and plan.x_vec == 4
+        ok, worst = oracle.within_tolerance(yd.cpu().numpy(), y_ref, ya_ref)
+        assert ok, worst
+        guard = ybuf.cpu().numpy()
+        assert np.isnan(guard[:off]).all() and np.isnan(guard[off + ny:]).all()    # nothing written outside y
 
 
 def test_runs_on_the_callers_stream():
