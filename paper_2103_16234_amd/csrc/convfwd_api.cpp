@@ -320,7 +320,12 @@ int pick_pointwise(const Shape& s)
 int pick_panel(const Shape& s, int x_cap, int y_cap)
 {
     const int64_t tiles = ((int64_t)s.N * s.H * s.W + 63) / 64;
-    if (tiles * ceil_div(s.K, 32) < 704) return -1;
+    if (tiles * ceil_div(s.K, 32) < 704) {
+        // fewer 32-channel units than that, but enough 16-channel ones: 16 channels per panel still beat the
+        // channel-splitting kernel by 5-25 % in the sweeps (deep layers on 7..14-pixel maps at batch 8..32)
+        if (tiles * ceil_div(s.K, 16) >= 704 && 16 * (round_up(s.C, 64) + 4) * 4 <= kLdsMax) return 5;  // {1, 4, 4}
+        return -1;
+    }
     const bool dwords = panel_pixel_mode(s, x_cap, y_cap) == 1;
     const int c64 = round_up(s.C, 32);
     if (dwords && s.K >= 64 && tiles * ceil_div(s.K, 64) >= 704 && 64 * (c64 + 4) * 4 <= kLdsMax) return 6;  // {4, 4, 2}
