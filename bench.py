@@ -209,9 +209,10 @@ def paper_shapes(torch, binding, inputs, oracle):
     return rows
 
 
-def sweep(torch, binding, inputs, oracle, only=None):
+def sweep(torch, binding, inputs, oracle, only=None, find=False):
     """Second workload: every shape of the synthetic sweep grid, timed like the layers and spot-checked against the oracle."""
     rows = []
+    flush = torch.empty(128 * 1024 * 1024, device="cuda") if find else None   # 512 MiB: twice the Infinity Cache
     for shape in inputs.sweep_shapes():
         if only and only not in shape.name:
             continue
@@ -222,9 +223,17 @@ def sweep(torch, binding, inputs, oracle, only=None):
         roof = layer.roofline(e_ms)
         par = layer.parity_sample(oracle, 128)
         p = layer.plan
-        rows.append({"shape": shape.name, "kernel_us": e_ms * 1e3, "tflops": shape.flops / e_ms / 1e9,
-                     "gbs": shape.algorithmic_bytes / e_ms / 1e6, "bound": roof["bound"], "frac": roof["frac"],
-                     "plan": [p.kernel, p.variant, p.tile_pix, p.grid, p.block], "parity_ok": par["ok"]})
+        rec = {"shape": shape.name, "kernel_us": e_ms * 1e3, "tflops": shape.flops / e_ms / 1e9,
+               "gbs": shape.algorithmic_bytes / e_ms / 1e6, "bound": roof["bound"], "frac": roof["frac"],
+               "plan": [p.kernel, p.variant, p.tile_pix, p.grid, p.block], "parity_ok": par["ok"]}
+        if find:
+            # measured choice of the mapping (conv_fwd_find), then the same rotating-buffer timing with it
+            _, fp, _ = binding.conv_fwd_find(layer.x[0], layer.w[0], shape.pad_h, shape.pad_w, y=layer.y[0], flush=flush)
+            _, f_ms = layer.measure(k, 3)
+            fpar = layer.parity_sample(oracle, 128)
+            rec.update({"found_us": f_ms * 1e3, "found_plan": [fp.kernel, fp.variant, fp.tile_pix, fp.grid, fp.block],
+                        "found_frac": layer.roofline(f_ms)["frac"], "found_parity_ok": fpar["ok"]})
+        rows.append(rec)
         print(f"sweep {shape.name}: {e_ms * 1e3:.1f} us {roof['bound']} {roof['frac']:.3f} parity {par['ok']}",
               file=sys.stderr, flush=True)
         del layer
@@ -244,6 +253,8 @@ def main():
                     help="also time the fused kernels and the paper's two-stage scheme on the shapes the paper profiles")
     ap.add_argument("--sweep", nargs="?", const="", default=None, metavar="SUBSTR",
                     help="also run the synthetic shape sweep (optionally only shapes whose name contains SUBSTR)")
+    ap.add_argument("--find", action="store_true",
+                    help="with --sweep: also time each layer with the mapping conv_fwd_find measures to be fastest")
     ns = ap.parse_args()
     if ns.gpus != 1:
         _fail("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -301,7 +312,7 @@ def main():
     if ns.paper_shapes:
         out["paper_shapes"] = paper_shapes(torch, binding, inputs, oracle)
     if ns.sweep is not None:
-        out["sweep"] = sweep(torch, binding, inputs, oracle, ns.sweep)
+        out["sweep"] = sweep(torch, binding, inputs, oracle, ns.sweep, ns.find)
     if not ns.no_cpu:
         out["cpu_baseline"] = cpu_baseline(oracle, inputs, ns.config)
     print(json.dumps(out))

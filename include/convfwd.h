@@ -107,6 +107,25 @@ int conv_fwd_planned(const float* x, const float* w, float* y,
                      const conv_plan_t* plan, conv_plan_t* resolved);
 
 /*
+ * Measured choice of the mapping, for callers who run a layer many times (what "the best algorithm of the
+ * library" means in the comparisons of Section 4): runs every mapping the kernels accept for this layer on
+ * the caller's tensors - all tile shapes of the matching families with the planner's candidate pixel tiles,
+ * tap shapes only while their modelled cost is within 2.5x of the best - times each with events on the
+ * library's stream, and keeps the fastest: it is stored in the plan cache, so conv_fwd and
+ * conv_fwd_bias_relu use it from then on for this shape and pointer alignment, and returned in *best_plan
+ * with its time per launch in *best_us (either may be null). Without a flush buffer each mapping is timed
+ * over a batch of 2..16 back-to-back launches on cache-warm tensors. With one (flush: 16-byte aligned device
+ * memory of flush_bytes >= 1 MiB owned by the caller, contents overwritten; 512 MiB clears the 256 MiB
+ * Infinity Cache) every timed launch runs alone after the buffer has been streamed through the caches,
+ * three times, and the fastest counts: the ranking a layer sees whose inputs come from HBM.
+ * y is overwritten repeatedly and finally holds conv(x, w). Synchronous (waits for the stream, so it cannot
+ * be captured into a graph); allocates no device memory. Returns CONV_OK or the error codes of conv_fwd.
+ */
+int conv_fwd_find(const float* x, const float* w, float* y,
+                  int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
+                  void* flush, long long flush_bytes, conv_plan_t* best_plan, float* best_us);
+
+/*
  * The layer with its fused epilogue: y = act(conv(x, w) + bias[k]). Section 2.1: the weighted sums of a
  * convolutional layer are usually passed through a non-linear function such as ReLU; the per-filter
  * constant is what CNN layers add before it (the paper does not mention one: pass null to leave it out).

@@ -18,7 +18,7 @@ CONV_KERNEL_TAP = 1
 CONV_KERNEL_POINTWISE = 2
 CONV_KERNEL_PANEL = 3
 
-EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_two_stage_workspace_bytes",
+EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_fwd_find", "conv_two_stage_workspace_bytes",
            "conv_fwd_two_stage",
            "conv_variant_count", "conv_variant_info", "conv_set_stream", "conv_strerror")
 
@@ -64,6 +64,8 @@ def load_library():
     lib.conv_fwd_plan.argtypes = dims + [ctypes.POINTER(ConvPlan)]
     lib.conv_fwd_planned.argtypes = [vp, vp, vp] + dims + [ctypes.POINTER(ConvPlan), ctypes.POINTER(ConvPlan)]
     lib.conv_fwd_bias_relu.argtypes = [vp, vp, vp, vp] + dims + [ci, ctypes.POINTER(ConvPlan), ctypes.POINTER(ConvPlan)]
+    lib.conv_fwd_find.argtypes = [vp, vp, vp] + dims + [vp, ctypes.c_longlong, ctypes.POINTER(ConvPlan),
+                                                        ctypes.POINTER(ctypes.c_float)]
     lib.conv_two_stage_workspace_bytes.argtypes = dims
     lib.conv_two_stage_workspace_bytes.restype = ctypes.c_longlong
     lib.conv_fwd_two_stage.argtypes = [vp, vp, vp, vp, ctypes.c_longlong] + dims
@@ -175,6 +177,21 @@ def conv_fwd_bias_relu(x, w, bias, pad_h: int, pad_w: int, relu: bool, kernel=No
                                   *dims, int(bool(relu)), ctypes.byref(req) if req is not None else None,
                                   ctypes.byref(res)))
     return y, res
+
+
+def conv_fwd_find(x, w, pad_h: int, pad_w: int, y=None, flush=None, use_current_stream: bool = True):
+    """Time every mapping for this layer, keep the fastest for later conv_fwd calls; returns (y, plan, microseconds).
+    flush: optional device tensor (>= 1 MiB, overwritten) streamed through the caches before every timed launch."""
+    import torch
+    y, dims = _device_args(x, w, y, pad_h, pad_w)
+    lib = load_library()
+    if use_current_stream:
+        conv_set_stream(torch.cuda.current_stream(x.device))
+    plan, us = ConvPlan(), ctypes.c_float(0)
+    fptr, fbytes = (flush.data_ptr(), flush.numel() * flush.element_size()) if flush is not None else (None, 0)
+    _check(lib.conv_fwd_find(x.data_ptr(), w.data_ptr(), y.data_ptr(), *dims, fptr, fbytes, ctypes.byref(plan),
+                             ctypes.byref(us)))
+    return y, plan, float(us.value)
 
 
 def conv_two_stage_workspace_bytes(N, C, H, W, K, R, S, pad_h, pad_w) -> int:

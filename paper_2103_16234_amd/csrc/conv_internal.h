@@ -180,6 +180,8 @@ hipError_t launch_panel(int variant, int pix, int grid, int lds_bytes, hipStream
 hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid, int lds_bytes,
                       hipStream_t stream, const KernelArgs& a);
 hipError_t launch_generic(int grid, int block, hipStream_t stream, const KernelArgs& a);
+// scratch: 16-byte aligned device memory of at least `bytes` bytes; contents are overwritten
+hipError_t launch_scratch_fill(void* scratch, long long bytes, hipStream_t stream);
 // temp: R*S*N*K*P*Q floats (unused for 1x1 filters)
 hipError_t launch_two_stage(hipStream_t stream, const KernelArgs& a, float* temp);
 

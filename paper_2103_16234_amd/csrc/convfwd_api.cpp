@@ -427,6 +427,28 @@ int plan_shape(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, 
     return rc;
 }
 
+// Candidate pixel tiles of a tap tile shape: full capacity, an even split, whole images, whole rows, halves, quarters.
+int tap_tile_candidates(const Shape& s, const TapVariant& tv, int (&cands)[8])
+{
+    const int PQ = s.P * s.Q;
+    const int64_t total = (int64_t)s.N * PQ;
+    const int cap = tv.max_pix();
+    int nc = 0;
+    cands[nc++] = (int)std::min<int64_t>(cap, total);
+    cands[nc++] = (int)((total + (total + cap - 1) / cap - 1) / ((total + cap - 1) / cap));
+    if (PQ <= cap) cands[nc++] = cap / PQ * PQ;
+    if (PQ > cap) {
+        const int parts = ceil_div(PQ, cap);
+        if (PQ % parts == 0) cands[nc++] = PQ / parts;
+        for (int d = parts; d <= std::min(PQ, parts + 8); ++d)
+            if (PQ % d == 0) { cands[nc++] = PQ / d; break; }
+    }
+    if (s.Q <= cap) cands[nc++] = cap / s.Q * s.Q;
+    if (cap >= 32) cands[nc++] = cap / 2;
+    if (cap >= 64) cands[nc++] = cap / 4;
+    return nc;
+}
+
 int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
 {
     const TunedEntry* const tuned = find_tuned(s);
@@ -444,26 +466,10 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_pl
             return CONV_OK;
         bool found = false;
         double best = 0;
-        const int PQ = s.P * s.Q;
-        const int64_t total = (int64_t)s.N * PQ;
         for (int v = 0; v < kNumTapVariants; ++v) {
             const TapVariant tv = kTapVariants[v];
-            const int cap = tv.max_pix();
-            // candidate pixel tiles: full capacity, an even split, whole images, whole rows
             int cands[8];
-            int nc = 0;
-            cands[nc++] = (int)std::min<int64_t>(cap, total);
-            cands[nc++] = (int)((total + (total + cap - 1) / cap - 1) / ((total + cap - 1) / cap));
-            if (PQ <= cap) cands[nc++] = cap / PQ * PQ;
-            if (PQ > cap) {
-                const int parts = ceil_div(PQ, cap);
-                if (PQ % parts == 0) cands[nc++] = PQ / parts;
-                for (int d = parts; d <= std::min(PQ, parts + 8); ++d)
-                    if (PQ % d == 0) { cands[nc++] = PQ / d; break; }
-            }
-            if (s.Q <= cap) cands[nc++] = cap / s.Q * s.Q;
-            if (cap >= 32) cands[nc++] = cap / 2;
-            if (cap >= 64) cands[nc++] = cap / 4;
+            const int nc = tap_tile_candidates(s, tv, cands);
             for (int i = 0; i < nc; ++i) {
                 conv_plan_t cp;
                 KernelArgs ca;
@@ -578,6 +584,123 @@ extern "C" int conv_fwd_bias_relu(const float* x, const float* w, const float* b
                                   conv_plan_t* resolved)
 {
     return run_planned(x, w, bias, y, N, C, H, W, K, R, S, pad_h, pad_w, relu != 0, plan, resolved);
+}
+
+// Every mapping worth timing for a layer: all pointwise and panel shapes (with the planner's grid), every tap shape x
+// candidate pixel tile whose modelled cost is within 2.5x of the best modelled one, or the generic kernel.
+struct Candidate {
+    conv_plan_t p;
+    KernelArgs a;
+    double model;  // tap family: modelled cycles; 0 elsewhere
+};
+
+static void enumerate_candidates(const Shape& s, int x_cap, int w_cap, int y_cap, std::vector<Candidate>* out)
+{
+    Candidate c;
+    c.model = 0;
+    if (pointwise_ok(s, x_cap, w_cap, y_cap)) {
+        for (int v = 0; v < kNumPointwiseVariants; ++v)
+            if (resolve_pointwise(s, v, x_cap, w_cap, y_cap, &c.p, &c.a)) out->push_back(c);
+        for (int v = 0; v < kNumPanelVariants; ++v)
+            if (resolve_panel(s, v, 0, x_cap, w_cap, y_cap, &c.p, &c.a)) out->push_back(c);
+    }
+    if (tap_rs_index(s) >= 0) {
+        std::vector<Candidate> taps;
+        double best = 0;
+        for (int v = 0; v < kNumTapVariants; ++v) {
+            const TapVariant tv = kTapVariants[v];
+            int cands[8];
+            const int nc = tap_tile_candidates(s, tv, cands);
+            for (int i = 0; i < nc; ++i) {
+                bool seen = false;
+                for (int k = 0; k < i; ++k) seen = seen || cands[k] == cands[i];
+                if (seen || cands[i] < 1 || !resolve_tap(s, v, cands[i], 0, x_cap, w_cap, &c.p, &c.a)) continue;
+                c.model = tap_cost(c.p, c.a, tv, s.R * s.S);
+                if (taps.empty() || c.model < best) best = c.model;
+                taps.push_back(c);
+            }
+        }
+        for (const Candidate& t : taps)
+            if (t.model <= 2.5 * best) out->push_back(t);
+    }
+    if (out->empty()) {
+        resolve_generic(s, &c.p, &c.a);
+        c.model = 0;
+        out->push_back(c);
+    }
+}
+
+extern "C" int conv_fwd_find(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,
+                             int pad_h, int pad_w, void* flush, long long flush_bytes, conv_plan_t* best_plan,
+                             float* best_us)
+{
+    if (!x || !w || !y) return CONV_E_NULL;
+    Shape s;
+    if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
+    int x_cap, w_cap, y_cap;
+    pointer_caps(x, w, y, &x_cap, &w_cap, &y_cap);
+    const bool cold = flush && flush_bytes >= (1 << 20) && reinterpret_cast<uintptr_t>(flush) % 16 == 0;
+    std::vector<Candidate> cands;
+    enumerate_candidates(s, x_cap, w_cap, y_cap, &cands);
+
+    hipStream_t stream = g_stream.load();
+    hipEvent_t t0, t1;
+    if (int rc = record_hip(hipEventCreate(&t0))) return rc;
+    if (int rc = record_hip(hipEventCreate(&t1))) { (void)hipEventDestroy(t0); return rc; }
+    int best = -1, rc_last = CONV_E_PLAN;
+    float best_ms = 0.f;
+    for (size_t i = 0; i < cands.size(); ++i) {
+        Candidate& c = cands[i];
+        int rc = launch(c.p, c.a, s, x, w, y);  // warm-up: kernel attributes, instruction caches
+        float ms = 0.f;
+        if (cold) {
+            // three single launches, each after the scratch buffer has been streamed through the caches; the fastest counts
+            for (int rep = 0; rep < 3 && rc == CONV_OK; ++rep) {
+                float one = 0.f;
+                rc = record_hip(launch_scratch_fill(flush, flush_bytes, stream));
+                if (rc == CONV_OK) rc = record_hip(hipEventRecord(t0, stream));
+                if (rc == CONV_OK) rc = launch(c.p, c.a, s, x, w, y);
+                if (rc == CONV_OK) rc = record_hip(hipEventRecord(t1, stream));
+                if (rc == CONV_OK) rc = record_hip(hipEventSynchronize(t1));
+                if (rc == CONV_OK) rc = record_hip(hipEventElapsedTime(&one, t0, t1));
+                ms = rep == 0 ? one : std::min(ms, one);
+            }
+        } else {
+            // one launch timed alone to size the batch, then a batch of 2..16
+            for (int pass = 0; pass < 2 && rc == CONV_OK; ++pass) {
+                const int reps = pass == 0 ? 1 : std::max(2, std::min(16, (int)(0.1f / std::max(ms, 1e-4f))));
+                rc = record_hip(hipEventRecord(t0, stream));
+                for (int r = 0; r < reps && rc == CONV_OK; ++r) rc = launch(c.p, c.a, s, x, w, y);
+                if (rc == CONV_OK) rc = record_hip(hipEventRecord(t1, stream));
+                if (rc == CONV_OK) rc = record_hip(hipEventSynchronize(t1));
+                if (rc == CONV_OK) rc = record_hip(hipEventElapsedTime(&ms, t0, t1));
+                ms /= reps;
+            }
+        }
+        if (rc != CONV_OK) { rc_last = rc; continue; }
+        if (best < 0 || ms < best_ms) { best = (int)i; best_ms = ms; }
+    }
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
+    if (best < 0) return rc_last;
+    {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        bool replaced = false;
+        for (CacheEntry& e : g_cache)
+            if (same_shape(e.s, s) && e.x_cap == x_cap && e.w_cap == w_cap && e.y_cap == y_cap) {
+                e.p = cands[best].p; e.a = cands[best].a;
+                replaced = true;
+            }
+        if (!replaced) {
+            if (g_cache.size() >= kCacheEntries) g_cache.erase(g_cache.begin());
+            g_cache.push_back(CacheEntry{s, x_cap, w_cap, y_cap, cands[best].p, cands[best].a});
+        }
+    }
+    // leave y holding the result of the mapping that won
+    if (int rc = launch(cands[best].p, cands[best].a, s, x, w, y)) return rc;
+    if (best_plan) *best_plan = cands[best].p;
+    if (best_us) *best_us = best_ms * 1000.f;
+    return CONV_OK;
 }
 
 extern "C" long long conv_two_stage_workspace_bytes(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w)

@@ -64,6 +64,8 @@ def test_argument_errors_are_codes_not_crashes(lib):
     assert lib.conv_fwd_two_stage(1 << 20, 1 << 20, 1 << 20, None, 0, *ok) == -1      # workspace needed but null
     assert lib.conv_fwd_two_stage(1 << 20, 1 << 20, 1 << 20, 1 << 20, 16, *ok) == -7   # too small
     assert lib.conv_fwd_two_stage(1 << 20, 1 << 20, 1 << 20, 1 << 20, 1 << 40, 1, 20000, 8, 8, 4, 3, 3, 1, 1) == -6
+    assert lib.conv_fwd_find(None, None, None, *ok, None, 0, None, None) == -1
+    assert lib.conv_fwd_find(1 << 20, 1 << 20, 1 << 20, 1, 4, 2, 8, 4, 5, 5, 1, 2, None, 0, None, None) == -3   # validated before any GPU call
     for code in (0, -1, -2, -3, -4, -5, -6, -7, -99):
         assert binding.conv_strerror(code)
     with pytest.raises(binding.ConvError) as e:

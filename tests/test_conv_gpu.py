@@ -437,3 +437,23 @@ def test_conv_fwd_replays_from_a_hip_graph():
             again = binding.conv_fwd(xd, wd, s.pad_h, s.pad_w)     # eager work between replays
             torch.cuda.synchronize()
             assert torch.equal(again, eager)
+
+
+@pytest.mark.parametrize("shape", [SMALL[0], SMALL[6], POINTWISE_SHAPES[0], PANEL_SHAPES[8], NONSQUARE[0]], ids=lambda s: s.name)
+def test_find_keeps_the_fastest_mapping(shape):
+    """conv_fwd_find times every mapping, leaves y correct, and later conv_fwd calls use the winner."""
+    x, w, y_ref, ya_ref = _reference(shape)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    yd = torch.full(shape.y_shape, float("nan"), device="cuda")
+    _say(f"[case] find {shape.name} dims={shape.dims}")
+    flush = torch.empty(1 << 20, device="cuda") if shape.R == 3 else None     # 4 MiB scratch: the cold-cache timing path
+    _, plan, us = binding.conv_fwd_find(xd, wd, shape.pad_h, shape.pad_w, y=yd, flush=flush)
+    torch.cuda.synchronize()
+    assert us > 0 and plan.workspace_bytes == 0 and plan.grid >= 1
+    ok, worst = oracle.within_tolerance(yd.cpu().numpy(), y_ref, ya_ref)
+    assert ok, worst
+    again = binding.conv_fwd_plan(*shape.dims)                  # aligned tensors: the same cache entry
+    assert (again.kernel, again.variant, again.tile_pix, again.grid) == (plan.kernel, plan.variant, plan.tile_pix, plan.grid)
+    y2 = binding.conv_fwd(xd, wd, shape.pad_h, shape.pad_w)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, yd)                                    # same mapping, same bits
