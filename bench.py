@@ -144,7 +144,10 @@ def cpu_baseline(oracle, inputs, index, budget_macs=4e9):
     n = int(max(1, min(s.N, budget_macs // macs_per_image)))
     cores = min(os.cpu_count() or 1, 16)
     oracle.conv_ref(x[:1, :, :4, :4], w[:1], s.pad_h, s.pad_w, nthreads=1)   # load the library
-    reps = int(max(1, min(20, 2e9 // (macs_per_image * n))))
+    t0 = time.perf_counter()
+    oracle.conv_ref(x[:n], w, s.pad_h, s.pad_w, nthreads=cores)
+    first = time.perf_counter() - t0
+    reps = int(max(1, min(1000, 10.0 / max(first, 1e-4))))      # about ten seconds of CPU work in all
     t0 = time.perf_counter()
     for _ in range(reps):
         oracle.conv_ref(x[:n], w, s.pad_h, s.pad_w, nthreads=cores)
