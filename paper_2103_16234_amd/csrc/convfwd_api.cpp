@@ -124,6 +124,7 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     const int64_t total64 = (int64_t)s.N * s.P * s.Q;
     if (tile_pix == 0) tile_pix = (int)std::min<int64_t>(tv.max_pix(), total64);
     if (tile_pix < 1 || tile_pix > tv.max_pix()) return false;
+    if (total64 > (int64_t)INT32_MAX - 4096) return false;  // pixel indices of the last, partly empty tile stay inside 32 bits
     const int total = (int)total64;
 
     int w_vec = (s.C % 4 == 0 && w_cap >= 4) ? 4 : 1;

@@ -457,3 +457,33 @@ def test_find_keeps_the_fastest_mapping(shape):
     y2 = binding.conv_fwd(xd, wd, shape.pad_h, shape.pad_w)
     torch.cuda.synchronize()
     assert torch.equal(y2, yd)                                    # same mapping, same bits
+
+
+@pytest.mark.parametrize("dims,period", [((4095, 8, 256, 256, 3, 3, 3, 1, 1), 7),        # x: 2,146,959,360 elements
+                                         ((4095, 4, 64, 64, 128, 1, 1, 0, 0), 7)],       # y: 2,146,959,360 elements
+                         ids=["x_near_2^31", "y_near_2^31"])
+def test_tensors_just_below_the_element_limit(dims, period):
+    """Maximum sizes: the largest tensors the boundary accepts (2^31 - 1 elements). The batch repeats a block of
+    `period` distinct seeded images, so the oracle can evaluate sampled outputs from the block alone."""
+    N, C, H, W, K, R, S, ph, pw = dims
+    block = inputs.ConvShape("block", period, C, H, W, K, R, S, ph, pw, "u01", "he", 71, 72)
+    xb, w = inputs.make_inputs(block)
+    assert N % period == 0 and N * C * H * W < 2 ** 31 and N * K * block.P * block.Q < 2 ** 31
+    xd = torch.from_numpy(xb).cuda().repeat(N // period, 1, 1, 1)
+    wd = torch.from_numpy(w).cuda()
+    _say(f"[case] near-limit tensors dims={dims}")
+    y = binding.conv_fwd(xd, wd, ph, pw)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    npts = 400
+    coords = np.stack([rng.integers(0, d, npts) for d in (N, K, block.P, block.Q)], axis=1)
+    coords[:40, 0] = N - 1                                   # the far end of the tensors
+    coords[:20, 2], coords[:20, 3] = block.P - 1, block.Q - 1
+    coords[40:60, 0] = 0
+    got = y[tuple(torch.from_numpy(coords.T).cuda())].cpu().numpy().astype(np.float64)
+    folded = coords.copy().astype(np.int32)
+    folded[:, 0] %= period
+    ref, ref_abs = oracle.conv_ref_points(xb, w, ph, pw, folded)
+    ok, worst = oracle.within_tolerance(got, ref, ref_abs)
+    assert ok, worst
+    assert not torch.isnan(y[-1]).any() and not torch.isnan(y[0]).any()
