@@ -135,9 +135,10 @@ constexpr TapVariant kTapVariants[] = {
     {1, 2, 1, 1, 8, 1, 2, 4, 16},   // 18: 16 ch x  32 px, 8 channel shares (32-channel chunks)
     {1, 7, 2, 1, 4, 2, 2, 8, 12},   // 19: as 12 with 32-channel chunks: half as many barriers per layer
     {1, 2, 1, 1, 4, 2, 2, 4, 16},   // 20: as 11 with 32-channel chunks
+    {1, 11, 4, 1, 2, 2, 2, 4, 12},  // 21: 64 ch x 176 px: a whole 13x13 image per work-group
 };
 constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
-#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18) X(19) X(20)
+#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18) X(19) X(20) X(21)
 
 // Tile shapes of the pointwise (1x1, no padding) family: a work-group is WC x WP waves on 16*MT output
 // channels x WP*64 contiguous pixels of one image; the WC shares split the input channels.

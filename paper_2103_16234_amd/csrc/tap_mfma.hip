@@ -152,7 +152,9 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
                 const int n = a.div_Hp.div(v);
                 const int h = v - n * a.Hp - a.pad_h;
                 if (n < a.N && h >= 0 && h < a.H) {
-                    xg[i] = ((n * a.C + c_l) * a.H + h) * a.W + cv * VX;
+                    // unsigned: a padding channel of the last image may lie past 2^31 elements before the ragged
+                    // chunk is retargeted
+                    xg[i] = (static_cast<unsigned>(n * a.C + c_l) * a.H + h) * a.W + cv * VX;
                     xl[i] = (c_l * a.lds_plane + row * a.lds_pitch + a.col_shift + a.pad_w + cv * VX) | (c_l << 16);
                 }
             }
