@@ -487,3 +487,23 @@ def test_tensors_just_below_the_element_limit(dims, period):
     ok, worst = oracle.within_tolerance(got, ref, ref_abs)
     assert ok, worst
     assert not torch.isnan(y[-1]).any() and not torch.isnan(y[0]).any()
+
+
+@pytest.mark.parametrize("shape", inputs.sweep_shapes()[3::13], ids=lambda s: s.name)
+def test_sweep_layers_at_full_size(shape):
+    """A slice of the synthetic sweep (every family, batch 1..128) at full size with the default plan: sampled
+    outputs against the oracle, plus the layer's corners and last image."""
+    x, w = inputs.make_inputs(shape)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    yd = torch.full(shape.y_shape, float("nan"), device="cuda")
+    _say(f"[case] sweep layer {shape.name} dims={shape.dims}")
+    binding.conv_fwd(xd, wd, shape.pad_h, shape.pad_w, y=yd)
+    torch.cuda.synchronize()
+    assert not torch.isnan(yd).any(), "some outputs were never written"
+    rng = np.random.default_rng(11)
+    coords = np.stack([rng.integers(0, d, 300) for d in shape.y_shape], axis=1).astype(np.int32)
+    coords[:8] = [[n, k, p, q] for n in (0, shape.N - 1) for k in (0, shape.K - 1) for (p, q) in ((0, 0), (shape.P - 1, shape.Q - 1))]
+    got = yd[tuple(torch.from_numpy(coords.T.astype(np.int64)).cuda())].cpu().numpy().astype(np.float64)
+    ref, ref_abs = oracle.conv_ref_points(x, w, shape.pad_h, shape.pad_w, coords)
+    ok, worst = oracle.within_tolerance(got, ref, ref_abs)
+    assert ok, worst
