@@ -136,6 +136,36 @@ class Layer:
         return {"points": npts, "ok": ok, "worst_ratio": worst}
 
 
+def probes(torch, binding):
+    """What this GPU attains, measured with the library's two micro-probes: fp32 MFMA rate and dwordx4 copy bandwidth."""
+    lib = binding.load_library()
+    sink = torch.zeros(1, device="cuda")
+    src = torch.ones(64 * 1024 * 1024, device="cuda")      # 256 MiB each way: past the Infinity Cache
+    dst = torch.empty_like(src)
+    nbytes = src.numel() * 4
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    out = {}
+    flops = lib.conv_probe_mfma(2000, sink.data_ptr())
+    assert flops > 0
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(5):
+        lib.conv_probe_mfma(2000, sink.data_ptr())
+    e1.record()
+    torch.cuda.synchronize()
+    out["mfma_fp32_tflops"] = 5 * flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    assert lib.conv_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes) == 0
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(10):
+        lib.conv_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes)
+    e1.record()
+    torch.cuda.synchronize()
+    out["copy_read_plus_write_gbs"] = 10 * 2 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    assert bool((dst[:: 1 << 20] == 1).all())
+    return out
+
+
 def cpu_baseline(oracle, inputs, index, budget_macs=4e9):
     """The oracle as it stands, on this host's cores, on the whole layer or on its first images."""
     s = inputs.config(index)
@@ -300,6 +330,12 @@ def main():
     }
     del head
     torch.cuda.empty_cache()
+    measured = probes(torch, binding)
+    out["probes"] = measured
+    roof = out["roofline"]
+    roof["frac_of_measured"] = roof["achieved"] / (measured["copy_read_plus_write_gbs"] if roof["bound"] == "hbm"
+                                                   else measured["mfma_fp32_tflops"])
+    torch.cuda.empty_cache()
     if not ns.no_layers:
         layers = []
         for i in range(1, 6):
@@ -308,6 +344,8 @@ def main():
             w_ms, e_ms = layer.measure(k, ns.warmup)
             rec = layer.report(w_ms, e_ms, k)
             rec["parity"] = layer.parity_sample(oracle, 256)
+            rec["frac_of_measured_mfma"] = rec["gflops"] / 1e3 / measured["mfma_fp32_tflops"]
+            rec["frac_of_measured_copy_bw"] = rec["gbs"] / measured["copy_read_plus_write_gbs"]
             layers.append(rec)
             del layer
             torch.cuda.empty_cache()

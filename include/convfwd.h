@@ -155,6 +155,17 @@ int conv_fwd_two_stage(const float* x, const float* w, float* y, float* workspac
                        int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w);
 
 /*
+ * Measurement aids, not part of the convolution: two micro-probes of what the GPU attains, so that the
+ * benchmark can quote fractions of measured peaks beside the datasheet ones. conv_probe_mfma enqueues a
+ * register-resident fp32 MFMA loop (8192 waves x iters x 16 v_mfma_f32_16x16x4_f32) and returns the
+ * number of floating-point operations it performs (or a negative CONV_E_*); sink: device pointer to one
+ * float, never written in practice. conv_probe_copy enqueues a dwordx4 copy of `bytes` bytes (rounded down to
+ * a multiple of 16) between two 16-byte aligned device buffers. Both run on the library's stream; the caller times them.
+ */
+long long conv_probe_mfma(int iters, float* sink);
+int conv_probe_copy(const void* src, void* dst, long long bytes);
+
+/*
  * Number of tile shapes of a kernel family (0 for an unknown family), and the
  * capacity of one: output channels and output pixels per work-group and
  * threads per work-group. Host-only. Returns CONV_E_PLAN for bad indices.

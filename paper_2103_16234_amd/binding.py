@@ -19,7 +19,7 @@ CONV_KERNEL_POINTWISE = 2
 CONV_KERNEL_PANEL = 3
 
 EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_fwd_find", "conv_two_stage_workspace_bytes",
-           "conv_fwd_two_stage",
+           "conv_fwd_two_stage", "conv_probe_mfma", "conv_probe_copy",
            "conv_variant_count", "conv_variant_info", "conv_set_stream", "conv_strerror")
 
 
@@ -69,13 +69,16 @@ def load_library():
     lib.conv_two_stage_workspace_bytes.argtypes = dims
     lib.conv_two_stage_workspace_bytes.restype = ctypes.c_longlong
     lib.conv_fwd_two_stage.argtypes = [vp, vp, vp, vp, ctypes.c_longlong] + dims
+    lib.conv_probe_mfma.argtypes = [ci, vp]
+    lib.conv_probe_mfma.restype = ctypes.c_longlong
+    lib.conv_probe_copy.argtypes = [vp, vp, ctypes.c_longlong]
     lib.conv_variant_count.argtypes = [ci]
     lib.conv_variant_info.argtypes = [ci, ci] + [ctypes.POINTER(ci)] * 3
     lib.conv_set_stream.argtypes = [vp]
     lib.conv_strerror.argtypes = [ci]
     lib.conv_strerror.restype = ctypes.c_char_p
     for name in EXPORTS:
-        if name not in ("conv_strerror", "conv_two_stage_workspace_bytes"):
+        if name not in ("conv_strerror", "conv_two_stage_workspace_bytes", "conv_probe_mfma"):
             getattr(lib, name).restype = ci
     _lib = lib
     return lib

@@ -183,6 +183,9 @@ hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid,
 hipError_t launch_generic(int grid, int block, hipStream_t stream, const KernelArgs& a);
 // scratch: 16-byte aligned device memory of at least `bytes` bytes; contents are overwritten
 hipError_t launch_scratch_fill(void* scratch, long long bytes, hipStream_t stream);
+// micro-probes: 8192 waves x iters x 16 fp32 MFMAs (2048 flops each); a dwordx4 copy of `bytes` (16-byte aligned pointers)
+hipError_t launch_probe_mfma(int iters, float* sink, hipStream_t stream);
+hipError_t launch_probe_copy(const void* src, void* dst, long long bytes, hipStream_t stream);
 // temp: R*S*N*K*P*Q floats (unused for 1x1 filters)
 hipError_t launch_two_stage(hipStream_t stream, const KernelArgs& a, float* temp);
 

@@ -728,6 +728,21 @@ extern "C" int conv_fwd_two_stage(const float* x, const float* w, float* y, floa
     return record_hip(launch_two_stage(g_stream.load(), a, workspace));
 }
 
+extern "C" long long conv_probe_mfma(int iters, float* sink)
+{
+    if (!sink) return CONV_E_NULL;
+    if (iters < 1 || iters > (1 << 24)) return CONV_E_DIM;
+    if (int rc = record_hip(launch_probe_mfma(iters, sink, g_stream.load()))) return rc;
+    return 8192LL * iters * 16 * 2048;
+}
+
+extern "C" int conv_probe_copy(const void* src, void* dst, long long bytes)
+{
+    if (!src || !dst) return CONV_E_NULL;
+    if (bytes < 16 || reinterpret_cast<uintptr_t>(src) % 16 || reinterpret_cast<uintptr_t>(dst) % 16) return CONV_E_DIM;
+    return record_hip(launch_probe_copy(src, dst, bytes, g_stream.load()));
+}
+
 extern "C" int conv_variant_count(int kernel)
 {
     if (kernel == CONV_KERNEL_GENERIC) return 1;

@@ -54,6 +54,49 @@ hipError_t launch_scratch_fill(void* scratch, long long bytes, hipStream_t strea
     return hipGetLastError();
 }
 
+// Two micro-probes of what this GPU attains, for the benchmark's "fraction of measured peak" figures:
+// a register-resident fp32 MFMA loop (16 independent accumulator tiles per wave, nothing else in the loop) and a
+// dwordx4 stream copy.
+typedef float probe_f32x4 __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256) probe_mfma(int iters, float* sink)
+{
+    probe_f32x4 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = probe_f32x4{0.f, 0.f, 0.f, 0.f};
+    const float a = 1.0f + threadIdx.x * 1e-6f, b = 1.0f - threadIdx.x * 1e-6f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[i], 0, 0, 0);
+    }
+    probe_f32x4 sum = acc[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) sum += acc[i];
+    if (sum.x + sum.y + sum.z + sum.w == 12345.678f) *sink = sum.x;  // keeps the loop alive, never true in practice
+}
+
+__global__ void __launch_bounds__(256) probe_copy(const float4* __restrict__ src, float4* __restrict__ dst, long long n16)
+{
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// 256 CUs x 8 work-groups of 4 waves: 8192 waves x iters x 16 MFMAs of 2048 flops
+hipError_t launch_probe_mfma(int iters, float* sink, hipStream_t stream)
+{
+    hipLaunchKernelGGL(probe_mfma, dim3(256 * 8), dim3(256), 0, stream, iters, sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_copy(const void* src, void* dst, long long bytes, hipStream_t stream)
+{
+    const long long n16 = bytes / 16;
+    if (n16 <= 0) return hipSuccess;
+    const int grid = (int)std::min<long long>((n16 + 255) / 256, 256 * 32);
+    hipLaunchKernelGGL(probe_copy, dim3(grid), dim3(256), 0, stream, reinterpret_cast<const float4*>(src),
+                       reinterpret_cast<float4*>(dst), n16);
+    return hipGetLastError();
+}
+
 hipError_t launch_generic(int grid, int block, hipStream_t stream, const KernelArgs& a)
 {
     hipLaunchKernelGGL(conv_generic, dim3(grid), dim3(block), 0, stream, a);

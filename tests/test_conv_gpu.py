@@ -507,3 +507,17 @@ def test_sweep_layers_at_full_size(shape):
     ref, ref_abs = oracle.conv_ref_points(x, w, shape.pad_h, shape.pad_w, coords)
     ok, worst = oracle.within_tolerance(got, ref, ref_abs)
     assert ok, worst
+
+
+def test_micro_probes_run_and_report_their_work():
+    lib = binding.load_library()
+    binding.conv_set_stream(torch.cuda.current_stream())
+    sink = torch.zeros(1, device="cuda")
+    assert lib.conv_probe_mfma(10, sink.data_ptr()) == 8192 * 10 * 16 * 2048
+    assert lib.conv_probe_mfma(0, sink.data_ptr()) == -2 and lib.conv_probe_mfma(10, None) == -1
+    src = torch.arange(1 << 16, device="cuda", dtype=torch.float32)
+    dst = torch.zeros_like(src)
+    assert lib.conv_probe_copy(src.data_ptr(), dst.data_ptr(), src.numel() * 4) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst) and float(sink) == 0.0
+    assert lib.conv_probe_copy(src.data_ptr() + 4, dst.data_ptr(), 1024) == -2       # not 16-byte aligned
