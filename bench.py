@@ -29,7 +29,7 @@ BOUND = {1: "hbm", 2: "hbm", 3: "mfma", 4: "mfma", 5: "mfma"}
 # Bytes per launch that the L2s exchanged with the fabric (Infinity Cache / HBM), measured with rocprofv3 --pmc
 # FETCH_SIZE and WRITE_SIZE and scaled by what the same counters read for a plain device copy of known size
 # (profiles/conv_kernels_hbm_traffic.txt); None = not measured.
-TRAFFIC_BYTES = {1: None, 2: 4792743, 3: 14200278, 4: None, 5: 101440967}
+TRAFFIC_BYTES = {1: None, 2: 4792720, 3: 14200244, 4: None, 5: 101440509}
 
 
 def _fail(msg: str, code: int = 2):
