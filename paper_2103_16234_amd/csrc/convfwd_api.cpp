@@ -300,7 +300,7 @@ bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w
 // Choice of the pointwise tile shape, from sweeps: with plenty of work, 32 channels x 64 pixels per
 // work-group and four channel shares (inputs are re-read through L2 by the second channel tile, which
 // costs less than fewer, longer-lived waves); for small layers 16 channels per work-group and as many
-// channel shares as it takes to put ~4 waves on every SIMD's queue.
+// channel shares (4 or 8) as it takes to put ~4 waves on every SIMD's queue.
 int pick_pointwise(const Shape& s)
 {
     const int64_t pix_tiles = (int64_t)s.N * ceil_div(s.H * s.W, 64);
@@ -309,8 +309,7 @@ int pick_pointwise(const Shape& s)
     const int64_t groups = pix_tiles * ceil_div(s.K, 16);
     const int steps = ceil_div(s.C, 16);
     if (groups * 4 >= 1024 || steps <= 8) return 0;   // {1, 4}
-    if (groups * 8 >= 1024 || steps <= 16) return 1;  // {1, 8}
-    return 6;                                          // {1, 16}
+    return 1;                                          // {1, 8}; 16 shares (1024 threads) measured 25 % slower even on 512..832 channels
 }
 
 // Panel kernel or not, from sweeps over batched 1x1 layers: it wins once there are about 700 units of
@@ -348,29 +347,33 @@ void resolve_generic(const Shape& s, conv_plan_t* p, KernelArgs* a)
 }
 
 // Estimated cycles of a tap mapping on 256 CUs, fitted to timings of every tile shape x pixel tile over a
-// grid of 3x3 and 5x5 layers (batch 1..128, maps 7..224): the mapping it picks is on average within 5 % of
-// the best one measured. Per chunk, the work-groups sharing a CU take the longest of
-//   their matrix instructions   (wpc x MFMA cycles per SIMD; issue efficiency 0.85 with two or more waves
-//                                 per SIMD, 0.6 with one),
-//   one chunk's latency chain   (~2500 cycles from a staging load's issue to its data sitting in LDS behind
-//                                 the barrier, plus the chunk's own matrix instructions), and
-//   their staging traffic       (halo rows + filter block through registers into LDS, ~16 B/clk per CU),
-// a work-group adds ~12000 cycles of prologue and epilogue (first loads, LDS fill, the reduction tree,
-// stores at ~32 B/clk), the launch ~5000 and the dispatcher ~24 per work-group.
+// grid of 3x3 and 5x5 layers (batch 1..128, maps 7..224): the mapping it picks is on average within 4 % of
+// the best one measured (worst case 1.24x). Work-groups are dealt round-robin, so the busiest CU runs
+// cu = ceil(grid / 256) of them, wpc at a time (registers, LDS). Per chunk that CU takes the longest of
+//   all its matrix instructions  (cu x MFMA cycles per SIMD; issue efficiency 0.8 with two or more waves
+//                                 per SIMD, 0.75 with one),
+//   its latency chains           (one per batch of co-resident work-groups: ~1500 cycles from a staging load's
+//                                 issue to its data sitting in LDS behind the barrier, plus the chunk's own
+//                                 matrix instructions), and
+//   its staging traffic          (halo rows + filter block through registers into LDS, ~12 B/clk per CU);
+// every batch of co-resident work-groups adds ~12000 cycles of prologue and epilogue (first loads, LDS fill),
+// every work-group its reduction tree and stores (~32 B/clk), the launch ~5000 and the dispatcher ~12 per
+// work-group.
 double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv, int RS)
 {
     const int by_regs = std::max(1, tv.occ * 256 / tv.block());
     const int by_lds = std::max(1, kLdsMax / std::max(p.lds_bytes, 1));
     const int wpc = std::min(std::min(by_regs, by_lds), 8);  // work-groups sharing a CU
+    const int cu = ceil_div(p.grid, kNumCU);                 // work-groups of the busiest CU
+    const int batches = ceil_div(cu, wpc);
     const double waves_per_simd = tv.block() / 256.0;
-    const double eff = wpc * waves_per_simd >= 2 ? 0.85 : 0.6;
+    const double eff = std::min(wpc, cu) * waves_per_simd >= 2 ? 0.8 : 0.75;
     const double mfma = waves_per_simd * tv.MT * tv.NT * tv.GPC * RS * 32.0;  // per SIMD, chunk and work-group
     const double staged = 4.0 * ((double)tv.chunk_c() * a.lds_rows * a.W + (double)tv.tile_k() * tv.chunk_c() * RS);
-    const double chunk = std::max(std::max(wpc * mfma / eff, 2500.0 + mfma), wpc * staged / 16.0);
+    const double chunk = std::max(std::max(cu * mfma / eff, batches * (1500.0 + mfma)), cu * staged / 12.0);
     const double tree = tv.WC > 1 ? tv.MT * tv.NT * 1024.0 * tv.WK * tv.WP / 64.0 * std::log2((double)tv.WC) : 0.0;
-    const double per_round = a.nchunks * chunk + 12000.0 + wpc * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree);
-    const double rounds = std::ceil((double)p.grid / (kNumCU * wpc));
-    return rounds * per_round + 5000.0 + 24.0 * p.grid;  // ... and ~24 cycles of dispatch per work-group
+    return a.nchunks * chunk + batches * 12000.0 + cu * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree) + 5000.0 +
+           12.0 * p.grid;
 }
 
 // Measured best mappings of known layer shapes (sweeps over tile shape x pixel tile on an MI355X);
