@@ -144,18 +144,20 @@ constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
 // channels x WP*64 contiguous pixels of one image; the WC shares split the input channels.
 struct PointwiseVariant {
     int MT, WC, WP;
+    int PD;  // 16-channel steps of loads a wave keeps in flight (every wave runs a multiple of PD steps)
     constexpr int tile_k() const { return 16 * MT; }
     constexpr int tile_pix() const { return 64 * WP; }
     constexpr int block() const { return 64 * WC * WP; }
     constexpr int lds_bytes() const { return WC > 1 ? (WC / 2) * WP * MT * 4 * 1024 : 0; }
-    constexpr int depth() const { return MT == 1 && WC == 16 ? 4 : 2; }  // 16-channel steps in flight per wave
+    constexpr int depth() const { return PD; }
 };
 constexpr PointwiseVariant kPointwiseVariants[] = {
-    {1, 4, 1}, {1, 8, 1}, {2, 4, 1}, {2, 8, 1}, {4, 4, 1}, {4, 8, 1}, {1, 16, 1}, {2, 16, 1},  // 0-7: channel shares only
-    {1, 1, 4}, {2, 1, 4}, {4, 1, 4}, {2, 1, 2}, {2, 2, 2}, {4, 2, 2},                          // 8-13: streaming shapes
+    {1, 4, 1, 2}, {1, 8, 1, 2}, {2, 4, 1, 2}, {2, 8, 1, 2}, {4, 4, 1, 2}, {4, 8, 1, 2}, {1, 16, 1, 4}, {2, 16, 1, 2},  // 0-7: channel shares only
+    {1, 1, 4, 2}, {2, 1, 4, 2}, {4, 1, 4, 2}, {2, 1, 2, 2}, {2, 2, 2, 2}, {4, 2, 2, 2},                            // 8-13: streaming shapes
+    {1, 8, 1, 4}, {1, 4, 1, 4},  // 14-15: four steps in flight: deep N=1 layers, where a wave's chain of dependent loads sets the time
 };
 constexpr int kNumPointwiseVariants = sizeof(kPointwiseVariants) / sizeof(kPointwiseVariants[0]);
-#define POINTWISE_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13)
+#define POINTWISE_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15)
 hipError_t launch_pointwise(int variant, int x_vec, int grid, int lds_bytes, hipStream_t stream, const KernelArgs& a);
 
 // Panel shapes of the pointwise family (batched 1x1 layers): a work-group of NW waves keeps the filters

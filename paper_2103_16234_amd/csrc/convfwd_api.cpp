@@ -308,8 +308,10 @@ int pick_pointwise(const Shape& s)
     if (waves_v2 >= 4096) return 2;  // {MT 2, WC 4}
     const int64_t groups = pix_tiles * ceil_div(s.K, 16);
     const int steps = ceil_div(s.C, 16);
-    if (groups * 4 >= 1024 || steps <= 8) return 0;   // {1, 4}
-    return 1;                                          // {1, 8}; 16 shares (1024 threads) measured 25 % slower even on 512..832 channels
+    // {1, 4} or {1, 8} shares (16 shares, 1024 threads, measured 25 % slower even on 512..832 channels); with three or
+    // more steps per wave the twin that keeps four steps of loads in flight (3-7 % on 512..1024-channel N=1 layers)
+    if (groups * 4 >= 1024 || steps <= 8) return steps >= 12 ? 15 : 0;
+    return steps >= 24 ? 14 : 1;
 }
 
 // Panel kernel or not, from sweeps over batched 1x1 layers: it wins once there are about 700 units of

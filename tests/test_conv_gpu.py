@@ -135,7 +135,7 @@ POINTWISE_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("variant", range(16))
+@pytest.mark.parametrize("variant", range(20))
 @pytest.mark.parametrize("shape", POINTWISE_SHAPES, ids=lambda s: s.name)
 def test_every_pointwise_variant_matches_oracle(shape, variant):
     if variant >= binding.conv_variant_count(POINTWISE):
