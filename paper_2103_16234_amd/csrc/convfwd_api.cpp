@@ -331,6 +331,13 @@ int pick_panel(const Shape& s, int x_cap, int y_cap)
     const bool dwords = panel_pixel_mode(s, x_cap, y_cap) == 1;
     const int c64 = round_up(s.C, 32);
     if (dwords && s.K >= 64 && tiles * ceil_div(s.K, 64) >= 704 && 64 * (c64 + 4) * 4 <= kLdsMax) return 6;  // {4, 4, 2}
+    // 64 channels per panel also win 8-10 % on layers with 256 or more filters whose panel still lets two work-groups
+    // share a CU (C <= 256)
+    if (s.K >= 256 && tiles * ceil_div(s.K, 64) >= 704 && 64 * (c64 + 4) * 4 <= kLdsMax / 2) return 6;
+    // a 32-channel panel of more than half the LDS leaves one work-group per CU: eight waves then (two per SIMD)
+    // when every CU still gets a work-group whose waves all have a tile
+    if (32 * (c64 + 4) * 4 > kLdsMax / 2 && 32 * (c64 + 4) * 4 <= kLdsMax &&
+        static_cast<long long>(ceil_div(s.K, 32)) * ceil_div(tiles, 8) >= kNumCU) return 8;                    // {2, 8, 2}
     if (32 * (c64 + 4) * 4 <= kLdsMax) return 7;                                                                // {2, 4, 2}
     if (16 * (round_up(s.C, 64) + 4) * 4 <= kLdsMax) return 5;                                                  // {1, 4, 4}
     return -1;
@@ -349,14 +356,15 @@ void resolve_generic(const Shape& s, conv_plan_t* p, KernelArgs* a)
 }
 
 // Estimated cycles of a tap mapping on 256 CUs, fitted to timings of every tile shape x pixel tile over a
-// grid of 3x3 and 5x5 layers (batch 1..128, maps 7..224): the mapping it picks is on average within 4 % of
+// grid of 3x3 and 5x5 layers (batch 1..128, maps 7..224): the mapping it picks is on average within 2 % of
 // the best one measured (worst case 1.24x). Work-groups are dealt round-robin, so the busiest CU runs
 // cu = ceil(grid / 256) of them, wpc at a time (registers, LDS). Per chunk that CU takes the longest of
-//   all its matrix instructions  (cu x MFMA cycles per SIMD; issue efficiency 0.8 with two or more waves
-//                                 per SIMD, 0.75 with one),
+//   all its matrix work          (cu x per-SIMD cycles: 32 per MFMA plus ~150 per staging slot of a thread - the
+//                                 load, the LDS store and their address arithmetic take issue slots from the
+//                                 matrix instructions; issue efficiency 0.92 with two or more waves per SIMD,
+//                                 0.82 with one),
 //   its latency chains           (one per batch of co-resident work-groups: ~1500 cycles from a staging load's
-//                                 issue to its data sitting in LDS behind the barrier, plus the chunk's own
-//                                 matrix instructions), and
+//                                 issue to its data sitting in LDS behind the barrier, plus the chunk's own work), and
 //   its staging traffic          (halo rows + filter block through registers into LDS, ~12 B/clk per CU);
 // every batch of co-resident work-groups adds ~12000 cycles of prologue and epilogue (first loads, LDS fill),
 // every work-group its reduction tree and stores (~32 B/clk), the launch ~5000 and the dispatcher ~12 per
@@ -369,10 +377,11 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
     const int cu = ceil_div(p.grid, kNumCU);                 // work-groups of the busiest CU
     const int batches = ceil_div(cu, wpc);
     const double waves_per_simd = tv.block() / 256.0;
-    const double eff = std::min(wpc, cu) * waves_per_simd >= 2 ? 0.8 : 0.75;
-    const double mfma = waves_per_simd * tv.MT * tv.NT * tv.GPC * RS * 32.0;  // per SIMD, chunk and work-group
+    const double eff = std::min(wpc, cu) * waves_per_simd >= 2 ? 0.92 : 0.82;
+    const int slots = ceil_div(a.x_items, tv.block()) + ceil_div(tv.tile_k() * tv.chunk_c() * RS / p.w_vec, tv.block());
+    const double work = waves_per_simd * (tv.MT * tv.NT * tv.GPC * RS * 32.0 + 150.0 * slots);  // per SIMD, chunk, work-group
     const double staged = 4.0 * ((double)tv.chunk_c() * a.lds_rows * a.W + (double)tv.tile_k() * tv.chunk_c() * RS);
-    const double chunk = std::max(std::max(cu * mfma / eff, batches * (1500.0 + mfma)), cu * staged / 12.0);
+    const double chunk = std::max(std::max(cu * work / eff, batches * (1500.0 + work)), cu * staged / 12.0);
     const double tree = tv.WC > 1 ? tv.MT * tv.NT * 1024.0 * tv.WK * tv.WP / 64.0 * std::log2((double)tv.WC) : 0.0;
     return a.nchunks * chunk + batches * 12000.0 + cu * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree) + 5000.0 +
            12.0 * p.grid;
