@@ -274,6 +274,46 @@ def sweep(torch, binding, inputs, oracle, only=None, find=False):
     return rows
 
 
+def split_c_layers(torch, binding, inputs, oracle):
+    """Channel splitting across work-groups (conv_fwd_split_c) against the single-kernel default, on every layer of the
+    sweep grid and of the paper's profiled shapes for which the splitting planner asks for more than one share."""
+    lib = binding.load_library()
+    shapes = list(inputs.sweep_shapes()) + [inputs.ConvShape(label, *dims, "u01", "he", 77, 78)
+                                            for label, dims, _, _ in PAPER_SHAPES]
+    rows = []
+    for shape in shapes:
+        sp = binding.conv_fwd_plan_split_c(*shape.dims)
+        if sp.c_splits <= 1:
+            continue
+        layer = Layer(shape, torch, binding, inputs, min_bytes=600e6, max_sets=256)
+        ws = torch.empty(sp.workspace_bytes // 4, device="cuda")
+
+        def split_step():
+            xa, wa, ya = layer.args[layer.calls % layer.sets]
+            layer.calls += 1
+            rc = lib.conv_fwd_split_c(xa, wa, None, ya, ctypes.c_void_p(ws.data_ptr()), sp.workspace_bytes, *layer.dims, 0,
+                                      None, None)
+            if rc != 0:
+                raise RuntimeError(f"conv_fwd_split_c failed with code {rc}")
+
+        k = 400
+        _, d_ms = layer.measure(k, 10)
+        default_step, layer.step = layer.step, split_step
+        _, s_ms = layer.measure(k, 10)
+        par = layer.parity_sample(oracle, 128)
+        layer.step = default_step
+        p = layer.plan
+        rows.append({"shape": shape.name, "dims": list(shape.dims), "default_us": d_ms * 1e3, "split_us": s_ms * 1e3,
+                     "default_plan": [p.kernel, p.variant, p.tile_pix, p.grid, p.block],
+                     "split_plan": [sp.kernel, sp.variant, sp.tile_pix, sp.grid, sp.block], "c_splits": sp.c_splits,
+                     "workspace_bytes": sp.workspace_bytes, "split_parity_ok": par["ok"]})
+        print(f"split-c {shape.name}: default {d_ms * 1e3:.1f} us, {sp.c_splits} shares {s_ms * 1e3:.1f} us, parity {par['ok']}",
+              file=sys.stderr, flush=True)
+        del layer, ws
+        torch.cuda.empty_cache()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -288,6 +328,8 @@ def main():
                     help="also run the synthetic shape sweep (optionally only shapes whose name contains SUBSTR)")
     ap.add_argument("--find", action="store_true",
                     help="with --sweep: also time each layer with the mapping conv_fwd_find measures to be fastest")
+    ap.add_argument("--split-c", action="store_true",
+                    help="also compare the channel-splitting mode with the default on the layers its planner splits")
     ns = ap.parse_args()
     if ns.gpus != 1:
         _fail("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -354,6 +396,8 @@ def main():
         out["paper_shapes"] = paper_shapes(torch, binding, inputs, oracle)
     if ns.sweep is not None:
         out["sweep"] = sweep(torch, binding, inputs, oracle, ns.sweep, ns.find)
+    if ns.split_c:
+        out["split_c"] = split_c_layers(torch, binding, inputs, oracle)
     if not ns.no_cpu:
         out["cpu_baseline"] = cpu_baseline(oracle, inputs, ns.config)
     print(json.dumps(out))

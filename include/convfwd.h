@@ -41,7 +41,7 @@ extern "C" {
 #define CONV_E_OVERFLOW (-4)  /* a tensor has 2^31 or more elements (kernels index with 32 bits) */
 #define CONV_E_HIP (-5)       /* a HIP runtime call failed; conv_strerror gives its text */
 #define CONV_E_PLAN (-6)      /* a caller-supplied plan does not fit the shape or the kernels */
-#define CONV_E_WORKSPACE (-7) /* the workspace given to conv_fwd_two_stage is too small */
+#define CONV_E_WORKSPACE (-7) /* the workspace given to conv_fwd_two_stage / conv_fwd_split_c is too small */
 
 /* Kernel families a plan can name. */
 #define CONV_KERNEL_GENERIC 0 /* one output per thread, fp32 FMA; any R, S, padding */
@@ -51,9 +51,11 @@ extern "C" {
 
 /*
  * How one layer is mapped onto the GPU. Filled by conv_fwd_plan; plain data.
- * The reduction over (c, r, s) stays inside one work-group, so no plan ever
- * needs a workspace (unlike the two-stage scheme of Section 3, whose first
- * stage writes R*S partial matrices per input/filter pair).
+ * In conv_fwd_plan's mappings the reduction over (c, r, s) stays inside one
+ * work-group, so they need no workspace (unlike the two-stage scheme of
+ * Section 3, whose first stage writes R*S partial matrices per input/filter
+ * pair). Only the channel-splitting mode (conv_fwd_plan_split_c) has
+ * c_splits > 1 and a workspace.
  */
 typedef struct conv_plan {
     int kernel;          /* CONV_KERNEL_* */
@@ -70,7 +72,8 @@ typedef struct conv_plan {
     int block;           /* threads per work-group */
     int lds_bytes;       /* dynamic LDS per work-group */
     int P, Q;            /* output height and width */
-    long long workspace_bytes; /* always 0 */
+    int c_splits;        /* work-groups that share the channels of one output tile; 1: the whole reduction in one */
+    long long workspace_bytes; /* 0 unless c_splits > 1: then 4 * c_splits * N*K*P*Q */
     long long flops;     /* 2*N*K*P*Q*C*R*S */
     long long bytes;     /* 4*(N*C*H*W + K*C*R*S + N*K*P*Q): compulsory HBM traffic */
 } conv_plan_t;
@@ -138,6 +141,27 @@ int conv_fwd_find(const float* x, const float* w, float* y,
 int conv_fwd_bias_relu(const float* x, const float* w, const float* bias, float* y,
                        int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
                        int relu, const conv_plan_t* plan, conv_plan_t* resolved);
+
+/*
+ * Channel splitting across work-groups, for layers with too few output tiles to fill 256 CUs (batch 1, small
+ * maps, many channels: the layers Section 4.2 singles out, where the number of thread blocks decides the
+ * time; Section 5 names fusing and redistributing the work as future work). The C channels are cut into
+ * c_splits shares of whole chunks; each (output tile, share) is one work-group of the tap kernel, which
+ * writes its partial sums into share-th slice of the workspace; a second kernel adds the slices in share
+ * order (results stay bitwise reproducible) and applies the epilogue of conv_fwd_bias_relu.
+ * conv_fwd_plan_split_c: host-only; as conv_fwd_plan, but tap-family layers may get c_splits > 1 and then
+ * workspace_bytes = 4 * c_splits * N*K*P*Q. Layers conv_fwd_plan maps to other families keep that mapping.
+ * conv_fwd_split_c: plan null -> conv_fwd_plan_split_c's choice for these pointers; otherwise a request as in
+ * conv_fwd_planned, where c_splits (0 or 1: none) is honoured up to the number of chunks C holds and needs
+ * kernel = CONV_KERNEL_TAP. workspace: device pointer owned by the caller, 16-byte aligned for the fastest second
+ * pass, at least resolved->workspace_bytes long (may be null when that is 0), not overlapping x, w or y;
+ * contents undefined afterwards. Returns CONV_OK, the error codes of conv_fwd_planned, CONV_E_NULL for a
+ * missing workspace or CONV_E_WORKSPACE for a short one.
+ */
+int conv_fwd_plan_split_c(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w, conv_plan_t* out);
+int conv_fwd_split_c(const float* x, const float* w, const float* bias, float* y, float* workspace,
+                     long long workspace_bytes, int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
+                     int relu, const conv_plan_t* plan, conv_plan_t* resolved);
 
 /*
  * The paper's own two-stage scheme (Section 3), opt-in and outside the planner, for comparison with the

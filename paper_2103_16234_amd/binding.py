@@ -19,7 +19,7 @@ CONV_KERNEL_POINTWISE = 2
 CONV_KERNEL_PANEL = 3
 
 EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_fwd_find", "conv_two_stage_workspace_bytes",
-           "conv_fwd_two_stage", "conv_probe_mfma", "conv_probe_copy",
+           "conv_fwd_two_stage", "conv_fwd_plan_split_c", "conv_fwd_split_c", "conv_probe_mfma", "conv_probe_copy",
            "conv_variant_count", "conv_variant_info", "conv_set_stream", "conv_strerror")
 
 
@@ -27,7 +27,7 @@ class ConvPlan(ctypes.Structure):
     """Mirror of conv_plan_t in include/convfwd.h."""
     _fields_ = [(n, ctypes.c_int) for n in (
         "kernel", "variant", "tile_k", "tile_pix", "chunk_c", "x_vec", "w_vec", "lds_rows", "lds_pitch",
-        "lds_plane", "grid", "block", "lds_bytes", "P", "Q")] + [
+        "lds_plane", "grid", "block", "lds_bytes", "P", "Q", "c_splits")] + [
         ("workspace_bytes", ctypes.c_longlong), ("flops", ctypes.c_longlong), ("bytes", ctypes.c_longlong)]
 
     def as_dict(self):
@@ -69,6 +69,9 @@ def load_library():
     lib.conv_two_stage_workspace_bytes.argtypes = dims
     lib.conv_two_stage_workspace_bytes.restype = ctypes.c_longlong
     lib.conv_fwd_two_stage.argtypes = [vp, vp, vp, vp, ctypes.c_longlong] + dims
+    lib.conv_fwd_plan_split_c.argtypes = dims + [ctypes.POINTER(ConvPlan)]
+    lib.conv_fwd_split_c.argtypes = [vp, vp, vp, vp, vp, ctypes.c_longlong] + dims + [ci, ctypes.POINTER(ConvPlan),
+                                                                                   ctypes.POINTER(ConvPlan)]
     lib.conv_probe_mfma.argtypes = [ci, vp]
     lib.conv_probe_mfma.restype = ctypes.c_longlong
     lib.conv_probe_copy.argtypes = [vp, vp, ctypes.c_longlong]
@@ -179,6 +182,40 @@ def conv_fwd_bias_relu(x, w, bias, pad_h: int, pad_w: int, relu: bool, kernel=No
     _check(lib.conv_fwd_bias_relu(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None, y.data_ptr(),
                                   *dims, int(bool(relu)), ctypes.byref(req) if req is not None else None,
                                   ctypes.byref(res)))
+    return y, res
+
+
+def conv_fwd_plan_split_c(N, C, H, W, K, R, S, pad_h, pad_w) -> ConvPlan:
+    plan = ConvPlan()
+    _check(load_library().conv_fwd_plan_split_c(N, C, H, W, K, R, S, pad_h, pad_w, ctypes.byref(plan)))
+    return plan
+
+
+def conv_fwd_split_c(x, w, pad_h: int, pad_w: int, bias=None, relu: bool = False, c_splits: int = 0, variant=None,
+                     tile_pix: int = 0, workspace=None, y=None, use_current_stream: bool = True):
+    """Channel-splitting mode: y = act(conv(x, w) + bias) with the channels of an output tile shared by c_splits
+    work-groups and a second pass that adds their partial outputs. variant=None lets the library choose the
+    mapping (then c_splits is ignored); otherwise the tap variant / tile_pix / c_splits are requested.
+    workspace: fp32 device tensor (allocated here when None). Returns (y, plan)."""
+    import torch
+    y, dims = _device_args(x, w, y, pad_h, pad_w)
+    if bias is not None and (not bias.is_cuda or bias.dtype != torch.float32 or not bias.is_contiguous()
+                             or bias.numel() != w.shape[0]):
+        raise ValueError("bias must be a contiguous fp32 device tensor of K elements")
+    lib = load_library()
+    if use_current_stream:
+        conv_set_stream(torch.cuda.current_stream(x.device))
+    res = ConvPlan()
+    req = None
+    if variant is not None:
+        req = ConvPlan()
+        req.kernel, req.variant, req.tile_pix, req.c_splits = 1, variant, tile_pix, c_splits
+    if workspace is None:
+        need = max(c_splits, 16) * y.numel() if variant is not None else conv_fwd_plan_split_c(*dims).workspace_bytes // 4
+        workspace = torch.empty(max(int(need), 4), dtype=torch.float32, device=x.device)
+    _check(lib.conv_fwd_split_c(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None, y.data_ptr(),
+                                workspace.data_ptr(), workspace.numel() * 4, *dims, int(bool(relu)),
+                                ctypes.byref(req) if req is not None else None, ctypes.byref(res)))
     return y, res
 
 

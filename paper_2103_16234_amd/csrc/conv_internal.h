@@ -52,7 +52,9 @@ struct KernelArgs {
     int tile_pix;    // output pixels per work-group
     int ktiles;      // work-groups along K
     int ptiles;      // work-groups along the flattened pixels
-    int nchunks;     // channel chunks (the chunk size is a property of the tile shape)
+    int nchunks;     // channel chunks (the chunk size is a property of the tile shape) of one work-group
+    int split_c;     // tap family: channels one work-group reduces (a multiple of the chunk, or >= C: no splitting);
+                     // work-group index = ((share * ptiles) + pixel tile) * ktiles + channel tile
     // LDS halo tile of the tap family
     int lds_rows, lds_pitch, lds_plane;
     int col_shift;   // LDS column of padded column 0 (keeps vector stores aligned)
@@ -188,6 +190,10 @@ hipError_t launch_scratch_fill(void* scratch, long long bytes, hipStream_t strea
 // micro-probes: 8192 waves x iters x 16 fp32 MFMAs (2048 flops each); a dwordx4 copy of `bytes` (16-byte aligned pointers)
 hipError_t launch_probe_mfma(int iters, float* sink, hipStream_t stream);
 hipError_t launch_probe_copy(const void* src, void* dst, long long bytes, hipStream_t stream);
+// y[i] = act(sum over shares of parts[share * total + i] + bias[channel of i]), shares added in index order;
+// total = N*K*P*Q floats per share
+hipError_t launch_split_reduce(const float* parts, float* y, const float* bias, int relu, int splits, int total, int PQ,
+                               int K, hipStream_t stream);
 // temp: R*S*N*K*P*Q floats (unused for 1x1 filters)
 hipError_t launch_two_stage(hipStream_t stream, const KernelArgs& a, float* temp);
 

@@ -85,12 +85,14 @@ void base_args(const Shape& s, KernelArgs* a)
     a->P = s.P; a->Q = s.Q; a->PQ = s.P * s.Q; a->HW = s.H * s.W; a->CRS = s.C * s.R * s.S;
     a->Hp = s.H + 2 * s.pad_h;
     a->total_pix = s.N * s.P * s.Q;
+    a->split_c = s.C;
 }
 
 void fill_common(const Shape& s, conv_plan_t* p)
 {
     p->P = s.P; p->Q = s.Q;
     p->workspace_bytes = 0;
+    p->c_splits = 1;
     p->flops = 2LL * s.N * s.K * s.P * s.Q * s.C * s.R * s.S;
     p->bytes = 4LL * ((int64_t)s.N * s.C * s.H * s.W + (int64_t)s.K * s.C * s.R * s.S + (int64_t)s.N * s.K * s.P * s.Q);
 }
@@ -113,9 +115,11 @@ int max_halo_rows(const Shape& s, int tile_pix)
     return rows;
 }
 
-// Resolve a tap-family mapping. tile_pix / chunk_c of 0 mean "choose". Returns false if it cannot run.
+// Resolve a tap-family mapping. tile_pix / chunk_c of 0 mean "choose". c_splits > 1 asks for that many channel
+// shares, each reduced by work-groups of its own into a partial output tensor (fewer if C has fewer chunks).
+// Returns false if it cannot run.
 bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_cap, int w_cap,
-                 conv_plan_t* p, KernelArgs* a)
+                 conv_plan_t* p, KernelArgs* a, int c_splits = 1)
 {
     const int rs_index = tap_rs_index(s);
     if (rs_index < 0 || variant < 0 || variant >= kNumTapVariants) return false;
@@ -154,8 +158,13 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     a->tile_pix = tile_pix;
     a->ktiles = ceil_div(s.K, TK);
     a->ptiles = ceil_div(total, tile_pix);
-    if ((int64_t)a->ktiles * a->ptiles >= ((int64_t)1 << 31)) return false;
-    a->nchunks = ceil_div(s.C, cc);
+    // shares hold whole chunks, all but the last the same number
+    const int chunks_all = ceil_div(s.C, cc);
+    const int chunks_share = ceil_div(chunks_all, std::max(1, std::min(c_splits, chunks_all)));
+    const int splits = ceil_div(chunks_all, chunks_share);
+    if ((int64_t)a->ktiles * a->ptiles * splits >= ((int64_t)1 << 31)) return false;
+    a->nchunks = chunks_share;
+    if (splits > 1) a->split_c = chunks_share * cc;
     a->lds_rows = rows; a->lds_pitch = pitch; a->lds_plane = plane; a->col_shift = col_shift;
     a->x_items = cc * rows * row_vecs;
     a->div_ktiles = make_fastdiv(a->ktiles); a->div_ptiles = make_fastdiv(a->ptiles);
@@ -167,9 +176,11 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     p->tile_k = TK; p->tile_pix = tile_pix; p->chunk_c = cc;
     p->x_vec = x_vec; p->w_vec = w_vec;
     p->lds_rows = rows; p->lds_pitch = pitch; p->lds_plane = plane;
-    p->grid = a->ktiles * a->ptiles; p->block = BLOCK;
+    p->grid = a->ktiles * a->ptiles * splits; p->block = BLOCK;
     p->lds_bytes = (int)lds;
     fill_common(s, p);
+    p->c_splits = splits;
+    if (splits > 1) p->workspace_bytes = 4LL * splits * s.K * total;
     return true;
 }
 
@@ -501,6 +512,70 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_pl
     return CONV_OK;
 }
 
+// Channel-splitting mode: as the tap branch of plan_shape_uncached, with the number of channel shares as a third
+// search dimension. The model sees a share as a layer with fewer chunks and more work-groups; the second pass costs
+// a dependent launch (~10000 cycles), ~500 per share and the traffic of the partial outputs (fitted to timings of
+// every tile shape x pixel tile x share count on the batch-1 layers of the shape grid; shares that would put more
+// than two work-groups on a CU never won there and are not considered).
+constexpr double kSplitPassCycles = 10000.0;
+constexpr double kSplitShareCycles = 500.0;
+constexpr int kSplitCandidates[] = {1, 2, 3, 4, 6, 8, 12, 16};
+void search_split_plans(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a);
+std::vector<CacheEntry> g_split_cache;  // under g_cache_mutex, like g_cache
+
+int plan_split_shape(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
+{
+    {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        for (const CacheEntry& e : g_split_cache)
+            if (same_shape(e.s, s) && e.x_cap == x_cap && e.w_cap == w_cap && e.y_cap == y_cap) {
+                *p = e.p; *a = e.a;
+                return CONV_OK;
+            }
+    }
+    if (int rc = plan_shape(s, x_cap, w_cap, y_cap, p, a)) return rc;
+    if (p->kernel == CONV_KERNEL_TAP) search_split_plans(s, x_cap, w_cap, p, a);
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    if (g_split_cache.size() >= kCacheEntries) g_split_cache.erase(g_split_cache.begin());
+    g_split_cache.push_back(CacheEntry{s, x_cap, w_cap, y_cap, *p, *a});
+    return CONV_OK;
+}
+
+void search_split_plans(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a)
+{
+    // the default plan stays unless a mapping with shares is modelled faster than every mapping without
+    double best_whole = 0, best_split = 0;
+    bool have_whole = false, have_split = false;
+    conv_plan_t sp;
+    KernelArgs sa;
+    for (int v = 0; v < kNumTapVariants; ++v) {
+        const TapVariant tv = kTapVariants[v];
+        int cands[8];
+        const int nc = tap_tile_candidates(s, tv, cands);
+        for (int i = 0; i < nc; ++i) {
+            for (int splits : kSplitCandidates) {
+                conv_plan_t cp;
+                KernelArgs ca;
+                if (cands[i] < 1 || !resolve_tap(s, v, cands[i], 0, x_cap, w_cap, &cp, &ca, splits)) continue;
+                if (cp.c_splits != splits) continue;  // fewer chunks than shares: same as a smaller candidate
+                double c = tap_cost(cp, ca, tv, s.R * s.S);
+                if (splits == 1) {
+                    if (!have_whole || c < best_whole) { have_whole = true; best_whole = c; }
+                    continue;
+                }
+                if (cp.grid > 2 * kNumCU) continue;
+                c += kSplitPassCycles + kSplitShareCycles * splits + 4.0 * (splits + 1) * s.K * ca.total_pix / (kNumCU * 16.0);
+                if (!have_split || c < best_split * 0.999) {
+                    have_split = true; best_split = c; sp = cp; sa = ca;
+                }
+            }
+        }
+    }
+    if (have_split && (!have_whole || best_split < 0.999 * best_whole)) {
+        *p = sp; *a = sa;
+    }
+}
+
 int record_hip(hipError_t e)
 {
     if (e == hipSuccess) return CONV_OK;
@@ -560,7 +635,8 @@ extern "C" int conv_fwd(const float* x, const float* w, float* y, int N, int C, 
 // Shared by conv_fwd_planned and conv_fwd_bias_relu: resolve the requested mapping (or plan, when none is
 // requested) and enqueue the kernel.
 static int run_planned(const float* x, const float* w, const float* bias, float* y, int N, int C, int H, int W, int K,
-                       int R, int S, int pad_h, int pad_w, int relu, const conv_plan_t* plan, conv_plan_t* resolved)
+                       int R, int S, int pad_h, int pad_w, int relu, const conv_plan_t* plan, conv_plan_t* resolved,
+                       bool may_split = false, float* workspace = nullptr, long long workspace_bytes = 0)
 {
     if (!x || !w || !y) return CONV_E_NULL;
     Shape s;
@@ -570,7 +646,10 @@ static int run_planned(const float* x, const float* w, const float* bias, float*
     conv_plan_t p;
     KernelArgs a;
     if (!plan) {
-        if (int rc = plan_shape(s, x_cap, w_cap, y_cap, &p, &a)) return rc;
+        if (int rc = may_split ? plan_split_shape(s, x_cap, w_cap, y_cap, &p, &a) : plan_shape(s, x_cap, w_cap, y_cap, &p, &a))
+            return rc;
+    } else if (plan->c_splits > 1 && (!may_split || plan->kernel != CONV_KERNEL_TAP)) {
+        return CONV_E_PLAN;  // only the tap family splits channels across work-groups, and only with a workspace
     } else if (plan->kernel == CONV_KERNEL_POINTWISE) {
         if (!resolve_pointwise(s, plan->variant, x_cap, w_cap, y_cap, &p, &a)) return CONV_E_PLAN;
     } else if (plan->kernel == CONV_KERNEL_PANEL) {
@@ -579,12 +658,36 @@ static int run_planned(const float* x, const float* w, const float* bias, float*
         resolve_generic(s, &p, &a);
     } else if (plan->kernel == CONV_KERNEL_TAP) {
         if (plan->tile_pix < 0 || plan->chunk_c < 0) return CONV_E_PLAN;
-        if (!resolve_tap(s, plan->variant, plan->tile_pix, plan->chunk_c, x_cap, w_cap, &p, &a)) return CONV_E_PLAN;
+        if (plan->c_splits < 0) return CONV_E_PLAN;
+        if (!resolve_tap(s, plan->variant, plan->tile_pix, plan->chunk_c, x_cap, w_cap, &p, &a, std::max(1, plan->c_splits)))
+            return CONV_E_PLAN;
     } else {
         return CONV_E_PLAN;
     }
     if (resolved) *resolved = p;
-    return launch(p, a, s, x, w, y, bias, relu);
+    if (p.c_splits <= 1) return launch(p, a, s, x, w, y, bias, relu);
+    // channel shares: the tap kernel writes c_splits partial outputs into the workspace, a second kernel adds them
+    if (!workspace) return CONV_E_NULL;
+    if (workspace_bytes < p.workspace_bytes) return CONV_E_WORKSPACE;
+    if (int rc = launch(p, a, s, x, w, workspace)) return rc;
+    return record_hip(launch_split_reduce(workspace, y, bias, relu, p.c_splits, s.K * a.total_pix, a.PQ, s.K, g_stream.load()));
+}
+
+extern "C" int conv_fwd_plan_split_c(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w, conv_plan_t* out)
+{
+    if (!out) return CONV_E_NULL;
+    Shape s;
+    if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
+    KernelArgs a;
+    return plan_split_shape(s, 4, 4, 4, out, &a);
+}
+
+extern "C" int conv_fwd_split_c(const float* x, const float* w, const float* bias, float* y, float* workspace,
+                                long long workspace_bytes, int N, int C, int H, int W, int K, int R, int S, int pad_h,
+                                int pad_w, int relu, const conv_plan_t* plan, conv_plan_t* resolved)
+{
+    return run_planned(x, w, bias, y, N, C, H, W, K, R, S, pad_h, pad_w, relu != 0, plan, resolved, true, workspace,
+                       workspace_bytes);
 }
 
 extern "C" int conv_fwd_planned(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R,

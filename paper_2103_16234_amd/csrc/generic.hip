@@ -97,6 +97,71 @@ hipError_t launch_probe_copy(const void* src, void* dst, long long bytes, hipStr
     return hipGetLastError();
 }
 
+// Second pass of the channel-splitting mode: adds the partial output tensors the work-groups of each channel share
+// wrote, always in share order (bitwise reproducible), then the epilogue. V floats per thread; V = 4 needs P*Q to be a
+// multiple of 4 (a vector then lies inside one channel) and 16-byte aligned pointers.
+template <int V>
+__global__ void __launch_bounds__(256) conv_split_reduce(const float* __restrict__ parts, float* __restrict__ y,
+                                                         const float* __restrict__ bias, int relu, int splits, int total,
+                                                         int K, FastDiv div_PQ, FastDiv div_K)
+{
+    const int i = (blockIdx.x * 256 + threadIdx.x) * V;
+    if (i >= total) return;
+    const unsigned nk = div_PQ.div(i);
+    const unsigned k = nk - div_K.div(nk) * K;
+    const float b = bias ? bias[k] : 0.f;
+    // four shares' loads in flight at a time; the additions keep the share order
+    const float* p = parts + i;
+    const size_t stride = static_cast<size_t>(total);
+    if constexpr (V == 4) {
+        float4 acc = *reinterpret_cast<const float4*>(p);
+        int s = 1;
+        for (; s + 4 <= splits; s += 4) {
+            float4 t[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) t[u] = *reinterpret_cast<const float4*>(p + (s + u) * stride);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { acc.x += t[u].x; acc.y += t[u].y; acc.z += t[u].z; acc.w += t[u].w; }
+        }
+        for (; s < splits; ++s) {
+            const float4 t = *reinterpret_cast<const float4*>(p + s * stride);
+            acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+        }
+        acc.x = finish_output(acc.x, b, relu); acc.y = finish_output(acc.y, b, relu);
+        acc.z = finish_output(acc.z, b, relu); acc.w = finish_output(acc.w, b, relu);
+        *reinterpret_cast<float4*>(y + i) = acc;
+    } else {
+        float acc = *p;
+        int s = 1;
+        for (; s + 4 <= splits; s += 4) {
+            float t[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) t[u] = p[(s + u) * stride];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc += t[u];
+        }
+        for (; s < splits; ++s) acc += p[s * stride];
+        y[i] = finish_output(acc, b, relu);
+    }
+}
+
+hipError_t launch_split_reduce(const float* parts, float* y, const float* bias, int relu, int splits, int total, int PQ,
+                               int K, hipStream_t stream)
+{
+    // vectors only once single floats would already give every CU four work-groups
+    const bool vec = PQ % 4 == 0 && total >= 256 * 256 * 4 && reinterpret_cast<uintptr_t>(parts) % 16 == 0 &&
+                     reinterpret_cast<uintptr_t>(y) % 16 == 0;
+    const FastDiv div_PQ = make_fastdiv(PQ), div_K = make_fastdiv(K);
+    if (vec) {
+        hipLaunchKernelGGL(conv_split_reduce<4>, dim3((total / 4 + 255) / 256), dim3(256), 0, stream, parts, y, bias, relu,
+                           splits, total, K, div_PQ, div_K);
+    } else {
+        hipLaunchKernelGGL(conv_split_reduce<1>, dim3((total + 255) / 256), dim3(256), 0, stream, parts, y, bias, relu,
+                           splits, total, K, div_PQ, div_K);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_generic(int grid, int block, hipStream_t stream, const KernelArgs& a)
 {
     hipLaunchKernelGGL(conv_generic, dim3(grid), dim3(block), 0, stream, a);

@@ -123,8 +123,19 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         const int per = nb >> 3, rem = nb & 7, xcd = b & 7;
         L = xcd * per + (xcd < rem ? xcd : rem) + (b >> 3);
     }
-    const int ptile = a.div_ktiles.div(L);
-    const int ktile = L - ptile * a.ktiles;
+    const int pt_all = a.div_ktiles.div(L);
+    const int ktile = L - pt_all * a.ktiles;
+    // Channel splitting across work-groups: share `split` reduces channels cb .. cb+C_l-1 and writes a whole
+    // partial output tensor of its own (a.y then points at the workspace; a second kernel adds the shares).
+    // Without splitting there is one share, all of C.
+    const int split = a.div_ptiles.div(pt_all);
+    const int ptile = pt_all - split * a.ptiles;
+    const int cb = split * a.split_c;
+    const int C_l = min(a.C - cb, a.split_c);
+    const int nchunks = (C_l + CC - 1) / CC;
+    const float* const x_share = a.x + static_cast<size_t>(cb) * a.HW;
+    const float* const w_share = a.w + cb * RS;
+    float* const y_share = a.y + static_cast<size_t>(split) * a.K * a.total_pix;
     const int k0 = ktile * TK;
     const int g0 = ptile * a.tile_pix;
     const int g_end = min(g0 + a.tile_pix, a.total_pix);
@@ -182,24 +193,24 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     // One slot of the staging pipeline: slot k < XS is a halo-tile slot, the others filter slots.
     auto slot_load = [&](auto kc, int c0) {
         constexpr int k = decltype(kc)::value;
-        if constexpr (k < XS) xv[k].load(a.x + c0 * a.HW + xg[k]);
-        else wv[k - XS].load(a.w + k0 * a.CRS + c0 * RS + wg[k - XS]);
+        if constexpr (k < XS) xv[k].load(x_share + c0 * a.HW + xg[k]);
+        else wv[k - XS].load(w_share + k0 * a.CRS + c0 * RS + wg[k - XS]);
     };
-    // When C is not a multiple of the chunk, the last chunk's slots past channel C - 1 would read past the
-    // tensors. Before the first load of the last chunk (no other chunk is loaded after it) their table
+    // When the share is not a multiple of the chunk, the last chunk's slots past its last channel would read past
+    // the tensors. Before the first load of the last chunk (no other chunk is loaded after it) their table
     // entries are moved back to the last valid channel (x) or the last VW floats of the filter row (w);
     // what they fetch is replaced by zeros at the store anyway.
-    const int last_c0 = (a.nchunks - 1) * CC;
-    const bool ragged = a.C % CC != 0;
+    const int last_c0 = (nchunks - 1) * CC;
+    const bool ragged = C_l % CC != 0;
     auto retarget_last_chunk = [&]() {
 #pragma unroll
         for (int i = 0; i < XS; ++i) {
-            const int over = last_c0 + static_cast<int>(xl[i] >> 16) - (a.C - 1);
+            const int over = last_c0 + static_cast<int>(xl[i] >> 16) - (C_l - 1);
             if (over > 0) xg[i] -= over * a.HW;
         }
 #pragma unroll
         for (int i = 0; i < WS; ++i) {
-            const int over = last_c0 * RS + static_cast<int>(wl[i] >> 16) - (a.CRS - VW);
+            const int over = last_c0 * RS + static_cast<int>(wl[i] >> 16) - (C_l * RS - VW);
             if (over > 0) wg[i] -= over;
         }
     };
@@ -208,11 +219,11 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         constexpr int k = decltype(kc)::value;
         if constexpr (k < XS) {
             Vec<VX> t = xv[k];
-            t.keep_if(c0 + static_cast<int>(xl[k] >> 16) < a.C);
+            t.keep_if(c0 + static_cast<int>(xl[k] >> 16) < C_l);
             t.store16(lds + dst_floats + (xl[k] & 0xffff));
         } else {
             Vec<VW> t = wv[k - XS];
-            t.keep_if(static_cast<int>(wl[k - XS] >> 16) < (a.C - c0) * RS);
+            t.keep_if(static_cast<int>(wl[k - XS] >> 16) < (C_l - c0) * RS);
             t.store16(lds + dst_floats + (wl[k - XS] & 0xffff));
         }
     };
@@ -230,7 +241,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     // Prologue: chunk 0 goes straight into copy 0, chunk 1 waits in the registers. While the first
     // loads are in flight, zero both staging copies (padding cells, rows past the batch and output
     // channels past K then stay zero for the whole kernel) and build the per-lane pixel table.
-    if (ragged && a.nchunks == 1) retarget_last_chunk();
+    if (ragged && nchunks == 1) retarget_last_chunk();
     for_each_slot([&](auto kc) { slot_load(kc, 0); });
     for (int i = tid; i < (2 * buf_floats) >> 2; i += BLOCK) smem4[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -251,7 +262,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
 
     __syncthreads();  // zero fill complete before any data lands
     for_each_slot([&](auto kc) { slot_store(kc, 0, 0); });
-    if (ragged && a.nchunks == 2) retarget_last_chunk();
+    if (ragged && nchunks == 2) retarget_last_chunk();
     for_each_slot([&](auto kc) { slot_load(kc, min(CC, last_c0)); });
     __syncthreads();
 
@@ -261,12 +272,12 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     };
     const char* const lds_bytes = reinterpret_cast<const char*>(lds);
 
-    for (int ch = 0; ch < a.nchunks; ++ch) {
+    for (int ch = 0; ch < nchunks; ++ch) {
         const int cur_bytes = (ch & 1) * buf_floats * 4;
         const int nxt_floats = ((ch + 1) & 1) * buf_floats;
         const int c0_regs = min((ch + 1) * CC, last_c0);  // chunk whose data the staging registers hold
         const int c0_load = min((ch + 2) * CC, last_c0);  // chunk to fetch next (the last one again at the end)
-        if (ragged && ch + 3 == a.nchunks) retarget_last_chunk();
+        if (ragged && ch + 3 == nchunks) retarget_last_chunk();
 
         const char* const a_base = lds_bytes + cur_bytes + arow;
         int xa[NT];  // B addresses of the filter row being read
@@ -375,7 +386,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
             const int yb = n * a.K * a.PQ + (g - n * a.PQ);
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                if (kbase + v < a.K) a.y[yb + (kbase + v) * a.PQ] = finish_output(acc[m][t][v], bk[m][v], a.relu);
+                if (kbase + v < a.K) y_share[yb + (kbase + v) * a.PQ] = finish_output(acc[m][t][v], bk[m][v], a.relu);
         }
     }
 }

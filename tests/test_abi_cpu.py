@@ -66,6 +66,10 @@ def test_argument_errors_are_codes_not_crashes(lib):
     assert lib.conv_fwd_two_stage(1 << 20, 1 << 20, 1 << 20, 1 << 20, 1 << 40, 1, 20000, 8, 8, 4, 3, 3, 1, 1) == -6
     assert lib.conv_fwd_find(None, None, None, *ok, None, 0, None, None) == -1
     assert lib.conv_fwd_find(1 << 20, 1 << 20, 1 << 20, 1, 4, 2, 8, 4, 5, 5, 1, 2, None, 0, None, None) == -3   # validated before any GPU call
+    assert lib.conv_fwd_plan_split_c(*ok, None) == -1
+    assert lib.conv_fwd_plan_split_c(1, 4, 2, 8, 4, 5, 5, 1, 2, ctypes.byref(plan)) == -3
+    assert lib.conv_fwd_split_c(None, None, None, None, None, 0, *ok, 0, None, None) == -1
+    assert lib.conv_fwd_split_c(1 << 20, 1 << 20, None, 1 << 20, None, 0, 1, 4, 8, 8, 4, 3, 3, -1, 1, 0, None, None) == -2
     for code in (0, -1, -2, -3, -4, -5, -6, -7, -99):
         assert binding.conv_strerror(code)
     with pytest.raises(binding.ConvError) as e:
@@ -143,6 +147,34 @@ def test_plans_of_the_sweep_grid_are_well_formed():
             assert 1 <= groups * (block // 64) <= tiles + block // 64   # no more waves than 64-pixel tiles (+ one work-group)
             assert p.lds_bytes >= 4 * p.tile_k * s.C                 # the whole filter panel of a channel tile
     assert families == {tap, pw, panel}
+
+
+def test_channel_splitting_plans_are_well_formed():
+    """Host-only: the splitting planner only ever changes tap-family layers, sizes its workspace as documented, keeps
+    at most two work-groups per CU when it splits, and splits the deep batch-1 layers it exists for."""
+    tap = binding.CONV_KERNEL_TAP
+    split_layers = 0
+    for s in inputs.sweep_shapes():
+        base = binding.conv_fwd_plan(*s.dims)
+        p = binding.conv_fwd_plan_split_c(*s.dims)
+        assert base.c_splits == 1 and base.workspace_bytes == 0
+        assert p.c_splits >= 1 and (p.P, p.Q) == (s.P, s.Q)
+        if base.kernel != tap:
+            assert (p.kernel, p.variant, p.tile_pix, p.grid, p.c_splits) == (base.kernel, base.variant, base.tile_pix, base.grid, 1)
+        if p.c_splits == 1:
+            assert p.workspace_bytes == 0
+            continue
+        split_layers += 1
+        assert p.kernel == tap
+        assert p.workspace_bytes == 4 * p.c_splits * s.N * s.K * s.P * s.Q
+        tiles = -(-s.K // p.tile_k) * -(-(s.N * s.P * s.Q) // p.tile_pix)
+        assert p.grid == tiles * p.c_splits <= 512
+        assert p.c_splits <= -(-s.C // p.chunk_c)                # every share holds at least one chunk
+    assert split_layers >= 3
+    deep = binding.conv_fwd_plan_split_c(1, 512, 7, 7, 512, 3, 3, 1, 1)
+    assert deep.c_splits > 1
+    wide = binding.conv_fwd_plan_split_c(32, 64, 56, 56, 64, 3, 3, 1, 1)
+    assert wide.c_splits == 1                                    # plenty of output tiles: nothing to gain
 
 
 def test_panel_plans_follow_the_batch():

@@ -4,6 +4,7 @@ Bar: |y_gpu - y_ref| <= 1e-5 * sum|x*w| + 1e-6 for every output element, the sum
 element's receptive field; exact equality where the inputs are small integers (all partial sums are
 then exact in fp32, so a dropped or duplicated tap cannot hide inside the tolerance).
 """
+import ctypes
 import sys
 
 import numpy as np
@@ -276,6 +277,102 @@ def test_fused_epilogue_integer_inputs_are_exact():
     y, _ = binding.conv_fwd_bias_relu(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(b).cuda(), 1, 1, True)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(y.cpu().numpy().astype(np.float64), y_ref)
+
+
+# Channel splitting across work-groups (the work redistribution Section 5 leaves as future work): layers with many channels
+# on few pixels, shares that are ragged (C = 100 over chunks of 16 / 32 / 64), scalar filter rows (C = 30), several
+# images per tile, every filter size of the tap family.
+SPLIT_SHAPES = [
+    S("split_3x3_deep", 1, 200, 7, 7, 48, 3, 3, 1, 1),
+    S("split_3x3_ragged_c", 2, 100, 6, 5, 37, 3, 3, 1, 1),
+    S("split_3x3_odd_c", 1, 30, 9, 9, 20, 3, 3, 1, 1),
+    S("split_5x5", 1, 72, 8, 8, 24, 5, 5, 2, 2),
+    S("split_1x1_pad", 3, 96, 5, 6, 33, 1, 1, 1, 1),
+]
+
+
+def _run_split(shape, variant, c_splits, tile_pix=0, bias=False, relu=False, exact=False, workspace=None):
+    x, w = inputs.make_inputs(shape)
+    b = inputs.uniform_pm1(900 + shape.K, shape.K) * np.float32(0.5) if bias else None
+    y_ref, ya_ref = oracle.conv_bias_relu_ref(x, w, b, shape.pad_h, shape.pad_w, relu)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    bd = torch.from_numpy(b).cuda() if bias else None
+    yd = torch.full(shape.y_shape, float("nan"), device="cuda")
+    _say(f"[case] split_c {shape.name} dims={shape.dims} variant={variant} c_splits={c_splits} tile_pix={tile_pix} bias={bias} relu={relu}")
+    _, plan = binding.conv_fwd_split_c(xd, wd, shape.pad_h, shape.pad_w, bd, relu, c_splits, variant, tile_pix, workspace=workspace, y=yd)
+    torch.cuda.synchronize()
+    y = yd.cpu().numpy().astype(np.float64)
+    assert not np.isnan(y).any(), "some outputs were never written"
+    if exact:
+        np.testing.assert_array_equal(y, y_ref)
+    ok, worst = oracle.within_tolerance(y, y_ref, ya_ref)
+    assert ok, f"worst ratio {worst:.3g} with plan {plan.as_dict()}"
+    return plan, yd
+
+
+@pytest.mark.parametrize("c_splits", [2, 3, 5, 16])
+@pytest.mark.parametrize("variant", [2, 5, 13, 17, 20, 7])
+@pytest.mark.parametrize("shape", SPLIT_SHAPES, ids=lambda s: s.name)
+def test_channel_splitting_matches_oracle(shape, variant, c_splits):
+    try:
+        plan, _ = _run_split(shape, variant, c_splits)
+    except binding.ConvError as e:
+        assert e.code == -6   # the tile shape does not fit the layer
+        return
+    chunks = -(-shape.C // plan.chunk_c)
+    assert 1 <= plan.c_splits <= min(c_splits, chunks)
+    tiles = -(-shape.K // plan.tile_k) * -(-shape.N * plan.P * plan.Q // plan.tile_pix)
+    assert plan.grid == tiles * plan.c_splits
+    assert plan.workspace_bytes == (4 * plan.c_splits * shape.N * shape.K * plan.P * plan.Q if plan.c_splits > 1 else 0)
+
+
+@pytest.mark.parametrize("bias,relu", [(True, False), (False, True), (True, True)])
+def test_channel_splitting_applies_the_epilogue_after_the_sum(bias, relu):
+    plan, _ = _run_split(SPLIT_SHAPES[0], 13, 4, bias=bias, relu=relu)
+    assert plan.c_splits == 4
+    _run_split(SPLIT_SHAPES[1], 2, 3, tile_pix=17, bias=bias, relu=relu)
+
+
+def test_channel_splitting_is_exact_on_integers_and_reproducible():
+    shape = inputs.ConvShape("split_ints", 1, 80, 7, 7, 40, 3, 3, 1, 1, "int", "int", 41, 42)
+    ys = []
+    for rep in range(2):
+        plan, yd = _run_split(shape, 13, 5, exact=True)
+        ys.append(yd.clone())
+    assert plan.c_splits == 5
+    assert torch.equal(ys[0], ys[1])
+    shape = S("split_repro", 1, 160, 7, 7, 32, 3, 3, 1, 1)
+    a = _run_split(shape, 20, 4)[1].clone()
+    b = _run_split(shape, 20, 4)[1]
+    assert torch.equal(a, b)     # the shares are added in share order, whichever work-group finishes first
+
+
+def test_channel_splitting_default_plan_and_workspace_checks():
+    shape = S("split_default", 1, 512, 7, 7, 512, 3, 3, 1, 1)
+    want = binding.conv_fwd_plan_split_c(*shape.dims)
+    assert want.kernel == TAP and want.c_splits > 1 and want.workspace_bytes == 4 * want.c_splits * shape.K * 49
+    plan, _ = _run_split(shape, None, 0)
+    assert (plan.variant, plan.tile_pix, plan.c_splits) == (want.variant, want.tile_pix, want.c_splits)
+    x, w = inputs.make_inputs(shape)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    short = torch.empty(want.workspace_bytes // 4 - 1, device="cuda")
+    with pytest.raises(binding.ConvError) as e:
+        binding.conv_fwd_split_c(xd, wd, 1, 1, workspace=short)
+    assert e.value.code == -7
+    lib = binding.load_library()
+    yd = torch.empty(shape.y_shape, device="cuda")
+    assert lib.conv_fwd_split_c(xd.data_ptr(), wd.data_ptr(), None, yd.data_ptr(), None, 0, *shape.dims, 0, None, None) == -1
+    # only the tap family splits; the workspace-free entry points refuse a plan that asks for shares
+    req = binding.ConvPlan()
+    req.kernel, req.c_splits = GENERIC, 2
+    ws = torch.empty(want.workspace_bytes // 4, device="cuda")
+    assert lib.conv_fwd_split_c(xd.data_ptr(), wd.data_ptr(), None, yd.data_ptr(), ws.data_ptr(), ws.numel() * 4, *shape.dims, 0,
+                                ctypes.byref(req), None) == -6
+    req.kernel, req.variant = TAP, 13
+    assert lib.conv_fwd_planned(xd.data_ptr(), wd.data_ptr(), yd.data_ptr(), *shape.dims, ctypes.byref(req), None) == -6
+    # a layer the planner maps to another family keeps that mapping and needs no workspace
+    other = binding.conv_fwd_plan_split_c(1, 256, 56, 56, 64, 1, 1, 0, 0)
+    assert other.kernel == POINTWISE and other.c_splits == 1 and other.workspace_bytes == 0
 
 
 @pytest.mark.parametrize("shape", NONSQUARE, ids=lambda s: s.name)
