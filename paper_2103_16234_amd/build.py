@@ -25,13 +25,23 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Wall", "-Wno-
 
 COMMON += os.environ.get("CONVFWD_EXTRA_HIPCC_FLAGS", "").split()
 
-TAP_SIZES = (1, 3, 5)
+TAP_SIZES = (1, 3, 5)   # every tile shape; the other filter sizes are read from TAP_EXTRA_SIZES in conv_internal.h
 
 
 def _num_tap_variants() -> int:
     text = open(os.path.join(CSRC, "conv_internal.h")).read()
     body = re.search(r"kTapVariants\[\]\s*=\s*\{(.*?)\n\};", text, re.S).group(1)
     return len(re.findall(r"^\s*\{", body, re.M))
+
+
+def _extra_tap_units():
+    """(R, S, variant) triples of the tap kernel's other filter sizes, from the two macros that also declare them."""
+    text = open(os.path.join(CSRC, "conv_internal.h")).read().replace("\\\n", " ")
+    variants = re.search(r"#define TAP_EXTRA_VARIANTS\(X, r, s\)(.*)", text).group(1)
+    variants = [int(v) for v in re.findall(r"X\(r, s, (\d+)\)", variants)]
+    sizes = re.search(r"#define TAP_EXTRA_SIZES\(X\)(.*)", text).group(1)
+    sizes = [(int(r), int(s)) for r, s in re.findall(r"TAP_EXTRA_VARIANTS\(X, (\d+), (\d+)\)", sizes)]
+    return [(r, s, v) for r, s in sizes for v in variants]
 
 
 def _jobs():
@@ -46,6 +56,9 @@ def _jobs():
         for v in range(_num_tap_variants()):
             jobs.append((os.path.join(OBJ, f"tap_{r}x{r}_v{v}.o"), os.path.join(CSRC, "tap_mfma.hip"),
                          [f"-DTAP_R={r}", f"-DTAP_S={r}", f"-DTAP_VARIANT={v}"]))
+    for r, s, v in _extra_tap_units():
+        jobs.append((os.path.join(OBJ, f"tap_{r}x{s}_v{v}.o"), os.path.join(CSRC, "tap_mfma.hip"),
+                     [f"-DTAP_R={r}", f"-DTAP_S={s}", f"-DTAP_VARIANT={v}"]))
     return jobs
 
 

@@ -142,6 +142,27 @@ constexpr TapVariant kTapVariants[] = {
 constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
 #define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18) X(19) X(20) X(21)
 
+// Filter sizes the tap kernel is instantiated for. The three the paper evaluates (Section 4: 1x1, 3x3, 5x5) get every
+// tile shape; the others (filter rows and columns, even and 7x7 filters, as the factorised layers of later CNNs use)
+// a small set that covers tiny, deep batch-1, medium and wide-map layers. Any other size runs the generic kernel.
+#define TAP_EXTRA_VARIANTS(X, r, s) X(r, s, 2) X(r, s, 5) X(r, s, 7) X(r, s, 14) X(r, s, 16) X(r, s, 20)
+#define TAP_EXTRA_SIZES(X)                                                                                         \
+    TAP_EXTRA_VARIANTS(X, 1, 3) TAP_EXTRA_VARIANTS(X, 3, 1) TAP_EXTRA_VARIANTS(X, 1, 5) TAP_EXTRA_VARIANTS(X, 5, 1) \
+    TAP_EXTRA_VARIANTS(X, 1, 7) TAP_EXTRA_VARIANTS(X, 7, 1) TAP_EXTRA_VARIANTS(X, 2, 2) TAP_EXTRA_VARIANTS(X, 4, 4) \
+    TAP_EXTRA_VARIANTS(X, 7, 7)
+struct TapSize {
+    int R, S;
+};
+constexpr TapSize kTapSizes[] = {{1, 1}, {3, 3}, {5, 5}, {1, 3}, {3, 1}, {1, 5}, {5, 1}, {1, 7}, {7, 1}, {2, 2}, {4, 4}, {7, 7}};
+constexpr int kNumTapSizes = sizeof(kTapSizes) / sizeof(kTapSizes[0]);
+constexpr int kNumFullTapSizes = 3;  // the leading entries of kTapSizes that have every tile shape
+constexpr int tap_size_index(int R, int S)
+{
+    for (int i = 0; i < kNumTapSizes; ++i)
+        if (kTapSizes[i].R == R && kTapSizes[i].S == S) return i;
+    return -1;
+}
+
 // Tile shapes of the pointwise (1x1, no padding) family: a work-group is WC x WP waves on 16*MT output
 // channels x WP*64 contiguous pixels of one image; the WC shares split the input channels.
 struct PointwiseVariant {
@@ -181,7 +202,9 @@ constexpr int kNumPanelVariants = sizeof(kPanelVariants) / sizeof(kPanelVariants
 #define PANEL_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8)
 hipError_t launch_panel(int variant, int pix, int grid, int lds_bytes, hipStream_t stream, const KernelArgs& a);
 
-// rs_index: 0 -> 1x1, 1 -> 3x3, 2 -> 5x5. Returns hipSuccess or the launch error.
+// rs_index: index into kTapSizes. Returns hipSuccess, the launch error, or hipErrorInvalidValue for a (size, tile shape)
+// pair that is not built (tap_is_built tells).
+bool tap_is_built(int rs_index, int variant);
 hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid, int lds_bytes,
                       hipStream_t stream, const KernelArgs& a);
 hipError_t launch_generic(int grid, int block, hipStream_t stream, const KernelArgs& a);

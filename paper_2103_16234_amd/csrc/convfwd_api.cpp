@@ -18,20 +18,40 @@ using TapLauncher = hipError_t (*)(int, int, int, int, hipStream_t, const Kernel
 #define DECLARE_TAP1(v) hipError_t launch_tap_1x1_v##v(int, int, int, int, hipStream_t, const KernelArgs&);
 #define DECLARE_TAP3(v) hipError_t launch_tap_3x3_v##v(int, int, int, int, hipStream_t, const KernelArgs&);
 #define DECLARE_TAP5(v) hipError_t launch_tap_5x5_v##v(int, int, int, int, hipStream_t, const KernelArgs&);
+#define DECLARE_TAP_EXTRA(r, s, v) hipError_t launch_tap_##r##x##s##_v##v(int, int, int, int, hipStream_t, const KernelArgs&);
 TAP_VARIANT_LIST(DECLARE_TAP1)
 TAP_VARIANT_LIST(DECLARE_TAP3)
 TAP_VARIANT_LIST(DECLARE_TAP5)
-#define ENTRY_TAP1(v) launch_tap_1x1_v##v,
-#define ENTRY_TAP3(v) launch_tap_3x3_v##v,
-#define ENTRY_TAP5(v) launch_tap_5x5_v##v,
-static const TapLauncher kTapLaunchers[3][kNumTapVariants] = {
-    {TAP_VARIANT_LIST(ENTRY_TAP1)}, {TAP_VARIANT_LIST(ENTRY_TAP3)}, {TAP_VARIANT_LIST(ENTRY_TAP5)}};
+TAP_EXTRA_SIZES(DECLARE_TAP_EXTRA)
+
+// [filter size][tile shape]; null where the pair is not built
+struct TapLauncherTable {
+    TapLauncher fn[kNumTapSizes][kNumTapVariants] = {};
+    TapLauncherTable()
+    {
+#define ENTRY_TAP1(v) fn[0][v] = launch_tap_1x1_v##v;
+#define ENTRY_TAP3(v) fn[1][v] = launch_tap_3x3_v##v;
+#define ENTRY_TAP5(v) fn[2][v] = launch_tap_5x5_v##v;
+#define ENTRY_TAP_EXTRA(r, s, v) fn[tap_size_index(r, s)][v] = launch_tap_##r##x##s##_v##v;
+        TAP_VARIANT_LIST(ENTRY_TAP1)
+        TAP_VARIANT_LIST(ENTRY_TAP3)
+        TAP_VARIANT_LIST(ENTRY_TAP5)
+        TAP_EXTRA_SIZES(ENTRY_TAP_EXTRA)
+    }
+};
+static const TapLauncherTable kTapLaunchers;
+
+bool tap_is_built(int rs_index, int variant)
+{
+    return rs_index >= 0 && rs_index < kNumTapSizes && variant >= 0 && variant < kNumTapVariants &&
+           kTapLaunchers.fn[rs_index][variant] != nullptr;
+}
 
 hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid, int lds_bytes,
                       hipStream_t stream, const KernelArgs& a)
 {
-    if (rs_index < 0 || rs_index > 2 || variant < 0 || variant >= kNumTapVariants) return hipErrorInvalidValue;
-    return kTapLaunchers[rs_index][variant](x_vec, w_vec, grid, lds_bytes, stream, a);
+    if (!tap_is_built(rs_index, variant)) return hipErrorInvalidValue;
+    return kTapLaunchers.fn[rs_index][variant](x_vec, w_vec, grid, lds_bytes, stream, a);
 }
 
 namespace {
@@ -71,11 +91,7 @@ int validate(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-int tap_rs_index(const Shape& s)
-{
-    if (s.R != s.S) return -1;
-    return s.R == 1 ? 0 : s.R == 3 ? 1 : s.R == 5 ? 2 : -1;
-}
+int tap_rs_index(const Shape& s) { return tap_size_index(s.R, s.S); }
 
 void base_args(const Shape& s, KernelArgs* a)
 {
@@ -122,7 +138,7 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
                  conv_plan_t* p, KernelArgs* a, int c_splits = 1)
 {
     const int rs_index = tap_rs_index(s);
-    if (rs_index < 0 || variant < 0 || variant >= kNumTapVariants) return false;
+    if (!tap_is_built(rs_index, variant)) return false;
     const TapVariant tv = kTapVariants[variant];
     const int RS = s.R * s.S, TK = tv.tile_k(), BLOCK = tv.block();
     const int64_t total64 = (int64_t)s.N * s.P * s.Q;

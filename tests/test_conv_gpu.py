@@ -376,9 +376,57 @@ def test_channel_splitting_default_plan_and_workspace_checks():
 
 
 @pytest.mark.parametrize("shape", NONSQUARE, ids=lambda s: s.name)
-def test_other_filter_sizes_use_the_generic_kernel(shape):
+def test_other_filter_sizes_match_oracle(shape):
+    """Sizes the tap kernel is built for run on it; anything else (2x3 here) on the generic kernel."""
     plan, _ = _run(shape)
-    assert plan.kernel == GENERIC
+    assert plan.kernel == (GENERIC if (shape.R, shape.S) == (2, 3) else TAP)
+    _run(shape, kernel=GENERIC)
+
+
+# Filter rows and columns, even and 7x7 filters in the tap kernel (built for a few tile shapes each): ragged K, C not a
+# multiple of the chunk, padding that differs per axis, and one scalar-loader case (C = 6) per orientation.
+EXTRA_SIZE_SHAPES = [
+    S("t1x3", 2, 20, 9, 11, 37, 1, 3, 0, 1),
+    S("t3x1", 2, 20, 9, 12, 37, 3, 1, 1, 0),
+    S("t1x5", 1, 12, 7, 16, 20, 1, 5, 0, 2),
+    S("t5x1", 3, 24, 10, 6, 33, 5, 1, 2, 0),
+    S("t1x7", 1, 16, 6, 17, 18, 1, 7, 0, 3),
+    S("t7x1", 2, 8, 17, 8, 40, 7, 1, 3, 0),
+    S("t7x1_c6", 1, 6, 12, 8, 10, 7, 1, 3, 0),
+    S("t1x3_c6_odd_w", 2, 6, 5, 9, 10, 1, 3, 0, 1),
+    S("t2x2", 2, 16, 8, 8, 24, 2, 2, 0, 0),
+    S("t2x2_pad1", 1, 12, 7, 9, 17, 2, 2, 1, 1),
+    S("t4x4", 2, 8, 10, 12, 19, 4, 4, 1, 2),
+    S("t7x7", 1, 8, 12, 12, 20, 7, 7, 3, 3),
+]
+
+
+@pytest.mark.parametrize("variant", [None, 2, 5, 7, 14, 16, 20, 0])
+@pytest.mark.parametrize("shape", EXTRA_SIZE_SHAPES, ids=lambda s: s.name)
+def test_tap_kernel_on_other_filter_sizes(shape, variant):
+    if variant is None:
+        plan, _ = _run(shape)
+        assert plan.kernel == TAP
+        return
+    try:
+        _run(shape, kernel=TAP, variant=variant)
+    except binding.ConvError as e:
+        assert e.code == -6      # tile shape not built for this size (variant 0 never is), or it does not fit the layer
+
+
+def test_other_filter_sizes_are_exact_on_integers():
+    for dims in [(2, 12, 9, 10, 35, 1, 3, 0, 1), (1, 16, 8, 8, 20, 5, 1, 2, 0), (2, 8, 9, 9, 18, 2, 2, 1, 1),
+                 (1, 8, 10, 10, 12, 4, 4, 2, 2), (1, 4, 9, 12, 6, 7, 7, 3, 3), (1, 12, 6, 14, 9, 1, 7, 0, 3)]:
+        shape = inputs.ConvShape("ints_rs", *dims, "int", "int", 51, 52)
+        plan, _ = _run(shape, exact=True)
+        assert plan.kernel == TAP
+        for variant in (2, 5, 7, 14, 16, 20):
+            try:
+                _run(shape, kernel=TAP, variant=variant, exact=True)
+            except binding.ConvError as e:
+                assert e.code == -6
+    shape = S("split_1x7", 1, 96, 7, 7, 32, 1, 7, 0, 3)
+    _run_split(shape, 20, 3)
 
 
 @pytest.mark.parametrize("dims", [(2, 12, 9, 10, 35, 3, 3, 1, 1), (1, 16, 8, 8, 20, 5, 5, 2, 2),
