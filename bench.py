@@ -29,7 +29,7 @@ BOUND = {1: "hbm", 2: "hbm", 3: "mfma", 4: "mfma", 5: "mfma"}
 # Bytes per launch that the L2s exchanged with the fabric (Infinity Cache / HBM), measured with rocprofv3 --pmc
 # FETCH_SIZE and WRITE_SIZE and scaled by what the same counters read for a plain device copy of known size
 # (profiles/conv_kernels_hbm_traffic.txt); None = not measured.
-TRAFFIC_BYTES = {1: None, 2: 4792720, 3: 14200244, 4: None, 5: 101440509}
+TRAFFIC_BYTES = {1: None, 2: 4792895, 3: 14202266, 4: None, 5: 101456946}
 
 
 def _fail(msg: str, code: int = 2):
@@ -83,6 +83,22 @@ class Layer:
         wall_ms = (time.perf_counter() - t0) * 1e3 / steps
         event_ms = ev0.elapsed_time(ev1) / steps
         return wall_ms, event_ms
+
+    def single_launches(self, n=25):
+        """Every launch between an event pair of its own (the paper's protocol, Section 4: the mean of nine runs per
+        configuration): min / median / mean of n launches. Each figure includes the launch gap a lone launch sees."""
+        torch = self.torch
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for _ in range(5):
+            self.step()
+        torch.cuda.synchronize()
+        for e0, e1 in pairs:
+            e0.record()
+            self.step()
+            e1.record()
+        torch.cuda.synchronize()
+        us = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in pairs)
+        return {"n": n, "min": us[0], "median": us[n // 2], "mean": sum(us) / n}
 
     def report(self, wall_ms, event_ms, steps):
         s = self.shape
@@ -386,6 +402,7 @@ def main():
             w_ms, e_ms = layer.measure(k, ns.warmup)
             rec = layer.report(w_ms, e_ms, k)
             rec["parity"] = layer.parity_sample(oracle, 256)
+            rec["single_launch_us"] = layer.single_launches()
             rec["frac_of_measured_mfma"] = rec["gflops"] / 1e3 / measured["mfma_fp32_tflops"]
             rec["frac_of_measured_copy_bw"] = rec["gbs"] / measured["copy_read_plus_write_gbs"]
             layers.append(rec)
