@@ -105,8 +105,9 @@ __global__ void __launch_bounds__(256) conv_split_reduce(const float* __restrict
                                                          const float* __restrict__ bias, int relu, int splits, int total,
                                                          int K, FastDiv div_PQ, FastDiv div_K)
 {
-    const int i = (blockIdx.x * 256 + threadIdx.x) * V;
-    if (i >= total) return;
+    const long long i64 = (static_cast<long long>(blockIdx.x) * 256 + threadIdx.x) * V;  // may pass 2^31 in the last work-group
+    if (i64 >= total) return;
+    const int i = static_cast<int>(i64);
     const unsigned nk = div_PQ.div(i);
     const unsigned k = nk - div_K.div(nk) * K;
     const float b = bias ? bias[k] : 0.f;
