@@ -409,6 +409,23 @@ def main():
             del layer
             torch.cuda.empty_cache()
         out["layers"] = layers
+        # The headline 1x1 layer is launch-bound at batch 1 (its roofline time is below one kernel dispatch): the same layer
+        # at larger batches, and an HBM-bound 64 -> 64 channel layer, show what the 1x1 path sustains.
+        scaled = []
+        for name, dims in (("cfg2 at N=32", (32, 256, 56, 56, 64, 1, 1, 0, 0)), ("cfg2 at N=128", (128, 256, 56, 56, 64, 1, 1, 0, 0)),
+                           ("1x1 64->64 channels, 56x56, N=128", (128, 64, 56, 56, 64, 1, 1, 0, 0))):
+            layer = Layer(inputs.ConvShape(name, *dims, "u01", "he", 1002, 2002), torch, binding, inputs, max_sets=16)
+            k = auto_steps(layer)
+            _, e_ms = layer.measure(k, ns.warmup)
+            roof = layer.roofline(e_ms)
+            scaled.append({"layer": name, "kernel_us": e_ms * 1e3, "tflops": layer.shape.flops / e_ms / 1e9,
+                           "gbs": layer.shape.algorithmic_bytes / e_ms / 1e6, "bound": roof["bound"], "frac": roof["frac"],
+                           "frac_hbm_peak": layer.shape.algorithmic_bytes / e_ms / 1e6 / PEAK_HBM_GBS,
+                           "frac_of_measured_copy_bw": layer.shape.algorithmic_bytes / e_ms / 1e6 / measured["copy_read_plus_write_gbs"],
+                           "parity_ok": layer.parity_sample(oracle, 128)["ok"]})
+            del layer
+            torch.cuda.empty_cache()
+        out["batch_scaled_1x1"] = scaled
     if ns.paper_shapes:
         out["paper_shapes"] = paper_shapes(torch, binding, inputs, oracle)
     if ns.sweep is not None:
