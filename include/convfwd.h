@@ -11,17 +11,20 @@
  *   xpad = x inside [0,H) x [0,W) and 0 outside
  *   P = H + 2*pad_h - R + 1,   Q = W + 2*pad_w - S + 1
  *
- * The filter is not flipped, there is no bias, scaling or activation, and y is
- * overwritten. All arithmetic is fp32 (fp32 FMA or full-precision fp32 MFMA,
+ * The filter is not flipped, there is no scaling, y is overwritten, and bias and
+ * activation exist only as the optional fused epilogue of conv_fwd_bias_relu /
+ * conv_fwd_split_c. All arithmetic is fp32 (fp32 FMA or full-precision fp32 MFMA,
  * fp32 accumulation); no reduced-precision type is used anywhere.
  *
  * Layout: x is [N][C][H][W], w is [K][C][R][S], y is [N][K][P][Q], all dense
  * and contiguous, W / S / Q fastest. Stride, dilation and groups are fixed to 1.
  *
  * Ownership: x, w and y are DEVICE pointers owned by the caller; the library
- * never allocates, frees or keeps them and needs no workspace. x and w must not
- * overlap y. Calls are asynchronous on the stream given to conv_set_stream
- * (default: the null stream); the caller synchronises.
+ * never allocates, frees or keeps them, and needs no workspace except in the two
+ * opt-in entry points that take one from the caller (conv_fwd_split_c,
+ * conv_fwd_two_stage). x and w must not overlap y. Calls are asynchronous on
+ * the stream given to conv_set_stream (default: the null stream); the caller
+ * synchronises.
  *
  * Errors: every entry point returns 0 on success or a negative CONV_E_* code;
  * nothing throws or aborts. Results are bitwise reproducible for equal inputs
