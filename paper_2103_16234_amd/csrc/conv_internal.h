@@ -138,9 +138,13 @@ constexpr TapVariant kTapVariants[] = {
     {1, 7, 2, 1, 4, 2, 2, 8, 12},   // 19: as 12 with 32-channel chunks: half as many barriers per layer
     {1, 2, 1, 1, 4, 2, 2, 4, 16},   // 20: as 11 with 32-channel chunks
     {1, 11, 4, 1, 2, 2, 2, 4, 12},  // 21: 64 ch x 176 px: a whole 13x13 image per work-group
+    {1, 7, 1, 4, 1, 1, 3, 4, 8},    // 22: as 16 with three waves per SIMD: first layers are all prologue and stores, occupancy hides them
+    {1, 7, 2, 2, 1, 1, 3, 4, 8},    // 23: 32 ch x 224 px, 4-channel chunks, three waves per SIMD
+    {1, 1, 1, 4, 1, 2, 4, 4, 8},    // 24: as 2 with four waves per SIMD
+    {1, 2, 2, 2, 1, 2, 4, 4, 8},    // 25: as 4 with four waves per SIMD
 };
 constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
-#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18) X(19) X(20) X(21)
+#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18) X(19) X(20) X(21) X(22) X(23) X(24) X(25)
 
 // Filter sizes the tap kernel is instantiated for. The three the paper evaluates (Section 4: 1x1, 3x3, 5x5) get every
 // tile shape; the others (filter rows and columns, even and 7x7 filters, as the factorised layers of later CNNs use)

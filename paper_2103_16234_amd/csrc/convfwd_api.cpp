@@ -394,7 +394,7 @@ void resolve_generic(const Shape& s, conv_plan_t* p, KernelArgs* a)
 
 // Estimated cycles of a tap mapping on 256 CUs, fitted to timings of every tile shape x pixel tile over a
 // grid of 3x3 and 5x5 layers (batch 1..128, maps 7..224): the mapping it picks is on average within 2 % of
-// the best one measured (worst case 1.24x). Work-groups are dealt round-robin, so the busiest CU runs
+// the best one measured (worst case 1.22x). Work-groups are dealt round-robin, so the busiest CU runs
 // cu = ceil(grid / 256) of them, wpc at a time (registers, LDS). Per chunk that CU takes the longest of
 //   all its matrix work          (cu x per-SIMD cycles: 32 per MFMA plus ~150 per staging slot of a thread - the
 //                                 load, the LDS store and their address arithmetic take issue slots from the
@@ -420,8 +420,11 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
     const double staged = 4.0 * ((double)tv.chunk_c() * a.lds_rows * a.W + (double)tv.tile_k() * tv.chunk_c() * RS);
     const double chunk = std::max(std::max(cu * work / eff, batches * (1500.0 + work)), cu * staged / 12.0);
     const double tree = tv.WC > 1 ? tv.MT * tv.NT * 1024.0 * tv.WK * tv.WP / 64.0 * std::log2((double)tv.WC) : 0.0;
-    return a.nchunks * chunk + batches * 12000.0 + cu * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree) + 5000.0 +
-           12.0 * p.grid;
+    const double cycles = a.nchunks * chunk + batches * 12000.0 + cu * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree) + 5000.0 +
+                          12.0 * p.grid;
+    // Tile shapes compiled for three or four waves per SIMD measure ~3 % faster per step of occupancy than their
+    // two-wave twins even where the model sees no difference (all work-groups co-resident either way).
+    return cycles * (1.0 - 0.03 * std::max(0, tv.occ - 2));
 }
 
 // Measured best mappings of known layer shapes (sweeps over tile shape x pixel tile on an MI355X);
