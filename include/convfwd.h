@@ -49,7 +49,7 @@ extern "C" {
 /* Kernel families a plan can name. */
 #define CONV_KERNEL_GENERIC 0 /* one output per thread, fp32 FMA; any R, S, padding */
 #define CONV_KERNEL_TAP 1     /* LDS halo tile + filter block, fp32 MFMA over (channel, tap); 1x1, 3x3, 5x5 with every tile
-                                 shape; 1x3, 3x1, 1x5, 5x1, 1x7, 7x1, 2x2, 4x4, 7x7 with tile shapes 2, 5, 7, 14, 16, 20 */
+                                 shape; 1x3, 3x1, 1x5, 5x1, 1x7, 7x1, 2x2, 4x4, 7x7 with tile shapes 2, 5, 7, 14, 16, 20, 22 */
 #define CONV_KERNEL_POINTWISE 2 /* 1x1, pad 0: inputs and filters streamed HBM -> registers -> fp32 MFMA, waves split C */
 #define CONV_KERNEL_PANEL 3   /* 1x1, pad 0, batched: filters of a channel tile resident in LDS, waves stream pixel tiles */
 

@@ -149,7 +149,7 @@ constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
 // Filter sizes the tap kernel is instantiated for. The three the paper evaluates (Section 4: 1x1, 3x3, 5x5) get every
 // tile shape; the others (filter rows and columns, even and 7x7 filters, as the factorised layers of later CNNs use)
 // a small set that covers tiny, deep batch-1, medium and wide-map layers. Any other size runs the generic kernel.
-#define TAP_EXTRA_VARIANTS(X, r, s) X(r, s, 2) X(r, s, 5) X(r, s, 7) X(r, s, 14) X(r, s, 16) X(r, s, 20)
+#define TAP_EXTRA_VARIANTS(X, r, s) X(r, s, 2) X(r, s, 5) X(r, s, 7) X(r, s, 14) X(r, s, 16) X(r, s, 20) X(r, s, 22)
 #define TAP_EXTRA_SIZES(X)                                                                                         \
     TAP_EXTRA_VARIANTS(X, 1, 3) TAP_EXTRA_VARIANTS(X, 3, 1) TAP_EXTRA_VARIANTS(X, 1, 5) TAP_EXTRA_VARIANTS(X, 5, 1) \
     TAP_EXTRA_VARIANTS(X, 1, 7) TAP_EXTRA_VARIANTS(X, 7, 1) TAP_EXTRA_VARIANTS(X, 2, 2) TAP_EXTRA_VARIANTS(X, 4, 4) \

@@ -117,7 +117,7 @@ def test_plans_cover_odd_shapes():
     # filter rows / columns, even and 7x7 filters have tap kernels too (a few tile shapes each); other sizes do not
     for R, S in [(1, 3), (3, 1), (1, 5), (5, 1), (1, 7), (7, 1), (2, 2), (4, 4), (7, 7)]:
         p = binding.conv_fwd_plan(8, 64, 17, 17, 96, R, S, (R - 1) // 2, (S - 1) // 2)
-        assert p.kernel == binding.CONV_KERNEL_TAP and p.variant in (2, 5, 7, 14, 16, 20)
+        assert p.kernel == binding.CONV_KERNEL_TAP and p.variant in (2, 5, 7, 14, 16, 20, 22)
     for R, S in [(2, 3), (6, 6), (3, 5), (9, 9), (1, 2)]:
         assert binding.conv_fwd_plan(8, 64, 17, 17, 96, R, S, 0, 0).kernel == binding.CONV_KERNEL_GENERIC
 

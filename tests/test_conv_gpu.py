@@ -401,7 +401,7 @@ EXTRA_SIZE_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("variant", [None, 2, 5, 7, 14, 16, 20, 0])
+@pytest.mark.parametrize("variant", [None, 2, 5, 7, 14, 16, 20, 22, 0])
 @pytest.mark.parametrize("shape", EXTRA_SIZE_SHAPES, ids=lambda s: s.name)
 def test_tap_kernel_on_other_filter_sizes(shape, variant):
     if variant is None:
@@ -420,7 +420,7 @@ def test_other_filter_sizes_are_exact_on_integers():
         shape = inputs.ConvShape("ints_rs", *dims, "int", "int", 51, 52)
         plan, _ = _run(shape, exact=True)
         assert plan.kernel == TAP
-        for variant in (2, 5, 7, 14, 16, 20):
+        for variant in (2, 5, 7, 14, 16, 20, 22):
             try:
                 _run(shape, kernel=TAP, variant=variant, exact=True)
             except binding.ConvError as e:
