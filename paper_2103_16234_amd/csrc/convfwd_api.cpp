@@ -32,7 +32,9 @@ struct TapLauncherTable {
 #define ENTRY_TAP1(v) fn[0][v] = launch_tap_1x1_v##v;
 #define ENTRY_TAP3(v) fn[1][v] = launch_tap_3x3_v##v;
 #define ENTRY_TAP5(v) fn[2][v] = launch_tap_5x5_v##v;
-#define ENTRY_TAP_EXTRA(r, s, v) fn[tap_size_index(r, s)][v] = launch_tap_##r##x##s##_v##v;
+#define ENTRY_TAP_EXTRA(r, s, v)                                                                                      \
+    static_assert(tap_size_index(r, s) >= kNumFullTapSizes && v < kNumTapVariants, "size or tile shape missing from the tables"); \
+    fn[tap_size_index(r, s)][v] = launch_tap_##r##x##s##_v##v;
         TAP_VARIANT_LIST(ENTRY_TAP1)
         TAP_VARIANT_LIST(ENTRY_TAP3)
         TAP_VARIANT_LIST(ENTRY_TAP5)

@@ -523,6 +523,40 @@ def test_runs_on_the_callers_stream():
     binding.conv_set_stream(None)
 
 
+def test_repeated_plan_requests_hit_the_cache_and_stay_apart():
+    """Resolved requests are remembered per (shape, request): the same request twice gives the same bits, and requests
+    that differ in one field only (tile shape, pixel tile, work-groups per channel tile) are not mixed up."""
+    shape = SMALL[1]
+    x, w, y_ref, ya_ref = _reference(shape)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    seen = {}
+    for rep in range(2):
+        for variant, tile_pix in ((2, 0), (2, 16), (5, 0), (5, 17), (2, 0)):
+            y, plan = binding.conv_fwd_planned(xd, wd, shape.pad_h, shape.pad_w, TAP, variant, tile_pix, 0)
+            torch.cuda.synchronize()
+            assert plan.variant == variant and (tile_pix == 0 or plan.tile_pix == tile_pix)
+            ok, worst = oracle.within_tolerance(y.cpu().numpy().astype(np.float64), y_ref, ya_ref)
+            assert ok, worst
+            key = (variant, tile_pix)
+            if key in seen:
+                assert torch.equal(seen[key][0], y) and seen[key][1] == (plan.tile_pix, plan.grid)
+            seen[key] = (y.clone(), (plan.tile_pix, plan.grid))
+    assert seen[(2, 0)][1] != seen[(2, 16)][1] and seen[(5, 0)][1] != seen[(5, 17)][1]
+    pshape = PANEL_SHAPES[8]
+    x, w, y_ref, ya_ref = _reference(pshape)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    grids = set()
+    for rep in range(2):
+        for groups in (0, 1, 3):
+            y, plan = binding.conv_fwd_planned(xd, wd, 0, 0, PANEL, 7, groups, 0)
+            torch.cuda.synchronize()
+            assert oracle.within_tolerance(y.cpu().numpy().astype(np.float64), y_ref, ya_ref)[0]
+            if groups:
+                assert plan.tile_pix == groups
+            grids.add((groups, plan.grid))
+    assert len(grids) == 3
+
+
 def test_bad_plan_requests_are_refused():
     shape = S("badplan", 1, 8, 6, 6, 8, 3, 3, 1, 1)
     x, w = inputs.make_inputs(shape)
