@@ -97,7 +97,7 @@ def test_generic_kernel_matches_oracle(shape):
     _run(shape, kernel=GENERIC)
 
 
-@pytest.mark.parametrize("variant", range(24))
+@pytest.mark.parametrize("variant", range(30))
 @pytest.mark.parametrize("shape", SMALL, ids=lambda s: s.name)
 def test_every_tap_variant_matches_oracle(shape, variant):
     if variant >= binding.conv_variant_count(TAP):
