@@ -116,8 +116,9 @@ int conv_fwd_planned(const float* x, const float* w, float* y,
 /*
  * Measured choice of the mapping, for callers who run a layer many times (what "the best algorithm of the
  * library" means in the comparisons of Section 4): runs every mapping the kernels accept for this layer on
- * the caller's tensors - all tile shapes of the matching families with the planner's candidate pixel tiles,
- * tap shapes only while their modelled cost is within 2.5x of the best - times each with events on the
+ * the caller's tensors - all tile shapes of the matching families with the planner's candidate pixel tiles
+ * (panel kernel: the planner's grid and one and two work-groups per CU), tap shapes only while their
+ * modelled cost is within 2.5x of the best - times each with events on the
  * library's stream, and keeps the fastest: it is stored in the plan cache, so conv_fwd and
  * conv_fwd_bias_relu use it from then on for this shape and pointer alignment, and returned in *best_plan
  * with its time per launch in *best_us (either may be null). Without a flush buffer each mapping is timed

@@ -279,10 +279,10 @@ bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w
         // Layers near or below the machine balance (~20 flop per byte) stream: there one work-group per CU is fastest
         // (measured on 128 x 64 x 56 x 56 -> 64: 40.7 us with 256 work-groups, 45.0 with 512; 128 x 64 x 27 x 27 -> 64:
         // 11.6 against 14.4), a second wave per SIMD buys nothing and every further work-group per CU costs ~8 %.
-        // That holds for long layers only (eight or more tiles per wave at one work-group per CU); short ones gain more
+        // That holds for long layers only (six or more tiles per wave at one work-group per CU); short ones gain more
         // from the extra waves that hide their start-up latencies.
         const bool streaming = 2.0 * s.C * s.K / (4.0 * (s.C + s.K)) < 32.0 &&
-                               (int64_t)tiles * a->ktiles >= (int64_t)8 * kNumCU * pv.NW;
+                               (int64_t)tiles * a->ktiles >= (int64_t)6 * kNumCU * pv.NW;
         double best = 0;
         auto consider = [&](int g) {
             g = std::max(1, std::min(g, most));
@@ -767,8 +767,9 @@ extern "C" int conv_fwd_bias_relu(const float* x, const float* w, const float* b
     return run_planned(x, w, bias, y, N, C, H, W, K, R, S, pad_h, pad_w, relu != 0, plan, resolved);
 }
 
-// Every mapping worth timing for a layer: all pointwise and panel shapes (with the planner's grid), every tap shape x
-// candidate pixel tile whose modelled cost is within 2.5x of the best modelled one, or the generic kernel.
+// Every mapping worth timing for a layer: all pointwise and panel shapes (panel: with the planner's grid and with one
+// and two work-groups per CU), every tap shape x candidate pixel tile whose modelled cost is within 2.5x of the best
+// modelled one, or the generic kernel.
 struct Candidate {
     conv_plan_t p;
     KernelArgs a;
@@ -782,8 +783,17 @@ static void enumerate_candidates(const Shape& s, int x_cap, int w_cap, int y_cap
     if (pointwise_ok(s, x_cap, w_cap, y_cap)) {
         for (int v = 0; v < kNumPointwiseVariants; ++v)
             if (resolve_pointwise(s, v, x_cap, w_cap, y_cap, &c.p, &c.a)) out->push_back(c);
-        for (int v = 0; v < kNumPanelVariants; ++v)
-            if (resolve_panel(s, v, 0, x_cap, w_cap, y_cap, &c.p, &c.a)) out->push_back(c);
+        for (int v = 0; v < kNumPanelVariants; ++v) {
+            if (!resolve_panel(s, v, 0, x_cap, w_cap, y_cap, &c.p, &c.a)) continue;
+            out->push_back(c);
+            // besides the planner's grid: one and two work-groups per CU
+            const int planned = c.p.tile_pix, ktiles = c.a.ktiles;
+            for (int per_cu = 1; per_cu <= 2; ++per_cu) {
+                const int groups = std::max(1, ceil_div(kNumCU * per_cu, ktiles));
+                if (groups != planned && resolve_panel(s, v, groups, x_cap, w_cap, y_cap, &c.p, &c.a) && c.p.tile_pix != planned)
+                    out->push_back(c);
+            }
+        }
     }
     if (tap_rs_index(s) >= 0) {
         std::vector<Candidate> taps;
