@@ -114,6 +114,17 @@ int conv_fwd_planned(const float* x, const float* w, float* y,
                      const conv_plan_t* plan, conv_plan_t* resolved);
 
 /*
+ * Host-only "what if": resolves a request exactly as conv_fwd_planned / conv_fwd_split_c would for 16-byte aligned
+ * tensors (request fields as in conv_fwd_planned, plus c_splits), without touching a device. resolved receives
+ * the launch; model_cycles (may be null) the planner's cost estimate of it in GPU cycles - tap family only
+ * (0 for the others), second pass included when c_splits > 1. The planner of Section 3's "number of thread
+ * blocks" question is this estimate minimised over the tile shapes and pixel tiles. Returns CONV_OK,
+ * CONV_E_NULL / _DIM / _EMPTY / _OVERFLOW, or CONV_E_PLAN if the request cannot be honoured.
+ */
+int conv_fwd_plan_request(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
+                          const conv_plan_t* request, conv_plan_t* resolved, double* model_cycles);
+
+/*
  * Measured choice of the mapping, for callers who run a layer many times (what "the best algorithm of the
  * library" means in the comparisons of Section 4): runs every mapping the kernels accept for this layer on
  * the caller's tensors - all tile shapes of the matching families with the planner's candidate pixel tiles

@@ -19,7 +19,7 @@ CONV_KERNEL_POINTWISE = 2
 CONV_KERNEL_PANEL = 3
 
 EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_fwd_find", "conv_two_stage_workspace_bytes",
-           "conv_fwd_two_stage", "conv_fwd_plan_split_c", "conv_fwd_split_c", "conv_probe_mfma", "conv_probe_copy",
+           "conv_fwd_two_stage", "conv_fwd_plan_split_c", "conv_fwd_split_c", "conv_fwd_plan_request", "conv_probe_mfma", "conv_probe_copy",
            "conv_variant_count", "conv_variant_info", "conv_set_stream", "conv_strerror")
 
 
@@ -70,6 +70,7 @@ def load_library():
     lib.conv_two_stage_workspace_bytes.restype = ctypes.c_longlong
     lib.conv_fwd_two_stage.argtypes = [vp, vp, vp, vp, ctypes.c_longlong] + dims
     lib.conv_fwd_plan_split_c.argtypes = dims + [ctypes.POINTER(ConvPlan)]
+    lib.conv_fwd_plan_request.argtypes = dims + [ctypes.POINTER(ConvPlan), ctypes.POINTER(ConvPlan), ctypes.POINTER(ctypes.c_double)]
     lib.conv_fwd_split_c.argtypes = [vp, vp, vp, vp, vp, ctypes.c_longlong] + dims + [ci, ctypes.POINTER(ConvPlan),
                                                                                    ctypes.POINTER(ConvPlan)]
     lib.conv_probe_mfma.argtypes = [ci, vp]
@@ -183,6 +184,16 @@ def conv_fwd_bias_relu(x, w, bias, pad_h: int, pad_w: int, relu: bool, kernel=No
                                   *dims, int(bool(relu)), ctypes.byref(req) if req is not None else None,
                                   ctypes.byref(res)))
     return y, res
+
+
+def conv_fwd_plan_request(N, C, H, W, K, R, S, pad_h, pad_w, kernel: int, variant: int = 0, tile_pix: int = 0,
+                          c_splits: int = 0):
+    """Host-only: resolve a requested mapping without launching it; returns (plan, modelled cycles - tap family only)."""
+    req, res, cycles = ConvPlan(), ConvPlan(), ctypes.c_double(0)
+    req.kernel, req.variant, req.tile_pix, req.c_splits = kernel, variant, tile_pix, c_splits
+    _check(load_library().conv_fwd_plan_request(N, C, H, W, K, R, S, pad_h, pad_w, ctypes.byref(req), ctypes.byref(res),
+                                                ctypes.byref(cycles)))
+    return res, float(cycles.value)
 
 
 def conv_fwd_plan_split_c(N, C, H, W, K, R, S, pad_h, pad_w) -> ConvPlan:

@@ -552,6 +552,10 @@ constexpr double kSplitPassCycles = 10000.0;
 constexpr double kSplitShareCycles = 500.0;
 constexpr int kSplitCandidates[] = {1, 2, 3, 4, 6, 8, 12, 16};
 void search_split_plans(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a);
+double split_pass_cycles(int splits, int K, int total_pix)
+{
+    return kSplitPassCycles + kSplitShareCycles * splits + 4.0 * (splits + 1) * K * total_pix / (kNumCU * 16.0);
+}
 std::vector<CacheEntry> g_split_cache;  // under g_cache_mutex, like g_cache
 
 int plan_split_shape(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
@@ -595,7 +599,7 @@ void search_split_plans(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, Ke
                     continue;
                 }
                 if (cp.grid > 2 * kNumCU) continue;
-                c += kSplitPassCycles + kSplitShareCycles * splits + 4.0 * (splits + 1) * s.K * ca.total_pix / (kNumCU * 16.0);
+                c += split_pass_cycles(splits, s.K, ca.total_pix);
                 if (!have_split || c < best_split * 0.999) {
                     have_split = true; best_split = c; sp = cp; sa = ca;
                 }
@@ -734,6 +738,24 @@ static int run_planned(const float* x, const float* w, const float* bias, float*
     if (workspace_bytes < p.workspace_bytes) return CONV_E_WORKSPACE;
     if (int rc = launch(p, a, s, x, w, workspace)) return rc;
     return record_hip(launch_split_reduce(workspace, y, bias, relu, p.c_splits, s.K * a.total_pix, a.PQ, s.K, g_stream.load()));
+}
+
+extern "C" int conv_fwd_plan_request(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
+                                     const conv_plan_t* request, conv_plan_t* resolved, double* model_cycles)
+{
+    if (!request || !resolved) return CONV_E_NULL;
+    Shape s;
+    if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
+    KernelArgs a;
+    if (int rc = resolve_request(s, 4, 4, 4, *request, true, resolved, &a)) return rc;
+    if (model_cycles) {
+        *model_cycles = 0.0;
+        if (resolved->kernel == CONV_KERNEL_TAP) {
+            *model_cycles = tap_cost(*resolved, a, kTapVariants[resolved->variant], s.R * s.S);
+            if (resolved->c_splits > 1) *model_cycles += split_pass_cycles(resolved->c_splits, s.K, a.total_pix);
+        }
+    }
+    return CONV_OK;
 }
 
 extern "C" int conv_fwd_plan_split_c(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w, conv_plan_t* out)

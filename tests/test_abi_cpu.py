@@ -183,6 +183,48 @@ def test_channel_splitting_plans_are_well_formed():
     assert wide.c_splits == 1                                    # plenty of output tiles: nothing to gain
 
 
+def test_plan_requests_resolve_on_the_host_and_the_planner_minimises_the_model():
+    """conv_fwd_plan_request is conv_fwd_planned without the launch; for tap-family layers the default plan is the
+    request with the smallest modelled cost among every tile shape at its capacity tile and at the default's tile."""
+    tap = binding.CONV_KERNEL_TAP
+    lib = binding.load_library()
+    req, res = binding.ConvPlan(), binding.ConvPlan()
+    ok = (1, 4, 8, 8, 4, 3, 3, 1, 1)
+    assert lib.conv_fwd_plan_request(*ok, None, ctypes.byref(res), None) == -1
+    assert lib.conv_fwd_plan_request(*ok, ctypes.byref(req), None, None) == -1
+    assert lib.conv_fwd_plan_request(1, 4, 2, 8, 4, 5, 5, 1, 2, ctypes.byref(req), ctypes.byref(res), None) == -3
+    req.kernel, req.variant = tap, 999
+    assert lib.conv_fwd_plan_request(*ok, ctypes.byref(req), ctypes.byref(res), None) == -6
+    req.kernel, req.variant = binding.CONV_KERNEL_POINTWISE, 0
+    assert lib.conv_fwd_plan_request(*ok, ctypes.byref(req), ctypes.byref(res), None) == -6       # 3x3: not a pointwise layer
+    checked = 0
+    for s in inputs.sweep_shapes()[5::9]:
+        base = binding.conv_fwd_plan(*s.dims)
+        same, cost = binding.conv_fwd_plan_request(*s.dims, base.kernel, base.variant, base.tile_pix)
+        assert (same.kernel, same.variant, same.tile_pix, same.grid, same.block, same.lds_bytes) == \
+               (base.kernel, base.variant, base.tile_pix, base.grid, base.block, base.lds_bytes)
+        if base.kernel != tap:
+            assert cost == 0.0
+            continue
+        assert cost > 0.0
+        if s.dims in [tuple(c.dims) for c in (inputs.config(i) for i in range(1, 6))]:
+            continue                                             # the five benchmark layers use measured mappings
+        for variant in range(binding.conv_variant_count(tap)):
+            for tile in (0, base.tile_pix):
+                try:
+                    other, c = binding.conv_fwd_plan_request(*s.dims, tap, variant, tile)
+                except binding.ConvError as e:
+                    assert e.code == -6
+                    continue
+                assert c >= cost * 0.998, (s.name, variant, other.tile_pix, c, cost)
+        checked += 1
+    assert checked >= 5
+    split, c2 = binding.conv_fwd_plan_request(1, 512, 7, 7, 512, 3, 3, 1, 1, tap, 13, 25, c_splits=8)
+    whole, c1 = binding.conv_fwd_plan_request(1, 512, 7, 7, 512, 3, 3, 1, 1, tap, 13, 25)
+    assert split.c_splits == 8 and split.grid == 8 * whole.grid and split.workspace_bytes == 4 * 8 * 512 * 49
+    assert c2 < c1                                               # the model agrees that this layer wants shares
+
+
 def test_panel_plans_follow_the_batch():
     """The panel kernel takes over from the register-streaming kernel once a 1x1 layer has enough tiles."""
     small = binding.conv_fwd_plan(1, 256, 56, 56, 64, 1, 1, 0, 0)
