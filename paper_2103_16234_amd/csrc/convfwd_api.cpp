@@ -347,6 +347,10 @@ int pick_pointwise(const Shape& s)
     if (waves_v2 >= 4096) return 2;  // {MT 2, WC 4}
     const int64_t groups = pix_tiles * ceil_div(s.K, 16);
     const int steps = ceil_div(s.C, 16);
+    // about one 32-channel work-group per CU and 256 or more channels: eight shares of them (measured 4-18 % over the
+    // 16-channel shapes on 32 x 832 x 7 x 7 -> 256, 4 x 512 x 14 x 14 -> 512, 16 x 320 x 7 x 7 -> 512)
+    const int64_t groups32 = pix_tiles * ceil_div(s.K, 32);
+    if (groups32 >= 224 && groups32 <= 288 && steps >= 16) return 3;  // {MT 2, WC 8}
     // {1, 4} or {1, 8} shares (16 shares, 1024 threads, measured 25 % slower even on 512..832 channels); with three or
     // more steps per wave the twin that keeps four steps of loads in flight (3-7 % on 512..1024-channel N=1 layers)
     if (groups * 4 >= 1024 || steps <= 8) return steps >= 12 ? 15 : 0;
@@ -362,9 +366,9 @@ int pick_panel(const Shape& s, int x_cap, int y_cap)
 {
     const int64_t tiles = ((int64_t)s.N * s.H * s.W + 63) / 64;
     if (tiles * ceil_div(s.K, 32) < 704) {
-        // fewer 32-channel units than that, but enough 16-channel ones: 16 channels per panel still beat the
+        // fewer 32-channel units than that, but 512 or more 16-channel ones: 16 channels per panel still beat the
         // channel-splitting kernel by 5-25 % in the sweeps (deep layers on 7..14-pixel maps at batch 8..32)
-        if (tiles * ceil_div(s.K, 16) >= 704 && 16 * (round_up(s.C, 64) + 4) * 4 <= kLdsMax) return 5;  // {1, 4, 4}
+        if (tiles * ceil_div(s.K, 16) >= 512 && 16 * (round_up(s.C, 64) + 4) * 4 <= kLdsMax) return 5;  // {1, 4, 4}
         return -1;
     }
     const bool dwords = panel_pixel_mode(s, x_cap, y_cap) == 1;
