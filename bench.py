@@ -290,6 +290,47 @@ def sweep(torch, binding, inputs, oracle, only=None, find=False):
     return rows
 
 
+def holdout(torch, binding, inputs, oracle, seed, count=40):
+    """Planner check on layers it was not fitted on: `count` random shapes inside the paper's ranges but off the sweep
+    grid (other batch sizes, channel counts and map sizes), each timed with the default mapping and with the one
+    conv_fwd_find measures to be fastest."""
+    import random
+    rng = random.Random(seed)
+    flush = torch.empty(128 * 1024 * 1024, device="cuda")
+    shapes = []
+    while len(shapes) < count:
+        f = rng.choice([1, 3, 3, 5])
+        n = rng.choice([1, 2, 4, 16, 64])
+        h = rng.choice([7, 10, 14, 17, 20, 28, 35, 40, 56, 80, 112])
+        c = rng.choice([16, 24, 48, 80, 128, 160, 320, 448, 640])
+        k = rng.choice([24, 48, 96, 160, 256, 320, 512, 768])
+        if (f == 5 and c > 128) or n * c * h * h > 2 ** 24 or n * k * h * h > 2 ** 24:
+            continue
+        shapes.append(inputs.ConvShape(f"holdout_{f}x{f}_n{n}_c{c}_{h}_k{k}", n, c, h, h, k, f, f, f // 2, f // 2, "u01", "he",
+                                       5000 + len(shapes), 6000 + len(shapes)))
+    rows = []
+    for shape in shapes:
+        layer = Layer(shape, torch, binding, inputs, min_bytes=400e6, max_sets=32)
+        _, ev = layer.measure(10, 5)
+        k = int(max(20, min(500, 0.02 / max(ev * 1e-3, 1e-7))))
+        layer.measure(k, 3)                                   # clocks and caches settle: the second run counts
+        _, d_ms = layer.measure(k, 3)
+        _, fp, _ = binding.conv_fwd_find(layer.x[0], layer.w[0], shape.pad_h, shape.pad_w, y=layer.y[0], flush=flush)
+        _, f_ms = layer.measure(k, 3)
+        par = layer.parity_sample(oracle, 64)
+        p = layer.plan
+        rows.append({"shape": shape.name, "default_us": d_ms * 1e3, "found_us": f_ms * 1e3, "frac": layer.roofline(d_ms)["frac"],
+                     "default_plan": [p.kernel, p.variant, p.tile_pix, p.grid, p.block],
+                     "found_plan": [fp.kernel, fp.variant, fp.tile_pix, fp.grid, fp.block], "found_parity_ok": par["ok"]})
+        print(f"holdout {shape.name}: default {d_ms * 1e3:.1f} us, found {f_ms * 1e3:.1f} us, parity {par['ok']}", file=sys.stderr,
+              flush=True)
+        del layer
+        torch.cuda.empty_cache()
+    ratios = [r["default_us"] / min(r["default_us"], r["found_us"]) for r in rows]
+    return {"seed": seed, "layers": rows, "default_over_found_geomean": float(np.exp(np.mean(np.log(ratios)))),
+            "default_over_found_worst": max(ratios)}
+
+
 def split_c_layers(torch, binding, inputs, oracle):
     """Channel splitting across work-groups (conv_fwd_split_c) against the single-kernel default, on every layer of the
     sweep grid and of the paper's profiled shapes for which the splitting planner asks for more than one share."""
@@ -344,6 +385,8 @@ def main():
                     help="also run the synthetic shape sweep (optionally only shapes whose name contains SUBSTR)")
     ap.add_argument("--find", action="store_true",
                     help="with --sweep: also time each layer with the mapping conv_fwd_find measures to be fastest")
+    ap.add_argument("--holdout", type=int, default=None, metavar="SEED",
+                    help="also compare default and measured-best mappings on 40 random layers off the sweep grid")
     ap.add_argument("--split-c", action="store_true",
                     help="also compare the channel-splitting mode with the default on the layers its planner splits")
     ns = ap.parse_args()
@@ -430,6 +473,8 @@ def main():
         out["paper_shapes"] = paper_shapes(torch, binding, inputs, oracle)
     if ns.sweep is not None:
         out["sweep"] = sweep(torch, binding, inputs, oracle, ns.sweep, ns.find)
+    if ns.holdout is not None:
+        out["holdout"] = holdout(torch, binding, inputs, oracle, ns.holdout)
     if ns.split_c:
         out["split_c"] = split_c_layers(torch, binding, inputs, oracle)
     if not ns.no_cpu:

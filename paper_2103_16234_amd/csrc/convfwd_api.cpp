@@ -368,7 +368,9 @@ int pick_panel(const Shape& s, int x_cap, int y_cap)
     if (tiles * ceil_div(s.K, 32) < 704) {
         // fewer 32-channel units than that, but 512 or more 16-channel ones: 16 channels per panel still beat the
         // channel-splitting kernel by 5-25 % in the sweeps (deep layers on 7..14-pixel maps at batch 8..32)
-        if (tiles * ceil_div(s.K, 16) >= 512 && 16 * (round_up(s.C, 64) + 4) * 4 <= kLdsMax) return 5;  // {1, 4, 4}
+        // (at batch 1 only with 256 or more input channels: with fewer the resident filters save too little to pay for
+        // the panel's start-up)
+        if ((s.N > 1 || s.C >= 256) && tiles * ceil_div(s.K, 16) >= 512 && 16 * (round_up(s.C, 64) + 4) * 4 <= kLdsMax) return 5;  // {1, 4, 4}
         return -1;
     }
     const bool dwords = panel_pixel_mode(s, x_cap, y_cap) == 1;
@@ -523,7 +525,7 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_pl
         // beats the panel kernel by 10-20 % there (measured on 64 x 48 x 14 x 14 -> 64, 4 x 16 x 80 x 80 -> 48,
         // 1 x 32 x 112 x 112 -> 64, ...).
         const bool small_thin = s.C <= 80 && (s.H * s.W) % 4 == 0 && 2.0 * s.N * s.H * s.W * s.C * s.K <= 1.5e8;
-        if (pv >= 0 && small_thin && resolve_pointwise(s, 8, x_cap, w_cap, y_cap, p, a)) return CONV_OK;
+        if (small_thin && resolve_pointwise(s, 8, x_cap, w_cap, y_cap, p, a)) return CONV_OK;
         if (pv >= 0 && resolve_panel(s, pv, 0, x_cap, w_cap, y_cap, p, a)) return CONV_OK;
         if (resolve_pointwise(s, pick_pointwise(s), x_cap, w_cap, y_cap, p, a)) return CONV_OK;
     }
