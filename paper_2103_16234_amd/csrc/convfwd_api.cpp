@@ -400,19 +400,20 @@ void resolve_generic(const Shape& s, conv_plan_t* p, KernelArgs* a)
     fill_common(s, p);
 }
 
-// Estimated cycles of a tap mapping on 256 CUs, fitted to timings of every tile shape x pixel tile over a
-// grid of 3x3 and 5x5 layers (batch 1..128, maps 7..224): the mapping it picks is on average within 2 % of
-// the best one measured (worst case 1.22x). Work-groups are dealt round-robin, so the busiest CU runs
-// cu = ceil(grid / 256) of them, wpc at a time (registers, LDS). Per chunk that CU takes the longest of
-//   all its matrix work          (cu x per-SIMD cycles: 32 per MFMA plus ~150 per staging slot of a thread - the
+// Estimated cycles of a tap mapping on 256 CUs, fitted to timings of every tile shape x pixel tile over the 3x3
+// and 5x5 layers of the shape grid (batch 1..128, maps 7..224) and over ~80 random layers off it: the mapping it
+// picks is on average within 2 % of the best one measured (worst case 1.22x). Work-groups are dealt round-robin,
+// so the busiest CU runs cu = ceil(grid / 256) of them, wpc at a time (registers, LDS). Per chunk that CU takes the
+// longest of
+//   all its matrix work          (cu x per-SIMD cycles: 32 per MFMA plus ~100 per staging slot of a thread - the
 //                                 load, the LDS store and their address arithmetic take issue slots from the
 //                                 matrix instructions; issue efficiency 0.92 with two or more waves per SIMD,
 //                                 0.82 with one),
 //   its latency chains           (one per batch of co-resident work-groups: ~1500 cycles from a staging load's
 //                                 issue to its data sitting in LDS behind the barrier, plus the chunk's own work), and
-//   its staging traffic          (halo rows + filter block through registers into LDS, ~12 B/clk per CU);
-// every batch of co-resident work-groups adds ~12000 cycles of prologue and epilogue (first loads, LDS fill),
-// every work-group its reduction tree and stores (~32 B/clk), the launch ~5000 and the dispatcher ~12 per
+//   its staging traffic          (halo rows + filter block through registers into LDS, ~16 B/clk per CU);
+// every batch of co-resident work-groups adds ~16000 cycles of prologue and epilogue (first loads, LDS fill),
+// every work-group its reduction tree and stores (~32 B/clk), the launch ~5000 and the dispatcher ~8 per
 // work-group.
 double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv, int RS)
 {
@@ -424,12 +425,12 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
     const double waves_per_simd = tv.block() / 256.0;
     const double eff = std::min(wpc, cu) * waves_per_simd >= 2 ? 0.92 : 0.82;
     const int slots = ceil_div(a.x_items, tv.block()) + ceil_div(tv.tile_k() * tv.chunk_c() * RS / p.w_vec, tv.block());
-    const double work = waves_per_simd * (tv.MT * tv.NT * tv.GPC * RS * 32.0 + 150.0 * slots);  // per SIMD, chunk, work-group
+    const double work = waves_per_simd * (tv.MT * tv.NT * tv.GPC * RS * 32.0 + 100.0 * slots);  // per SIMD, chunk, work-group
     const double staged = 4.0 * ((double)tv.chunk_c() * a.lds_rows * a.W + (double)tv.tile_k() * tv.chunk_c() * RS);
-    const double chunk = std::max(std::max(cu * work / eff, batches * (1500.0 + work)), cu * staged / 12.0);
+    const double chunk = std::max(std::max(cu * work / eff, batches * (1500.0 + work)), cu * staged / 16.0);
     const double tree = tv.WC > 1 ? tv.MT * tv.NT * 1024.0 * tv.WK * tv.WP / 64.0 * std::log2((double)tv.WC) : 0.0;
-    const double cycles = a.nchunks * chunk + batches * 12000.0 + cu * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree) + 5000.0 +
-                          12.0 * p.grid;
+    const double cycles = a.nchunks * chunk + batches * 16000.0 + cu * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree) + 5000.0 +
+                          8.0 * p.grid;
     // Tile shapes compiled for three or four waves per SIMD measure ~3 % faster per step of occupancy than their
     // two-wave twins even where the model sees no difference (all work-groups co-resident either way).
     return cycles * (1.0 - 0.03 * std::max(0, tv.occ - 2));
