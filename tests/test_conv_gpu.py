@@ -688,6 +688,54 @@ def test_sweep_layers_at_full_size(shape):
     assert ok, worst
 
 
+def _random_layers(seed, count):
+    """Layers inside the paper's ranges but off the sweep grid (other batches, channel counts, map sizes)."""
+    import random
+    rng = random.Random(seed)
+    out = []
+    while len(out) < count:
+        f = rng.choice([1, 3, 3, 5])
+        n, h = rng.choice([1, 2, 4, 16, 64]), rng.choice([7, 10, 14, 17, 20, 28, 35, 40, 56, 80])
+        c, k = rng.choice([16, 24, 48, 80, 128, 160, 320, 448, 640]), rng.choice([24, 48, 96, 160, 256, 320, 512])
+        if (f == 5 and c > 128) or n * c * h * h > 2 ** 22 or n * k * h * h > 2 ** 22:
+            continue
+        out.append(inputs.ConvShape(f"rand_{f}x{f}_n{n}_c{c}_{h}_k{k}", n, c, h, h, k, f, f, f // 2, f // 2, "u01", "he",
+                                    9000 + len(out), 9500 + len(out)))
+    return out
+
+
+@pytest.mark.parametrize("shape", _random_layers(21, 16), ids=lambda s: s.name)
+def test_random_layers_off_the_grid(shape):
+    """Whatever the planner picks for shapes nobody tuned - default mapping, channel-splitting mapping and, for the tap
+    family, the measured-best one - matches the oracle on sampled outputs."""
+    x, w = inputs.make_inputs(shape)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    rng = np.random.default_rng(13)
+    coords = np.stack([rng.integers(0, d, 200) for d in shape.y_shape], axis=1).astype(np.int32)
+    coords[:8] = [[n, k, p, q] for n in (0, shape.N - 1) for k in (0, shape.K - 1) for (p, q) in ((0, 0), (shape.P - 1, shape.Q - 1))]
+    ref, ref_abs = oracle.conv_ref_points(x, w, shape.pad_h, shape.pad_w, coords)
+    index = tuple(torch.from_numpy(coords.T.astype(np.int64)).cuda())
+
+    def check(yd, what):
+        assert not torch.isnan(yd).any(), f"{what}: some outputs were never written"
+        ok, worst = oracle.within_tolerance(yd[index].cpu().numpy().astype(np.float64), ref, ref_abs)
+        assert ok, (what, worst)
+
+    _say(f"[case] random layer {shape.name} dims={shape.dims}")
+    yd = torch.full(shape.y_shape, float("nan"), device="cuda")
+    binding.conv_fwd(xd, wd, shape.pad_h, shape.pad_w, y=yd)
+    torch.cuda.synchronize()
+    check(yd, "default")
+    yd.fill_(float("nan"))
+    _, plan = binding.conv_fwd_split_c(xd, wd, shape.pad_h, shape.pad_w, y=yd)
+    torch.cuda.synchronize()
+    check(yd, f"split plan with {plan.c_splits} shares")
+    yd.fill_(float("nan"))
+    _, found, _ = binding.conv_fwd_find(xd, wd, shape.pad_h, shape.pad_w, y=yd)
+    torch.cuda.synchronize()
+    check(yd, f"found plan {found.kernel}/{found.variant}")
+
+
 def test_micro_probes_run_and_report_their_work():
     lib = binding.load_library()
     binding.conv_set_stream(torch.cuda.current_stream())
