@@ -144,6 +144,20 @@ constexpr TapVariant kTapVariants[] = {
     {1, 2, 2, 2, 1, 2, 4, 4, 8},    // 25: as 4 with four waves per SIMD
 };
 constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
+
+// Every staging slot a kernel instance is compiled with runs in every chunk, needed or not (a slot without data loads
+// element 0 and stores to a dump row). A tile shape's slot count is sized for the largest halo tile it accepts, so the
+// common loaders are also built with half of it and - for rows that move as single dwords, where the capacity is
+// 4x the vector one - a quarter: the launcher takes the smallest build that covers the layer (on 7x7 maps that is
+// 2 slots instead of 8, and a quarter less time for the deep batch-1 layers). Returns the divisor 1, 2 or 4.
+constexpr int tap_x_slot_divisor(const TapVariant& tv, int x_vec, int w_vec, int x_items)
+{
+    if (w_vec != 4 || (x_vec != 1 && x_vec != 4)) return 1;
+    const int need = (x_items + tv.block() - 1) / tv.block();
+    const int full = tv.xs(x_vec);
+    if (x_vec == 1 && (full + 3) / 4 >= need) return 4;
+    return (full + 1) / 2 >= need ? 2 : 1;
+}
 #define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18) X(19) X(20) X(21) X(22) X(23) X(24) X(25)
 
 // Filter sizes the tap kernel is instantiated for. The three the paper evaluates (Section 4: 1x1, 3x3, 5x5) get every

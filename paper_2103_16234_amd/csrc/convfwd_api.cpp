@@ -405,13 +405,13 @@ void resolve_generic(const Shape& s, conv_plan_t* p, KernelArgs* a)
 // picks is on average within 2 % of the best one measured (worst case 1.22x). Work-groups are dealt round-robin,
 // so the busiest CU runs cu = ceil(grid / 256) of them, wpc at a time (registers, LDS). Per chunk that CU takes the
 // longest of
-//   all its matrix work          (cu x per-SIMD cycles: 32 per MFMA plus ~100 per staging slot of a thread - the
+//   all its matrix work          (cu x per-SIMD cycles: 32 per MFMA plus ~75 per staging slot of a thread - the
 //                                 load, the LDS store and their address arithmetic take issue slots from the
 //                                 matrix instructions; issue efficiency 0.92 with two or more waves per SIMD,
-//                                 0.82 with one),
-//   its latency chains           (one per batch of co-resident work-groups: ~1500 cycles from a staging load's
+//                                 0.70 with one),
+//   its latency chains           (one per batch of co-resident work-groups: ~1000 cycles from a staging load's
 //                                 issue to its data sitting in LDS behind the barrier, plus the chunk's own work), and
-//   its staging traffic          (halo rows + filter block through registers into LDS, ~16 B/clk per CU);
+//   its staging traffic          (halo rows + filter block through registers into LDS, ~24 B/clk per CU);
 // every batch of co-resident work-groups adds ~16000 cycles of prologue and epilogue (first loads, LDS fill),
 // every work-group its reduction tree and stores (~32 B/clk), the launch ~5000 and the dispatcher ~8 per
 // work-group.
@@ -423,17 +423,19 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
     const int cu = ceil_div(p.grid, kNumCU);                 // work-groups of the busiest CU
     const int batches = ceil_div(cu, wpc);
     const double waves_per_simd = tv.block() / 256.0;
-    const double eff = std::min(wpc, cu) * waves_per_simd >= 2 ? 0.92 : 0.82;
-    const int slots = ceil_div(a.x_items, tv.block()) + ceil_div(tv.tile_k() * tv.chunk_c() * RS / p.w_vec, tv.block());
-    const double work = waves_per_simd * (tv.MT * tv.NT * tv.GPC * RS * 32.0 + 100.0 * slots);  // per SIMD, chunk, work-group
+    const double eff = std::min(wpc, cu) * waves_per_simd >= 2 ? 0.92 : 0.70;
+    // staging slots that run per chunk: the loader build the launcher will take, not just the slots with data
+    const int x_slots = ceil_div(tv.xs(p.x_vec), tap_x_slot_divisor(tv, p.x_vec, p.w_vec, a.x_items));
+    const int slots = x_slots + ceil_div(tv.tile_k() * tv.chunk_c() * RS / p.w_vec, tv.block());
+    const double work = waves_per_simd * (tv.MT * tv.NT * tv.GPC * RS * 32.0 + 75.0 * slots);  // per SIMD, chunk, work-group
     const double staged = 4.0 * ((double)tv.chunk_c() * a.lds_rows * a.W + (double)tv.tile_k() * tv.chunk_c() * RS);
-    const double chunk = std::max(std::max(cu * work / eff, batches * (1500.0 + work)), cu * staged / 16.0);
+    const double chunk = std::max(std::max(cu * work / eff, batches * (1000.0 + work)), cu * staged / 24.0);
     const double tree = tv.WC > 1 ? tv.MT * tv.NT * 1024.0 * tv.WK * tv.WP / 64.0 * std::log2((double)tv.WC) : 0.0;
     const double cycles = a.nchunks * chunk + batches * 16000.0 + cu * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree) + 5000.0 +
                           8.0 * p.grid;
-    // Tile shapes compiled for three or four waves per SIMD measure ~3 % faster per step of occupancy than their
+    // Tile shapes compiled for three or four waves per SIMD measure 3-5 % faster per step of occupancy than their
     // two-wave twins even where the model sees no difference (all work-groups co-resident either way).
-    return cycles * (1.0 - 0.03 * std::max(0, tv.occ - 2));
+    return cycles * (1.0 - 0.05 * std::max(0, tv.occ - 2));
 }
 
 // Measured best mappings of known layer shapes (sweeps over tile shape x pixel tile on an MI355X);

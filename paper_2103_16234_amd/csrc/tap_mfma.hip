@@ -397,13 +397,13 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
 
 using KernFn = void (*)(const KernelArgs);
 
-template <int VX, int VW> static KernFn instance()
+template <int VX, int VW, int DIV = 1> static KernFn instance()
 {
     constexpr TapVariant tv = kTapVariants[TAP_VARIANT];
     if constexpr (!tv.supports(TAP_R * TAP_S) || (VW == 1 && !tv.supports_scalar(TAP_R * TAP_S, VX))) {
         return nullptr;  // the filter block of this filter size does not fit the variant's registers
     } else {
-        return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, tv.occ, tv.xs(VX),
+        return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, tv.occ, (tv.xs(VX) + DIV - 1) / DIV,
                              tv.wslots(TAP_R * TAP_S, VW), VX, VW>;
     }
 }
@@ -414,11 +414,19 @@ template <int VX, int VW> static KernFn instance()
 hipError_t TAP_CAT(TAP_R, TAP_S, TAP_VARIANT)(int x_vec, int w_vec, int grid, int lds_bytes, hipStream_t stream,
                                               const KernelArgs& a)
 {
+    constexpr TapVariant tv = kTapVariants[TAP_VARIANT];
+    const int div = tap_x_slot_divisor(tv, x_vec, w_vec, a.x_items);
     KernFn fn = nullptr;
     int mode = -1;
-    if (w_vec == 4) {
-        fn = x_vec == 4 ? instance<4, 4>() : x_vec == 2 ? instance<2, 4>() : x_vec == 1 ? instance<1, 4>() : nullptr;
-        mode = x_vec == 4 ? 0 : x_vec == 2 ? 1 : 2;
+    if (w_vec == 4 && x_vec == 4) {
+        fn = div == 2 ? instance<4, 4, 2>() : instance<4, 4>();
+        mode = div == 2 ? 5 : 0;
+    } else if (w_vec == 4 && x_vec == 2) {
+        fn = instance<2, 4>();
+        mode = 1;
+    } else if (w_vec == 4 && x_vec == 1) {
+        fn = div == 4 ? instance<1, 4, 4>() : div == 2 ? instance<1, 4, 2>() : instance<1, 4>();
+        mode = div == 4 ? 7 : div == 2 ? 6 : 2;
     } else if (w_vec == 1 && x_vec == 1) {
         fn = instance<1, 1>();
         mode = 3;
@@ -428,7 +436,7 @@ hipError_t TAP_CAT(TAP_R, TAP_S, TAP_VARIANT)(int x_vec, int w_vec, int grid, in
     }
     if (!fn) return hipErrorInvalidValue;
     // Kernels may use all 160 KB of a CU's LDS; the runtime wants to be told once per kernel (and device).
-    static std::atomic<int> lds_allowed[5][kMaxDevices] = {};
+    static std::atomic<int> lds_allowed[8][kMaxDevices] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
     if (lds_bytes > 48 * 1024 && lds_allowed[mode][dev].load(std::memory_order_acquire) < lds_bytes) {
@@ -437,7 +445,6 @@ hipError_t TAP_CAT(TAP_R, TAP_S, TAP_VARIANT)(int x_vec, int w_vec, int grid, in
         if (e != hipSuccess) return e;
         lds_allowed[mode][dev].store(160 * 1024, std::memory_order_release);
     }
-    constexpr TapVariant tv = kTapVariants[TAP_VARIANT];
     hipLaunchKernelGGL(fn, dim3(grid), dim3(tv.block()), lds_bytes, stream, a);
     return hipGetLastError();
 }
