@@ -147,12 +147,12 @@ constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
 
 // Every staging slot a kernel instance is compiled with runs in every chunk, needed or not (a slot without data loads
 // element 0 and stores to a dump row). A tile shape's slot count is sized for the largest halo tile it accepts, so the
-// common loaders are also built with half of it and - for rows that move as single dwords, where the capacity is
-// 4x the vector one - a quarter: the launcher takes the smallest build that covers the layer (on 7x7 maps that is
+// loaders for filter rows of whole dwordx4 are also built with half of it and - for input rows that move as single
+// dwords, where the capacity is 4x the vector one - a quarter: the launcher takes the smallest build that covers the layer (on 7x7 maps that is
 // 2 slots instead of 8, and a quarter less time for the deep batch-1 layers). Returns the divisor 1, 2 or 4.
 constexpr int tap_x_slot_divisor(const TapVariant& tv, int x_vec, int w_vec, int x_items)
 {
-    if (w_vec != 4 || (x_vec != 1 && x_vec != 4)) return 1;
+    if (w_vec != 4) return 1;
     const int need = (x_items + tv.block() - 1) / tv.block();
     const int full = tv.xs(x_vec);
     if (x_vec == 1 && (full + 3) / 4 >= need) return 4;

@@ -422,8 +422,8 @@ hipError_t TAP_CAT(TAP_R, TAP_S, TAP_VARIANT)(int x_vec, int w_vec, int grid, in
         fn = div == 2 ? instance<4, 4, 2>() : instance<4, 4>();
         mode = div == 2 ? 5 : 0;
     } else if (w_vec == 4 && x_vec == 2) {
-        fn = instance<2, 4>();
-        mode = 1;
+        fn = div == 2 ? instance<2, 4, 2>() : instance<2, 4>();
+        mode = div == 2 ? 8 : 1;
     } else if (w_vec == 4 && x_vec == 1) {
         fn = div == 4 ? instance<1, 4, 4>() : div == 2 ? instance<1, 4, 2>() : instance<1, 4>();
         mode = div == 4 ? 7 : div == 2 ? 6 : 2;
@@ -436,7 +436,7 @@ hipError_t TAP_CAT(TAP_R, TAP_S, TAP_VARIANT)(int x_vec, int w_vec, int grid, in
     }
     if (!fn) return hipErrorInvalidValue;
     // Kernels may use all 160 KB of a CU's LDS; the runtime wants to be told once per kernel (and device).
-    static std::atomic<int> lds_allowed[8][kMaxDevices] = {};
+    static std::atomic<int> lds_allowed[9][kMaxDevices] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
     if (lds_bytes > 48 * 1024 && lds_allowed[mode][dev].load(std::memory_order_acquire) < lds_bytes) {
