@@ -114,7 +114,7 @@ class Layer:
             "frac_fp32_peak": gflops / (PEAK_FP32_TFLOPS * 1e3), "frac_hbm_peak": gbs / PEAK_HBM_GBS,
             "bound": bound, "buffer_sets": self.sets,
             "plan": {k: getattr(self.plan, k) for k in ("kernel", "variant", "tile_k", "tile_pix", "chunk_c",
-                                                         "x_vec", "w_vec", "grid", "block", "lds_bytes")},
+                                                         "x_vec", "w_vec", "grid", "block", "lds_bytes", "loader")},
         }
 
     def bound(self):

@@ -61,6 +61,12 @@ extern "C" {
  * pair). Only the channel-splitting mode (conv_fwd_plan_split_c) has
  * c_splits > 1 and a workspace.
  */
+/* Loaders of the tap family (conv_plan_t.loader): through the registers (global load, then LDS store, two chunks
+ * ahead of the arithmetic), or straight from global memory into LDS (one chunk ahead, no register staging; it also
+ * fetches the padding cells of the halo tile, from a block of zeros). */
+#define CONV_LOADER_REGISTERS 1
+#define CONV_LOADER_DIRECT 2
+
 typedef struct conv_plan {
     int kernel;          /* CONV_KERNEL_* */
     int variant;         /* tile shape index inside the family (see conv_variant_info) */
@@ -77,6 +83,8 @@ typedef struct conv_plan {
     int lds_bytes;       /* dynamic LDS per work-group */
     int P, Q;            /* output height and width */
     int c_splits;        /* work-groups that share the channels of one output tile; 1: the whole reduction in one */
+    int loader;          /* CONV_KERNEL_TAP: how a chunk reaches LDS, CONV_LOADER_REGISTERS or CONV_LOADER_DIRECT
+                            (as a request: 0 = the planner's rule); 0 for the other families */
     long long workspace_bytes; /* 0 unless c_splits > 1: then 4 * c_splits * N*K*P*Q */
     long long flops;     /* 2*N*K*P*Q*C*R*S */
     long long bytes;     /* 4*(N*C*H*W + K*C*R*S + N*K*P*Q): compulsory HBM traffic */
@@ -107,7 +115,9 @@ int conv_fwd_plan(int N, int C, int H, int W, int K, int R, int S, int pad_h, in
  * may be left 0); every derived field is recomputed and checked, and
  * CONV_E_PLAN is returned if the request cannot be honoured (family does not
  * support R x S, tile exceeds the variant's capacity, staging does not fit
- * the variant's registers or LDS). If resolved is not null it receives the plan actually used.
+ * the variant's registers or LDS). plan->loader may also name the tap family's loader (0: the planner's rule;
+ * CONV_LOADER_DIRECT needs filter slices of whole dwordx4 - C a multiple of 4 - and input rows that move as
+ * dwordx4 or single dwords). If resolved is not null it receives the plan actually used.
  */
 int conv_fwd_planned(const float* x, const float* w, float* y,
                      int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
@@ -128,8 +138,8 @@ int conv_fwd_plan_request(int N, int C, int H, int W, int K, int R, int S, int p
  * Measured choice of the mapping, for callers who run a layer many times (what "the best algorithm of the
  * library" means in the comparisons of Section 4): runs every mapping the kernels accept for this layer on
  * the caller's tensors - all tile shapes of the matching families with the planner's candidate pixel tiles
- * (panel kernel: the planner's grid and one and two work-groups per CU), tap shapes only while their
- * modelled cost is within 2.5x of the best - times each with events on the
+ * (panel kernel: the planner's grid and one and two work-groups per CU; tap shapes with either loader, and only
+ * while their modelled cost is within 2.5x of the best) - times each with events on the
  * library's stream, and keeps the fastest: it is stored in the plan cache, so conv_fwd and
  * conv_fwd_bias_relu use it from then on for this shape and pointer alignment, and returned in *best_plan
  * with its time per launch in *best_us (either may be null). Without a flush buffer each mapping is timed

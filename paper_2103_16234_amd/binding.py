@@ -17,6 +17,8 @@ CONV_KERNEL_GENERIC = 0
 CONV_KERNEL_TAP = 1
 CONV_KERNEL_POINTWISE = 2
 CONV_KERNEL_PANEL = 3
+CONV_LOADER_REGISTERS = 1
+CONV_LOADER_DIRECT = 2
 
 EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_fwd_find", "conv_two_stage_workspace_bytes",
            "conv_fwd_two_stage", "conv_fwd_plan_split_c", "conv_fwd_split_c", "conv_fwd_plan_request", "conv_probe_mfma", "conv_probe_copy",
@@ -27,7 +29,7 @@ class ConvPlan(ctypes.Structure):
     """Mirror of conv_plan_t in include/convfwd.h."""
     _fields_ = [(n, ctypes.c_int) for n in (
         "kernel", "variant", "tile_k", "tile_pix", "chunk_c", "x_vec", "w_vec", "lds_rows", "lds_pitch",
-        "lds_plane", "grid", "block", "lds_bytes", "P", "Q", "c_splits")] + [
+        "lds_plane", "grid", "block", "lds_bytes", "P", "Q", "c_splits", "loader")] + [
         ("workspace_bytes", ctypes.c_longlong), ("flops", ctypes.c_longlong), ("bytes", ctypes.c_longlong)]
 
     def as_dict(self):
@@ -151,7 +153,7 @@ def conv_fwd(x, w, pad_h: int, pad_w: int, y=None, use_current_stream: bool = Tr
 
 
 def conv_fwd_planned(x, w, pad_h: int, pad_w: int, kernel: int, variant: int = 0, tile_pix: int = 0,
-                     chunk_c: int = 0, y=None, use_current_stream: bool = True):
+                     chunk_c: int = 0, y=None, use_current_stream: bool = True, loader: int = 0):
     """As conv_fwd with a requested kernel family / tile shape; returns (y, resolved ConvPlan)."""
     import torch
     y, dims = _device_args(x, w, y, pad_h, pad_w)
@@ -159,13 +161,13 @@ def conv_fwd_planned(x, w, pad_h: int, pad_w: int, kernel: int, variant: int = 0
     if use_current_stream:
         conv_set_stream(torch.cuda.current_stream(x.device))
     req, res = ConvPlan(), ConvPlan()
-    req.kernel, req.variant, req.tile_pix, req.chunk_c = kernel, variant, tile_pix, chunk_c
+    req.kernel, req.variant, req.tile_pix, req.chunk_c, req.loader = kernel, variant, tile_pix, chunk_c, loader
     _check(lib.conv_fwd_planned(x.data_ptr(), w.data_ptr(), y.data_ptr(), *dims, ctypes.byref(req), ctypes.byref(res)))
     return y, res
 
 
 def conv_fwd_bias_relu(x, w, bias, pad_h: int, pad_w: int, relu: bool, kernel=None, variant: int = 0, tile_pix: int = 0,
-                       y=None, use_current_stream: bool = True):
+                       y=None, use_current_stream: bool = True, loader: int = 0):
     """y = act(conv(x, w) + bias) in one kernel; bias may be None. kernel=None plans as conv_fwd does. Returns (y, plan)."""
     import torch
     y, dims = _device_args(x, w, y, pad_h, pad_w)
@@ -179,7 +181,7 @@ def conv_fwd_bias_relu(x, w, bias, pad_h: int, pad_w: int, relu: bool, kernel=No
     req = None
     if kernel is not None:
         req = ConvPlan()
-        req.kernel, req.variant, req.tile_pix = kernel, variant, tile_pix
+        req.kernel, req.variant, req.tile_pix, req.loader = kernel, variant, tile_pix, loader
     _check(lib.conv_fwd_bias_relu(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None, y.data_ptr(),
                                   *dims, int(bool(relu)), ctypes.byref(req) if req is not None else None,
                                   ctypes.byref(res)))
@@ -187,10 +189,10 @@ def conv_fwd_bias_relu(x, w, bias, pad_h: int, pad_w: int, relu: bool, kernel=No
 
 
 def conv_fwd_plan_request(N, C, H, W, K, R, S, pad_h, pad_w, kernel: int, variant: int = 0, tile_pix: int = 0,
-                          c_splits: int = 0):
+                          c_splits: int = 0, loader: int = 0):
     """Host-only: resolve a requested mapping without launching it; returns (plan, modelled cycles - tap family only)."""
     req, res, cycles = ConvPlan(), ConvPlan(), ctypes.c_double(0)
-    req.kernel, req.variant, req.tile_pix, req.c_splits = kernel, variant, tile_pix, c_splits
+    req.kernel, req.variant, req.tile_pix, req.c_splits, req.loader = kernel, variant, tile_pix, c_splits, loader
     _check(load_library().conv_fwd_plan_request(N, C, H, W, K, R, S, pad_h, pad_w, ctypes.byref(req), ctypes.byref(res),
                                                 ctypes.byref(cycles)))
     return res, float(cycles.value)
@@ -203,7 +205,7 @@ def conv_fwd_plan_split_c(N, C, H, W, K, R, S, pad_h, pad_w) -> ConvPlan:
 
 
 def conv_fwd_split_c(x, w, pad_h: int, pad_w: int, bias=None, relu: bool = False, c_splits: int = 0, variant=None,
-                     tile_pix: int = 0, workspace=None, y=None, use_current_stream: bool = True):
+                     tile_pix: int = 0, workspace=None, y=None, use_current_stream: bool = True, loader: int = 0):
     """Channel-splitting mode: y = act(conv(x, w) + bias) with the channels of an output tile shared by c_splits
     work-groups and a second pass that adds their partial outputs. variant=None lets the library choose the
     mapping (then c_splits is ignored); otherwise the tap variant / tile_pix / c_splits are requested.
@@ -220,7 +222,7 @@ def conv_fwd_split_c(x, w, pad_h: int, pad_w: int, bias=None, relu: bool = False
     req = None
     if variant is not None:
         req = ConvPlan()
-        req.kernel, req.variant, req.tile_pix, req.c_splits = 1, variant, tile_pix, c_splits
+        req.kernel, req.variant, req.tile_pix, req.c_splits, req.loader = 1, variant, tile_pix, c_splits, loader
     if workspace is None:
         need = max(c_splits, 16) * y.numel() if variant is not None else conv_fwd_plan_split_c(*dims).workspace_bytes // 4
         workspace = torch.empty(max(int(need), 4), dtype=torch.float32, device=x.device)

@@ -59,6 +59,10 @@ struct KernelArgs {
     int lds_rows, lds_pitch, lds_plane;
     int col_shift;   // LDS column of padded column 0 (keeps vector stores aligned)
     int x_items;     // vector loads per chunk for the halo tile
+    int direct;      // tap family: nonzero = the loader that moves global memory straight into LDS. Then x_items counts the
+                     // vectors of the LDS halo tile of a chunk, padding included (chunk_c * lds_plane / x_vec), and
+                     // div_slot_c / div_row_vecs divide by lds_plane / x_vec and lds_pitch / x_vec
+    const float* zeros;  // 16 bytes of zeros in device memory (source of the padding cells for the direct loader)
     // dividers for the index arithmetic of the prologue
     FastDiv div_ktiles, div_ptiles, div_PQ, div_Q, div_Hp, div_row_vecs, div_slot_c;
 };
@@ -86,6 +90,15 @@ struct TapVariant {
     int xslots;  // dwordx4 halo-tile loads a thread keeps in flight (x2 as many when rows force dwordx2)
     int xslots1; // the same for rows that force single dwords (maps of odd width are small: fewer than 4 * xslots do)
     constexpr int xs(int x_vec) const { return x_vec == 1 ? xslots1 : xslots * 4 / x_vec; }
+    // Direct loads (global memory -> LDS without passing the registers) also fetch the padding cells of the halo tile,
+    // and a slot costs half the registers: half as many slots again.
+    constexpr int xs_direct(int x_vec) const { return xs(x_vec) + (xs(x_vec) + 1) / 2; }
+    constexpr int wslots_direct(int RS) const { return (tile_k() * (chunk_c() * RS / 4 + 1) + block() - 1) / block(); }
+    // LDS floats of one staging copy with direct loads: both regions are whole runs of 64 dwordx4
+    constexpr int staging_floats_direct(int RS, int plane) const
+    {
+        return (chunk_c() * plane + 255) / 256 * 256 + (tile_k() * (chunk_c() * RS + 4) + 255) / 256 * 256;
+    }
     constexpr int tile_k() const { return 16 * MT * WK; }
     constexpr int max_pix() const { return 16 * NT * WP; }
     constexpr int block() const { return 64 * WK * WP * WC; }
@@ -150,11 +163,11 @@ constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
 // loaders for filter rows of whole dwordx4 are also built with half of it and - for input rows that move as single
 // dwords, where the capacity is 4x the vector one - a quarter: the launcher takes the smallest build that covers the layer (on 7x7 maps that is
 // 2 slots instead of 8, and a quarter less time for the deep batch-1 layers). Returns the divisor 1, 2 or 4.
-constexpr int tap_x_slot_divisor(const TapVariant& tv, int x_vec, int w_vec, int x_items)
+constexpr int tap_x_slot_divisor(const TapVariant& tv, int x_vec, int w_vec, int x_items, bool direct = false)
 {
     if (w_vec != 4) return 1;
     const int need = (x_items + tv.block() - 1) / tv.block();
-    const int full = tv.xs(x_vec);
+    const int full = direct ? tv.xs_direct(x_vec) : tv.xs(x_vec);
     if (x_vec == 1 && (full + 3) / 4 >= need) return 4;
     return (full + 1) / 2 >= need ? 2 : 1;
 }
@@ -226,6 +239,8 @@ bool tap_is_built(int rs_index, int variant);
 hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid, int lds_bytes,
                       hipStream_t stream, const KernelArgs& a);
 hipError_t launch_generic(int grid, int block, hipStream_t stream, const KernelArgs& a);
+// *zeros = 16 bytes of zeros in the current device's memory (a static device array, looked up once per device)
+hipError_t zero_block(const float** zeros);
 // scratch: 16-byte aligned device memory of at least `bytes` bytes; contents are overwritten
 hipError_t launch_scratch_fill(void* scratch, long long bytes, hipStream_t stream);
 // micro-probes: 8192 waves x iters x 16 fp32 MFMAs (2048 flops each); a dwordx4 copy of `bytes` (16-byte aligned pointers)

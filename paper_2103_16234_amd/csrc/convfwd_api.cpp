@@ -136,9 +136,11 @@ int max_halo_rows(const Shape& s, int tile_pix)
 // Resolve a tap-family mapping. tile_pix / chunk_c of 0 mean "choose". c_splits > 1 asks for that many channel
 // shares, each reduced by work-groups of its own into a partial output tensor (fewer if C has fewer chunks).
 // Returns false if it cannot run.
+// loader: 0 = by rule, else CONV_LOADER_REGISTERS / CONV_LOADER_DIRECT.
 bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_cap, int w_cap,
-                 conv_plan_t* p, KernelArgs* a, int c_splits = 1)
+                 conv_plan_t* p, KernelArgs* a, int c_splits = 1, int loader = 0)
 {
+    if (loader < 0 || loader > CONV_LOADER_DIRECT) return false;
     const int rs_index = tap_rs_index(s);
     if (!tap_is_built(rs_index, variant)) return false;
     const TapVariant tv = kTapVariants[variant];
@@ -160,6 +162,17 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     // channel planes start 16 banks apart (mod 32): the four channels one B operand spans do not collide
     const int plane = round_up(std::max(rows * pitch - 16, 0), 32) + 16;
     const int row_vecs = s.W / x_vec;
+    // The direct loader moves dwordx4 or single dwords; its slots also cover the padding cells of the halo tile.
+    const bool direct_fits = w_vec == 4 && (x_vec == 4 || x_vec == 1) &&
+                             (int64_t)tv.chunk_c() * plane / x_vec <= (int64_t)tv.xs_direct(x_vec) * BLOCK &&
+                             (int64_t)tv.chunk_c() * s.H * s.W * 4 < ((int64_t)1 << 32);  // a slot's step from chunk to chunk, in bytes
+    if (loader == CONV_LOADER_DIRECT && !direct_fits) return false;
+    // Rule, from the shape sweep with both loaders: direct loads win 2-10 % wherever rows move as dwordx4; with single
+    // dwords (maps of odd width) only on batched layers (5-15 % at batch 32 and more on 13x13 and 27x27 maps), while
+    // short batch-1 layers lose up to 19 % (one chunk of look-ahead instead of two, and 7x7 maps carry almost as much
+    // padding as data).
+    const bool direct = loader == CONV_LOADER_DIRECT ||
+                        (loader == 0 && direct_fits && (x_vec == 4 || (s.N >= 32 && s.W >= 13)));
 
     // The chunk is a property of the tile shape; a caller may only name that size.
     const int cc = tv.chunk_c();
@@ -167,8 +180,8 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     chunk_c = cc;
     if (!tv.supports(RS) || (w_vec == 1 && !tv.supports_scalar(RS, x_vec))) return false;  // staging would not fit the registers
     const int64_t x_floats = (int64_t)cc * rows * s.W;
-    if (x_floats > (int64_t)tv.xs(x_vec) * x_vec * BLOCK) return false;
-    const int64_t copy_floats = tv.staging_floats(RS, plane);
+    if (!direct && x_floats > (int64_t)tv.xs(x_vec) * x_vec * BLOCK) return false;
+    const int64_t copy_floats = direct ? tv.staging_floats_direct(RS, plane) : tv.staging_floats(RS, plane);
     const int64_t lds = 4 * std::max<int64_t>(2 * copy_floats, tv.reduce_floats());
     if (lds > tv.lds_limit() || lds > kLdsMax || copy_floats >= (1 << 16)) return false;
 
@@ -184,10 +197,12 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     a->nchunks = chunks_share;
     if (splits > 1) a->split_c = chunks_share * cc;
     a->lds_rows = rows; a->lds_pitch = pitch; a->lds_plane = plane; a->col_shift = col_shift;
-    a->x_items = cc * rows * row_vecs;
+    a->x_items = direct ? cc * plane / x_vec : cc * rows * row_vecs;
+    a->direct = direct;
     a->div_ktiles = make_fastdiv(a->ktiles); a->div_ptiles = make_fastdiv(a->ptiles);
     a->div_PQ = make_fastdiv(a->PQ); a->div_Q = make_fastdiv(s.Q); a->div_Hp = make_fastdiv(a->Hp);
-    a->div_row_vecs = make_fastdiv(row_vecs); a->div_slot_c = make_fastdiv(rows * row_vecs);
+    a->div_row_vecs = make_fastdiv(direct ? pitch / x_vec : row_vecs);
+    a->div_slot_c = make_fastdiv(direct ? plane / x_vec : rows * row_vecs);
 
     std::memset(p, 0, sizeof(*p));
     p->kernel = CONV_KERNEL_TAP; p->variant = variant;
@@ -198,6 +213,7 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     p->lds_bytes = (int)lds;
     fill_common(s, p);
     p->c_splits = splits;
+    p->loader = direct ? CONV_LOADER_DIRECT : CONV_LOADER_REGISTERS;
     if (splits > 1) p->workspace_bytes = 4LL * splits * s.K * total;
     return true;
 }
@@ -405,16 +421,19 @@ void resolve_generic(const Shape& s, conv_plan_t* p, KernelArgs* a)
 // picks is on average within 2 % of the best one measured (worst case 1.22x). Work-groups are dealt round-robin,
 // so the busiest CU runs cu = ceil(grid / 256) of them, wpc at a time (registers, LDS). Per chunk that CU takes the
 // longest of
-//   all its matrix work          (cu x per-SIMD cycles: 32 per MFMA plus ~75 per staging slot of a thread - the
+//   all its matrix work          (cu x per-SIMD cycles: 32 per MFMA plus ~110 per staging slot of a thread - the
 //                                 load, the LDS store and their address arithmetic take issue slots from the
-//                                 matrix instructions; issue efficiency 0.92 with two or more waves per SIMD,
-//                                 0.70 with one),
-//   its latency chains           (one per batch of co-resident work-groups: ~1000 cycles from a staging load's
-//                                 issue to its data sitting in LDS behind the barrier, plus the chunk's own work), and
-//   its staging traffic          (halo rows + filter block through registers into LDS, ~24 B/clk per CU);
-// every batch of co-resident work-groups adds ~16000 cycles of prologue and epilogue (first loads, LDS fill),
-// every work-group its reduction tree and stores (~32 B/clk), the launch ~5000 and the dispatcher ~8 per
-// work-group.
+//                                 matrix instructions - or ~50 per slot of the direct loader, which has no LDS
+//                                 store and no masking; issue efficiency 0.88 with two or more waves per SIMD,
+//                                 0.64 with one),
+//   its latency chains           (one per batch of co-resident work-groups: ~750 cycles from a staging load's
+//                                 issue to its data sitting in LDS behind the barrier - 1500 for the direct loader,
+//                                 whose loads run one chunk ahead instead of two - plus the chunk's own work), and
+//   its staging traffic          (halo rows + filter block into LDS, ~16 B/clk per CU);
+// every batch of co-resident work-groups adds ~12000 cycles of prologue and epilogue (first loads, LDS fill; 20000
+// with the direct loader, which cannot start chunk 1 before chunk 0 has landed), every work-group its reduction tree
+// and stores (~32 B/clk), the launch ~5000 and the dispatcher ~8 per work-group. Constants fitted to timings of every
+// tile shape x candidate pixel tile x loader on the 3x3 / 5x5 layers of the shape grid and on 84 random layers off it.
 double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv, int RS)
 {
     const int by_regs = std::max(1, tv.occ * 256 / tv.block());
@@ -423,15 +442,15 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
     const int cu = ceil_div(p.grid, kNumCU);                 // work-groups of the busiest CU
     const int batches = ceil_div(cu, wpc);
     const double waves_per_simd = tv.block() / 256.0;
-    const double eff = std::min(wpc, cu) * waves_per_simd >= 2 ? 0.92 : 0.70;
+    const double eff = std::min(wpc, cu) * waves_per_simd >= 2 ? 0.88 : 0.64;
     // staging slots that run per chunk: the loader build the launcher will take, not just the slots with data
-    const int x_slots = ceil_div(tv.xs(p.x_vec), tap_x_slot_divisor(tv, p.x_vec, p.w_vec, a.x_items));
-    const int slots = x_slots + ceil_div(tv.tile_k() * tv.chunk_c() * RS / p.w_vec, tv.block());
-    const double work = waves_per_simd * (tv.MT * tv.NT * tv.GPC * RS * 32.0 + 75.0 * slots);  // per SIMD, chunk, work-group
+    const int x_slots = ceil_div(a.direct ? tv.xs_direct(p.x_vec) : tv.xs(p.x_vec), tap_x_slot_divisor(tv, p.x_vec, p.w_vec, a.x_items, a.direct != 0));
+    const int slots = x_slots + (a.direct ? tv.wslots_direct(RS) : ceil_div(tv.tile_k() * tv.chunk_c() * RS / p.w_vec, tv.block()));
+    const double work = waves_per_simd * (tv.MT * tv.NT * tv.GPC * RS * 32.0 + (a.direct ? 50.0 : 110.0) * slots);  // per SIMD, chunk, work-group
     const double staged = 4.0 * ((double)tv.chunk_c() * a.lds_rows * a.W + (double)tv.tile_k() * tv.chunk_c() * RS);
-    const double chunk = std::max(std::max(cu * work / eff, batches * (1000.0 + work)), cu * staged / 24.0);
+    const double chunk = std::max(std::max(cu * work / eff, batches * ((a.direct ? 1500.0 : 750.0) + work)), cu * staged / 16.0);
     const double tree = tv.WC > 1 ? tv.MT * tv.NT * 1024.0 * tv.WK * tv.WP / 64.0 * std::log2((double)tv.WC) : 0.0;
-    const double cycles = a.nchunks * chunk + batches * 16000.0 + cu * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree) + 5000.0 +
+    const double cycles = a.nchunks * chunk + batches * (a.direct ? 20000.0 : 12000.0) + cu * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree) + 5000.0 +
                           8.0 * p.grid;
     // Tile shapes compiled for three or four waves per SIMD measure 3-5 % faster per step of occupancy than their
     // two-wave twins even where the model sees no difference (all work-groups co-resident either way).
@@ -593,7 +612,7 @@ int plan_split_shape(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_
 
 void search_split_plans(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a)
 {
-    // the default plan stays unless a mapping with shares is modelled faster than every mapping without
+    // the default plan stays unless a mapping with shares is modelled at least 4 % faster than every mapping without
     double best_whole = 0, best_split = 0;
     bool have_whole = false, have_split = false;
     conv_plan_t sp;
@@ -621,7 +640,7 @@ void search_split_plans(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, Ke
             }
         }
     }
-    if (have_split && (!have_whole || best_split < 0.999 * best_whole)) {
+    if (have_split && (!have_whole || best_split < 0.96 * best_whole)) {
         *p = sp; *a = sa;
     }
 }
@@ -638,6 +657,10 @@ int launch(const conv_plan_t& p, KernelArgs& a, const Shape& s, const float* x, 
 {
     a.x = x; a.w = w; a.y = y; a.bias = bias; a.relu = relu;
     hipStream_t stream = g_stream.load();
+    if (p.kernel == CONV_KERNEL_TAP && a.direct) {
+        const hipError_t e = zero_block(&a.zeros);
+        if (e != hipSuccess) return record_hip(e);
+    }
     if (p.kernel == CONV_KERNEL_TAP)
         return record_hip(launch_tap(tap_rs_index(s), p.variant, p.x_vec, p.w_vec, p.grid, p.lds_bytes, stream, a));
     if (p.kernel == CONV_KERNEL_POINTWISE) return record_hip(launch_pointwise(p.variant, p.x_vec, p.grid, p.lds_bytes, stream, a));
@@ -689,7 +712,7 @@ extern "C" int conv_fwd(const float* x, const float* w, float* y, int N, int C, 
 struct RequestEntry {
     Shape s;
     int x_cap, w_cap, y_cap;
-    int kernel, variant, tile_pix, chunk_c, c_splits;
+    int kernel, variant, tile_pix, chunk_c, c_splits, loader;
     conv_plan_t p;
     KernelArgs a;
 };
@@ -704,7 +727,8 @@ static int resolve_request(const Shape& s, int x_cap, int w_cap, int y_cap, cons
         std::lock_guard<std::mutex> lock(g_cache_mutex);
         for (const RequestEntry& e : g_request_cache)
             if (same_shape(e.s, s) && e.x_cap == x_cap && e.w_cap == w_cap && e.y_cap == y_cap && e.kernel == req.kernel &&
-                e.variant == req.variant && e.tile_pix == req.tile_pix && e.chunk_c == req.chunk_c && e.c_splits == req.c_splits) {
+                e.variant == req.variant && e.tile_pix == req.tile_pix && e.chunk_c == req.chunk_c && e.c_splits == req.c_splits &&
+                e.loader == req.loader) {
                 *p = e.p; *a = e.a;
                 return CONV_OK;
             }
@@ -717,7 +741,7 @@ static int resolve_request(const Shape& s, int x_cap, int w_cap, int y_cap, cons
         resolve_generic(s, p, a);
     } else if (req.kernel == CONV_KERNEL_TAP) {
         if (req.tile_pix < 0 || req.chunk_c < 0 || req.c_splits < 0) return CONV_E_PLAN;
-        if (!resolve_tap(s, req.variant, req.tile_pix, req.chunk_c, x_cap, w_cap, p, a, std::max(1, req.c_splits)))
+        if (!resolve_tap(s, req.variant, req.tile_pix, req.chunk_c, x_cap, w_cap, p, a, std::max(1, req.c_splits), req.loader))
             return CONV_E_PLAN;
     } else {
         return CONV_E_PLAN;
@@ -725,7 +749,7 @@ static int resolve_request(const Shape& s, int x_cap, int w_cap, int y_cap, cons
     std::lock_guard<std::mutex> lock(g_cache_mutex);
     if (g_request_cache.size() >= kCacheEntries) g_request_cache.erase(g_request_cache.begin());
     g_request_cache.push_back(RequestEntry{s, x_cap, w_cap, y_cap, req.kernel, req.variant, req.tile_pix, req.chunk_c,
-                                           req.c_splits, *p, *a});
+                                           req.c_splits, req.loader, *p, *a});
     return CONV_OK;
 }
 
@@ -842,10 +866,13 @@ static void enumerate_candidates(const Shape& s, int x_cap, int w_cap, int y_cap
             for (int i = 0; i < nc; ++i) {
                 bool seen = false;
                 for (int k = 0; k < i; ++k) seen = seen || cands[k] == cands[i];
-                if (seen || cands[i] < 1 || !resolve_tap(s, v, cands[i], 0, x_cap, w_cap, &c.p, &c.a)) continue;
-                c.model = tap_cost(c.p, c.a, tv, s.R * s.S);
-                if (taps.empty() || c.model < best) best = c.model;
-                taps.push_back(c);
+                if (seen || cands[i] < 1) continue;
+                for (int loader = CONV_LOADER_REGISTERS; loader <= CONV_LOADER_DIRECT; ++loader) {  // both, where both can run
+                    if (!resolve_tap(s, v, cands[i], 0, x_cap, w_cap, &c.p, &c.a, 1, loader)) continue;
+                    c.model = tap_cost(c.p, c.a, tv, s.R * s.S);
+                    if (taps.empty() || c.model < best) best = c.model;
+                    taps.push_back(c);
+                }
             }
         }
         for (const Candidate& t : taps)

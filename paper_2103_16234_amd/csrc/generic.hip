@@ -4,6 +4,8 @@
 // taps skipped. Lanes of a wave hold consecutive q, so input reads are coalesced along X (Section 3).
 #include "conv_internal.h"
 
+#include <atomic>
+
 #include <algorithm>
 
 namespace convfwd {
@@ -43,6 +45,27 @@ __global__ void __launch_bounds__(256) scratch_fill(float4* p, long long n16)
 {
     const long long stride = (long long)gridDim.x * blockDim.x;
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) p[i] = float4{0.f, 0.f, 0.f, 0.f};
+}
+
+__device__ __attribute__((aligned(16))) float g_zero_block[4];  // static storage: zeros, never written
+
+hipError_t zero_block(const float** zeros)
+{
+    static std::atomic<const float*> known[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    const float* p = known[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void* q = nullptr;
+        e = hipGetSymbolAddress(&q, HIP_SYMBOL(g_zero_block));
+        if (e != hipSuccess) return e;
+        p = static_cast<const float*>(q);
+        known[dev].store(p, std::memory_order_release);
+    }
+    *zeros = p;
+    return hipSuccess;
 }
 
 hipError_t launch_scratch_fill(void* scratch, long long bytes, hipStream_t stream)

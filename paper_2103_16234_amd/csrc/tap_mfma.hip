@@ -28,6 +28,13 @@
 //   * waves can split the channels of a chunk (WC) and each own a larger tile, which cuts the LDS
 //     reads per MFMA; their partial tiles are added through LDS in a fixed order at the end.
 //
+//   * the second loader (template flag DMA) skips the registers: global_load_lds moves 64 consecutive dwordx4 (or
+//     dwords) per wave instruction from 64 arbitrary addresses straight into LDS. A slot is then a run of 64
+//     vectors of a staging copy, padding cells included (those lanes read a block of zeros, so nothing is ever
+//     zero-filled or masked), one pointer and one step per slot instead of a table entry and a data register,
+//     no LDS store instructions, and chunk ch+1 is fetched while chunk ch is multiplied (one chunk of look-ahead:
+//     long layers gain, short latency-bound ones prefer the register loader's two).
+//
 // Compiled once per (filter size, tile shape): TAP_R, TAP_S, TAP_VARIANT come from the build.
 #include "conv_internal.h"
 
@@ -38,6 +45,8 @@ namespace convfwd {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 template <int V> struct Vec;
 template <> struct Vec<4> {
@@ -84,7 +93,7 @@ template <int N_MFMA> __device__ __forceinline__ void interleave_with_mfma()
     __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int R, int S, int MT, int NT, int WK, int WP, int WC, int GPC, int OCC, int XS, int WS, int VX, int VW>
+template <int R, int S, int MT, int NT, int WK, int WP, int WC, int GPC, int OCC, int XS, int WS, int VX, int VW, bool DMA = false>
 __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const KernelArgs a)
 {
     static_assert(WC >= 1 && WC <= 16 && (WC & (WC - 1)) == 0, "the cross-wave reduction is a binary tree");
@@ -102,9 +111,12 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     float* const lds = reinterpret_cast<float*>(smem4);
     // One staging copy: halo tile [CC][plane], filter block [TK][WPITCH], then a 64 x 16 B dump that
     // absorbs the stores of slots a thread does not own.
-    const int xs_floats = CC * a.lds_plane;
+    // With direct loads (DMA) a wave instruction fills 64 consecutive vectors of LDS, so both regions are rounded
+    // up to whole runs of 64 dwordx4 and there is no dump.
+    constexpr int WREG = DMA ? (TK * WPITCH + 255) / 256 * 256 : TK * WPITCH;
+    const int xs_floats = DMA ? (CC * a.lds_plane + 255) & ~255 : CC * a.lds_plane;
     const int dump_off = (xs_floats + TK * WPITCH + 3) & ~3;
-    const int buf_floats = dump_off + 256;
+    const int buf_floats = DMA ? xs_floats + WREG : dump_off + 256;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -145,8 +157,59 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     // Staging slots. xg / wg: offset in floats from the chunk's first channel in x / w; xl / wl: float
     // offset inside a staging copy in the low 16 bits, the slot's channel (x) or element offset in the
     // chunk's filter slice (w) above. Slots the thread does not own read element 0 and write the dump.
-    unsigned xg[XS], xl[XS], wg[WS], wl[WS];
-    {
+    constexpr int XR = DMA ? 1 : XS, WR = DMA ? 1 : WS;
+    unsigned xg[XR], xl[XR], wg[WR], wl[WR];
+    // Direct loads: slot i of a wave fills the vectors start .. start+63 of a region (start in xdst / wdst, as a float
+    // offset inside a staging copy), lane l the l-th of them, from xp / wq; after each load the pointer moves on by
+    // xstep / wstep bytes (one chunk). Vectors that hold padding, rows outside the images, output channels past K or
+    // nothing at all are fetched from a 16-byte block of zeros, with step 0. Runs that would reach past the region
+    // start earlier and repeat part of the previous run.
+    const float* xp[DMA ? XS : 1];
+    const float* wq[DMA ? WS : 1];
+    unsigned xstep[DMA ? XS : 1], wstep[DMA ? WS : 1];
+    int xdst[DMA ? XS : 1], wdst[DMA ? WS : 1];
+    constexpr int WPV = WPITCH / 4;  // vectors per output channel of the LDS filter block, the last one padding
+    auto x_position = [&](int i) { return min(i * BLOCK + wave * 64, xs_floats / VX - 64); };
+    auto w_position = [&](int i) { return min(i * BLOCK + wave * 64, WREG / 4 - 64); };
+    if constexpr (DMA) {
+        static_assert(!DMA || VW == 4, "filters move as dwordx4");
+        const int plane_v = a.lds_plane / VX, pitch_v = a.lds_pitch / VX;
+#pragma unroll
+        for (int i = 0; i < XS; ++i) {
+            const int start = x_position(i);
+            const int e = start + lane;
+            xdst[i] = start * VX;
+            xp[i] = a.zeros;
+            xstep[i] = 0;
+            if (e < a.x_items) {
+                const int c_l = a.div_slot_c.div(e);
+                const int rem = e - c_l * plane_v;
+                const int row = a.div_row_vecs.div(rem);
+                const int col = (rem - row * pitch_v) * VX - a.col_shift - a.pad_w;
+                const int v = V0 + row;
+                const int n = a.div_Hp.div(v);
+                const int h = v - n * a.Hp - a.pad_h;
+                if (row < a.lds_rows && col >= 0 && col < a.W && n < a.N && h >= 0 && h < a.H) {
+                    xp[i] = x_share + ((static_cast<size_t>(n) * a.C + c_l) * a.H + h) * a.W + col;
+                    xstep[i] = 4u * CC * a.HW;
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < WS; ++i) {
+            const int start = w_position(i);
+            const int e = start + lane;
+            wdst[i] = xs_floats + start * 4;
+            wq[i] = a.zeros;
+            wstep[i] = 0;
+            const int kl = e / WPV;
+            const int ev = e - kl * WPV;
+            if (kl < TK && ev < WPV - 1 && k0 + kl < a.K) {
+                wq[i] = w_share + static_cast<size_t>(k0 + kl) * a.CRS + ev * 4;
+                wstep[i] = CC * RS * 4;
+            }
+        }
+    } else {
         const int XV = a.W / VX;
         const int per_c = a.lds_rows * XV;
 #pragma unroll
@@ -187,8 +250,8 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         }
     }
 
-    Vec<VX> xv[XS];
-    Vec<VW> wv[WS];
+    Vec<VX> xv[XR];
+    Vec<VW> wv[WR];
 
     // One slot of the staging pipeline: slot k < XS is a halo-tile slot, the others filter slots.
     auto slot_load = [&](auto kc, int c0) {
@@ -203,15 +266,17 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     const int last_c0 = (nchunks - 1) * CC;
     const bool ragged = C_l % CC != 0;
     auto retarget_last_chunk = [&]() {
+        if constexpr (!DMA) {
 #pragma unroll
-        for (int i = 0; i < XS; ++i) {
-            const int over = last_c0 + static_cast<int>(xl[i] >> 16) - (C_l - 1);
-            if (over > 0) xg[i] -= over * a.HW;
-        }
+            for (int i = 0; i < XS; ++i) {
+                const int over = last_c0 + static_cast<int>(xl[i] >> 16) - (C_l - 1);
+                if (over > 0) xg[i] -= over * a.HW;
+            }
 #pragma unroll
-        for (int i = 0; i < WS; ++i) {
-            const int over = last_c0 * RS + static_cast<int>(wl[i] >> 16) - (C_l * RS - VW);
-            if (over > 0) wg[i] -= over;
+            for (int i = 0; i < WS; ++i) {
+                const int over = last_c0 * RS + static_cast<int>(wl[i] >> 16) - (C_l * RS - VW);
+                if (over > 0) wg[i] -= over;
+            }
         }
     };
     // c0: first channel of the chunk the slot's data belongs to; channels past C are stored as zeros.
@@ -225,6 +290,35 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
             Vec<VW> t = wv[k - XS];
             t.keep_if(static_cast<int>(wl[k - XS] >> 16) < (C_l - c0) * RS);
             t.store16(lds + dst_floats + (wl[k - XS] & 0xffff));
+        }
+    };
+    // Direct loads: fetch the slot's vectors into the staging copy at dst_floats, then step to the next chunk
+    // (gate: all ones, or zero when there is none).
+    auto slot_fetch = [&](auto kc, int dst_floats, unsigned gate) {
+        constexpr int k = decltype(kc)::value;
+        if constexpr (k < XS) {
+            if constexpr (VX == 4) __builtin_amdgcn_global_load_lds(GLOBAL_PTR(xp[k]), LDS_PTR(lds + dst_floats + xdst[k]), 16, 0, 0);
+            else __builtin_amdgcn_global_load_lds(GLOBAL_PTR(xp[k]), LDS_PTR(lds + dst_floats + xdst[k]), 4, 0, 0);
+            xp[k] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(xp[k]) + (xstep[k] & gate));
+        } else {
+            __builtin_amdgcn_global_load_lds(GLOBAL_PTR(wq[k - XS]), LDS_PTR(lds + dst_floats + wdst[k - XS]), 16, 0, 0);
+            wq[k - XS] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(wq[k - XS]) + (wstep[k - XS] & gate));
+        }
+    };
+    // The pointers have just reached the last chunk of a share that is not a multiple of the chunk: vectors of
+    // channels past the share come from the zeros instead.
+    auto zero_past_share = [&]() {
+        if constexpr (DMA) {
+#pragma unroll
+            for (int i = 0; i < XS; ++i) {
+                const int e = x_position(i) + lane;
+                if (e < a.x_items && last_c0 + static_cast<int>(a.div_slot_c.div(e)) >= C_l) xp[i] = a.zeros;
+            }
+#pragma unroll
+            for (int i = 0; i < WS; ++i) {
+                const int ev = (w_position(i) + lane) % WPV;
+                if (ev * 4 >= (C_l - last_c0) * RS) wq[i] = a.zeros;
+            }
         }
     };
     auto for_each_slot = [&](auto&& f) {
@@ -241,9 +335,17 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     // Prologue: chunk 0 goes straight into copy 0, chunk 1 waits in the registers. While the first
     // loads are in flight, zero both staging copies (padding cells, rows past the batch and output
     // channels past K then stay zero for the whole kernel) and build the per-lane pixel table.
-    if (ragged && nchunks == 1) retarget_last_chunk();
-    for_each_slot([&](auto kc) { slot_load(kc, 0); });
-    for (int i = tid; i < (2 * buf_floats) >> 2; i += BLOCK) smem4[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // With direct loads chunk 0 is on its way to copy 0 at once and nothing has to be zeroed: every cell of a copy is
+    // written by every chunk, padding included.
+    if constexpr (DMA) {
+        if (ragged && nchunks == 1) zero_past_share();
+        for_each_slot([&](auto kc) { slot_fetch(kc, 0, nchunks > 1 ? ~0u : 0u); });
+        if (ragged && nchunks == 2) zero_past_share();
+    } else {
+        if (ragged && nchunks == 1) retarget_last_chunk();
+        for_each_slot([&](auto kc) { slot_load(kc, 0); });
+        for (int i = tid; i < (2 * buf_floats) >> 2; i += BLOCK) smem4[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
 
     // Per-lane pixel table: byte offset inside a staging copy of the origin of the pixel's window, for
     // this lane's channel of this wave's first group (lanes past the end of the tile read the tile's
@@ -260,10 +362,14 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     }
     const int arow = 4 * (xs_floats + (wk * MT * 16 + j) * WPITCH + (4 * wc + kq) * RS);
 
-    __syncthreads();  // zero fill complete before any data lands
-    for_each_slot([&](auto kc) { slot_store(kc, 0, 0); });
-    if (ragged && nchunks == 2) retarget_last_chunk();
-    for_each_slot([&](auto kc) { slot_load(kc, min(CC, last_c0)); });
+    if constexpr (DMA) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's part of chunk 0 is in LDS
+    } else {
+        __syncthreads();  // zero fill complete before any data lands
+        for_each_slot([&](auto kc) { slot_store(kc, 0, 0); });
+        if (ragged && nchunks == 2) retarget_last_chunk();
+        for_each_slot([&](auto kc) { slot_load(kc, min(CC, last_c0)); });
+    }
     __syncthreads();
 
     struct Operands {
@@ -277,7 +383,10 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         const int nxt_floats = ((ch + 1) & 1) * buf_floats;
         const int c0_regs = min((ch + 1) * CC, last_c0);  // chunk whose data the staging registers hold
         const int c0_load = min((ch + 2) * CC, last_c0);  // chunk to fetch next (the last one again at the end)
-        if (ragged && ch + 3 == nchunks) retarget_last_chunk();
+        if constexpr (!DMA) {
+            if (ragged && ch + 3 == nchunks) retarget_last_chunk();
+        }
+        const unsigned more = ch + 2 < nchunks ? ~0u : 0u;  // direct loads: a chunk ch+2 exists
 
         const char* const a_base = lds_bytes + cur_bytes + arow;
         int xa[NT];  // B addresses of the filter row being read
@@ -324,8 +433,12 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
             if constexpr (ui + 1 < U) load_unit(nxt, IntC<ui + 1>{});
             for_each_slot([&](auto kc) {
                 if constexpr (decltype(kc)::value * U / TS == ui) {
-                    slot_store(kc, c0_regs, nxt_floats);
-                    slot_load(kc, c0_load);
+                    if constexpr (DMA) {
+                        slot_fetch(kc, nxt_floats, more);  // chunk ch+1 (at the end the last chunk again, unused)
+                    } else {
+                        slot_store(kc, c0_regs, nxt_floats);
+                        slot_load(kc, c0_load);
+                    }
                 }
             });
             mfma_unit(cur);
@@ -336,6 +449,10 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         [&]<int... UIs>(std::integer_sequence<int, UIs...>) { (unit(IntC<UIs>{}), ...); }
         (std::make_integer_sequence<int, U>{});
 
+        if constexpr (DMA) {
+            if (ragged && ch + 3 == nchunks) zero_past_share();  // the pointers now stand at chunk ch+2, the last
+            __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this wave's part of chunk ch+1 is in LDS
+        }
         __syncthreads();  // every wave is done reading this copy and writing the other
     }
 
@@ -397,11 +514,14 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
 
 using KernFn = void (*)(const KernelArgs);
 
-template <int VX, int VW, int DIV = 1> static KernFn instance()
+template <int VX, int VW, int DIV = 1, bool DMA = false> static KernFn instance()
 {
     constexpr TapVariant tv = kTapVariants[TAP_VARIANT];
     if constexpr (!tv.supports(TAP_R * TAP_S) || (VW == 1 && !tv.supports_scalar(TAP_R * TAP_S, VX))) {
         return nullptr;  // the filter block of this filter size does not fit the variant's registers
+    } else if constexpr (DMA) {
+        return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, tv.occ, (tv.xs_direct(VX) + DIV - 1) / DIV,
+                             tv.wslots_direct(TAP_R * TAP_S), VX, VW, true>;
     } else {
         return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, tv.occ, (tv.xs(VX) + DIV - 1) / DIV,
                              tv.wslots(TAP_R * TAP_S, VW), VX, VW>;
@@ -415,10 +535,18 @@ hipError_t TAP_CAT(TAP_R, TAP_S, TAP_VARIANT)(int x_vec, int w_vec, int grid, in
                                               const KernelArgs& a)
 {
     constexpr TapVariant tv = kTapVariants[TAP_VARIANT];
-    const int div = tap_x_slot_divisor(tv, x_vec, w_vec, a.x_items);
+    const int div = tap_x_slot_divisor(tv, x_vec, w_vec, a.x_items, a.direct);
     KernFn fn = nullptr;
     int mode = -1;
-    if (w_vec == 4 && x_vec == 4) {
+    if (a.direct && w_vec == 4 && x_vec == 4) {
+        fn = div == 2 ? instance<4, 4, 2, true>() : instance<4, 4, 1, true>();
+        mode = div == 2 ? 10 : 9;
+    } else if (a.direct && w_vec == 4 && x_vec == 1) {
+        fn = div == 4 ? instance<1, 4, 4, true>() : div == 2 ? instance<1, 4, 2, true>() : instance<1, 4, 1, true>();
+        mode = div == 4 ? 13 : div == 2 ? 12 : 11;
+    } else if (a.direct) {
+        return hipErrorInvalidValue;
+    } else if (w_vec == 4 && x_vec == 4) {
         fn = div == 2 ? instance<4, 4, 2>() : instance<4, 4>();
         mode = div == 2 ? 5 : 0;
     } else if (w_vec == 4 && x_vec == 2) {
@@ -436,7 +564,7 @@ hipError_t TAP_CAT(TAP_R, TAP_S, TAP_VARIANT)(int x_vec, int w_vec, int grid, in
     }
     if (!fn) return hipErrorInvalidValue;
     // Kernels may use all 160 KB of a CU's LDS; the runtime wants to be told once per kernel (and device).
-    static std::atomic<int> lds_allowed[9][kMaxDevices] = {};
+    static std::atomic<int> lds_allowed[14][kMaxDevices] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
     if (lds_bytes > 48 * 1024 && lds_allowed[mode][dev].load(std::memory_order_acquire) < lds_bytes) {

@@ -232,3 +232,29 @@ def test_panel_plans_follow_the_batch():
     assert small.kernel == binding.CONV_KERNEL_POINTWISE and big.kernel == binding.CONV_KERNEL_PANEL
     deep = binding.conv_fwd_plan(128, 4096, 7, 7, 64, 1, 1, 0, 0)      # 16 x 4096 floats of filters do not fit LDS
     assert deep.kernel != binding.CONV_KERNEL_PANEL
+
+
+def test_tap_plans_name_their_loader():
+    """Tap-family plans report how chunks reach LDS; a request may name the loader, and the direct one is refused
+    where it cannot run (dword filter rows, input rows that move as dwordx2)."""
+    tap, registers, direct = binding.CONV_KERNEL_TAP, binding.CONV_LOADER_REGISTERS, binding.CONV_LOADER_DIRECT
+    for dims, want in [((8, 64, 56, 56, 64, 3, 3, 1, 1), direct),        # rows of whole dwordx4
+                       ((1, 48, 28, 28, 128, 5, 5, 2, 2), direct),
+                       ((1, 256, 13, 13, 384, 3, 3, 1, 1), registers),   # odd width, batch 1
+                       ((64, 256, 13, 13, 384, 3, 3, 1, 1), direct),     # odd width, batched
+                       ((32, 192, 7, 7, 384, 3, 3, 1, 1), registers),    # 7x7 maps: more padding than data in LDS
+                       ((32, 512, 14, 14, 512, 3, 3, 1, 1), registers),  # rows of dwordx2
+                       ((8, 3, 224, 224, 64, 3, 3, 1, 1), registers)]:   # 3 input channels
+        plan = binding.conv_fwd_plan(*dims)
+        assert plan.kernel == tap and plan.loader == want, (dims, plan.as_dict())
+        for loader in (registers, direct):
+            try:
+                other, _ = binding.conv_fwd_plan_request(*dims, tap, plan.variant, plan.tile_pix, loader=loader)
+            except binding.ConvError as e:
+                assert e.code == -6 and loader == direct and (dims[1] % 4 != 0 or dims[3] % 4 == 2), (dims, loader)
+                continue
+            assert other.loader == loader and other.grid == plan.grid
+            assert other.lds_bytes <= 160 * 1024
+    assert binding.conv_fwd_plan(32, 256, 56, 56, 64, 1, 1, 0, 0).loader == 0      # panel kernel: not a tap plan
+    with pytest.raises(binding.ConvError):
+        binding.conv_fwd_plan_request(8, 64, 56, 56, 64, 3, 3, 1, 1, tap, 7, 0, loader=3)

@@ -40,17 +40,18 @@ def _reference(shape):
     return _ref_cache[key]
 
 
-def _run(shape, kernel=None, variant=0, tile_pix=0, chunk_c=0, exact=False):
+def _run(shape, kernel=None, variant=0, tile_pix=0, chunk_c=0, exact=False, loader=0):
     x, w, y_ref, ya_ref = _reference(shape)
     xd = torch.from_numpy(x).cuda()
     wd = torch.from_numpy(w).cuda()
     yd = torch.full(shape.y_shape, float("nan"), device="cuda", dtype=torch.float32)   # every element must be written
-    _say(f"[case] {shape.name} dims={shape.dims} kernel={kernel} variant={variant} tile_pix={tile_pix} chunk_c={chunk_c}")
+    _say(f"[case] {shape.name} dims={shape.dims} kernel={kernel} variant={variant} tile_pix={tile_pix} chunk_c={chunk_c} loader={loader}")
     if kernel is None:
         binding.conv_fwd(xd, wd, shape.pad_h, shape.pad_w, y=yd)
         plan = binding.conv_fwd_plan(*shape.dims)
     else:
-        _, plan = binding.conv_fwd_planned(xd, wd, shape.pad_h, shape.pad_w, kernel, variant, tile_pix, chunk_c, y=yd)
+        _, plan = binding.conv_fwd_planned(xd, wd, shape.pad_h, shape.pad_w, kernel, variant, tile_pix, chunk_c, y=yd, loader=loader)
+        assert loader == 0 or plan.loader == loader
     torch.cuda.synchronize()
     y = yd.cpu().numpy().astype(np.float64)
     assert not np.isnan(y).any(), "some outputs were never written"
@@ -97,17 +98,53 @@ def test_generic_kernel_matches_oracle(shape):
     _run(shape, kernel=GENERIC)
 
 
+# Layers for the loader that moves global memory straight into LDS: every padding width's column shift, a batch that
+# makes it the default on an odd width, rows of whole dwordx4 with ragged channel chunks, a 7x7 filter.
+DIRECT = [
+    S("d3x3_w8_pad2", 2, 24, 7, 8, 33, 3, 3, 2, 2),
+    S("d3x3_n33_w13", 33, 8, 13, 13, 20, 3, 3, 1, 1),
+    S("d5x5_w16", 1, 36, 6, 16, 17, 5, 5, 2, 2),
+    S("d3x3_w4_c68", 3, 68, 5, 4, 70, 3, 3, 1, 1),
+    S("d1x1_w20", 2, 52, 3, 20, 35, 1, 1, 0, 0),
+]
+REGISTERS, DIRECT_LOADS = 1, 2
+
+
+@pytest.mark.parametrize("loader", [REGISTERS, DIRECT_LOADS])
 @pytest.mark.parametrize("variant", range(30))
-@pytest.mark.parametrize("shape", SMALL, ids=lambda s: s.name)
-def test_every_tap_variant_matches_oracle(shape, variant):
+@pytest.mark.parametrize("shape", SMALL + DIRECT, ids=lambda s: s.name)
+def test_every_tap_variant_matches_oracle(shape, variant, loader):
     if variant >= binding.conv_variant_count(TAP):
         pytest.skip("no such variant")
     try:
-        _run(shape, kernel=TAP, variant=variant)
+        _run(shape, kernel=TAP, variant=variant, loader=loader)
     except binding.ConvError as e:
-        # a tile shape may not fit a layer (too few channels for its channel-splitting waves, LDS):
-        # the library must say so instead of running it
+        # a tile shape may not fit a layer (too few channels for its channel-splitting waves, LDS), and the direct
+        # loader needs filter slices of whole dwordx4 and rows of dwordx4 or dwords: the library must say so instead
+        # of running it
         assert e.code == -6
+
+
+def test_direct_loader_runs_where_it_should():
+    ran = 0
+    for shape in SMALL + DIRECT:
+        can = shape.C % 4 == 0 and (shape.W % 4 == 0 or shape.W % 2 == 1)
+        for variant in (2, 4, 7, 23):
+            try:
+                plan, _ = binding.conv_fwd_plan_request(*shape.dims, TAP, variant, 0, 0, DIRECT_LOADS)
+            except binding.ConvError as e:
+                assert e.code == -6
+                continue
+            assert can and plan.loader == DIRECT_LOADS and plan.x_vec in (1, 4) and plan.w_vec == 4
+            ran += 1
+    assert ran >= 30
+    # the default: direct wherever rows move as dwordx4, on odd widths only for batched layers
+    assert binding.conv_fwd_plan(8, 64, 56, 56, 64, 3, 3, 1, 1).loader == DIRECT_LOADS
+    assert binding.conv_fwd_plan(1, 256, 13, 13, 384, 3, 3, 1, 1).loader == REGISTERS
+    assert binding.conv_fwd_plan(32, 256, 13, 13, 384, 3, 3, 1, 1).loader == DIRECT_LOADS
+    assert binding.conv_fwd_plan(32, 512, 14, 14, 512, 3, 3, 1, 1).loader == REGISTERS
+    assert binding.conv_fwd_plan(8, 3, 224, 224, 64, 3, 3, 1, 1).loader == REGISTERS   # C = 3: dword filter rows
+    _run(DIRECT[1])   # default plan of the batched 13x13 layer
 
 
 @pytest.mark.parametrize("tile_pix,chunk_c", [(1, 0), (17, 0), (33, 0), (50, 0), (64, 0)])
@@ -288,10 +325,11 @@ SPLIT_SHAPES = [
     S("split_3x3_odd_c", 1, 30, 9, 9, 20, 3, 3, 1, 1),
     S("split_5x5", 1, 72, 8, 8, 24, 5, 5, 2, 2),
     S("split_1x1_pad", 3, 96, 5, 6, 33, 1, 1, 1, 1),
+    S("split_3x3_w8", 2, 88, 5, 8, 20, 3, 3, 1, 1),          # rows of whole dwordx4, shares with a ragged last chunk
 ]
 
 
-def _run_split(shape, variant, c_splits, tile_pix=0, bias=False, relu=False, exact=False, workspace=None):
+def _run_split(shape, variant, c_splits, tile_pix=0, bias=False, relu=False, exact=False, workspace=None, loader=0):
     x, w = inputs.make_inputs(shape)
     b = inputs.uniform_pm1(900 + shape.K, shape.K) * np.float32(0.5) if bias else None
     y_ref, ya_ref = oracle.conv_bias_relu_ref(x, w, b, shape.pad_h, shape.pad_w, relu)
@@ -299,7 +337,7 @@ def _run_split(shape, variant, c_splits, tile_pix=0, bias=False, relu=False, exa
     bd = torch.from_numpy(b).cuda() if bias else None
     yd = torch.full(shape.y_shape, float("nan"), device="cuda")
     _say(f"[case] split_c {shape.name} dims={shape.dims} variant={variant} c_splits={c_splits} tile_pix={tile_pix} bias={bias} relu={relu}")
-    _, plan = binding.conv_fwd_split_c(xd, wd, shape.pad_h, shape.pad_w, bd, relu, c_splits, variant, tile_pix, workspace=workspace, y=yd)
+    _, plan = binding.conv_fwd_split_c(xd, wd, shape.pad_h, shape.pad_w, bd, relu, c_splits, variant, tile_pix, workspace=workspace, y=yd, loader=loader)
     torch.cuda.synchronize()
     y = yd.cpu().numpy().astype(np.float64)
     assert not np.isnan(y).any(), "some outputs were never written"
@@ -310,12 +348,13 @@ def _run_split(shape, variant, c_splits, tile_pix=0, bias=False, relu=False, exa
     return plan, yd
 
 
+@pytest.mark.parametrize("loader", [REGISTERS, DIRECT_LOADS])
 @pytest.mark.parametrize("c_splits", [2, 3, 5, 16])
 @pytest.mark.parametrize("variant", [2, 5, 13, 17, 20, 7])
 @pytest.mark.parametrize("shape", SPLIT_SHAPES, ids=lambda s: s.name)
-def test_channel_splitting_matches_oracle(shape, variant, c_splits):
+def test_channel_splitting_matches_oracle(shape, variant, c_splits, loader):
     try:
-        plan, _ = _run_split(shape, variant, c_splits)
+        plan, _ = _run_split(shape, variant, c_splits, loader=loader)
     except binding.ConvError as e:
         assert e.code == -6   # the tile shape does not fit the layer
         return
