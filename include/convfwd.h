@@ -22,7 +22,9 @@
  * Ownership: x, w and y are DEVICE pointers owned by the caller; the library
  * never allocates, frees or keeps them, and needs no workspace except in the two
  * opt-in entry points that take one from the caller (conv_fwd_split_c,
- * conv_fwd_two_stage). x and w must not overlap y. Calls are asynchronous on
+ * conv_fwd_two_stage). Its only device memory is a static 16-byte block of zeros
+ * (read by the tap family's direct loader; its address is looked up at the first
+ * launch on a device). x and w must not overlap y. Calls are asynchronous on
  * the stream given to conv_set_stream (default: the null stream); the caller
  * synchronises.
  *

@@ -167,12 +167,14 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
                              (int64_t)tv.chunk_c() * plane / x_vec <= (int64_t)tv.xs_direct(x_vec) * BLOCK &&
                              (int64_t)tv.chunk_c() * s.H * s.W * 4 < ((int64_t)1 << 32);  // a slot's step from chunk to chunk, in bytes
     if (loader == CONV_LOADER_DIRECT && !direct_fits) return false;
-    // Rule, from the shape sweep with both loaders: direct loads win 2-10 % wherever rows move as dwordx4; with single
-    // dwords (maps of odd width) only on batched layers (5-15 % at batch 32 and more on 13x13 and 27x27 maps), while
-    // short batch-1 layers lose up to 19 % (one chunk of look-ahead instead of two, and 7x7 maps carry almost as much
-    // padding as data).
+    // Rule, from timings of every tile shape with both loaders on the shape grid and on random layers off it: direct
+    // loads win 2-16 % wherever rows move as dwordx4 (a few layers of 10 us and less lose up to 7 %); with single dwords
+    // (maps of odd width) they win 5-20 % on layers of 0.6 GFLOP and more on maps 13 wide and wider, while shorter
+    // layers lose up to 17 % (one chunk of look-ahead instead of two) and 7x7 maps never gain (their LDS tile holds
+    // almost as much padding as data).
+    const double flops = 2.0 * s.N * s.K * s.P * s.Q * s.C * RS;
     const bool direct = loader == CONV_LOADER_DIRECT ||
-                        (loader == 0 && direct_fits && (x_vec == 4 || (s.N >= 32 && s.W >= 13)));
+                        (loader == 0 && direct_fits && (x_vec == 4 || (s.W >= 13 && flops >= 6e8)));
 
     // The chunk is a property of the tile shape; a caller may only name that size.
     const int cc = tv.chunk_c();

@@ -321,6 +321,16 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
             }
         }
     };
+    // After the loads of the last chunk have been issued, the slots still run once (the loop is branch-free): point
+    // them at the zeros, one cache line for the whole wave, instead of fetching the last chunk a second time.
+    auto park_slots = [&]() {
+        if constexpr (DMA) {
+#pragma unroll
+            for (int i = 0; i < XS; ++i) xp[i] = a.zeros;
+#pragma unroll
+            for (int i = 0; i < WS; ++i) wq[i] = a.zeros;
+        }
+    };
     auto for_each_slot = [&](auto&& f) {
         [&]<int... Ks>(std::integer_sequence<int, Ks...>) { (f(IntC<Ks>{}), ...); }
         (std::make_integer_sequence<int, TS>{});
@@ -341,6 +351,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         if (ragged && nchunks == 1) zero_past_share();
         for_each_slot([&](auto kc) { slot_fetch(kc, 0, nchunks > 1 ? ~0u : 0u); });
         if (ragged && nchunks == 2) zero_past_share();
+        if (nchunks == 1) park_slots();
     } else {
         if (ragged && nchunks == 1) retarget_last_chunk();
         for_each_slot([&](auto kc) { slot_load(kc, 0); });
@@ -434,7 +445,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
             for_each_slot([&](auto kc) {
                 if constexpr (decltype(kc)::value * U / TS == ui) {
                     if constexpr (DMA) {
-                        slot_fetch(kc, nxt_floats, more);  // chunk ch+1 (at the end the last chunk again, unused)
+                        slot_fetch(kc, nxt_floats, more);  // chunk ch+1 (in the last round: zeros, unused)
                     } else {
                         slot_store(kc, c0_regs, nxt_floats);
                         slot_load(kc, c0_load);
@@ -451,6 +462,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
 
         if constexpr (DMA) {
             if (ragged && ch + 3 == nchunks) zero_past_share();  // the pointers now stand at chunk ch+2, the last
+            if (ch + 2 == nchunks) park_slots();                 // chunk ch+1 was the last one to fetch
             __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this wave's part of chunk ch+1 is in LDS
         }
         __syncthreads();  // every wave is done reading this copy and writing the other

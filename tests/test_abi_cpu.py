@@ -240,8 +240,8 @@ def test_tap_plans_name_their_loader():
     tap, registers, direct = binding.CONV_KERNEL_TAP, binding.CONV_LOADER_REGISTERS, binding.CONV_LOADER_DIRECT
     for dims, want in [((8, 64, 56, 56, 64, 3, 3, 1, 1), direct),        # rows of whole dwordx4
                        ((1, 48, 28, 28, 128, 5, 5, 2, 2), direct),
-                       ((1, 256, 13, 13, 384, 3, 3, 1, 1), registers),   # odd width, batch 1
-                       ((64, 256, 13, 13, 384, 3, 3, 1, 1), direct),     # odd width, batched
+                       ((1, 256, 13, 13, 384, 3, 3, 1, 1), registers),   # odd width, 0.3 GFLOP
+                       ((8, 256, 13, 13, 384, 3, 3, 1, 1), direct),      # odd width, 2.4 GFLOP
                        ((32, 192, 7, 7, 384, 3, 3, 1, 1), registers),    # 7x7 maps: more padding than data in LDS
                        ((32, 512, 14, 14, 512, 3, 3, 1, 1), registers),  # rows of dwordx2
                        ((8, 3, 224, 224, 64, 3, 3, 1, 1), registers)]:   # 3 input channels

@@ -138,13 +138,12 @@ def test_direct_loader_runs_where_it_should():
             assert can and plan.loader == DIRECT_LOADS and plan.x_vec in (1, 4) and plan.w_vec == 4
             ran += 1
     assert ran >= 30
-    # the default: direct wherever rows move as dwordx4, on odd widths only for batched layers
+    # the default: direct wherever rows move as dwordx4, on odd widths only for layers with enough work
     assert binding.conv_fwd_plan(8, 64, 56, 56, 64, 3, 3, 1, 1).loader == DIRECT_LOADS
     assert binding.conv_fwd_plan(1, 256, 13, 13, 384, 3, 3, 1, 1).loader == REGISTERS
     assert binding.conv_fwd_plan(32, 256, 13, 13, 384, 3, 3, 1, 1).loader == DIRECT_LOADS
     assert binding.conv_fwd_plan(32, 512, 14, 14, 512, 3, 3, 1, 1).loader == REGISTERS
     assert binding.conv_fwd_plan(8, 3, 224, 224, 64, 3, 3, 1, 1).loader == REGISTERS   # C = 3: dword filter rows
-    _run(DIRECT[1])   # default plan of the batched 13x13 layer
 
 
 @pytest.mark.parametrize("tile_pix,chunk_c", [(1, 0), (17, 0), (33, 0), (50, 0), (64, 0)])
@@ -624,7 +623,7 @@ def test_benchmark_layers_full_size(i):
 def test_conv_fwd_replays_from_a_hip_graph():
     """conv_fwd enqueues one kernel and nothing else, so it can be captured; every replay (with eager launches and
     synchronisations in between) must reproduce the eager result bit for bit."""
-    shapes = [SMALL[0], POINTWISE_SHAPES[0], PANEL_SHAPES[8]]
+    shapes = [SMALL[0], SMALL[2], POINTWISE_SHAPES[0], PANEL_SHAPES[8]]      # SMALL[2]: rows of dwordx4, the direct loader
     tensors = []
     for s in shapes:
         x, w = inputs.make_inputs(s)
