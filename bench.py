@@ -274,13 +274,13 @@ def sweep(torch, binding, inputs, oracle, only=None, find=False):
         p = layer.plan
         rec = {"shape": shape.name, "kernel_us": e_ms * 1e3, "tflops": shape.flops / e_ms / 1e9,
                "gbs": shape.algorithmic_bytes / e_ms / 1e6, "bound": roof["bound"], "frac": roof["frac"],
-               "plan": [p.kernel, p.variant, p.tile_pix, p.grid, p.block], "parity_ok": par["ok"]}
+               "plan": [p.kernel, p.variant, p.tile_pix, p.grid, p.block, p.loader], "parity_ok": par["ok"]}
         if find:
             # measured choice of the mapping (conv_fwd_find), then the same rotating-buffer timing with it
             _, fp, _ = binding.conv_fwd_find(layer.x[0], layer.w[0], shape.pad_h, shape.pad_w, y=layer.y[0], flush=flush)
             _, f_ms = layer.measure(k, 3)
             fpar = layer.parity_sample(oracle, 128)
-            rec.update({"found_us": f_ms * 1e3, "found_plan": [fp.kernel, fp.variant, fp.tile_pix, fp.grid, fp.block],
+            rec.update({"found_us": f_ms * 1e3, "found_plan": [fp.kernel, fp.variant, fp.tile_pix, fp.grid, fp.block, fp.loader],
                         "found_frac": layer.roofline(f_ms)["frac"], "found_parity_ok": fpar["ok"]})
         rows.append(rec)
         print(f"sweep {shape.name}: {e_ms * 1e3:.1f} us {roof['bound']} {roof['frac']:.3f} parity {par['ok']}",
@@ -320,8 +320,8 @@ def holdout(torch, binding, inputs, oracle, seed, count=40):
         par = layer.parity_sample(oracle, 64)
         p = layer.plan
         rows.append({"shape": shape.name, "default_us": d_ms * 1e3, "found_us": f_ms * 1e3, "frac": layer.roofline(d_ms)["frac"],
-                     "default_plan": [p.kernel, p.variant, p.tile_pix, p.grid, p.block],
-                     "found_plan": [fp.kernel, fp.variant, fp.tile_pix, fp.grid, fp.block], "found_parity_ok": par["ok"]})
+                     "default_plan": [p.kernel, p.variant, p.tile_pix, p.grid, p.block, p.loader],
+                     "found_plan": [fp.kernel, fp.variant, fp.tile_pix, fp.grid, fp.block, fp.loader], "found_parity_ok": par["ok"]})
         print(f"holdout {shape.name}: default {d_ms * 1e3:.1f} us, found {f_ms * 1e3:.1f} us, parity {par['ok']}", file=sys.stderr,
               flush=True)
         del layer
@@ -361,8 +361,8 @@ def split_c_layers(torch, binding, inputs, oracle):
         layer.step = default_step
         p = layer.plan
         rows.append({"shape": shape.name, "dims": list(shape.dims), "default_us": d_ms * 1e3, "split_us": s_ms * 1e3,
-                     "default_plan": [p.kernel, p.variant, p.tile_pix, p.grid, p.block],
-                     "split_plan": [sp.kernel, sp.variant, sp.tile_pix, sp.grid, sp.block], "c_splits": sp.c_splits,
+                     "default_plan": [p.kernel, p.variant, p.tile_pix, p.grid, p.block, p.loader],
+                     "split_plan": [sp.kernel, sp.variant, sp.tile_pix, sp.grid, sp.block, sp.loader], "c_splits": sp.c_splits,
                      "workspace_bytes": sp.workspace_bytes, "split_parity_ok": par["ok"]})
         print(f"split-c {shape.name}: default {d_ms * 1e3:.1f} us, {sp.c_splits} shares {s_ms * 1e3:.1f} us, parity {par['ok']}",
               file=sys.stderr, flush=True)
