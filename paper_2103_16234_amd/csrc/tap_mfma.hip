@@ -292,17 +292,17 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
             t.store16(lds + dst_floats + (wl[k - XS] & 0xffff));
         }
     };
-    // Direct loads: fetch the slot's vectors into the staging copy at dst_floats, then step to the next chunk
-    // (gate: all ones, or zero when there is none).
-    auto slot_fetch = [&](auto kc, int dst_floats, unsigned gate) {
+    // Direct loads: fetch the slot's vectors into the staging copy at dst_floats, then step to the next chunk. (The
+    // step past the last chunk leaves a pointer that is never used: the slots are parked right after.)
+    auto slot_fetch = [&](auto kc, int dst_floats) {
         constexpr int k = decltype(kc)::value;
         if constexpr (k < XS) {
             if constexpr (VX == 4) __builtin_amdgcn_global_load_lds(GLOBAL_PTR(xp[k]), LDS_PTR(lds + dst_floats + xdst[k]), 16, 0, 0);
             else __builtin_amdgcn_global_load_lds(GLOBAL_PTR(xp[k]), LDS_PTR(lds + dst_floats + xdst[k]), 4, 0, 0);
-            xp[k] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(xp[k]) + (xstep[k] & gate));
+            xp[k] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(xp[k]) + xstep[k]);
         } else {
             __builtin_amdgcn_global_load_lds(GLOBAL_PTR(wq[k - XS]), LDS_PTR(lds + dst_floats + wdst[k - XS]), 16, 0, 0);
-            wq[k - XS] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(wq[k - XS]) + (wstep[k - XS] & gate));
+            wq[k - XS] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(wq[k - XS]) + wstep[k - XS]);
         }
     };
     // The pointers have just reached the last chunk of a share that is not a multiple of the chunk: vectors of
@@ -349,7 +349,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     // written by every chunk, padding included.
     if constexpr (DMA) {
         if (ragged && nchunks == 1) zero_past_share();
-        for_each_slot([&](auto kc) { slot_fetch(kc, 0, nchunks > 1 ? ~0u : 0u); });
+        for_each_slot([&](auto kc) { slot_fetch(kc, 0); });
         if (ragged && nchunks == 2) zero_past_share();
         if (nchunks == 1) park_slots();
     } else {
@@ -397,7 +397,6 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         if constexpr (!DMA) {
             if (ragged && ch + 3 == nchunks) retarget_last_chunk();
         }
-        const unsigned more = ch + 2 < nchunks ? ~0u : 0u;  // direct loads: a chunk ch+2 exists
 
         const char* const a_base = lds_bytes + cur_bytes + arow;
         int xa[NT];  // B addresses of the filter row being read
@@ -445,7 +444,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
             for_each_slot([&](auto kc) {
                 if constexpr (decltype(kc)::value * U / TS == ui) {
                     if constexpr (DMA) {
-                        slot_fetch(kc, nxt_floats, more);  // chunk ch+1 (in the last round: zeros, unused)
+                        slot_fetch(kc, nxt_floats);  // chunk ch+1 (in the last round: zeros, unused)
                     } else {
                         slot_store(kc, c0_regs, nxt_floats);
                         slot_load(kc, c0_load);
