@@ -451,7 +451,9 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
     const double work = waves_per_simd * (tv.MT * tv.NT * tv.GPC * RS * 32.0 + (a.direct ? 50.0 : 110.0) * slots);  // per SIMD, chunk, work-group
     const double staged = 4.0 * ((double)tv.chunk_c() * a.lds_rows * a.W + (double)tv.tile_k() * tv.chunk_c() * RS);
     const double chunk = std::max(std::max(cu * work / eff, batches * ((a.direct ? 1500.0 : 750.0) + work)), cu * staged / 16.0);
-    const double tree = tv.WC > 1 ? tv.MT * tv.NT * 1024.0 * tv.WK * tv.WP / 64.0 * std::log2((double)tv.WC) : 0.0;
+    // cross-wave reduction: per round of the tree every tile goes through LDS once each way (~8 cycles per 64 B with
+    // the waves of a round writing at once, then reading), plus ~1000 cycles of barriers
+    const double tree = tv.WC > 1 ? tv.MT * tv.NT * 128.0 * tv.WK * tv.WP * std::log2((double)tv.WC) + 1000.0 : 0.0;
     const double cycles = a.nchunks * chunk + batches * (a.direct ? 20000.0 : 12000.0) + cu * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree) + 5000.0 +
                           8.0 * p.grid;
     // Tile shapes compiled for three or four waves per SIMD measure 3-5 % faster per step of occupancy than their
