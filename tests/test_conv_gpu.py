@@ -726,6 +726,42 @@ def test_sweep_layers_at_full_size(shape):
     assert ok, worst
 
 
+def _small_random_layers(seed, count):
+    """Small layers with every kind of ragged edge: C a multiple of 4 (so that both loaders can run), any K, maps from a
+    single row or column up to 25 wide whose rows move as dwordx4 or single dwords, padding from none to more than "same"."""
+    import random
+    rng = random.Random(seed)
+    out = []
+    for i in range(count):
+        r = rng.choice([1, 3, 3, 5])
+        pad = rng.choice([0, r // 2, r // 2, r // 2 + 1])
+        lo = max(1, r - 2 * pad)
+        h, w = rng.randint(lo, 20), rng.choice([v for v in range(lo, 26) if v % 4 == 0 or v % 2 == 1])
+        out.append(inputs.ConvShape(f"fuzz{i}_{r}x{r}", rng.choice([1, 1, 2, 3, 5, 9]), 4 * rng.randint(1, 18), h, w,
+                                    rng.randint(1, 70), r, r, pad, pad, "upm1", "he", 5000 + i, 6000 + i))
+    return out
+
+
+@pytest.mark.parametrize("shape", _small_random_layers(7, 24), ids=lambda s: s.name)
+def test_both_loaders_on_random_small_layers(shape):
+    """Random tile shapes and pixel tiles, with and without channel shares, through the register loader and through the
+    direct one: every element against the oracle."""
+    import random
+    rng = random.Random(shape.x_seed)
+    ran = 0
+    for variant in rng.sample(range(binding.conv_variant_count(TAP)), 6):
+        cap = binding.conv_variant_info(TAP, variant)[1]
+        tile_pix = rng.choice([0, rng.randint(1, cap)])
+        for loader in (REGISTERS, DIRECT_LOADS):
+            try:
+                _run(shape, kernel=TAP, variant=variant, tile_pix=tile_pix, loader=loader)
+                _run_split(shape, variant, rng.choice([2, 3, 4]), tile_pix=tile_pix, loader=loader)
+                ran += 1
+            except binding.ConvError as e:
+                assert e.code == -6
+    assert ran >= 2
+
+
 def _random_layers(seed, count):
     """Layers inside the paper's ranges but off the sweep grid (other batches, channel counts, map sizes)."""
     import random
