@@ -389,6 +389,9 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     };
     const char* const lds_bytes = reinterpret_cast<const char*>(lds);
 
+    // Where work-groups share a CU, waves in the chunk loop go ahead of waves in a prologue, reduction or epilogue
+    // (measured: +0.4-0.8 % on layers of 60 us and more, nothing elsewhere).
+    __builtin_amdgcn_s_setprio(1);
     for (int ch = 0; ch < nchunks; ++ch) {
         const int cur_bytes = (ch & 1) * buf_floats * 4;
         const int nxt_floats = ((ch + 1) & 1) * buf_floats;
@@ -466,6 +469,8 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         }
         __syncthreads();  // every wave is done reading this copy and writing the other
     }
+
+    __builtin_amdgcn_s_setprio(0);
 
     // Waves that split the channels add their partial tiles through LDS, as a binary tree in a fixed
     // order (so results stay bitwise reproducible); the wc == 0 waves end up with the full sums.
