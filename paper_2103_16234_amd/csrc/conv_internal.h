@@ -68,14 +68,17 @@ struct KernelArgs {
 };
 
 // Taps per software-pipeline unit of the tap kernel: the shortest of {1, S, R*S} that keeps at least
-// 24 matrix instructions between an LDS read and its use, stepped down again if two operand sets
-// would not fit ~96 registers (~64 with two waves per SIMD).
+// 24 matrix instructions between an LDS read and its use - 7 with three or more waves per SIMD, whose other
+// waves cover the latency (measured on the 32 x 224 shape: 2.5-3 % faster with units of one tap than of three;
+// the 64 x 112 shape with two waves per SIMD is 2 % slower that way, and units longer than the rule's make the
+// 64 x 208 shape 2-4 % slower) -, stepped down again if two operand sets would not fit ~96 registers (~64 with
+// two or more waves per SIMD).
 constexpr int tap_unit_taps(int S, int RS, int MT, int NT, int occ)
 {
     const int cand[3] = {1, S, RS};
     int pick = 2;
     for (int i = 2; i >= 0; --i)
-        if (cand[i] * MT * NT >= 24) pick = i;
+        if (cand[i] * MT * NT >= (occ >= 3 ? 7 : 24)) pick = i;
     while (pick > 0 && 2 * cand[pick] * (MT + NT) > (occ > 1 ? 64 : 96)) --pick;
     return cand[pick];
 }
