@@ -55,6 +55,12 @@ extern "C" {
 #define CONV_KERNEL_POINTWISE 2 /* 1x1, pad 0: inputs and filters streamed HBM -> registers -> fp32 MFMA, waves split C */
 #define CONV_KERNEL_PANEL 3   /* 1x1, pad 0, batched: filters of a channel tile resident in LDS, waves stream pixel tiles */
 
+/* Loaders of the tap family (conv_plan_t.loader): through the registers (global load, then LDS store, two chunks
+ * ahead of the arithmetic), or straight from global memory into LDS (one chunk ahead, no register staging; it also
+ * fetches the padding cells of the halo tile, from a block of zeros). */
+#define CONV_LOADER_REGISTERS 1
+#define CONV_LOADER_DIRECT 2
+
 /*
  * How one layer is mapped onto the GPU. Filled by conv_fwd_plan; plain data.
  * In conv_fwd_plan's mappings the reduction over (c, r, s) stays inside one
@@ -63,12 +69,6 @@ extern "C" {
  * pair). Only the channel-splitting mode (conv_fwd_plan_split_c) has
  * c_splits > 1 and a workspace.
  */
-/* Loaders of the tap family (conv_plan_t.loader): through the registers (global load, then LDS store, two chunks
- * ahead of the arithmetic), or straight from global memory into LDS (one chunk ahead, no register staging; it also
- * fetches the padding cells of the halo tile, from a block of zeros). */
-#define CONV_LOADER_REGISTERS 1
-#define CONV_LOADER_DIRECT 2
-
 typedef struct conv_plan {
     int kernel;          /* CONV_KERNEL_* */
     int variant;         /* tile shape index inside the family (see conv_variant_info) */
