@@ -67,18 +67,21 @@ struct KernelArgs {
     FastDiv div_ktiles, div_ptiles, div_PQ, div_Q, div_Hp, div_row_vecs, div_slot_c;
 };
 
-// Taps per software-pipeline unit of the tap kernel: the shortest of {1, S, R*S} that keeps at least
-// 24 matrix instructions between an LDS read and its use - 7 with three or more waves per SIMD, whose other
-// waves cover the latency (measured on the 32 x 224 shape: 2.5-3 % faster with units of one tap than of three;
-// the 64 x 112 shape with two waves per SIMD is 2 % slower that way, and units longer than the rule's make the
-// 64 x 208 shape 2-4 % slower) -, stepped down again if two operand sets would not fit ~96 registers (~64 with
-// two or more waves per SIMD).
+// Taps per software-pipeline unit of the tap kernel: the shortest of {1, S, R*S} that keeps enough matrix
+// instructions between an LDS read and its use - 24 for the large tiles at one or two waves per SIMD, 3 where a wave
+// holds one or two MFMA tiles, 7 at three waves per SIMD and a single tap at four, whose other waves cover the latency
+// -, stepped down again if two operand sets would not fit ~96 registers (~64 with two or more waves per SIMD). Short
+// units also spread the staging slots over more places in a chunk. Measured per tile shape over the shape grid: the
+// 32 x 224 shape at three waves 3 % faster with units of one tap than of three; the four-wave shapes 2-9 % and the
+// 16- and 32-channel shapes with channel shares 3-5 % faster with units of a tap or a filter row than of a whole
+// filter; but 64 x 112 at two waves 2 % slower with one tap than with three, and 64 x 208 2-4 % slower with three
+// than with one.
 constexpr int tap_unit_taps(int S, int RS, int MT, int NT, int occ)
 {
     const int cand[3] = {1, S, RS};
     int pick = 2;
     for (int i = 2; i >= 0; --i)
-        if (cand[i] * MT * NT >= (occ >= 3 ? 7 : 24)) pick = i;
+        if (cand[i] * MT * NT >= (occ >= 4 ? 1 : occ >= 3 ? 7 : MT * NT <= 2 ? 3 : 24)) pick = i;
     while (pick > 0 && 2 * cand[pick] * (MT + NT) > (occ > 1 ? 64 : 96)) --pick;
     return cand[pick];
 }
