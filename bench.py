@@ -1,14 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the stride-1 forward convolution on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I] [--no-layers] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I | --shape N,C,H,W,K,R,S,pad_h,pad_w]
+                    [--no-layers] [--no-cpu] [--no-probes]
 
 A step is one conv_fwd call (plan, halo/filter staging, MAC loop, store: the whole hot path) on one
 batch of seeded synthetic input that already sits in HBM. The step rotates through enough
 (x, w, y) buffer sets to exceed the 256 MB Infinity Cache, so the HBM figures are not cache hits.
-Prints ONE JSON line: the headline layer at top level (`config.workload`), plus `layers` with the same
-measurement for all five benchmark layers, `roofline` for the headline layer's kernel and
-`cpu_baseline` (the CPU oracle timed on this host on a bounded sample of the same layer).
+Prints ONE JSON line: the headline layer at top level (`config.workload`; by default the largest of the five
+benchmark layers, the 3x3 layer with 512 channels at batch 32), plus `layers` with the same measurement for all
+five benchmark layers - each with the library's measured mapping and with the cost model's own pick -,
+`roofline` for the headline layer's kernel and `cpu_baseline` (the CPU oracle timed on this host on a bounded
+sample of the same layer).
 """
 from __future__ import annotations
 
@@ -26,10 +29,27 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
 # Which roofline binds each layer (arithmetic intensity against the 19.7 FLOP/B machine balance; the 1x1
 # layer sits near the balance point and is treated as HBM-bound, the tiny first layer is launch-bound).
 BOUND = {1: "hbm", 2: "hbm", 3: "mfma", 4: "mfma", 5: "mfma"}
-# Bytes per launch that the L2s exchanged with the fabric (Infinity Cache / HBM), measured with rocprofv3 --pmc
-# FETCH_SIZE and WRITE_SIZE and scaled by what the same counters read for a plain device copy of known size
-# (profiles/conv_kernels_hbm_traffic.txt); None = not measured.
-TRAFFIC_BYTES = {1: None, 2: 4792895, 3: 14202266, 4: None, 5: 101456946}
+ROOT = os.path.dirname(os.path.abspath(__file__))
+# Offline counter readings: bytes per launch that the L2s exchanged with the fabric (Infinity Cache / HBM), from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by what the same counters read for a plain device
+# copy of known size. `python -m paper_2103_16234_amd.profiling traffic` writes the table together with the summary
+# under profiles/; an entry is only reported while the layer still runs the mapping it was measured with.
+TRAFFIC_TABLE = os.path.join(ROOT, "paper_2103_16234_amd", "measured_traffic.json")
+KERNEL_NAMES = {0: "conv_generic", 1: "conv_tap_mfma", 2: "conv_pointwise_mfma", 3: "conv_pointwise_panel"}
+
+
+def measured_traffic(shape, plan):
+    """HBM-side bytes per launch from the offline counter table, or None (not measured, or measured with another mapping)."""
+    try:
+        table = json.load(open(TRAFFIC_TABLE))
+    except (OSError, ValueError):
+        return None
+    rec = table.get("layers", {}).get(",".join(str(d) for d in shape.dims))
+    if not rec:
+        return None
+    if [plan.kernel, plan.variant, plan.tile_pix, plan.loader] != rec.get("plan"):
+        return None
+    return int(rec["fetch_bytes"] + rec["write_bytes"])
 
 
 def _fail(msg: str, code: int = 2):
@@ -59,13 +79,27 @@ class Layer:
         self.dims = tuple(self.shape.dims)
         self.plan = binding.conv_fwd_plan(*self.dims)
         self.calls = 0
+        self.request = None
 
     def step(self):
         xa, wa, ya = self.args[self.calls % self.sets]
         self.calls += 1
-        rc = self.lib.conv_fwd(xa, wa, ya, *self.dims)
+        if self.request is not None:
+            rc = self.lib.conv_fwd_planned(xa, wa, ya, *self.dims, ctypes.byref(self.request), None)
+        else:
+            rc = self.lib.conv_fwd(xa, wa, ya, *self.dims)
         if rc != 0:
             raise RuntimeError(f"conv_fwd failed with code {rc}")
+
+    def use_plan(self, plan):
+        """Later steps launch the mapping `plan` names (conv_fwd_planned) instead of the library's default; None: default."""
+        if plan is None:
+            self.request = None
+            return
+        from paper_2103_16234_amd import binding
+        req = binding.ConvPlan()
+        req.kernel, req.variant, req.tile_pix, req.loader = plan.kernel, plan.variant, plan.tile_pix, plan.loader
+        self.request = req
 
     def measure(self, steps, warmup):
         """Wall clock and HIP-event time over exactly `steps` launches (after `warmup` untimed ones)."""
@@ -133,8 +167,9 @@ class Layer:
         else:
             achieved, peak, unit = s.flops / t / 1e12, PEAK_FP32_TFLOPS, "TFLOP/s"
         return {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
-                "traffic": TRAFFIC_BYTES.get(self.index), "kernel": "conv_tap_mfma" if self.plan.kernel == 1 else
-                ("conv_pointwise_mfma" if self.plan.kernel == 2 else "conv_generic"),
+                "traffic": measured_traffic(s, self.plan), "traffic_source": "offline rocprofv3 FETCH_SIZE + WRITE_SIZE "
+                "readings (profiles/conv_kernels_hbm_traffic.txt), not measured in this run",
+                "kernel": KERNEL_NAMES.get(self.plan.kernel, "?"),
                 "kernel_us": event_ms * 1e3, "algorithmic_bytes": s.algorithmic_bytes, "algorithmic_flops": s.flops}
 
     def parity_sample(self, oracle, npts=512):
@@ -182,24 +217,36 @@ def probes(torch, binding):
     return out
 
 
-def cpu_baseline(oracle, inputs, index, budget_macs=4e9):
-    """The oracle as it stands, on this host's cores, on the whole layer or on its first images."""
-    s = inputs.config(index)
-    x, w = inputs.make_inputs(s)
-    macs_per_image = s.flops / 2 / s.N
-    n = int(max(1, min(s.N, budget_macs // macs_per_image)))
+def cpu_baseline(oracle, inputs, shape, budget_macs=4e9, others=()):
+    """The oracle as it stands, on this host's cores, on the whole layer or on its first images; plus one
+    single-threaded pass over (a bounded sample of) each layer in `others`."""
+    def timed(s, threads, seconds):
+        x, w = inputs.make_inputs(s)
+        macs_per_image = s.flops / 2 / s.N
+        n = int(max(1, min(s.N, budget_macs // macs_per_image)))
+        t0 = time.perf_counter()
+        oracle.conv_ref(x[:n], w, s.pad_h, s.pad_w, nthreads=threads)
+        first = time.perf_counter() - t0
+        reps = int(max(1, min(1000, seconds / max(first, 1e-4))))
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            oracle.conv_ref(x[:n], w, s.pad_h, s.pad_w, nthreads=threads)
+        dt = (time.perf_counter() - t0) / reps
+        return 2 * macs_per_image * n / dt / 1e9, f"{s.name}: images 0..{n - 1} of {s.N}, all {s.K} filters, {reps} pass(es), {dt:.3f} s per pass"
+
+    x, w = inputs.make_inputs(shape)
+    oracle.conv_ref(x[:1, :, :4, :4], w[:1], shape.pad_h, shape.pad_w, nthreads=1)   # load the library
+    # threads the oracle runs with: the host's cores, at most 16 (one GPU's share of the cores of a multi-GPU host)
     cores = min(os.cpu_count() or 1, 16)
-    oracle.conv_ref(x[:1, :, :4, :4], w[:1], s.pad_h, s.pad_w, nthreads=1)   # load the library
-    t0 = time.perf_counter()
-    oracle.conv_ref(x[:n], w, s.pad_h, s.pad_w, nthreads=cores)
-    first = time.perf_counter() - t0
-    reps = int(max(1, min(1000, 10.0 / max(first, 1e-4))))      # about ten seconds of CPU work in all
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        oracle.conv_ref(x[:n], w, s.pad_h, s.pad_w, nthreads=cores)
-    dt = (time.perf_counter() - t0) / reps
-    return {"value": 2 * macs_per_image * n / dt / 1e9, "unit": "GFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": f"{s.name}: images 0..{n - 1} of {s.N}, all {s.K} filters, {reps} pass(es), {dt:.3f} s per pass"}
+    value, sample = timed(shape, cores, 10.0)                  # about ten seconds of CPU work
+    out = {"value": value, "unit": "GFLOP/s", "cores": cores, "kind": "oracle", "sample": sample}
+    single = []
+    for s in others:                                           # about two seconds each
+        v, smp = timed(s, 1, 2.0)
+        single.append({"value": v, "unit": "GFLOP/s", "cores": 1, "sample": smp})
+    if single:
+        out["single_thread"] = single
+    return out
 
 
 # The shapes whose kernel times the paper prints (Tables 3-5: H - N - filter - K - C), with its own stage-1 (+ stage-2)
@@ -371,14 +418,46 @@ def split_c_layers(torch, binding, inputs, oracle):
     return rows
 
 
+def layer_record(layer, torch, binding, oracle, measured, warmup, auto_steps):
+    """One entry of `layers`: the default mapping (a measured one for the five benchmark layers), then the cost model's
+    own pick for the same layer timed the same way, so that the table of measured mappings hides nothing."""
+    k = auto_steps(layer)
+    w_ms, e_ms = layer.measure(k, warmup)
+    rec = layer.report(w_ms, e_ms, k)
+    rec["parity"] = layer.parity_sample(oracle, 256)
+    rec["single_launch_us"] = layer.single_launches()
+    rec["frac_of_measured_mfma"] = rec["gflops"] / 1e3 / measured["mfma_fp32_tflops"]
+    rec["frac_of_measured_copy_bw"] = rec["gbs"] / measured["copy_read_plus_write_gbs"]
+    rec["roofline"] = layer.roofline(e_ms)
+    model = binding.conv_fwd_plan_untuned(*layer.dims)
+    same = all(getattr(model, f) == getattr(layer.plan, f) for f in ("kernel", "variant", "tile_pix", "loader"))
+    pick = {"plan": {f: getattr(model, f) for f in ("kernel", "variant", "tile_pix", "grid", "block", "loader")},
+            "same_as_default": same}
+    if same:
+        pick["kernel_us"] = rec["kernel_us"]
+    else:
+        layer.use_plan(model)
+        _, m_ms = layer.measure(k, warmup)
+        pick["kernel_us"] = m_ms * 1e3
+        pick["parity"] = layer.parity_sample(oracle, 256)
+        layer.use_plan(None)
+    pick["over_default"] = pick["kernel_us"] / rec["kernel_us"]
+    rec["cost_model_pick"] = pick
+    return rec
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=0, help="timed launches of the headline layer (0 = auto)")
+    ap.add_argument("--steps", type=int, default=0, help="timed launches of the headline layer (0 = auto: about 0.25 s)")
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="headline layer, 1..5 (default 2: the 1x1 layer)")
+    ap.add_argument("--config", type=int, default=5,
+                    help="headline layer, 1..5 (default 5: the largest one, 3x3 with 512 channels at batch 32)")
+    ap.add_argument("--shape", default=None, metavar="N,C,H,W,K,R,S,PAD_H,PAD_W",
+                    help="headline layer given by its nine dimensions instead of --config (counter runs on other layers)")
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-probes", action="store_true", help="skip the two micro-probes of attainable peaks")
     ap.add_argument("--paper-shapes", action="store_true",
                     help="also time the fused kernels and the paper's two-stage scheme on the shapes the paper profiles")
     ap.add_argument("--sweep", nargs="?", const="", default=None, metavar="SUBSTR",
@@ -413,7 +492,16 @@ def main():
         _, ev = layer.measure(5, 3)
         return int(max(50, min(5000, 0.25 / max(ev * 1e-3, 1e-7))))
 
-    head = Layer(ns.config, torch, binding, inputs)
+    if ns.shape:
+        try:
+            dims = tuple(int(v) for v in ns.shape.split(","))
+            assert len(dims) == 9
+        except (ValueError, AssertionError):
+            _fail("bench.py: --shape takes nine comma-separated integers")
+        head_shape = inputs.ConvShape("shape_" + "_".join(str(d) for d in dims), *dims, "u01", "he", 1100, 2100)
+        head = Layer(head_shape, torch, binding, inputs)
+    else:
+        head = Layer(ns.config, torch, binding, inputs)
     steps = ns.steps or auto_steps(head)
     wall_ms, event_ms = head.measure(steps, ns.warmup)
     parity = head.parity_sample(oracle)
@@ -423,36 +511,32 @@ def main():
         "value": s.flops / (wall_ms * 1e-3) / 1e9, "unit": "GFLOP/s",
         "n_gpus": 1, "steps": steps, "warmup": ns.warmup, "ms_per_step": wall_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{s.name}: N={s.N} C={s.C} H=W={s.H} K={s.K} R=S={s.R} pad={s.pad_h} stride 1, "
-                               f"NCHW fp32, {head.sets} rotating buffer sets",
-                   "gbs": s.algorithmic_bytes / (wall_ms * 1e-3) / 1e9},
+        "config": {"workload": f"{s.name}: N={s.N} C={s.C} H={s.H} W={s.W} K={s.K} R={s.R} S={s.S} pad={s.pad_h},{s.pad_w} "
+                               f"stride 1, NCHW fp32, {head.sets} rotating buffer sets",
+                   "gbs": s.algorithmic_bytes / (wall_ms * 1e-3) / 1e9,
+                   "plan": {k: getattr(head.plan, k) for k in ("kernel", "variant", "tile_pix", "grid", "block", "lds_bytes", "loader")}},
         "roofline": head.roofline(event_ms),
         "parity": parity,
     }
     del head
     torch.cuda.empty_cache()
-    measured = probes(torch, binding)
-    out["probes"] = measured
-    roof = out["roofline"]
-    roof["frac_of_measured"] = roof["achieved"] / (measured["copy_read_plus_write_gbs"] if roof["bound"] == "hbm"
-                                                   else measured["mfma_fp32_tflops"])
-    torch.cuda.empty_cache()
-    if not ns.no_layers:
+    measured = None
+    if not ns.no_probes:
+        measured = probes(torch, binding)
+        out["probes"] = measured
+        roof = out["roofline"]
+        roof["frac_of_measured"] = roof["achieved"] / (measured["copy_read_plus_write_gbs"] if roof["bound"] == "hbm"
+                                                       else measured["mfma_fp32_tflops"])
+        torch.cuda.empty_cache()
+    if not ns.no_layers and measured is not None:
         layers = []
         for i in range(1, 6):
             layer = Layer(i, torch, binding, inputs)
-            k = auto_steps(layer)
-            w_ms, e_ms = layer.measure(k, ns.warmup)
-            rec = layer.report(w_ms, e_ms, k)
-            rec["parity"] = layer.parity_sample(oracle, 256)
-            rec["single_launch_us"] = layer.single_launches()
-            rec["frac_of_measured_mfma"] = rec["gflops"] / 1e3 / measured["mfma_fp32_tflops"]
-            rec["frac_of_measured_copy_bw"] = rec["gbs"] / measured["copy_read_plus_write_gbs"]
-            layers.append(rec)
+            layers.append(layer_record(layer, torch, binding, oracle, measured, ns.warmup, auto_steps))
             del layer
             torch.cuda.empty_cache()
         out["layers"] = layers
-        # The headline 1x1 layer is launch-bound at batch 1 (its roofline time is below one kernel dispatch): the same layer
+        # The 1x1 benchmark layer is launch-bound at batch 1 (its roofline time is below one kernel dispatch): the same layer
         # at larger batches, and an HBM-bound 64 -> 64 channel layer, show what the 1x1 path sustains.
         scaled = []
         for name, dims in (("cfg2 at N=32", (32, 256, 56, 56, 64, 1, 1, 0, 0)), ("cfg2 at N=128", (128, 256, 56, 56, 64, 1, 1, 0, 0)),
@@ -465,6 +549,7 @@ def main():
                            "gbs": layer.shape.algorithmic_bytes / e_ms / 1e6, "bound": roof["bound"], "frac": roof["frac"],
                            "frac_hbm_peak": layer.shape.algorithmic_bytes / e_ms / 1e6 / PEAK_HBM_GBS,
                            "frac_of_measured_copy_bw": layer.shape.algorithmic_bytes / e_ms / 1e6 / measured["copy_read_plus_write_gbs"],
+                           "traffic": roof["traffic"],
                            "parity_ok": layer.parity_sample(oracle, 128)["ok"]})
             del layer
             torch.cuda.empty_cache()
@@ -478,7 +563,8 @@ def main():
     if ns.split_c:
         out["split_c"] = split_c_layers(torch, binding, inputs, oracle)
     if not ns.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(oracle, inputs, ns.config)
+        others = [inputs.config(i) for i in range(1, 5)] if not ns.shape and not ns.no_layers else []
+        out["cpu_baseline"] = cpu_baseline(oracle, inputs, s, others=others)
     print(json.dumps(out))
 
 

@@ -50,8 +50,10 @@ extern "C" {
 
 /* Kernel families a plan can name. */
 #define CONV_KERNEL_GENERIC 0 /* one output per thread, fp32 FMA; any R, S, padding */
-#define CONV_KERNEL_TAP 1     /* LDS halo tile + filter block, fp32 MFMA over (channel, tap); 1x1, 3x3, 5x5 with every tile
-                                 shape; 1x3, 3x1, 1x5, 5x1, 1x7, 7x1, 2x2, 4x4, 7x7 with tile shapes 2, 5, 7, 14, 16, 20, 22 */
+#define CONV_KERNEL_TAP 1     /* LDS halo tile + filter block, fp32 MFMA over (channel, tap). Built for 1x1 and 3x3 with all
+                                 26 tile shapes; for 5x5 with the 13 whose filter block fits the staging registers (2, 4,
+                                 8-12, 14-16, 22-24); for 1x3, 3x1, 1x5, 5x1, 1x7, 7x1, 2x2, 4x4 with shapes 2, 5, 7, 14, 16,
+                                 20, 22 and for 7x7 with 2, 14, 16, 22. conv_fwd_plan_request tells whether a pair exists */
 #define CONV_KERNEL_POINTWISE 2 /* 1x1, pad 0: inputs and filters streamed HBM -> registers -> fp32 MFMA, waves split C */
 #define CONV_KERNEL_PANEL 3   /* 1x1, pad 0, batched: filters of a channel tile resident in LDS, waves stream pixel tiles */
 
@@ -109,6 +111,15 @@ int conv_fwd(const float* x, const float* w, float* y,
  */
 int conv_fwd_plan(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
                   conv_plan_t* out);
+
+/*
+ * Host-only: conv_fwd_plan's choice without the short table of measured mappings the library keeps for a few
+ * known layer shapes - the planner's cost model alone (for the tap family; Section 5 of the paper: the best work
+ * distribution depends on all five layer parameters). Lets a benchmark report how far the model's pick is from
+ * the measured one. Arguments and errors as conv_fwd_plan.
+ */
+int conv_fwd_plan_untuned(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
+                          conv_plan_t* out);
 
 /*
  * As conv_fwd, with the mapping requested by the caller. Only plan->kernel,
@@ -226,8 +237,10 @@ int conv_variant_count(int kernel);
 int conv_variant_info(int kernel, int variant, int* tile_k, int* max_tile_pix, int* block);
 
 /*
- * Stream used by later conv_fwd / conv_fwd_planned / conv_fwd_bias_relu / conv_fwd_two_stage calls of the calling
- * thread's process (a hipStream_t passed as void*; NULL = null stream).
+ * Stream used by later launching calls (conv_fwd, conv_fwd_planned, conv_fwd_bias_relu, conv_fwd_split_c,
+ * conv_fwd_two_stage, conv_fwd_find, the probes) OF THE CALLING HOST THREAD: a hipStream_t passed as void*,
+ * NULL = null stream. The setting is per thread (a thread that never called it launches on the null stream), so
+ * two threads driving different streams do not disturb each other.
  */
 int conv_set_stream(void* hip_stream);
 

@@ -61,7 +61,7 @@ namespace {
 constexpr int kNumCU = 256;              // MI355X: 8 XCDs x 32 CUs
 constexpr int kLdsMax = 160 * 1024;      // LDS of one CU
 
-std::atomic<hipStream_t> g_stream{nullptr};
+thread_local hipStream_t g_stream = nullptr;  // per host thread: selecting a stream and launching on it cannot be split by another thread
 thread_local std::string g_hip_error = "no HIP error recorded";
 
 struct Shape {
@@ -122,6 +122,13 @@ int max_halo_rows(const Shape& s, int tile_pix)
     const int64_t total = (int64_t)s.N * s.P * s.Q;
     const int PQ = s.P * s.Q, Hp = s.H + 2 * s.pad_h;
     const int64_t period = PQ / std::gcd(PQ, tile_pix);
+    if (period > 4096) {
+        // Too many phases to walk (maps of millions of pixels): an upper bound instead - the rows a run of tile_pix
+        // pixels can touch at the worst phase, the filter's R-1 more, and the padding rows between images it crosses.
+        const int64_t bound = ((int64_t)tile_pix + s.Q - 2) / s.Q + 1 + (s.R - 1) +
+                              (((int64_t)tile_pix + PQ - 2) / PQ) * (Hp - s.P);
+        return (int)std::min<int64_t>(bound, INT32_MAX / 2);
+    }
     int rows = 0;
     int64_t g0 = 0;
     for (int64_t i = 0; i <= period && g0 < total; ++i, g0 += tile_pix) {
@@ -157,10 +164,16 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     if (w_vec == 1 && x_vec != 4) x_vec = 1;  // the loaders built: (4, 4), (2, 4), (1, 4), (4, 1), (1, 1)
 
     const int col_shift = (x_vec - s.pad_w % x_vec) % x_vec;
-    const int pitch = round_up(s.W + 2 * s.pad_w + col_shift, x_vec);
+    // Sizes of the halo tile in 64 bits first: a padded row, R of them, or a plane that cannot fit LDS ends the attempt
+    // here, before any product of them is narrowed to int (a copy holds fewer than 2^16 floats, checked below).
+    const int64_t pitch64 = ((int64_t)s.W + 2 * (int64_t)s.pad_w + col_shift + x_vec - 1) / x_vec * x_vec;
+    if (pitch64 * s.R * 4 > kLdsMax) return false;
+    const int pitch = (int)pitch64;
     const int rows = max_halo_rows(s, tile_pix);
     // channel planes start 16 banks apart (mod 32): the four channels one B operand spans do not collide
-    const int plane = round_up(std::max(rows * pitch - 16, 0), 32) + 16;
+    const int64_t plane64 = (std::max<int64_t>((int64_t)rows * pitch - 16, 0) + 31) / 32 * 32 + 16;
+    if (plane64 * tv.chunk_c() * 4 > kLdsMax) return false;
+    const int plane = (int)plane64;
     const int row_vecs = s.W / x_vec;
     // The direct loader moves dwordx4 or single dwords; its slots also cover the padding cells of the halo tile.
     const bool direct_fits = w_vec == 4 && (x_vec == 4 || x_vec == 1) &&
@@ -495,7 +508,7 @@ constexpr size_t kCacheEntries = 64;
 
 bool same_shape(const Shape& a, const Shape& b) { return std::memcmp(&a, &b, sizeof(Shape)) == 0; }
 
-int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a);
+int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a, bool use_tuned = true);
 
 int plan_shape(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
 {
@@ -538,9 +551,9 @@ int tap_tile_candidates(const Shape& s, const TapVariant& tv, int (&cands)[8])
     return nc;
 }
 
-int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
+int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a, bool use_tuned)
 {
-    const TunedEntry* const tuned = find_tuned(s);
+    const TunedEntry* const tuned = use_tuned ? find_tuned(s) : nullptr;
     if (tuned && tuned->kernel == CONV_KERNEL_POINTWISE &&
         resolve_pointwise(s, tuned->variant, x_cap, w_cap, y_cap, p, a))
         return CONV_OK;
@@ -660,7 +673,7 @@ int launch(const conv_plan_t& p, KernelArgs& a, const Shape& s, const float* x, 
            const float* bias = nullptr, int relu = 0)
 {
     a.x = x; a.w = w; a.y = y; a.bias = bias; a.relu = relu;
-    hipStream_t stream = g_stream.load();
+    hipStream_t stream = g_stream;
     if (p.kernel == CONV_KERNEL_TAP && a.direct) {
         const hipError_t e = zero_block(&a.zeros);
         if (e != hipSuccess) return record_hip(e);
@@ -693,6 +706,15 @@ extern "C" int conv_fwd_plan(int N, int C, int H, int W, int K, int R, int S, in
     if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
     KernelArgs a;
     return plan_shape(s, 4, 4, 4, out, &a);
+}
+
+extern "C" int conv_fwd_plan_untuned(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w, conv_plan_t* out)
+{
+    if (!out) return CONV_E_NULL;
+    Shape s;
+    if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
+    KernelArgs a;
+    return plan_shape_uncached(s, 4, 4, 4, out, &a, false);
 }
 
 extern "C" int conv_fwd(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,
@@ -780,7 +802,7 @@ static int run_planned(const float* x, const float* w, const float* bias, float*
     if (!workspace) return CONV_E_NULL;
     if (workspace_bytes < p.workspace_bytes) return CONV_E_WORKSPACE;
     if (int rc = launch(p, a, s, x, w, workspace)) return rc;
-    return record_hip(launch_split_reduce(workspace, y, bias, relu, p.c_splits, s.K * a.total_pix, a.PQ, s.K, g_stream.load()));
+    return record_hip(launch_split_reduce(workspace, y, bias, relu, p.c_splits, s.K * a.total_pix, a.PQ, s.K, g_stream));
 }
 
 extern "C" int conv_fwd_plan_request(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
@@ -902,7 +924,7 @@ extern "C" int conv_fwd_find(const float* x, const float* w, float* y, int N, in
     std::vector<Candidate> cands;
     enumerate_candidates(s, x_cap, w_cap, y_cap, &cands);
 
-    hipStream_t stream = g_stream.load();
+    hipStream_t stream = g_stream;
     hipEvent_t t0, t1;
     if (int rc = record_hip(hipEventCreate(&t0))) return rc;
     if (int rc = record_hip(hipEventCreate(&t1))) { (void)hipEventDestroy(t0); return rc; }
@@ -983,14 +1005,14 @@ extern "C" int conv_fwd_two_stage(const float* x, const float* w, float* y, floa
     KernelArgs a;
     base_args(s, &a);
     a.x = x; a.w = w; a.y = y;
-    return record_hip(launch_two_stage(g_stream.load(), a, workspace));
+    return record_hip(launch_two_stage(g_stream, a, workspace));
 }
 
 extern "C" long long conv_probe_mfma(int iters, float* sink)
 {
     if (!sink) return CONV_E_NULL;
     if (iters < 1 || iters > (1 << 24)) return CONV_E_DIM;
-    if (int rc = record_hip(launch_probe_mfma(iters, sink, g_stream.load()))) return rc;
+    if (int rc = record_hip(launch_probe_mfma(iters, sink, g_stream))) return rc;
     return 8192LL * iters * 16 * 2048;
 }
 
@@ -998,7 +1020,7 @@ extern "C" int conv_probe_copy(const void* src, void* dst, long long bytes)
 {
     if (!src || !dst) return CONV_E_NULL;
     if (bytes < 16 || reinterpret_cast<uintptr_t>(src) % 16 || reinterpret_cast<uintptr_t>(dst) % 16) return CONV_E_DIM;
-    return record_hip(launch_probe_copy(src, dst, bytes, g_stream.load()));
+    return record_hip(launch_probe_copy(src, dst, bytes, g_stream));
 }
 
 extern "C" int conv_variant_count(int kernel)
@@ -1031,7 +1053,7 @@ extern "C" int conv_variant_info(int kernel, int variant, int* tile_k, int* max_
 
 extern "C" int conv_set_stream(void* hip_stream)
 {
-    g_stream.store(reinterpret_cast<hipStream_t>(hip_stream));
+    g_stream = reinterpret_cast<hipStream_t>(hip_stream);
     return CONV_OK;
 }
 

@@ -258,3 +258,81 @@ def test_tap_plans_name_their_loader():
     assert binding.conv_fwd_plan(32, 256, 56, 56, 64, 1, 1, 0, 0).loader == 0      # panel kernel: not a tap plan
     with pytest.raises(binding.ConvError):
         binding.conv_fwd_plan_request(8, 64, 56, 56, 64, 3, 3, 1, 1, tap, 7, 0, loader=3)
+
+
+# Which (filter size, tile shape) pairs of the tap family are built. Written out by hand from the rule in the
+# kernels' header (a shape takes a filter size if its filter block per chunk fits the staging registers); a change
+# of the build that drops or adds an instance must change this table too.
+_ALL = set(range(26))
+_EXTRA = {2, 5, 7, 14, 16, 20, 22}
+BUILT_TAP_INSTANCES = {
+    (1, 1): _ALL, (3, 3): _ALL, (5, 5): {2, 4, 8, 9, 10, 11, 12, 14, 15, 16, 22, 23, 24},
+    (1, 3): _EXTRA, (3, 1): _EXTRA, (1, 5): _EXTRA, (5, 1): _EXTRA, (1, 7): _EXTRA, (7, 1): _EXTRA,
+    (2, 2): _EXTRA, (4, 4): _EXTRA, (7, 7): {2, 14, 16, 22},
+}
+
+
+def built_tap_instances():
+    """(R, S) -> tile shapes the library accepts for that filter size, asked of the host-only resolver on layers
+    small enough for every tile shape's LDS and staging registers (a pair counts as built if any of them resolves)."""
+    tap = binding.CONV_KERNEL_TAP
+    found = {}
+    for (R, S) in BUILT_TAP_INSTANCES:
+        ok = set()
+        for v in range(binding.conv_variant_count(tap)):
+            for N, C, H, tile in ((2, 8, 8, 16), (2, 8, 4, 16), (1, 4, 4, 16), (1, 4, 2, 1)):
+                try:
+                    binding.conv_fwd_plan_request(N, C, H, H, 16, R, S, R // 2, S // 2, tap, v, tile)
+                    ok.add(v)
+                except binding.ConvError as e:
+                    assert e.code == -6
+        found[(R, S)] = ok
+    return found
+
+
+def test_the_set_of_built_tap_instances_is_pinned():
+    assert binding.conv_variant_count(binding.CONV_KERNEL_TAP) == 26
+    assert built_tap_instances() == BUILT_TAP_INSTANCES
+    # sizes outside the table have no tap kernel at all
+    for R, S in [(2, 3), (6, 6), (3, 5), (9, 9), (1, 2), (11, 11)]:
+        with pytest.raises(binding.ConvError):
+            binding.conv_fwd_plan_request(2, 8, 16, 16, 16, R, S, 0, 0, binding.CONV_KERNEL_TAP, 2, 16)
+
+
+def test_halo_tiles_that_cannot_fit_lds_never_reach_the_tap_kernel():
+    """Padded rows of millions of floats: every size of the halo tile is computed in 64 bits, and what cannot fit LDS goes
+    to the generic kernel instead of a tap launch with wrapped-around sizes (host-only; nothing is launched)."""
+    import time
+    tap = binding.CONV_KERNEL_TAP
+    for dims in [(1, 64, 3, 7, 16, 3, 3, 0, 5600000), (1, 4, 3, 7, 1, 3, 3, 0, 400000000), (1, 8, 5, 5, 8, 3, 3, 0, 30000),
+                 (1, 16, 3, 40000, 16, 3, 3, 1, 1), (1, 5, 1, 46000, 3, 1, 1, 0, 0)]:
+        t0 = time.perf_counter()
+        p = binding.conv_fwd_plan(*dims)
+        assert time.perf_counter() - t0 < 2.0, dims            # the search gives up early instead of walking every phase
+        assert p.kernel == binding.CONV_KERNEL_GENERIC, (dims, p.as_dict())
+        for v in (2, 17, 10):
+            with pytest.raises(binding.ConvError):
+                binding.conv_fwd_plan_request(*dims, tap, v, 0)
+    # every tap plan of the grid holds its whole double-buffered halo tile inside the LDS it asks for
+    for s in inputs.sweep_shapes():
+        p = binding.conv_fwd_plan(*s.dims)
+        if p.kernel == tap:
+            assert p.lds_bytes >= 2 * 4 * p.chunk_c * p.lds_plane
+            assert p.lds_plane >= p.lds_rows * p.lds_pitch - 16 and p.lds_pitch >= s.W + 2 * s.pad_w
+
+
+def test_measured_mappings_of_the_benchmark_layers_still_resolve():
+    """The library keeps measured mappings for the five benchmark layers; conv_fwd_plan_untuned is the cost model's own
+    pick for the same layers. Both must resolve, and the model must not price the measured mapping absurdly."""
+    tap = binding.CONV_KERNEL_TAP
+    for i in range(1, 6):
+        dims = inputs.config(i).dims
+        tuned = binding.conv_fwd_plan(*dims)
+        model = binding.conv_fwd_plan_untuned(*dims)
+        assert model.workspace_bytes == 0 and (model.P, model.Q) == (tuned.P, tuned.Q)
+        again, cost_tuned = binding.conv_fwd_plan_request(*dims, tuned.kernel, tuned.variant, tuned.tile_pix, loader=tuned.loader)
+        assert (again.grid, again.block, again.lds_bytes) == (tuned.grid, tuned.block, tuned.lds_bytes)
+        if tuned.kernel == tap and model.kernel == tap:
+            _, cost_model = binding.conv_fwd_plan_request(*dims, tap, model.variant, model.tile_pix, loader=model.loader)
+            assert cost_model <= cost_tuned * 1.001              # the model's pick is its own minimum ...
+            assert cost_tuned <= 1.5 * cost_model                # ... and it prices the measured mapping within 1.5x of it

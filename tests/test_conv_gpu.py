@@ -822,3 +822,34 @@ def test_micro_probes_run_and_report_their_work():
     torch.cuda.synchronize()
     assert torch.equal(src, dst) and float(sink) == 0.0
     assert lib.conv_probe_copy(src.data_ptr() + 4, dst.data_ptr(), 1024) == -2       # not 16-byte aligned
+
+
+def test_every_built_tap_instance_runs_on_some_layer():
+    """No dropped kernel can hide behind a refused plan: every (filter size, tile shape) pair the build is pinned to
+    (tests/test_abi_cpu.py) runs on at least one small layer with the register loader, every pair whose direct-load
+    build a small layer can reach runs with that one too, and each run matches the oracle."""
+    from test_abi_cpu import BUILT_TAP_INSTANCES
+    probes = ((2, 8, 8, 8, 16), (2, 8, 4, 4, 16), (1, 4, 4, 4, 16), (1, 4, 2, 2, 1), (3, 8, 5, 5, 16))
+    ran = {REGISTERS: set(), DIRECT_LOADS: set()}
+    reachable_direct = set()
+    for (R, S_), variants in sorted(BUILT_TAP_INSTANCES.items()):
+        for v in sorted(variants):
+            for loader in (REGISTERS, DIRECT_LOADS):
+                for N, C, H, W, tile in probes:
+                    dims = (N, C, H, W, 20, R, S_, R // 2, S_ // 2)
+                    try:
+                        binding.conv_fwd_plan_request(*dims, TAP, v, tile, loader=loader)      # host-only
+                    except binding.ConvError as e:
+                        assert e.code == -6
+                        continue
+                    if loader == DIRECT_LOADS:
+                        reachable_direct.add((R, S_, v))
+                    shape = S(f"inst_{R}x{S_}_v{v}_l{loader}_h{H}", *dims)
+                    plan, _ = _run(shape, kernel=TAP, variant=v, tile_pix=tile, loader=loader)   # a refusal here is a failure
+                    assert plan.variant == v and plan.loader == loader
+                    ran[loader].add((R, S_, v))
+                    break
+    want = {(R, S_, v) for (R, S_), variants in BUILT_TAP_INSTANCES.items() for v in variants}
+    assert ran[REGISTERS] == want, sorted(want - ran[REGISTERS])
+    assert ran[DIRECT_LOADS] == reachable_direct
+    assert len(reachable_direct) >= len(want) * 3 // 4, sorted(want - reachable_direct)
