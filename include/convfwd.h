@@ -22,9 +22,10 @@
  * Ownership: x, w and y are DEVICE pointers owned by the caller; the library
  * never allocates, frees or keeps them, and needs no workspace except in the two
  * opt-in entry points that take one from the caller (conv_fwd_split_c,
- * conv_fwd_two_stage). Its only device memory is a static 16-byte block of zeros
- * (read by the tap family's direct loader; its address is looked up at the first
- * launch on a device). x and w must not overlap y. Calls are asynchronous on
+ * conv_fwd_two_stage). Its only device memory is static: a 16-byte block of zeros
+ * (read by the tap family's direct loader) and the scratch array of
+ * conv_fwd_split_c_static; their addresses are looked up at the first use on a
+ * device. x and w must not overlap y. Calls are asynchronous on
  * the stream given to conv_set_stream (default: the null stream); the caller
  * synchronises.
  *
@@ -201,6 +202,24 @@ int conv_fwd_plan_split_c(int N, int C, int H, int W, int K, int R, int S, int p
 int conv_fwd_split_c(const float* x, const float* w, const float* bias, float* y, float* workspace,
                      long long workspace_bytes, int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
                      int relu, const conv_plan_t* plan, conv_plan_t* resolved);
+
+/*
+ * conv_fwd_split_c for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc. The partial outputs of the channel shares go
+ * into a static device array of CONV_STATIC_SCRATCH_BYTES bytes that the library's code object carries (every
+ * GPU the library runs on holds its own copy until the process ends; its address is looked up once per device,
+ * at the first call on that device). Arguments, results (bit for bit) and errors are those of conv_fwd_split_c
+ * without workspace / workspace_bytes; a layer whose mapping needs more than CONV_STATIC_SCRATCH_BYTES
+ * (resolved->workspace_bytes = 4 * c_splits * N*K*P*Q) is refused with CONV_E_WORKSPACE and nothing is launched.
+ * The call allocates and frees nothing on the device and enqueues the same two kernels on the calling thread's
+ * stream. All calls on one GPU share the array: it keeps the last call's partial sums (nothing needs clearing -
+ * every element the second kernel reads was written by the first), and calls that overlap on one GPU (two streams,
+ * two threads) race on it - serialise them. Mappings without channel shares (c_splits == 1) do not touch it.
+ */
+#define CONV_STATIC_SCRATCH_BYTES (16ll << 20)
+int conv_fwd_split_c_static(const float* x, const float* w, const float* bias, float* y,
+                            int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
+                            int relu, const conv_plan_t* plan, conv_plan_t* resolved);
 
 /*
  * The paper's own two-stage scheme (Section 3), opt-in and outside the planner, for comparison with the

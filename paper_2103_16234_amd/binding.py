@@ -21,7 +21,7 @@ CONV_LOADER_REGISTERS = 1
 CONV_LOADER_DIRECT = 2
 
 EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_plan_untuned", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_fwd_find", "conv_two_stage_workspace_bytes",
-           "conv_fwd_two_stage", "conv_fwd_plan_split_c", "conv_fwd_split_c", "conv_fwd_plan_request", "conv_probe_mfma", "conv_probe_copy",
+           "conv_fwd_two_stage", "conv_fwd_plan_split_c", "conv_fwd_split_c", "conv_fwd_split_c_static", "conv_fwd_plan_request", "conv_probe_mfma", "conv_probe_copy",
            "conv_variant_count", "conv_variant_info", "conv_set_stream", "conv_strerror")
 
 
@@ -76,6 +76,7 @@ def load_library():
     lib.conv_fwd_plan_request.argtypes = dims + [ctypes.POINTER(ConvPlan), ctypes.POINTER(ConvPlan), ctypes.POINTER(ctypes.c_double)]
     lib.conv_fwd_split_c.argtypes = [vp, vp, vp, vp, vp, ctypes.c_longlong] + dims + [ci, ctypes.POINTER(ConvPlan),
                                                                                    ctypes.POINTER(ConvPlan)]
+    lib.conv_fwd_split_c_static.argtypes = [vp, vp, vp, vp] + dims + [ci, ctypes.POINTER(ConvPlan), ctypes.POINTER(ConvPlan)]
     lib.conv_probe_mfma.argtypes = [ci, vp]
     lib.conv_probe_mfma.restype = ctypes.c_longlong
     lib.conv_probe_copy.argtypes = [vp, vp, ctypes.c_longlong]
@@ -237,6 +238,28 @@ def conv_fwd_split_c(x, w, pad_h: int, pad_w: int, bias=None, relu: bool = False
     _check(lib.conv_fwd_split_c(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None, y.data_ptr(),
                                 workspace.data_ptr(), workspace.numel() * 4, *dims, int(bool(relu)),
                                 ctypes.byref(req) if req is not None else None, ctypes.byref(res)))
+    return y, res
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def conv_fwd_split_c_static(x, w, pad_h: int, pad_w: int, y, bias=None, relu: bool = False, c_splits: int = 0, variant=None,
+                            tile_pix: int = 0, use_current_stream: bool = True, loader: int = 0):
+    """conv_fwd_split_c on the library's static scratch array: no workspace, and nothing is allocated here either
+    (y must be given). Returns (y, plan)."""
+    import torch
+    y, dims = _device_args(x, w, y, pad_h, pad_w)
+    lib = load_library()
+    if use_current_stream:
+        conv_set_stream(torch.cuda.current_stream(x.device))
+    res = ConvPlan()
+    req = None
+    if variant is not None:
+        req = ConvPlan()
+        req.kernel, req.variant, req.tile_pix, req.c_splits, req.loader = 1, variant, tile_pix, c_splits, loader
+    _check(lib.conv_fwd_split_c_static(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None, y.data_ptr(),
+                                       *dims, int(bool(relu)), ctypes.byref(req) if req is not None else None, ctypes.byref(res)))
     return y, res
 
 

@@ -247,8 +247,12 @@ hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid,
 hipError_t launch_generic(int grid, int block, hipStream_t stream, const KernelArgs& a);
 // *zeros = 16 bytes of zeros in the current device's memory (a static device array, looked up once per device)
 hipError_t zero_block(const float** zeros);
-// scratch: 16-byte aligned device memory of at least `bytes` bytes; contents are overwritten
-hipError_t launch_scratch_fill(void* scratch, long long bytes, hipStream_t stream);
+// *ptr = the current device's copy of the library's static scratch array (kStaticScratchBytes bytes, 256-byte aligned),
+// looked up once per device
+constexpr long long kStaticScratchBytes = 16ll << 20;
+hipError_t static_scratch(float** ptr);
+// buffer: 16-byte aligned device memory of at least `bytes` bytes; contents are overwritten
+hipError_t launch_scratch_fill(void* buffer, long long bytes, hipStream_t stream);
 // micro-probes: 8192 waves x iters x 16 fp32 MFMAs (2048 flops each); a dwordx4 copy of `bytes` (16-byte aligned pointers)
 hipError_t launch_probe_mfma(int iters, float* sink, hipStream_t stream);
 hipError_t launch_probe_copy(const void* src, void* dst, long long bytes, hipStream_t stream);

@@ -781,7 +781,8 @@ static int resolve_request(const Shape& s, int x_cap, int w_cap, int y_cap, cons
 
 static int run_planned(const float* x, const float* w, const float* bias, float* y, int N, int C, int H, int W, int K,
                        int R, int S, int pad_h, int pad_w, int relu, const conv_plan_t* plan, conv_plan_t* resolved,
-                       bool may_split = false, float* workspace = nullptr, long long workspace_bytes = 0)
+                       bool may_split = false, float* workspace = nullptr, long long workspace_bytes = 0,
+                       bool static_workspace = false)
 {
     if (!x || !w || !y) return CONV_E_NULL;
     Shape s;
@@ -799,6 +800,12 @@ static int run_planned(const float* x, const float* w, const float* bias, float*
     if (resolved) *resolved = p;
     if (p.c_splits <= 1) return launch(p, a, s, x, w, y, bias, relu);
     // channel shares: the tap kernel writes c_splits partial outputs into the workspace, a second kernel adds them
+    if (static_workspace) {
+        // the library's own static array takes the caller's place; larger layers are refused, never allocated for
+        if (p.workspace_bytes > kStaticScratchBytes) return CONV_E_WORKSPACE;
+        if (int rc = record_hip(static_scratch(&workspace))) return rc;
+        workspace_bytes = kStaticScratchBytes;
+    }
     if (!workspace) return CONV_E_NULL;
     if (workspace_bytes < p.workspace_bytes) return CONV_E_WORKSPACE;
     if (int rc = launch(p, a, s, x, w, workspace)) return rc;
@@ -838,6 +845,14 @@ extern "C" int conv_fwd_split_c(const float* x, const float* w, const float* bia
 {
     return run_planned(x, w, bias, y, N, C, H, W, K, R, S, pad_h, pad_w, relu != 0, plan, resolved, true, workspace,
                        workspace_bytes);
+}
+
+static_assert(kStaticScratchBytes == CONV_STATIC_SCRATCH_BYTES, "header and library disagree on the static scratch size");
+extern "C" int conv_fwd_split_c_static(const float* x, const float* w, const float* bias, float* y, int N, int C, int H, int W,
+                                       int K, int R, int S, int pad_h, int pad_w, int relu, const conv_plan_t* plan,
+                                       conv_plan_t* resolved)
+{
+    return run_planned(x, w, bias, y, N, C, H, W, K, R, S, pad_h, pad_w, relu != 0, plan, resolved, true, nullptr, 0, true);
 }
 
 extern "C" int conv_fwd_planned(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R,

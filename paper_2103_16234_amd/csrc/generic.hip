@@ -68,12 +68,38 @@ hipError_t zero_block(const float** zeros)
     return hipSuccess;
 }
 
-hipError_t launch_scratch_fill(void* scratch, long long bytes, hipStream_t stream)
+// Scratch of conv_fwd_split_c_static, the entry point for callers that cannot allocate: the partial output tensors
+// of the channel shares live here instead of in a caller's workspace. Every GPU the library runs on holds its own copy
+// until the process ends. The name stands for the array in host code only as a symbol: its device address is looked up
+// once per device (below) and everything - kernel arguments included - uses that address.
+static __device__ __align__(256) float scratch[kStaticScratchBytes / 4];
+
+hipError_t static_scratch(float** ptr)
+{
+    static std::atomic<float*> known[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    float* p = known[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void* q = nullptr;
+        e = hipGetSymbolAddress(&q, HIP_SYMBOL(scratch));  // the current device's copy of the array
+        if (e != hipSuccess) return e;
+        if (!q) return hipErrorInvalidSymbol;
+        p = static_cast<float*>(q);
+        known[dev].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return hipSuccess;
+}
+
+hipError_t launch_scratch_fill(void* buffer, long long bytes, hipStream_t stream)
 {
     const long long n16 = bytes / 16;
     if (n16 <= 0) return hipSuccess;
     const int grid = (int)std::min<long long>((n16 + 255) / 256, 256 * 16);
-    hipLaunchKernelGGL(scratch_fill, dim3(grid), dim3(256), 0, stream, reinterpret_cast<float4*>(scratch), n16);
+    hipLaunchKernelGGL(scratch_fill, dim3(grid), dim3(256), 0, stream, reinterpret_cast<float4*>(buffer), n16);
     return hipGetLastError();
 }
 
