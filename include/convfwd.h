@@ -63,6 +63,9 @@ extern "C" {
  * fetches the padding cells of the halo tile, from a block of zeros). */
 #define CONV_LOADER_REGISTERS 1
 #define CONV_LOADER_DIRECT 2
+/* Direct loads issued by four loader waves of their own (tile shapes of eight waves only): the waves that multiply
+ * then issue no memory instruction between prologue and stores; conv_plan_t.block counts the loader waves too. */
+#define CONV_LOADER_DIRECT_WAVES 3
 
 /*
  * How one layer is mapped onto the GPU. Filled by conv_fwd_plan; plain data.

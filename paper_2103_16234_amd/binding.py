@@ -19,6 +19,7 @@ CONV_KERNEL_POINTWISE = 2
 CONV_KERNEL_PANEL = 3
 CONV_LOADER_REGISTERS = 1
 CONV_LOADER_DIRECT = 2
+CONV_LOADER_DIRECT_WAVES = 3
 
 EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_plan_untuned", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_fwd_find", "conv_two_stage_workspace_bytes",
            "conv_fwd_two_stage", "conv_fwd_plan_split_c", "conv_fwd_split_c", "conv_fwd_split_c_static", "conv_fwd_plan_request", "conv_probe_mfma", "conv_probe_copy",

@@ -59,12 +59,16 @@ struct KernelArgs {
     int lds_rows, lds_pitch, lds_plane;
     int col_shift;   // LDS column of padded column 0 (keeps vector stores aligned)
     int x_items;     // vector loads per chunk for the halo tile
-    int direct;      // tap family: nonzero = the loader that moves global memory straight into LDS. Then x_items counts the
+    int direct;      // tap family: nonzero = the loader that moves global memory straight into LDS (2: issued by loader waves
+                     // of their own). Then x_items counts the
                      // vectors of the LDS halo tile of a chunk, padding included (chunk_c * lds_plane / x_vec), and
                      // div_slot_c / div_row_vecs divide by lds_plane / x_vec and lds_pitch / x_vec
     const float* zeros;  // 16 bytes of zeros in device memory (source of the padding cells for the direct loader)
     // dividers for the index arithmetic of the prologue
     FastDiv div_ktiles, div_ptiles, div_PQ, div_Q, div_Hp, div_row_vecs, div_slot_c;
+    // tap family: correctly rounded float reciprocals of the divisors of the per-lane index arithmetic (the divisors of
+    // div_slot_c and div_row_vecs, Hp, Q, P, P*Q); the dividends there are small, see small_div in the kernel
+    float inv_slot_c, inv_row_vecs, inv_Hp, inv_Q, inv_P, inv_PQ;
 };
 
 // Taps per software-pipeline unit of the tap kernel: the shortest of {1, S, R*S} that keeps enough matrix
@@ -130,6 +134,9 @@ struct TapVariant {
     }
     // LDS floats the cross-wave reduction needs (the first round of the tree is the widest)
     constexpr int reduce_floats() const { return WC > 1 ? (WC / 2) * WK * WP * MT * NT * 256 : 0; }
+    // Loader waves a build of this shape with dedicated loading waves adds (0: no such build). Built for the shapes of
+    // eight waves at two per SIMD: a ninth to twelfth wave then fits the register file at three per SIMD.
+    constexpr int loader_waves() const { return block() == 512 && occ == 2 ? 4 : 0; }
     // LDS bytes a work-group may take so that as many work-groups as the registers allow share a CU
     constexpr int lds_limit() const { return 160 * 1024 / (occ * 256 / block() > 0 ? occ * 256 / block() : 1); }
 };

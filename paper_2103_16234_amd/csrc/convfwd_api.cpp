@@ -147,10 +147,18 @@ int max_halo_rows(const Shape& s, int tile_pix)
 bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_cap, int w_cap,
                  conv_plan_t* p, KernelArgs* a, int c_splits = 1, int loader = 0)
 {
-    if (loader < 0 || loader > CONV_LOADER_DIRECT) return false;
+    if (loader < 0 || loader > CONV_LOADER_DIRECT_WAVES) return false;
     const int rs_index = tap_rs_index(s);
     if (!tap_is_built(rs_index, variant)) return false;
     const TapVariant tv = kTapVariants[variant];
+    // Rule for the loader waves, from timings of the same mapping with each loader on the layers of the shape grid that
+    // run the eight-wave tile shapes: where the rule below would leave a deep layer (12 chunks or more) to the register
+    // loader - rows of dwordx2 on 14-wide maps, 7 x 7 maps - the shapes with two channel shares run 1-4 % faster with
+    // four loader waves (32 x 256 x 14 x 14 -> 256: 76.7 -> 73.7 us; 128 x 512 x 7 x 7 -> 512: 258 -> 248 us); the shapes
+    // with four shares, short layers and layers whose rows already move as direct dwordx4 lose 1-10 %.
+    if (loader == 0 && tv.loader_waves() > 0 && tv.WC == 2 && s.C % 4 == 0 && w_cap >= 4 && s.C >= 12 * tv.chunk_c() &&
+        (s.W % 4 == 2 || s.W < 13) && resolve_tap(s, variant, tile_pix, chunk_c, x_cap, w_cap, p, a, c_splits, CONV_LOADER_DIRECT_WAVES))
+        return true;
     const int RS = s.R * s.S, TK = tv.tile_k(), BLOCK = tv.block();
     const int64_t total64 = (int64_t)s.N * s.P * s.Q;
     if (tile_pix == 0) tile_pix = (int)std::min<int64_t>(tv.max_pix(), total64);
@@ -162,6 +170,10 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     int x_vec = s.W % 4 == 0 ? 4 : s.W % 2 == 0 ? 2 : 1;
     x_vec = std::min(x_vec, x_cap);
     if (w_vec == 1 && x_vec != 4) x_vec = 1;  // the loaders built: (4, 4), (2, 4), (1, 4), (4, 1), (1, 1)
+    // Loader waves only know direct loads, which move dwordx4 or single dwords: rows of dwordx2 go dword by dword.
+    const bool loader_waves = loader == CONV_LOADER_DIRECT_WAVES;
+    if (loader_waves && (tv.loader_waves() == 0 || w_vec != 4)) return false;
+    if (loader_waves && x_vec == 2) x_vec = 1;
 
     const int col_shift = (x_vec - s.pad_w % x_vec) % x_vec;
     // Sizes of the halo tile in 64 bits first: a padded row, R of them, or a plane that cannot fit LDS ends the attempt
@@ -179,14 +191,14 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     const bool direct_fits = w_vec == 4 && (x_vec == 4 || x_vec == 1) &&
                              (int64_t)tv.chunk_c() * plane / x_vec <= (int64_t)tv.xs_direct(x_vec) * BLOCK &&
                              (int64_t)tv.chunk_c() * s.H * s.W * 4 < ((int64_t)1 << 32);  // a slot's step from chunk to chunk, in bytes
-    if (loader == CONV_LOADER_DIRECT && !direct_fits) return false;
+    if ((loader == CONV_LOADER_DIRECT || loader_waves) && !direct_fits) return false;
     // Rule, from timings of every tile shape with both loaders on the shape grid and on random layers off it: direct
     // loads win 2-16 % wherever rows move as dwordx4 (a few layers of 10 us and less lose up to 7 %); with single dwords
     // (maps of odd width) they win 5-20 % on layers of 0.6 GFLOP and more on maps 13 wide and wider, while shorter
     // layers lose up to 17 % (one chunk of look-ahead instead of two) and 7x7 maps never gain (their LDS tile holds
     // almost as much padding as data).
     const double flops = 2.0 * s.N * s.K * s.P * s.Q * s.C * RS;
-    const bool direct = loader == CONV_LOADER_DIRECT ||
+    const bool direct = loader == CONV_LOADER_DIRECT || loader_waves ||
                         (loader == 0 && direct_fits && (x_vec == 4 || (s.W >= 13 && flops >= 6e8)));
 
     // The chunk is a property of the tile shape; a caller may only name that size.
@@ -213,22 +225,26 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     if (splits > 1) a->split_c = chunks_share * cc;
     a->lds_rows = rows; a->lds_pitch = pitch; a->lds_plane = plane; a->col_shift = col_shift;
     a->x_items = direct ? cc * plane / x_vec : cc * rows * row_vecs;
-    a->direct = direct;
+    a->direct = loader_waves ? 2 : direct ? 1 : 0;
     a->div_ktiles = make_fastdiv(a->ktiles); a->div_ptiles = make_fastdiv(a->ptiles);
     a->div_PQ = make_fastdiv(a->PQ); a->div_Q = make_fastdiv(s.Q); a->div_Hp = make_fastdiv(a->Hp);
     a->div_row_vecs = make_fastdiv(direct ? pitch / x_vec : row_vecs);
     a->div_slot_c = make_fastdiv(direct ? plane / x_vec : rows * row_vecs);
+    a->inv_row_vecs = 1.0f / static_cast<float>(direct ? pitch / x_vec : row_vecs);
+    a->inv_slot_c = 1.0f / static_cast<float>(direct ? plane / x_vec : rows * row_vecs);
+    a->inv_Hp = 1.0f / static_cast<float>(a->Hp); a->inv_Q = 1.0f / static_cast<float>(s.Q);
+    a->inv_P = 1.0f / static_cast<float>(s.P); a->inv_PQ = 1.0f / static_cast<float>(a->PQ);
 
     std::memset(p, 0, sizeof(*p));
     p->kernel = CONV_KERNEL_TAP; p->variant = variant;
     p->tile_k = TK; p->tile_pix = tile_pix; p->chunk_c = cc;
     p->x_vec = x_vec; p->w_vec = w_vec;
     p->lds_rows = rows; p->lds_pitch = pitch; p->lds_plane = plane;
-    p->grid = a->ktiles * a->ptiles * splits; p->block = BLOCK;
+    p->grid = a->ktiles * a->ptiles * splits; p->block = BLOCK + (loader_waves ? 64 * tv.loader_waves() : 0);
     p->lds_bytes = (int)lds;
     fill_common(s, p);
     p->c_splits = splits;
-    p->loader = direct ? CONV_LOADER_DIRECT : CONV_LOADER_REGISTERS;
+    p->loader = loader_waves ? CONV_LOADER_DIRECT_WAVES : direct ? CONV_LOADER_DIRECT : CONV_LOADER_REGISTERS;
     if (splits > 1) p->workspace_bytes = 4LL * splits * s.K * total;
     return true;
 }
@@ -461,7 +477,9 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
     // staging slots that run per chunk: the loader build the launcher will take, not just the slots with data
     const int x_slots = ceil_div(a.direct ? tv.xs_direct(p.x_vec) : tv.xs(p.x_vec), tap_x_slot_divisor(tv, p.x_vec, p.w_vec, a.x_items, a.direct != 0));
     const int slots = x_slots + (a.direct ? tv.wslots_direct(RS) : ceil_div(tv.tile_k() * tv.chunk_c() * RS / p.w_vec, tv.block()));
-    const double work = waves_per_simd * (tv.MT * tv.NT * tv.GPC * RS * 32.0 + (a.direct ? 50.0 : 110.0) * slots);  // per SIMD, chunk, work-group
+    // (with loader waves the slots are not the multiplying waves' business, but their traffic into LDS still is: measured
+    // 2-4 % under the register loader on deep layers)
+    const double work = waves_per_simd * (tv.MT * tv.NT * tv.GPC * RS * 32.0 + (a.direct == 2 ? 80.0 : a.direct ? 50.0 : 110.0) * slots);  // per SIMD, chunk, work-group
     const double staged = 4.0 * ((double)tv.chunk_c() * a.lds_rows * a.W + (double)tv.tile_k() * tv.chunk_c() * RS);
     const double chunk = std::max(std::max(cu * work / eff, batches * ((a.direct ? 1500.0 : 750.0) + work)), cu * staged / 16.0);
     // cross-wave reduction: per round of the tree every tile goes through LDS once each way (~8 cycles per 64 B with
@@ -908,7 +926,7 @@ static void enumerate_candidates(const Shape& s, int x_cap, int w_cap, int y_cap
                 bool seen = false;
                 for (int k = 0; k < i; ++k) seen = seen || cands[k] == cands[i];
                 if (seen || cands[i] < 1) continue;
-                for (int loader = CONV_LOADER_REGISTERS; loader <= CONV_LOADER_DIRECT; ++loader) {  // both, where both can run
+                for (int loader = CONV_LOADER_REGISTERS; loader <= CONV_LOADER_DIRECT_WAVES; ++loader) {  // each one that can run
                     if (!resolve_tap(s, v, cands[i], 0, x_cap, w_cap, &c.p, &c.a, 1, loader)) continue;
                     c.model = tap_cost(c.p, c.a, tv, s.R * s.S);
                     if (taps.empty() || c.model < best) best = c.model;

@@ -77,6 +77,13 @@ template <> struct Vec<1> {
 
 template <int N> using IntC = std::integral_constant<int, N>;
 
+// x / d for a small non-negative x (below 2^22) and a launch-time divisor d whose correctly rounded float reciprocal
+// the host supplies: (x + 1/2) / d is at least 1/(2d) away from every integer, and the two roundings (the reciprocal, the
+// fused multiply-add) move it by less than (x + 1/2) * 2^-23 / d, so truncation gives the exact quotient. Three full-rate
+// vector instructions, where the multiply-high method takes a quarter-rate multiply and four more; the prologue's
+// per-lane index arithmetic (slot tables, pixel table) and the epilogue's are made of these.
+__device__ __forceinline__ int small_div(int x, float inv) { return static_cast<int>(fmaf(static_cast<float>(x), inv, 0.5f * inv)); }
+
 // Scheduling directive for the straight-line code since the previous fence: issue the matrix
 // instructions in order and slip in front of each a few address adds, up to two LDS reads, one LDS
 // store and one global load; then fence so nothing moves across.
@@ -93,19 +100,31 @@ template <int N_MFMA> __device__ __forceinline__ void interleave_with_mfma()
     __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int R, int S, int MT, int NT, int WK, int WP, int WC, int GPC, int OCC, int XS, int WS, int VX, int VW, bool DMA = false>
-__global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const KernelArgs a)
+// LW > 0: the work-group has LW more waves, the loader waves, which do nothing but the direct loads of the staging copies
+// (all slots are theirs, XS and WS count slots per loader thread); the other waves then contain no memory instruction
+// between the prologue and the stores. OCC counts all waves of a SIMD.
+template <int R, int S, int MT, int NT, int WK, int WP, int WC, int GPC, int OCC, int XS, int WS, int VX, int VW, bool DMA = false, int LW = 0>
+__global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(const KernelArgs a)
 {
     static_assert(WC >= 1 && WC <= 16 && (WC & (WC - 1)) == 0, "the cross-wave reduction is a binary tree");
-    constexpr int BLOCK = 64 * WK * WP * WC;
+    static_assert(LW == 0 || DMA, "loader waves move data with direct loads");
+    constexpr int BLOCK = 64 * WK * WP * WC;  // threads of the waves that multiply
+    constexpr int NWC = WK * WP * WC;
+    constexpr int LB = LW > 0 ? 64 * LW : BLOCK;  // threads that own staging slots
     constexpr int RS = R * S;
     constexpr int TK = 16 * MT * WK;
     constexpr int CC = 4 * WC * GPC;     // channels per chunk
     constexpr int WPITCH = CC * RS + 4;  // floats per output channel in the LDS filter block (rows stay 16-byte aligned)
-    constexpr int UT = tap_unit_taps(S, RS, MT, NT, OCC);
+    constexpr int UT = tap_unit_taps(S, RS, MT, NT, LW > 0 ? (NWC + 3) / 4 : OCC);  // (by the waves per SIMD that multiply)
     constexpr int UNITS = RS / UT;       // pipeline units per 4-channel group
     constexpr int U = GPC * UNITS;       // pipeline units per chunk (per wave)
     constexpr int TS = XS + WS;          // staging slots per thread
+    // Pipeline units of a chunk over which a thread's staging slots are spread: all of them, or - direct dwordx4 loads of
+    // tile shapes whose chunk is short (64 matrix instructions per wave or fewer) - the first third, so that the data of
+    // the next chunk is not still on its way when this one ends. Measured on the 3x3 / 5x5 layers of the shape grid that
+    // run such shapes: batch-1 layers on 28..56-pixel maps 2-14 % faster (1 x 64 x 56 x 56 -> 64: 8.9 -> 7.7 us), layers of
+    // 100 us and more unchanged; with single-dword rows (odd map widths: four times the slots) it loses 1-4 % instead.
+    constexpr int UI = (DMA && LW == 0 && VX == 4 && MT * NT * GPC * RS <= 64) ? (U + 2) / 3 : U;
 
     extern __shared__ f32x4 smem4[];
     float* const lds = reinterpret_cast<float*>(smem4);
@@ -126,6 +145,8 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     const int wk = wave % WK;
     const int wp = (wave / WK) % WP;
     const int wc = wave / (WK * WP);  // this wave reduces the chunk's channel groups wc + WC*gi
+    const bool is_loader = LW > 0 && wave >= NWC;      // wave-uniform
+    const int lwave = LW > 0 ? wave - NWC : wave;       // position among the waves that own staging slots
 
     // Work-groups are dealt round-robin to the 8 XCDs; renumber them so that each XCD (one L2)
     // gets a contiguous run of tiles: neighbours share the pixel tile and walk the K tiles.
@@ -151,47 +172,66 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     const int k0 = ktile * TK;
     const int g0 = ptile * a.tile_pix;
     const int g_end = min(g0 + a.tile_pix, a.total_pix);
+    // the tile's first pixel (n0, p0, q0): wave-uniform, kept in scalar registers. Every per-lane position below is this
+    // plus a small offset, so the per-lane divisions only ever see small numbers.
     const int n0 = a.div_PQ.div(g0);
-    const int V0 = n0 * a.Hp + a.div_Q.div(g0 - n0 * a.PQ);  // first stacked padded row held in LDS
+    const int pq0 = g0 - n0 * a.PQ;
+    const int p0 = a.div_Q.div(pq0);
+    const int q0 = pq0 - p0 * a.Q;
+    const int V0 = n0 * a.Hp + p0;  // first stacked padded row held in LDS
+    // row `row` of the LDS halo tile (stacked padded row V0 + row) -> image and input row of that image
+    auto image_row = [&](int row, int& n, int& h) {
+        int t = p0 + row;  // padded row counted from the top of image n0; runs on into the following images
+        int dn = 0;
+        const int r = t - a.Hp;
+        if (r >= 0) {
+            const int m = small_div(r, a.inv_Hp);
+            dn = 1 + m;
+            t = r - __mul24(m, a.Hp);  // (m > 0 only where an image has fewer rows than the halo tile)
+        }
+        n = n0 + dn;
+        h = t - a.pad_h;
+    };
 
     // Staging slots. xg / wg: offset in floats from the chunk's first channel in x / w; xl / wl: float
     // offset inside a staging copy in the low 16 bits, the slot's channel (x) or element offset in the
     // chunk's filter slice (w) above. Slots the thread does not own read element 0 and write the dump.
     constexpr int XR = DMA ? 1 : XS, WR = DMA ? 1 : WS;
     unsigned xg[XR], xl[XR], wg[WR], wl[WR];
-    // Direct loads: slot i of a wave fills the vectors start .. start+63 of a region (start in xdst / wdst, as a float
-    // offset inside a staging copy), lane l the l-th of them, from xp / wq; after each load the pointer moves on by
+    // Direct loads: slot i of a wave fills the vectors start .. start+63 of a region (start = x_position(i) /
+    // w_position(i), wave-uniform), lane l the l-th of them, from xp / wq; after each load the pointer moves on by
     // xstep / wstep bytes (one chunk). Vectors that hold padding, rows outside the images, output channels past K or
     // nothing at all are fetched from a 16-byte block of zeros, with step 0. Runs that would reach past the region
     // start earlier and repeat part of the previous run.
     const float* xp[DMA ? XS : 1];
     const float* wq[DMA ? WS : 1];
-    unsigned xstep[DMA ? XS : 1], wstep[DMA ? WS : 1];
-    int xdst[DMA ? XS : 1], wdst[DMA ? WS : 1];
+    // (Loader waves hold many more slots per thread and keep no step: a pointer that still equals the zeros' address does
+    // not move, any other moves by the chunk.)
+    constexpr bool STEPS = DMA && LW == 0;
+    unsigned xstep[STEPS ? XS : 1], wstep[STEPS ? WS : 1];
     constexpr int WPV = WPITCH / 4;  // vectors per output channel of the LDS filter block, the last one padding
-    auto x_position = [&](int i) { return min(i * BLOCK + wave * 64, xs_floats / VX - 64); };
-    auto w_position = [&](int i) { return min(i * BLOCK + wave * 64, WREG / 4 - 64); };
-    if constexpr (DMA) {
+    auto x_position = [&](int i) { return min(i * LB + lwave * 64, xs_floats / VX - 64); };  // wave-uniform
+    auto w_position = [&](int i) { return min(i * LB + lwave * 64, WREG / 4 - 64); };
+    auto build_direct_slots = [&]() {
         static_assert(!DMA || VW == 4, "filters move as dwordx4");
         const int plane_v = a.lds_plane / VX, pitch_v = a.lds_pitch / VX;
 #pragma unroll
         for (int i = 0; i < XS; ++i) {
             const int start = x_position(i);
             const int e = start + lane;
-            xdst[i] = start * VX;
             xp[i] = a.zeros;
-            xstep[i] = 0;
+            if constexpr (STEPS) xstep[i] = 0;
             if (e < a.x_items) {
-                const int c_l = a.div_slot_c.div(e);
-                const int rem = e - c_l * plane_v;
-                const int row = a.div_row_vecs.div(rem);
-                const int col = (rem - row * pitch_v) * VX - a.col_shift - a.pad_w;
-                const int v = V0 + row;
-                const int n = a.div_Hp.div(v);
-                const int h = v - n * a.Hp - a.pad_h;
+                const int c_l = small_div(e, a.inv_slot_c);
+                const int rem = e - __mul24(c_l, plane_v);
+                const int row = small_div(rem, a.inv_row_vecs);
+                const int col = (rem - __mul24(row, pitch_v)) * VX - a.col_shift - a.pad_w;
+                int n, h;
+                image_row(row, n, h);
                 if (row < a.lds_rows && col >= 0 && col < a.W && n < a.N && h >= 0 && h < a.H) {
-                    xp[i] = x_share + ((static_cast<size_t>(n) * a.C + c_l) * a.H + h) * a.W + col;
-                    xstep[i] = 4u * CC * a.HW;
+                    // (x holds fewer than 2^31 elements: the offset of a valid cell fits 32 bits)
+                    xp[i] = x_share + ((static_cast<unsigned>(n * a.C + c_l) * a.H + h) * a.W + col);
+                    if constexpr (STEPS) xstep[i] = 4u * CC * a.HW;
                 }
             }
         }
@@ -199,16 +239,18 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         for (int i = 0; i < WS; ++i) {
             const int start = w_position(i);
             const int e = start + lane;
-            wdst[i] = xs_floats + start * 4;
             wq[i] = a.zeros;
-            wstep[i] = 0;
+            if constexpr (STEPS) wstep[i] = 0;
             const int kl = e / WPV;
             const int ev = e - kl * WPV;
             if (kl < TK && ev < WPV - 1 && k0 + kl < a.K) {
                 wq[i] = w_share + static_cast<size_t>(k0 + kl) * a.CRS + ev * 4;
-                wstep[i] = CC * RS * 4;
+                if constexpr (STEPS) wstep[i] = CC * RS * 4;
             }
         }
+    };
+    if constexpr (DMA) {
+        if constexpr (LW == 0) build_direct_slots();  // (with loader waves: theirs, built where their role starts)
     } else {
         const int XV = a.W / VX;
         const int per_c = a.lds_rows * XV;
@@ -218,13 +260,12 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
             xg[i] = 0;
             xl[i] = dump_off + lane * 4;
             if (e < a.x_items) {
-                const int c_l = a.div_slot_c.div(e);
-                const int rem = e - c_l * per_c;
-                const int row = a.div_row_vecs.div(rem);
-                const int cv = rem - row * XV;
-                const int v = V0 + row;
-                const int n = a.div_Hp.div(v);
-                const int h = v - n * a.Hp - a.pad_h;
+                const int c_l = small_div(e, a.inv_slot_c);
+                const int rem = e - __mul24(c_l, per_c);
+                const int row = small_div(rem, a.inv_row_vecs);
+                const int cv = rem - __mul24(row, XV);
+                int n, h;
+                image_row(row, n, h);
                 if (n < a.N && h >= 0 && h < a.H) {
                     // unsigned: a padding channel of the last image may lie past 2^31 elements before the ragged
                     // chunk is retargeted
@@ -297,12 +338,20 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     auto slot_fetch = [&](auto kc, int dst_floats) {
         constexpr int k = decltype(kc)::value;
         if constexpr (k < XS) {
-            if constexpr (VX == 4) __builtin_amdgcn_global_load_lds(GLOBAL_PTR(xp[k]), LDS_PTR(lds + dst_floats + xdst[k]), 16, 0, 0);
-            else __builtin_amdgcn_global_load_lds(GLOBAL_PTR(xp[k]), LDS_PTR(lds + dst_floats + xdst[k]), 4, 0, 0);
-            xp[k] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(xp[k]) + xstep[k]);
+            float* const dst = lds + dst_floats + x_position(k) * VX;  // (uniform)
+            if constexpr (VX == 4) __builtin_amdgcn_global_load_lds(GLOBAL_PTR(xp[k]), LDS_PTR(dst), 16, 0, 0);
+            else __builtin_amdgcn_global_load_lds(GLOBAL_PTR(xp[k]), LDS_PTR(dst), 4, 0, 0);
+            unsigned step;
+            if constexpr (STEPS) step = xstep[k];
+            else step = xp[k] == a.zeros ? 0u : 4u * CC * a.HW;
+            xp[k] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(xp[k]) + step);
         } else {
-            __builtin_amdgcn_global_load_lds(GLOBAL_PTR(wq[k - XS]), LDS_PTR(lds + dst_floats + wdst[k - XS]), 16, 0, 0);
-            wq[k - XS] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(wq[k - XS]) + wstep[k - XS]);
+            float* const dst = lds + dst_floats + xs_floats + w_position(k - XS) * 4;
+            __builtin_amdgcn_global_load_lds(GLOBAL_PTR(wq[k - XS]), LDS_PTR(dst), 16, 0, 0);
+            unsigned step;
+            if constexpr (STEPS) step = wstep[k - XS];
+            else step = wq[k - XS] == a.zeros ? 0u : static_cast<unsigned>(CC * RS * 4);
+            wq[k - XS] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(wq[k - XS]) + step);
         }
     };
     // The pointers have just reached the last chunk of a share that is not a multiple of the chunk: vectors of
@@ -312,7 +361,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
 #pragma unroll
             for (int i = 0; i < XS; ++i) {
                 const int e = x_position(i) + lane;
-                if (e < a.x_items && last_c0 + static_cast<int>(a.div_slot_c.div(e)) >= C_l) xp[i] = a.zeros;
+                if (e < a.x_items && last_c0 + small_div(e, a.inv_slot_c) >= C_l) xp[i] = a.zeros;
             }
 #pragma unroll
             for (int i = 0; i < WS; ++i) {
@@ -336,6 +385,39 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         (std::make_integer_sequence<int, TS>{});
     };
 
+    // Loader waves: chunk 0 into copy 0, then always one chunk ahead of the arithmetic - chunk ch+1 is fetched into the
+    // other copy while the multiplying waves work on chunk ch, and the barrier at the end of a chunk is passed once the
+    // fetched data has landed. They take part in every barrier of the work-group (those of the cross-wave reduction
+    // too) and leave.
+    if constexpr (LW > 0) {
+        if (is_loader) {
+            __builtin_amdgcn_s_setprio(3);  // their few instructions go ahead of the matrix work that shares the SIMD
+            build_direct_slots();
+            if (ragged && nchunks == 1) zero_past_share();
+            for_each_slot([&](auto kc) { slot_fetch(kc, 0); });
+            if (ragged && nchunks == 2) zero_past_share();
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+            __syncthreads();
+            for (int ch = 0; ch < nchunks; ++ch) {
+                if (ch + 1 < nchunks) {
+                    const int nxt_floats = ((ch + 1) & 1) * buf_floats;
+                    for_each_slot([&](auto kc) { slot_fetch(kc, nxt_floats); });
+                    if (ragged && ch + 3 == nchunks) zero_past_share();  // the pointers now stand at chunk ch+2, the last
+                    __builtin_amdgcn_s_waitcnt(0x0F70);
+                }
+                __syncthreads();
+            }
+            if constexpr (WC > 1) {
+#pragma unroll
+                for (int stride = WC / 2; stride >= 1; stride /= 2) {
+                    if (stride != WC / 2) __syncthreads();
+                    __syncthreads();
+                }
+            }
+            return;
+        }
+    }
+
     f32x4 acc[MT][NT];
 #pragma unroll
     for (int m = 0; m < MT; ++m)
@@ -347,7 +429,9 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     // channels past K then stay zero for the whole kernel) and build the per-lane pixel table.
     // With direct loads chunk 0 is on its way to copy 0 at once and nothing has to be zeroed: every cell of a copy is
     // written by every chunk, padding included.
-    if constexpr (DMA) {
+    if constexpr (LW > 0) {
+        // (the loader waves fetch)
+    } else if constexpr (DMA) {
         if (ragged && nchunks == 1) zero_past_share();
         for_each_slot([&](auto kc) { slot_fetch(kc, 0); });
         if (ragged && nchunks == 2) zero_past_share();
@@ -364,16 +448,24 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
     int xb[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        const int gc = min(g0 + (wp * NT + t) * 16 + j, g_end - 1);
-        const int n = a.div_PQ.div(gc);
-        const int pq = gc - n * a.PQ;
-        const int p = a.div_Q.div(pq);
-        const int q = pq - p * a.Q;
-        xb[t] = 4 * ((4 * wc + kq) * a.lds_plane + (n * a.Hp + p - V0) * a.lds_pitch + q + a.col_shift);
+        const int d = min((wp * NT + t) * 16 + j, g_end - 1 - g0);  // pixel g0 + d
+        int q = q0 + d;  // below Q + the tile: small
+        const int dp = small_div(q, a.inv_Q);
+        q -= __mul24(dp, a.Q);
+        int p = p0 + dp, dn = 0;  // output row counted from the top of image n0; may run on into the following images
+        const int r = p - a.P;
+        if (r >= 0) {
+            const int m = small_div(r, a.inv_P);
+            dn = 1 + m;
+            p = r - __mul24(m, a.P);  // (m > 0 only on maps smaller than the tile)
+        }
+        // rows of LDS between this pixel's window and the tile's first: (n0 + dn) * Hp + p - V0
+        xb[t] = 4 * ((4 * wc + kq) * a.lds_plane + __mul24(dn * a.Hp + p - p0, a.lds_pitch) + q + a.col_shift);
     }
     const int arow = 4 * (xs_floats + (wk * MT * 16 + j) * WPITCH + (4 * wc + kq) * RS);
 
-    if constexpr (DMA) {
+    if constexpr (LW > 0) {
+    } else if constexpr (DMA) {
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's part of chunk 0 is in LDS
     } else {
         __syncthreads();  // zero fill complete before any data lands
@@ -444,8 +536,8 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
             Operands& cur = (ui & 1) ? o1 : o0;
             Operands& nxt = (ui & 1) ? o0 : o1;
             if constexpr (ui + 1 < U) load_unit(nxt, IntC<ui + 1>{});
-            for_each_slot([&](auto kc) {
-                if constexpr (decltype(kc)::value * U / TS == ui) {
+            if constexpr (LW == 0) for_each_slot([&](auto kc) {
+                if constexpr (decltype(kc)::value * UI / TS == ui) {
                     if constexpr (DMA) {
                         slot_fetch(kc, nxt_floats);  // chunk ch+1 (in the last round: zeros, unused)
                     } else {
@@ -462,7 +554,7 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         [&]<int... UIs>(std::integer_sequence<int, UIs...>) { (unit(IntC<UIs>{}), ...); }
         (std::make_integer_sequence<int, U>{});
 
-        if constexpr (DMA) {
+        if constexpr (DMA && LW == 0) {
             if (ragged && ch + 3 == nchunks) zero_past_share();  // the pointers now stand at chunk ch+2, the last
             if (ch + 2 == nchunks) park_slots();                 // chunk ch+1 was the last one to fetch
             __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this wave's part of chunk ch+1 is in LDS
@@ -508,18 +600,40 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
         for (int v = 0; v < 4; ++v)
             bk[m][v] = a.bias ? a.bias[min(k0 + (wk * MT + m) * 16 + 4 * kq + v, a.K - 1)] : 0.f;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    // Offsets in y of the lane's pixels (image n0 + dn, pixel pq of it); lanes past the end of the tile get -1.
+    const int kpq = a.K * a.PQ;
+    float* const y_tile = y_share + static_cast<size_t>(n0) * kpq;
+    int yb[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int d = (wp * NT + t) * 16 + j;
+        int pq = pq0 + d, dn = 0;
+        const int r = pq - a.PQ;
+        if (r >= 0) {
+            const int m = small_div(r, a.inv_PQ);
+            dn = 1 + m;
+            pq = r - __mul24(m, a.PQ);  // (m > 0 only on maps smaller than the tile)
+        }
+        yb[t] = g0 + d < g_end ? dn * kpq + pq : -1;
+    }
+    // Work-groups whose channel tile lies inside K (all but the last one along K) store without a test per channel.
+    const bool whole_k = k0 + TK <= a.K;
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
         const int kbase = k0 + (wk * MT + m) * 16 + 4 * kq;
+        float* const y_row = y_tile + static_cast<size_t>(kbase) * a.PQ;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const int g = g0 + (wp * NT + t) * 16 + j;
-            if (g >= g_end) continue;
-            const int n = a.div_PQ.div(g);
-            const int yb = n * a.K * a.PQ + (g - n * a.PQ);
+            if (yb[t] < 0) continue;
+            float* const yp = y_row + yb[t];
+            if (whole_k) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if (kbase + v < a.K) y_share[yb + (kbase + v) * a.PQ] = finish_output(acc[m][t][v], bk[m][v], a.relu);
+                for (int v = 0; v < 4; ++v) yp[static_cast<size_t>(v) * a.PQ] = finish_output(acc[m][t][v], bk[m][v], a.relu);
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (kbase + v < a.K) yp[static_cast<size_t>(v) * a.PQ] = finish_output(acc[m][t][v], bk[m][v], a.relu);
+            }
         }
     }
 }
@@ -530,11 +644,22 @@ __global__ void __launch_bounds__(64 * WK * WP * WC, OCC) conv_tap_mfma(const Ke
 
 using KernFn = void (*)(const KernelArgs);
 
-template <int VX, int VW, int DIV = 1, bool DMA = false> static KernFn instance()
+template <int VX, int VW, int DIV = 1, bool DMA = false, bool LOADER_WAVES = false> static KernFn instance()
 {
     constexpr TapVariant tv = kTapVariants[TAP_VARIANT];
     if constexpr (!tv.supports(TAP_R * TAP_S) || (VW == 1 && !tv.supports_scalar(TAP_R * TAP_S, VX))) {
         return nullptr;  // the filter block of this filter size does not fit the variant's registers
+    } else if constexpr (LOADER_WAVES) {
+        constexpr int LW = tv.loader_waves();
+        if constexpr (LW == 0) {
+            return nullptr;
+        } else {
+            // the slots of the whole work-group, dealt to the loader threads
+            constexpr int XS_ALL = (tv.xs_direct(VX) + DIV - 1) / DIV * tv.block();
+            constexpr int WS_ALL = tv.wslots_direct(TAP_R * TAP_S) * tv.block();
+            return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, (tv.block() / 64 + LW + 3) / 4,
+                                 (XS_ALL + 64 * LW - 1) / (64 * LW), (WS_ALL + 64 * LW - 1) / (64 * LW), VX, VW, true, LW>;
+        }
     } else if constexpr (DMA) {
         return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, tv.occ, (tv.xs_direct(VX) + DIV - 1) / DIV,
                              tv.wslots_direct(TAP_R * TAP_S), VX, VW, true>;
@@ -554,7 +679,18 @@ hipError_t TAP_CAT(TAP_R, TAP_S, TAP_VARIANT)(int x_vec, int w_vec, int grid, in
     const int div = tap_x_slot_divisor(tv, x_vec, w_vec, a.x_items, a.direct);
     KernFn fn = nullptr;
     int mode = -1;
-    if (a.direct && w_vec == 4 && x_vec == 4) {
+    int block = tv.block();
+    if (a.direct == 2 && w_vec == 4 && x_vec == 4) {
+        fn = div == 2 ? instance<4, 4, 2, true, true>() : instance<4, 4, 1, true, true>();
+        mode = div == 2 ? 15 : 14;
+        block += 64 * tv.loader_waves();
+    } else if (a.direct == 2 && w_vec == 4 && x_vec == 1) {
+        fn = div == 4 ? instance<1, 4, 4, true, true>() : div == 2 ? instance<1, 4, 2, true, true>() : instance<1, 4, 1, true, true>();
+        mode = div == 4 ? 18 : div == 2 ? 17 : 16;
+        block += 64 * tv.loader_waves();
+    } else if (a.direct == 2) {
+        return hipErrorInvalidValue;
+    } else if (a.direct && w_vec == 4 && x_vec == 4) {
         fn = div == 2 ? instance<4, 4, 2, true>() : instance<4, 4, 1, true>();
         mode = div == 2 ? 10 : 9;
     } else if (a.direct && w_vec == 4 && x_vec == 1) {
@@ -580,7 +716,7 @@ hipError_t TAP_CAT(TAP_R, TAP_S, TAP_VARIANT)(int x_vec, int w_vec, int grid, in
     }
     if (!fn) return hipErrorInvalidValue;
     // Kernels may use all 160 KB of a CU's LDS; the runtime wants to be told once per kernel (and device).
-    static std::atomic<int> lds_allowed[14][kMaxDevices] = {};
+    static std::atomic<int> lds_allowed[19][kMaxDevices] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
     if (lds_bytes > 48 * 1024 && lds_allowed[mode][dev].load(std::memory_order_acquire) < lds_bytes) {
@@ -589,7 +725,7 @@ hipError_t TAP_CAT(TAP_R, TAP_S, TAP_VARIANT)(int x_vec, int w_vec, int grid, in
         if (e != hipSuccess) return e;
         lds_allowed[mode][dev].store(160 * 1024, std::memory_order_release);
     }
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(tv.block()), lds_bytes, stream, a);
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(block), lds_bytes, stream, a);
     return hipGetLastError();
 }
 

@@ -97,7 +97,7 @@ def test_plans_of_the_benchmark_layers(i):
     assert (p.P, p.Q) == (c.P, c.Q)
     assert p.flops == c.flops and p.bytes == c.algorithmic_bytes
     assert p.kernel != binding.CONV_KERNEL_GENERIC          # 1x1, 3x3 and 5x5 have specialised kernels
-    assert p.lds_bytes <= 160 * 1024 and p.grid >= 1 and p.block in (64, 128, 256, 512)
+    assert p.lds_bytes <= 160 * 1024 and p.grid >= 1 and p.block in (64, 128, 256, 512, 768)
     tiles_k = -(-c.K // p.tile_k)
     tiles_p = -(-(c.N * c.P * c.Q) // p.tile_pix)
     assert p.grid == tiles_k * tiles_p
@@ -131,11 +131,11 @@ def test_plans_of_the_sweep_grid_are_well_formed():
         families.add(p.kernel)
         assert p.workspace_bytes == 0 and (p.P, p.Q) == (s.P, s.Q)
         assert p.flops == s.flops and p.bytes == s.algorithmic_bytes
-        assert 1 <= p.grid < 2 ** 31 and p.block in (64, 128, 256, 512, 1024) and 0 <= p.lds_bytes <= 160 * 1024
+        assert 1 <= p.grid < 2 ** 31 and p.block in (64, 128, 256, 512, 768, 1024) and 0 <= p.lds_bytes <= 160 * 1024
         assert p.kernel in (tap, pw, panel)                      # every sweep layer has a specialised kernel
         assert 0 <= p.variant < binding.conv_variant_count(p.kernel)
         tile_k, cap, block = binding.conv_variant_info(p.kernel, p.variant)
-        assert p.block == block and p.tile_k == tile_k
+        assert p.block == block + (256 if p.loader == 3 else 0) and p.tile_k == tile_k     # (four loader waves)
         total = s.N * s.P * s.Q
         if p.kernel == tap:
             assert 1 <= p.tile_pix <= cap
@@ -243,7 +243,8 @@ def test_tap_plans_name_their_loader():
                        ((1, 256, 13, 13, 384, 3, 3, 1, 1), registers),   # odd width, 0.3 GFLOP
                        ((8, 256, 13, 13, 384, 3, 3, 1, 1), direct),      # odd width, 2.4 GFLOP
                        ((32, 192, 7, 7, 384, 3, 3, 1, 1), registers),    # 7x7 maps: more padding than data in LDS
-                       ((32, 512, 14, 14, 512, 3, 3, 1, 1), registers),  # rows of dwordx2
+                       ((32, 512, 14, 14, 512, 3, 3, 1, 1), binding.CONV_LOADER_DIRECT_WAVES),  # rows of dwordx2, deep: loader waves
+                       ((32, 64, 14, 14, 64, 3, 3, 1, 1), registers),    # rows of dwordx2, four chunks
                        ((8, 3, 224, 224, 64, 3, 3, 1, 1), registers)]:   # 3 input channels
         plan = binding.conv_fwd_plan(*dims)
         assert plan.kernel == tap and plan.loader == want, (dims, plan.as_dict())
@@ -254,10 +255,18 @@ def test_tap_plans_name_their_loader():
                 assert e.code == -6 and loader == direct and (dims[1] % 4 != 0 or dims[3] % 4 == 2), (dims, loader)
                 continue
             assert other.loader == loader and other.grid == plan.grid
+            assert other.block == plan.block - (256 if plan.loader == 3 else 0)
             assert other.lds_bytes <= 160 * 1024
     assert binding.conv_fwd_plan(32, 256, 56, 56, 64, 1, 1, 0, 0).loader == 0      # panel kernel: not a tap plan
     with pytest.raises(binding.ConvError):
-        binding.conv_fwd_plan_request(8, 64, 56, 56, 64, 3, 3, 1, 1, tap, 7, 0, loader=3)
+        binding.conv_fwd_plan_request(8, 64, 56, 56, 64, 3, 3, 1, 1, tap, 7, 0, loader=4)
+    # loader waves: a build of the eight-wave tile shapes only; four more waves in the work-group, rows of dwordx2 as dwords
+    waves, _ = binding.conv_fwd_plan_request(32, 512, 14, 14, 512, 3, 3, 1, 1, tap, 6, 196, loader=binding.CONV_LOADER_DIRECT_WAVES)
+    assert waves.loader == 3 and waves.block == 768 and waves.x_vec == 1 and waves.grid == 256
+    with pytest.raises(binding.ConvError):
+        binding.conv_fwd_plan_request(32, 512, 14, 14, 512, 3, 3, 1, 1, tap, 0, 196, loader=3)       # four waves: no such build
+    with pytest.raises(binding.ConvError):
+        binding.conv_fwd_plan_request(8, 6, 14, 14, 64, 3, 3, 1, 1, tap, 6, 196, loader=3)           # dword filter rows
 
 
 # Which (filter size, tile shape) pairs of the tap family are built. Written out by hand from the rule in the

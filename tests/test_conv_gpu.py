@@ -107,10 +107,10 @@ DIRECT = [
     S("d3x3_w4_c68", 3, 68, 5, 4, 70, 3, 3, 1, 1),
     S("d1x1_w20", 2, 52, 3, 20, 35, 1, 1, 0, 0),
 ]
-REGISTERS, DIRECT_LOADS = 1, 2
+REGISTERS, DIRECT_LOADS, LOADER_WAVES = 1, 2, 3
 
 
-@pytest.mark.parametrize("loader", [REGISTERS, DIRECT_LOADS])
+@pytest.mark.parametrize("loader", [REGISTERS, DIRECT_LOADS, LOADER_WAVES])
 @pytest.mark.parametrize("variant", range(30))
 @pytest.mark.parametrize("shape", SMALL + DIRECT, ids=lambda s: s.name)
 def test_every_tap_variant_matches_oracle(shape, variant, loader):
@@ -142,7 +142,8 @@ def test_direct_loader_runs_where_it_should():
     assert binding.conv_fwd_plan(8, 64, 56, 56, 64, 3, 3, 1, 1).loader == DIRECT_LOADS
     assert binding.conv_fwd_plan(1, 256, 13, 13, 384, 3, 3, 1, 1).loader == REGISTERS
     assert binding.conv_fwd_plan(32, 256, 13, 13, 384, 3, 3, 1, 1).loader == DIRECT_LOADS
-    assert binding.conv_fwd_plan(32, 512, 14, 14, 512, 3, 3, 1, 1).loader == REGISTERS
+    assert binding.conv_fwd_plan(32, 512, 14, 14, 512, 3, 3, 1, 1).loader == LOADER_WAVES   # deep, rows of dwordx2
+    assert binding.conv_fwd_plan(32, 64, 14, 14, 64, 3, 3, 1, 1).loader == REGISTERS
     assert binding.conv_fwd_plan(8, 3, 224, 224, 64, 3, 3, 1, 1).loader == REGISTERS   # C = 3: dword filter rows
 
 
@@ -347,7 +348,7 @@ def _run_split(shape, variant, c_splits, tile_pix=0, bias=False, relu=False, exa
     return plan, yd
 
 
-@pytest.mark.parametrize("loader", [REGISTERS, DIRECT_LOADS])
+@pytest.mark.parametrize("loader", [REGISTERS, DIRECT_LOADS, LOADER_WAVES])
 @pytest.mark.parametrize("c_splits", [2, 3, 5, 16])
 @pytest.mark.parametrize("variant", [2, 5, 13, 17, 20, 7])
 @pytest.mark.parametrize("shape", SPLIT_SHAPES, ids=lambda s: s.name)
@@ -752,7 +753,7 @@ def test_both_loaders_on_random_small_layers(shape):
     for variant in rng.sample(range(binding.conv_variant_count(TAP)), 6):
         cap = binding.conv_variant_info(TAP, variant)[1]
         tile_pix = rng.choice([0, rng.randint(1, cap)])
-        for loader in (REGISTERS, DIRECT_LOADS):
+        for loader in (REGISTERS, DIRECT_LOADS, LOADER_WAVES):
             try:
                 _run(shape, kernel=TAP, variant=variant, tile_pix=tile_pix, loader=loader)
                 _run_split(shape, variant, rng.choice([2, 3, 4]), tile_pix=tile_pix, loader=loader)
@@ -849,6 +850,25 @@ def test_every_built_tap_instance_runs_on_some_layer():
                     assert plan.variant == v and plan.loader == loader
                     ran[loader].add((R, S_, v))
                     break
+    # the builds with loader waves: the five tile shapes of eight waves at two per SIMD, for every filter size they take
+    waves_ran = set()
+    for (R, S_), variants in sorted(BUILT_TAP_INSTANCES.items()):
+        for v in sorted(variants & {6, 7, 12, 19, 21}):
+            for N, C, H, W, tile in probes:
+                dims = (N, C, H, W, 20, R, S_, R // 2, S_ // 2)
+                try:
+                    binding.conv_fwd_plan_request(*dims, TAP, v, tile, loader=LOADER_WAVES)
+                except binding.ConvError as e:
+                    assert e.code == -6
+                    continue
+                plan, _ = _run(S(f"inst_{R}x{S_}_v{v}_l3_h{H}", *dims), kernel=TAP, variant=v, tile_pix=tile, loader=LOADER_WAVES)
+                assert plan.loader == LOADER_WAVES and plan.block == 768
+                waves_ran.add((R, S_, v))
+                break
+    assert waves_ran >= {(R, S_, v) for (R, S_) in ((1, 1), (3, 3)) for v in (6, 7, 12, 19, 21)} | {(5, 5, 12)}, sorted(waves_ran)
+    for v in (0, 2, 5, 13, 22):                                     # other tile shapes have no such build
+        with pytest.raises(binding.ConvError):
+            binding.conv_fwd_plan_request(2, 8, 8, 8, 20, 3, 3, 1, 1, TAP, v, 16, loader=LOADER_WAVES)
     want = {(R, S_, v) for (R, S_), variants in BUILT_TAP_INSTANCES.items() for v in variants}
     assert ran[REGISTERS] == want, sorted(want - ran[REGISTERS])
     assert ran[DIRECT_LOADS] == reachable_direct
