@@ -214,6 +214,17 @@ def probes(torch, binding):
     torch.cuda.synchronize()
     out["copy_read_plus_write_gbs"] = 10 * 2 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
     assert bool((dst[:: 1 << 20] == 1).all())
+    # What one launch costs when the kernel has nothing to do (a 16-byte copy by one work-group), back to back on the
+    # library's stream from this same Python loop: the floor under every figure of the batch-1 layers.
+    for _ in range(50):
+        lib.conv_probe_copy(src.data_ptr(), dst.data_ptr(), 16)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(2000):
+        lib.conv_probe_copy(src.data_ptr(), dst.data_ptr(), 16)
+    e1.record()
+    torch.cuda.synchronize()
+    out["empty_launch_us"] = e0.elapsed_time(e1) / 2000 * 1e3
     return out
 
 
@@ -446,6 +457,36 @@ def layer_record(layer, torch, binding, oracle, measured, warmup, auto_steps):
     return rec
 
 
+# Layers with a short reduction (C*R*S of 27 ... 400): is the matrix unit the right tool there?
+SHORT_REDUCTIONS = (
+    ("cfg1: 3x3 C16 14x14 K16 N1 (C*R*S = 144)", (1, 16, 14, 14, 16, 3, 3, 1, 1)),
+    ("first layer: 3x3 C3 224x224 K64 N1 (C*R*S = 27)", (1, 3, 224, 224, 64, 3, 3, 1, 1)),
+    ("first layer: 3x3 C3 224x224 K64 N8 (C*R*S = 27)", (8, 3, 224, 224, 64, 3, 3, 1, 1)),
+    ("3x3 C16 224x224 K16 N1 (C*R*S = 144)", (1, 16, 224, 224, 16, 3, 3, 1, 1)),
+    ("3x3 C16 56x56 K16 N8 (C*R*S = 144)", (8, 16, 56, 56, 16, 3, 3, 1, 1)),
+    ("5x5 C16 28x28 K32 N1 (C*R*S = 400)", (1, 16, 28, 28, 32, 5, 5, 2, 2)),
+)
+
+
+def short_reductions(torch, binding, inputs, oracle):
+    """The library's two ways of multiplying on layers with a short reduction: the default mapping (fp32 MFMA in the
+    specialised kernels) against the generic kernel (one output per thread, plain vector fp32 FMA)."""
+    rows = []
+    for name, dims in SHORT_REDUCTIONS:
+        layer = Layer(inputs.ConvShape(name, *dims, "u01", "he", 31, 32), torch, binding, inputs, max_sets=256)
+        rec = {"layer": name, "dims": list(dims), "crs": dims[1] * dims[5] * dims[6],
+               "default_plan": [layer.plan.kernel, layer.plan.variant, layer.plan.tile_pix, layer.plan.loader]}
+        for label, plan in (("mfma", None), ("valu", binding.ConvPlan())):      # a zeroed request names the generic kernel
+            layer.use_plan(plan)
+            _, e_ms = layer.measure(500, 20)
+            rec[label + "_us"] = e_ms * 1e3
+            rec[label + "_parity_ok"] = layer.parity_sample(oracle, 128)["ok"]
+        rows.append(rec)
+        del layer
+        torch.cuda.empty_cache()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -466,6 +507,8 @@ def main():
                     help="with --sweep: also time each layer with the mapping conv_fwd_find measures to be fastest")
     ap.add_argument("--holdout", type=int, default=None, metavar="SEED",
                     help="also compare default and measured-best mappings on 40 random layers off the sweep grid")
+    ap.add_argument("--short-reductions", action="store_true",
+                    help="also time MFMA against plain vector FMA (the generic kernel) on layers with a short reduction")
     ap.add_argument("--split-c", action="store_true",
                     help="also compare the channel-splitting mode with the default on the layers its planner splits")
     ns = ap.parse_args()
@@ -562,6 +605,8 @@ def main():
         out["holdout"] = holdout(torch, binding, inputs, oracle, ns.holdout)
     if ns.split_c:
         out["split_c"] = split_c_layers(torch, binding, inputs, oracle)
+    if ns.short_reductions:
+        out["short_reductions"] = short_reductions(torch, binding, inputs, oracle)
     if not ns.no_cpu:
         others = [inputs.config(i) for i in range(1, 5)] if not ns.shape and not ns.no_layers else []
         out["cpu_baseline"] = cpu_baseline(oracle, inputs, s, others=others)

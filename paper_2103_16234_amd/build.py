@@ -63,14 +63,15 @@ def _jobs():
 
 
 def _newest_dep() -> float:
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".h", ".hip", ".cpp"))]
+    """What every translation unit depends on: the headers and this script (its own source comes on top)."""
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
     deps += [os.path.join(HERE, "..", "include", "convfwd.h"), os.path.abspath(__file__)]
     return max(os.path.getmtime(d) for d in deps)
 
 
 def _compile(job, force, stamp):
     obj, src, extra = job
-    if not force and os.path.exists(obj) and os.path.getmtime(obj) >= stamp:
+    if not force and os.path.exists(obj) and os.path.getmtime(obj) >= max(stamp, os.path.getmtime(src)):
         return obj, 0, ""
     cmd = [HIPCC] + COMMON + extra + ["-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)

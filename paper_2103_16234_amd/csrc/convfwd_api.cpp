@@ -90,8 +90,9 @@ int validate(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad
     return CONV_OK;
 }
 
-inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
-inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+// (in 64 bits: a dimension may be close to 2^31)
+inline int ceil_div(int a, int b) { return (int)(((int64_t)a + b - 1) / b); }
+inline int round_up(int v, int m) { return (int)std::min<int64_t>(((int64_t)v + m - 1) / m * m, INT32_MAX); }
 
 int tap_rs_index(const Shape& s) { return tap_size_index(s.R, s.S); }
 
@@ -400,8 +401,18 @@ int pick_pointwise(const Shape& s)
     if (groups32 >= 224 && groups32 <= 288 && steps >= 16) return 3;  // {MT 2, WC 8}
     // {1, 4} or {1, 8} shares (16 shares, 1024 threads, measured 25 % slower even on 512..832 channels); with three or
     // more steps per wave the twin that keeps four steps of loads in flight (3-7 % on 512..1024-channel N=1 layers)
-    if (groups * 4 >= 1024 || steps <= 8) return steps >= 12 ? 15 : 0;
-    return steps >= 24 ? 14 : 1;
+    const int pick = (groups * 4 >= 1024 || steps <= 8) ? (steps >= 12 ? 15 : 0) : (steps >= 24 ? 14 : 1);
+    // Every wave runs the same multiple of (channel shares x steps in flight) steps: where that rounds the layer's steps up
+    // by more than 40 % (640 channels = 40 steps on the shape of 8 shares x 4 in flight: 64), the shape among these four
+    // that pads least runs 12-25 % faster (timed on batch 1..4 layers with 320 and 640 channels)
+    auto padded = [&](int v) { return round_up(steps, kPointwiseVariants[v].WC * kPointwiseVariants[v].PD); };
+    if (padded(pick) * 10 > steps * 14) {
+        int best = pick;
+        for (int v : {14, 1, 15, 0})
+            if (padded(v) < padded(best)) best = v;
+        return best;
+    }
+    return pick;
 }
 
 // Panel kernel or not, from sweeps over batched 1x1 layers: it wins once there are about 700 units of
@@ -581,7 +592,12 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_pl
         // to share between waves: the register-streaming shape whose four waves each take 64 pixels and all channels
         // beats the panel kernel by 10-20 % there (measured on 64 x 48 x 14 x 14 -> 64, 4 x 16 x 80 x 80 -> 48,
         // 1 x 32 x 112 x 112 -> 64, ...).
-        const bool small_thin = s.C <= 80 && (s.H * s.W) % 4 == 0 && 2.0 * s.N * s.H * s.W * s.C * s.K <= 1.5e8;
+        // (with 32 channels or fewer it also wins on maps whose pixels move as dwords, up to ~300 MFLOP, as long as its
+        // 256-pixel tiles waste less than 30 % of an image: 64 x 24 x 35 x 35 -> 48: 12.7 -> 9.6 us)
+        const int64_t hw = (int64_t)s.H * s.W;
+        const double pw_flops = 2.0 * s.N * s.H * s.W * s.C * s.K;
+        const bool small_thin = (s.C <= 80 && hw % 4 == 0 && pw_flops <= 1.5e8) ||
+                                (s.C <= 32 && pw_flops <= 3e8 && (hw + 255) / 256 * 256 * 10 <= hw * 13);
         if (small_thin && resolve_pointwise(s, 8, x_cap, w_cap, y_cap, p, a)) return CONV_OK;
         if (pv >= 0 && resolve_panel(s, pv, 0, x_cap, w_cap, y_cap, p, a)) return CONV_OK;
         if (resolve_pointwise(s, pick_pointwise(s), x_cap, w_cap, y_cap, p, a)) return CONV_OK;

@@ -169,15 +169,15 @@ def config(i: int) -> ConvShape:
 # Second workload: a product grid of synthetic layer shapes inside the ranges of the evaluation sweep (Section 4,
 # Table 1: batch 1..256, square maps 7..224, 16..2048 filters, 1x1 / 3x3 / 5x5 filters with "same" padding). It is
 # a grid over those ranges, not any network's layer list; channel counts shrink as maps grow, as they do in CNNs.
-_SWEEP_BATCHES = (1, 8, 32, 128)
+_SWEEP_BATCHES = (1, 8, 16, 32, 64, 128, 256)
 _SWEEP_CHANNELS = {   # map size -> (C, K) pairs, per filter size
     1: {7: ((512, 512), (832, 256), (1024, 2048)), 13: ((256, 384), (384, 384)), 14: ((256, 256), (512, 512), (256, 1024)),
         27: ((64, 256), (96, 256)), 28: ((128, 128), (192, 256), (512, 128)), 56: ((64, 64), (256, 64), (64, 256)),
         112: ((32, 64), (64, 128))},
-    3: {7: ((512, 512), (192, 384)), 13: ((256, 384), (384, 384)), 14: ((256, 256), (512, 512)),
+    3: {7: ((512, 512), (192, 384), (512, 2048)), 13: ((256, 384), (384, 384)), 14: ((256, 256), (512, 512), (512, 1024)),
         27: ((64, 192), (96, 256)), 28: ((128, 128), (128, 256)), 56: ((64, 64), (64, 192)),
         112: ((32, 64), (64, 128)), 224: ((3, 64), (16, 16), (64, 64))},
-    5: {7: ((48, 128), (32, 128)), 13: ((32, 96), (48, 128)), 14: ((16, 48), (32, 96)), 27: ((48, 128), (96, 256)),
+    5: {7: ((48, 128), (32, 128), (64, 512)), 13: ((32, 96), (48, 128)), 14: ((16, 48), (32, 96)), 27: ((48, 128), (96, 256)),
         28: ((16, 32), (32, 96), (48, 128))},
 }
 

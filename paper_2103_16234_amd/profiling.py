@@ -5,6 +5,10 @@ measured HBM-side traffic that bench.py reports as `roofline.traffic`.
                                                             #                                  + measured_traffic.json
     python -m paper_2103_16234_amd.profiling counters DIR   # SQ passes -> profiles/conv_kernels_sq_counters.txt
     python -m paper_2103_16234_amd.profiling stats    DIR   # kernel trace -> profiles/bench_five_layers_kernel_stats.txt
+    python -m paper_2103_16234_amd.profiling split_c | paper_shapes | short_reductions  FILE   # what bench.py printed with the
+                                                            # option of that name -> the summary of that measurement
+    python -m paper_2103_16234_amd.profiling sweep FILE...  # bench.py --sweep outputs (one, or one per filter size)
+    python -m paper_2103_16234_amd.profiling holdout FILE...   # one bench.py --holdout SEED output per seed
 
 DIR holds, per layer tag T (cfg1 .. cfg5 for the benchmark layers, any other name for a --shape run):
     T_fetch/, T_write/, T_sq/   output directories of `rocprofv3 --pmc ... --output-format csv -d DIR/T_pass -o pmc -- python3 bench.py ...`
@@ -87,7 +91,11 @@ def _tags(directory: str, which: str):
 
 def _layer_line(b):
     d = b["roofline"]
-    return b["config"]["workload"].split(":")[0], d["algorithmic_bytes"], d["algorithmic_flops"], b["config"]["plan"]
+    name = b["config"]["workload"].split(":")[0]
+    if name.startswith("shape_"):      # a --shape run: say what the layer is
+        n, c, h, w, k, r, s_, _, _ = (int(v) for v in _shape_arg(b).split(","))
+        name = f"{r}x{s_} N{n} C{c} {h}x{w} K{k}"
+    return name, d["algorithmic_bytes"], d["algorithmic_flops"], b["config"]["plan"]
 
 
 def _shape_arg(b):
@@ -215,7 +223,7 @@ def stats(directory: str):
         if "convfwd" in r["Name"]:
             name = r["Name"].replace("void convfwd::", "").replace("(convfwd::KernelArgs)", "")
             lines.append(f"{name[:78]:<78} {r['Calls']:>6} {float(r['AverageNs']):>10.0f} {r['MinNs']:>9} {r['MaxNs']:>9} {float(r['StdDev']):>8.0f}")
-    lines += ["", "template arguments of conv_tap_mfma: <R, S, MT, NT, WK, WP, WC, GPC, OCC, XS, WS, VX, VW, direct loader>", "",
+    lines += ["", "template arguments of conv_tap_mfma: <R, S, MT, NT, WK, WP, WC, GPC, OCC, XS, WS, VX, VW, direct loader, loader waves>", "",
               "headline of the untraced run of the same command (bench.py's own HIP events):",
               f"  {b['config']['workload']}",
               f"  kernel {b['roofline']['kernel']}: {b['roofline']['kernel_us']:.2f} us per launch over {b['steps']} launches -> "
@@ -236,12 +244,162 @@ def stats(directory: str):
     print("\n".join(lines))
 
 
+FAMILY = {0: "generic", 1: "tap", 2: "pointwise", 3: "panel"}
+LOADER = {1: " R", 2: " D", 3: " W"}
+PLAN_NOTE = ("plan: family, variant, tile_pix (panel: work-groups per channel tile), grid, block, loader of the tap family (R: through the\n"
+             "registers, D: direct to LDS, W: direct by loader waves).")
+
+
+def _plan(p):
+    return f"{FAMILY[p[0]]} v{p[1]} {p[2]} g{p[3]} b{p[4]}" + (LOADER.get(p[5], "") if len(p) > 5 else "")
+
+
+def _write(name, lines):
+    os.makedirs(PROFILES, exist_ok=True)
+    open(os.path.join(PROFILES, name), "w").write("\n".join(lines) + "\n")
+    print("\n".join(lines[-8:]))
+
+
+def _geomean(values):
+    import math
+    values = list(values)
+    return math.exp(sum(math.log(v) for v in values) / len(values))
+
+
+def sweep(paths):
+    """bench.py --no-layers --no-cpu --sweep [SUBSTR] [--find] > path; several outputs (one per filter size) are joined"""
+    import statistics
+    rows = [r for p in paths for r in _bench_json(p)["sweep"]]
+    found = all("found_us" in r for r in rows)
+    lines = [f"Second workload: the synthetic shape sweep ({len(rows)} layers inside the ranges of the paper's evaluation, Section 4 / Table 1:",
+             "batch 1, 8, 16, 32, 64, 128, 256; maps 7..224; 16..2048 filters; 1x1 / 3x3 / 5x5 with \"same\" padding; shapes from",
+             "paper_2103_16234_amd.inputs.sweep_shapes, tensors of at most 2^25 elements), HIP-event time per launch over rotating buffer",
+             "sets on one MI355X, each layer spot-checked against the oracle on 128 outputs."
+             + (" Two mappings per layer: the planner's default," if found else ""),
+             ("and the one conv_fwd_find measures to be fastest (cold-cache timing with a 512 MiB flush buffer)." if found else
+              "The planner's default mapping."),
+             "Command (from the repository root):",
+             "  python3 bench.py --no-layers --no-cpu --sweep" + (" --find" if found else "") + " > gpurun_out/prof/sweep.json"
+             + ("      (run as three: --sweep sweep_1x1, sweep_3x3, sweep_5x5)" if len(paths) > 1 else ""),
+             "bound/frac: the slower of the two roofline times (157.3 TFLOP/s fp32 MFMA, 8 TB/s HBM) over the measured time.", PLAN_NOTE, ""]
+    head = f"{'layer':<36}{'us':>8} {'TFLOP/s':>8} {'GB/s':>7} bound   frac  {'default plan':<30}"
+    lines.append(head + (" |  found us   frac  found plan" if found else ""))
+    for r in rows:
+        line = (f"{r['shape']:<36}{r['kernel_us']:8.1f} {r['tflops']:8.2f} {r['gbs']:7.0f} {r['bound']:<5} {r['frac']:6.3f}  "
+                f"{_plan(r['plan']):<30}")
+        if found:
+            line += f" | {r['found_us']:9.1f} {r['found_frac']:6.3f}  {_plan(r['found_plan'])}"
+        lines.append(line)
+    lines.append("")
+    ok = True
+    for f in ("1x1", "3x3", "5x5"):
+        rs = [r for r in rows if f"_{f}_" in r["shape"]]
+        big = [r for r in rs if int(r["shape"].split("_n")[1].split("_")[0]) >= 32]
+        text = (f"{f}: {len(rs)} layers; default plans: median fraction {statistics.median(r['frac'] for r in rs):.3f}, batch >= 32: "
+                f"median {statistics.median(r['frac'] for r in big):.3f}, best {max(r['frac'] for r in big):.3f}")
+        if found:
+            gm = _geomean(r["kernel_us"] / min(r["found_us"], r["kernel_us"]) for r in rs)
+            text += (f"; found plans: batch >= 32 median {statistics.median(max(r['found_frac'], r['frac']) for r in big):.3f}, best "
+                     f"{max(r['found_frac'] for r in big):.3f}; default / found time, geometric mean {gm:.3f}")
+        lines.append(text)
+        ok &= all(r["parity_ok"] and r.get("found_parity_ok", True) for r in rs)
+    lines.append(f"All {len(rows)} layers within tolerance on the sampled outputs." if ok else "PARITY FAILURES")
+    _write("synthetic_shape_sweep.txt", lines)
+
+
+def holdout(paths):
+    """bench.py --no-cpu --no-layers --holdout SEED > path, one path per seed"""
+    runs = [_bench_json(p)["holdout"] for p in paths]
+    lines = ["Planner check on layers it was not fitted on: 40 random layers per seed inside the paper's ranges but off the synthetic",
+             "sweep grid (batch 1, 2, 4, 16, 64; 16...640 channels; maps 7...112; 24...768 filters; 1x1 / 3x3 / 5x5), each timed on one",
+             "MI355X with the default mapping (conv_fwd) and with the mapping conv_fwd_find measures to be fastest (cold-cache timing),",
+             "HIP events over rotating buffer sets, the found mapping spot-checked against the oracle on 64 outputs.",
+             "Commands (from the repository root), one per seed:",
+             "  python3 bench.py --no-cpu --no-layers --holdout SEED > gpurun_out/prof/holdout_SEED.json      (SEED = "
+             + ", ".join(str(h["seed"]) for h in runs) + ")",
+             "frac: fraction of the binding roofline (157.3 TFLOP/s fp32 MFMA or 8 TB/s HBM) with the default mapping.", PLAN_NOTE, ""]
+    for h in runs:
+        ok = all(r["found_parity_ok"] for r in h["layers"])
+        lines.append(f"seed {h['seed']}: default / found time, geometric mean {h['default_over_found_geomean']:.3f}, worst "
+                     f"{h['default_over_found_worst']:.2f}; all found mappings within tolerance: {ok}")
+        lines.append(f"  {'layer':<34} {'default us':>10} {'frac':>6}  {'default plan':<30} {'found us':>9}  found plan")
+        for r in h["layers"]:
+            lines.append(f"  {r['shape']:<34} {r['default_us']:>10.1f} {r['frac']:>6.3f}  {_plan(r['default_plan']):<30} {r['found_us']:>9.1f}  "
+                         f"{_plan(r['found_plan'])}")
+        lines.append("")
+    _write("holdout_layers_default_vs_found.txt", lines)
+
+
+def split_c(path: str):
+    """bench.py --no-layers --no-cpu --split-c > path"""
+    rows = _bench_json(path)["split_c"]
+    lines = ["Channel splitting across work-groups (conv_fwd_split_c: the tap kernel writes one partial output per channel share into the",
+             "caller's workspace, a second kernel adds the shares in order and applies the epilogue) against the single-kernel default",
+             "(conv_fwd), on every layer of the synthetic shape grid and of the paper's profiled shapes (Tables 3-5) for which the splitting",
+             "planner (conv_fwd_plan_split_c) asks for more than one share. One MI355X, HIP-event time per call over 400 calls on rotating",
+             "buffer sets, both launches of the split mode included; each layer spot-checked against the oracle on 128 outputs.",
+             "Command (from the repository root):", "  python3 bench.py --no-layers --no-cpu --split-c > gpurun_out/prof/split_c.json",
+             "plan: family, variant, tile_pix, grid (work-groups, shares included), block, loader (R / D / W as in the sweep summary).", "",
+             f"{'layer':<32} {'default us':>10}  {'default plan':<28} {'split us':>8}  {'split plan':<28} {'shares':>6} {'workspace':>10} {'speed-up':>8} parity"]
+    for r in rows:
+        lines.append(f"{r['shape']:<32} {r['default_us']:>10.1f}  {_plan(r['default_plan']):<28} {r['split_us']:>8.1f}  {_plan(r['split_plan']):<28} "
+                     f"{r['c_splits']:>6} {r['workspace_bytes'] / 1e6:>8.1f}MB {r['default_us'] / r['split_us']:>7.2f}x "
+                     f"{'ok' if r['split_parity_ok'] else 'FAIL'}")
+    if rows:
+        ups = [r["default_us"] / r["split_us"] for r in rows]
+        lines += ["", f"{len(rows)} layers split; speed-up over the default: geometric mean {_geomean(ups):.2f}x, range {min(ups):.2f}x .. {max(ups):.2f}x."]
+    _write("channel_splitting_layers.txt", lines)
+
+
+def paper_shapes(path: str):
+    """bench.py --no-layers --no-cpu --paper-shapes > path"""
+    rows = _bench_json(path)["paper_shapes"]
+    lines = ["Fused kernels vs. the opt-in two-stage scheme on the seven shapes of the paper's kernel-profile tables (Tables 3-5; batch 1",
+             "except 5x5 B), HIP-event time per call over rotating buffer sets, one MI355X. Command (from the repository root):",
+             "  python3 bench.py --no-layers --no-cpu --paper-shapes > gpurun_out/prof/paper_shapes.json",
+             "The last two columns are the paper's own figures for its kernels and for the best vendor-library algorithm on a",
+             "V100: context from another machine, not a target.", "",
+             f"{'shape':<8} {'N,C,H,W,K,R,S,pad':<26} {'fused us':>9} {'plan':>14} {'two-stage us':>13} {'paper us':>9} {'vendor us':>10}  parity"]
+    for r in rows:
+        d = r["dims"]
+        dims = ",".join(str(d[k]) for k in ("N", "C", "H", "W", "K", "R", "S", "pad_h"))
+        p = r["fused_plan"]
+        lines.append(f"{r['shape']:<8} {dims:<26} {r['fused_us']:>9.2f} {'k%d v%d g%d' % (p['kernel'], p['variant'], p['grid']):>14} "
+                     f"{r['two_stage_us']:>13.2f} {r['paper_two_stage_us_v100']:>9.2f} {r['paper_best_vendor_us_v100']:>10.2f}  "
+                     f"{r['fused_parity_ok'] and r['two_stage_parity_ok']}")
+    lines += ["", "plan: k1 = tap kernel, k2 = pointwise kernel, k3 = panel kernel, v = variant index, g = work-groups"]
+    _write("paper_profile_shapes_fused_vs_two_stage.txt", lines)
+
+
+def short_reductions(path: str):
+    """bench.py --no-layers --no-cpu --short-reductions > path"""
+    rows = _bench_json(path)["short_reductions"]
+    lines = ["fp32 MFMA against plain vector fp32 FMA on layers with a short reduction (C*R*S of 27 ... 400), one MI355X, HIP-event time per",
+             "launch over 500 launches on rotating buffer sets; both checked against the oracle on 128 outputs.",
+             "  mfma: the library's default mapping (tap family: LDS halo tile and filter block, v_mfma_f32_16x16x4_f32)",
+             "  valu: the generic kernel (one output per thread, v_fma_f32, no LDS; the only plain-FMA kernel of the library - it has no",
+             "        register blocking, so this is vector FMA as the definition gives it, not the best a vector-FMA kernel could do)",
+             "Command (from the repository root):",
+             "  python3 bench.py --no-layers --no-cpu --short-reductions > gpurun_out/prof/short.json", "",
+             f"{'layer':<52} {'C*R*S':>6} {'mfma us':>8} {'valu us':>8} {'valu/mfma':>9}  default plan            parity"]
+    for r in rows:
+        p = r["default_plan"]
+        lines.append(f"{r['layer']:<52} {r['crs']:>6} {r['mfma_us']:>8.2f} {r['valu_us']:>8.2f} {r['valu_us'] / r['mfma_us']:>9.2f}  "
+                     f"{FAMILY[p[0]]} v{p[1]} tile {p[2]}{LOADER.get(p[3], ''):<3}   {r['mfma_parity_ok'] and r['valu_parity_ok']}")
+    _write("short_reductions_mfma_vs_valu.txt", lines)
+
+
 if __name__ == "__main__":
-    if len(sys.argv) != 3 or sys.argv[1] not in ("traffic", "counters", "stats", "commands"):
+    one = {"traffic": traffic, "counters": counters, "stats": stats, "split_c": split_c, "paper_shapes": paper_shapes,
+           "short_reductions": short_reductions}
+    if len(sys.argv) >= 3 and sys.argv[1] in ("holdout", "sweep"):
+        (holdout if sys.argv[1] == "holdout" else sweep)(sys.argv[2:])
+        sys.exit(0)
+    if len(sys.argv) != 3 or sys.argv[1] not in tuple(one) + ("commands",):
         sys.exit(__doc__)
     if sys.argv[1] == "commands":     # the counter runs of one layer tag[=shape], one per line
         tag, _, shape = sys.argv[2].partition("=")
         for which in PASSES:
             print(command(tag, shape or None, which))
     else:
-        {"traffic": traffic, "counters": counters, "stats": stats}[sys.argv[1]](sys.argv[2])
+        one[sys.argv[1]](sys.argv[2])

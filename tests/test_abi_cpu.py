@@ -123,7 +123,7 @@ def test_plans_cover_odd_shapes():
 
 
 def test_plans_of_the_sweep_grid_are_well_formed():
-    """Host-only planner over the 169 synthetic layers: every plan is a launch the kernels accept."""
+    """Host-only planner over the synthetic layers of the sweep grid: every plan is a launch the kernels accept."""
     tap, pw, panel = binding.CONV_KERNEL_TAP, binding.CONV_KERNEL_POINTWISE, binding.CONV_KERNEL_PANEL
     families = set()
     for s in inputs.sweep_shapes():
