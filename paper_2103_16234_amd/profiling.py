@@ -206,6 +206,37 @@ def counters(directory: str):
     os.makedirs(PROFILES, exist_ok=True)
     open(os.path.join(PROFILES, "conv_kernels_sq_counters.txt"), "w").write("\n".join(lines) + "\n")
     print("\n".join(lines))
+    _mfma_utilisation(body, [command(t, None, "sq") for t in tags if t in ("cfg3", "cfg5")])
+
+
+# The same two figures as measured with the kernels of commit 9ec1455 (registers-or-direct loaders only, per-lane integer division in the
+# prologue): layer -> (mapping, MFMA busy under the profiler, MFMA busy at the benchmark duration, benchmark us).
+EARLIER_MFMA = {
+    "cfg3_3x3_c64_56": ("variant 7 tile_pix 112 loader 2", 0.375, 0.495, 23.75),
+    "cfg5_3x3_c512_14": ("variant 6 tile_pix 196 loader 1", 0.760, 0.781, 255.58),
+}
+
+
+def _mfma_utilisation(body, commands):
+    lines = ["Matrix-unit utilisation of the compute-bound benchmark layers (rocprofv3 --pmc, averages per dispatch of the convolution kernel)",
+             "commands:"] + ["  " + c for c in commands]
+    lines += ["", "MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE / 8 x 1024 SIMDs); a v_mfma_f32_16x16x4_f32 holds its SIMD's matrix unit for",
+              "32 cycles. 'at bench' divides the same busy cycles by the kernel's duration in the unprofiled run (HIP events, 2.4 GHz); counter",
+              "collection slows the short kernel down. useful = the layer's flops over 2048 per issued MFMA.", "",
+              f"{'layer':<20} {'kernels':<10} {'mapping':<34} {'busy':>6} {'at bench':>9} {'useful':>7} {'bench us':>9}"]
+    for name, c, flops, plan, us in body:
+        if name not in EARLIER_MFMA:
+            continue
+        m, busy0, bench0, us0 = EARLIER_MFMA[name]
+        useful = flops / (c["SQ_INSTS_MFMA"] * 2048)
+        lines.append(f"{name:<20} {'9ec1455':<10} {m:<34} {busy0:>6.3f} {bench0:>9.3f} {useful:>7.3f} {us0:>9.2f}")
+        cyc = c["GRBM_GUI_ACTIVE"] / 8
+        now = f"variant {plan['variant']} tile_pix {plan['tile_pix']} loader {plan['loader']}"
+        lines.append(f"{name:<20} {'this tree':<10} {now:<34} {c['SQ_VALU_MFMA_BUSY_CYCLES'] / (cyc * 1024):>6.3f} "
+                     f"{c['SQ_VALU_MFMA_BUSY_CYCLES'] / (us * 1e-6 * 2.4e9 * 1024):>9.3f} {useful:>7.3f} {us:>9.2f}")
+    lines += ["", "The achieved fraction of the fp32 MFMA peak is 'at bench' x useful (x the share of the 256 CUs that hold a work-group).",
+              "Every counter of the same runs, for all five layers: conv_kernels_sq_counters.txt."]
+    _write("conv_kernels_mfma_utilisation.txt", lines)
 
 
 def stats(directory: str):
