@@ -47,7 +47,7 @@ def measured_traffic(shape, plan):
     rec = table.get("layers", {}).get(",".join(str(d) for d in shape.dims))
     if not rec:
         return None
-    if [plan.kernel, plan.variant, plan.tile_pix, plan.loader] != rec.get("plan"):
+    if [plan.kernel, plan.variant, plan.tile_pix, plan.loader, plan.order] != rec.get("plan"):
         return None
     return int(rec["fetch_bytes"] + rec["write_bytes"])
 
@@ -148,7 +148,7 @@ class Layer:
             "frac_fp32_peak": gflops / (PEAK_FP32_TFLOPS * 1e3), "frac_hbm_peak": gbs / PEAK_HBM_GBS,
             "bound": bound, "buffer_sets": self.sets,
             "plan": {k: getattr(self.plan, k) for k in ("kernel", "variant", "tile_k", "tile_pix", "chunk_c",
-                                                         "x_vec", "w_vec", "grid", "block", "lds_bytes", "loader")},
+                                                         "x_vec", "w_vec", "grid", "block", "lds_bytes", "loader", "order")},
         }
 
     def bound(self):
@@ -557,7 +557,7 @@ def main():
         "config": {"workload": f"{s.name}: N={s.N} C={s.C} H={s.H} W={s.W} K={s.K} R={s.R} S={s.S} pad={s.pad_h},{s.pad_w} "
                                f"stride 1, NCHW fp32, {head.sets} rotating buffer sets",
                    "gbs": s.algorithmic_bytes / (wall_ms * 1e-3) / 1e9,
-                   "plan": {k: getattr(head.plan, k) for k in ("kernel", "variant", "tile_pix", "grid", "block", "lds_bytes", "loader")}},
+                   "plan": {k: getattr(head.plan, k) for k in ("kernel", "variant", "tile_pix", "grid", "block", "lds_bytes", "loader", "order")}},
         "roofline": head.roofline(event_ms),
         "parity": parity,
     }

@@ -66,6 +66,13 @@ extern "C" {
 /* Direct loads issued by four loader waves of their own (tile shapes of eight waves only): the waves that multiply
  * then issue no memory instruction between prologue and stores; conv_plan_t.block counts the loader waves too. */
 #define CONV_LOADER_DIRECT_WAVES 3
+/* Direct loads into a ring of four staging copies instead of two (tile shapes whose waves hold one or two MFMA tiles):
+ * three chunks are on their way while one is multiplied, for layers whose chunks are shorter than a load takes. */
+#define CONV_LOADER_DIRECT_DEEP 4
+
+/* Work-group numbering of the tap family (conv_plan_t.order). */
+#define CONV_ORDER_CHANNEL_FAST 1
+#define CONV_ORDER_PIXEL_FAST 2
 
 /*
  * How one layer is mapped onto the GPU. Filled by conv_fwd_plan; plain data.
@@ -93,6 +100,11 @@ typedef struct conv_plan {
     int c_splits;        /* work-groups that share the channels of one output tile; 1: the whole reduction in one */
     int loader;          /* CONV_KERNEL_TAP: how a chunk reaches LDS, CONV_LOADER_REGISTERS or CONV_LOADER_DIRECT
                             (as a request: 0 = the planner's rule); 0 for the other families */
+    int order;           /* CONV_KERNEL_TAP: which tile index runs fastest in the work-group numbering, and so what the
+                            work-groups of one XCD (one L2) share: CONV_ORDER_CHANNEL_FAST (a few pixel tiles, every
+                            channel tile: the inputs are fetched once, the filters by every L2) or CONV_ORDER_PIXEL_FAST
+                            (the reverse, for layers whose filters outweigh their inputs); as a request: 0 = the
+                            planner's rule; 0 for the other families */
     long long workspace_bytes; /* 0 unless c_splits > 1: then 4 * c_splits * N*K*P*Q */
     long long flops;     /* 2*N*K*P*Q*C*R*S */
     long long bytes;     /* 4*(N*C*H*W + K*C*R*S + N*K*P*Q): compulsory HBM traffic */

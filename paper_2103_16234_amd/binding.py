@@ -20,6 +20,9 @@ CONV_KERNEL_PANEL = 3
 CONV_LOADER_REGISTERS = 1
 CONV_LOADER_DIRECT = 2
 CONV_LOADER_DIRECT_WAVES = 3
+CONV_LOADER_DIRECT_DEEP = 4
+CONV_ORDER_CHANNEL_FAST = 1
+CONV_ORDER_PIXEL_FAST = 2
 
 EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_plan_untuned", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_fwd_find", "conv_two_stage_workspace_bytes",
            "conv_fwd_two_stage", "conv_fwd_plan_split_c", "conv_fwd_split_c", "conv_fwd_split_c_static", "conv_fwd_plan_request", "conv_probe_mfma", "conv_probe_copy",
@@ -30,7 +33,7 @@ class ConvPlan(ctypes.Structure):
     """Mirror of conv_plan_t in include/convfwd.h."""
     _fields_ = [(n, ctypes.c_int) for n in (
         "kernel", "variant", "tile_k", "tile_pix", "chunk_c", "x_vec", "w_vec", "lds_rows", "lds_pitch",
-        "lds_plane", "grid", "block", "lds_bytes", "P", "Q", "c_splits", "loader")] + [
+        "lds_plane", "grid", "block", "lds_bytes", "P", "Q", "c_splits", "loader", "order")] + [
         ("workspace_bytes", ctypes.c_longlong), ("flops", ctypes.c_longlong), ("bytes", ctypes.c_longlong)]
 
     def as_dict(self):

@@ -55,17 +55,21 @@ struct KernelArgs {
     int nchunks;     // channel chunks (the chunk size is a property of the tile shape) of one work-group
     int split_c;     // tap family: channels one work-group reduces (a multiple of the chunk, or >= C: no splitting);
                      // work-group index = ((share * ptiles) + pixel tile) * ktiles + channel tile
+    int pixel_fast;  // tap family: nonzero = work-group index = channel tile * pt_all + (share * ptiles + pixel tile) instead,
+                     // so that the run of work-groups one XCD receives shares few channel tiles (filters) and many pixel
+                     // tiles; the host picks the order that makes the eight L2s fetch fewer bytes in total
+    int pt_all;      // ptiles * shares
     // LDS halo tile of the tap family
     int lds_rows, lds_pitch, lds_plane;
     int col_shift;   // LDS column of padded column 0 (keeps vector stores aligned)
     int x_items;     // vector loads per chunk for the halo tile
     int direct;      // tap family: nonzero = the loader that moves global memory straight into LDS (2: issued by loader waves
-                     // of their own). Then x_items counts the
+                     // of their own; 3: with deep_copies() staging copies instead of two). Then x_items counts the
                      // vectors of the LDS halo tile of a chunk, padding included (chunk_c * lds_plane / x_vec), and
                      // div_slot_c / div_row_vecs divide by lds_plane / x_vec and lds_pitch / x_vec
     const float* zeros;  // 16 bytes of zeros in device memory (source of the padding cells for the direct loader)
     // dividers for the index arithmetic of the prologue
-    FastDiv div_ktiles, div_ptiles, div_PQ, div_Q, div_Hp, div_row_vecs, div_slot_c;
+    FastDiv div_ktiles, div_ptiles, div_pt_all, div_PQ, div_Q, div_Hp, div_row_vecs, div_slot_c;
     // tap family: correctly rounded float reciprocals of the divisors of the per-lane index arithmetic (the divisors of
     // div_slot_c and div_row_vecs, Hp, Q, P, P*Q); the dividends there are small, see small_div in the kernel
     float inv_slot_c, inv_row_vecs, inv_Hp, inv_Q, inv_P, inv_PQ;
@@ -94,6 +98,10 @@ constexpr int tap_unit_taps(int S, int RS, int MT, int NT, int occ)
 // tiles of 16 output channels x 16 pixels. A chunk is 4*WC*GPC input channels: the WC waves that share
 // a tile position take the chunk's 4-channel groups in turn (GPC each) and add their partial tiles
 // through LDS at the end.
+#ifndef CONV_DEEP_COPIES
+#define CONV_DEEP_COPIES 4
+#endif
+constexpr int kDeepCopies = CONV_DEEP_COPIES;
 struct TapVariant {
     int MT, NT, WK, WP, WC, GPC;
     int occ;     // waves per SIMD the kernel is compiled for (bounds its registers)
@@ -137,6 +145,9 @@ struct TapVariant {
     // Loader waves a build of this shape with dedicated loading waves adds (0: no such build). Built for the shapes of
     // eight waves at two per SIMD: a ninth to twelfth wave then fits the register file at three per SIMD.
     constexpr int loader_waves() const { return block() == 512 && occ == 2 ? 4 : 0; }
+    // Staging copies of the deep direct loader (0: no such build): built for the shapes whose waves hold one or two MFMA
+    // tiles - the shapes of batch-1 and other small layers, whose chunks are short against the time a load takes.
+    constexpr int deep_copies() const { return MT * NT <= 2 ? kDeepCopies : 0; }
     // LDS bytes a work-group may take so that as many work-groups as the registers allow share a CU
     constexpr int lds_limit() const { return 160 * 1024 / (occ * 256 / block() > 0 ? occ * 256 / block() : 1); }
 };

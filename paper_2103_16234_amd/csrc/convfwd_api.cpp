@@ -143,12 +143,38 @@ int max_halo_rows(const Shape& s, int tile_pix)
 
 // Resolve a tap-family mapping. tile_pix / chunk_c of 0 mean "choose". c_splits > 1 asks for that many channel
 // shares, each reduced by work-groups of its own into a partial output tensor (fewer if C has fewer chunks).
-// Returns false if it cannot run.
-// loader: 0 = by rule, else CONV_LOADER_REGISTERS / CONV_LOADER_DIRECT.
-bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_cap, int w_cap,
-                 conv_plan_t* p, KernelArgs* a, int c_splits = 1, int loader = 0)
+// The eight XCDs (one L2 each) receive contiguous runs of the work-group numbering. With the output-channel tile as
+// the fast index a run holds every channel tile of a few pixel tiles, so each L2 fetches all the filters and an eighth of
+// the inputs; with the pixel tile fast it is the other way round. Bytes all eight L2s fetch, for either order: a run of
+// `per` work-groups touches min(fast, per) indices of the fast dimension and ceil(per / fast) (+1 where runs straddle) of
+// the slow one; with channel shares (splits) a pixel index is a (share, pixel tile) pair and reads 1/splits of the
+// channels. True if the pixel-fast order fetches at least a fifth less.
+bool pixel_fast_fetches_less(const Shape& s, int ktiles, int ptiles, int splits)
 {
-    if (loader < 0 || loader > CONV_LOADER_DIRECT_WAVES) return false;
+    const double pt_all = (double)ptiles * splits;
+    const double per = std::max(1.0, std::ceil(ktiles * pt_all / 8.0));
+    const double w_unit = 4.0 * s.K * s.C * s.R * s.S / ((double)ktiles * splits);  // one channel tile, one share
+    const double x_unit = 4.0 * s.N * s.C * s.H * s.W / pt_all;                      // one pixel tile, one share
+    auto slow_cover = [&](double fast, double slow) {
+        const double whole = std::ceil(per / fast);
+        return std::min(slow, whole + ((per > fast && std::fmod(per, fast) != 0.0) ? 1.0 : 0.0));
+    };
+    // channel tile fast
+    const double p0 = slow_cover(ktiles, pt_all), k0 = std::min<double>(ktiles, per);
+    const double bytes0 = p0 * x_unit + k0 * std::min<double>(splits, std::ceil(p0 / ptiles)) * w_unit;
+    // pixel tile fast
+    const double k1 = slow_cover(pt_all, ktiles), p1 = std::min(pt_all, per);
+    const double bytes1 = p1 * x_unit + k1 * std::min<double>(splits, std::ceil(p1 / ptiles)) * w_unit;
+    return bytes1 < 0.8 * bytes0;
+}
+
+// Returns false if it cannot run.
+// loader: 0 = by rule, else CONV_LOADER_REGISTERS / CONV_LOADER_DIRECT. order: 0 = by rule, else CONV_ORDER_*.
+bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_cap, int w_cap,
+                 conv_plan_t* p, KernelArgs* a, int c_splits = 1, int loader = 0, int order = 0)
+{
+    if (loader < 0 || loader > CONV_LOADER_DIRECT_DEEP) return false;
+    if (order < 0 || order > CONV_ORDER_PIXEL_FAST) return false;
     const int rs_index = tap_rs_index(s);
     if (!tap_is_built(rs_index, variant)) return false;
     const TapVariant tv = kTapVariants[variant];
@@ -158,7 +184,7 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     // four loader waves (32 x 256 x 14 x 14 -> 256: 76.7 -> 73.7 us; 128 x 512 x 7 x 7 -> 512: 258 -> 248 us); the shapes
     // with four shares, short layers and layers whose rows already move as direct dwordx4 lose 1-10 %.
     if (loader == 0 && tv.loader_waves() > 0 && tv.WC == 2 && s.C % 4 == 0 && w_cap >= 4 && s.C >= 12 * tv.chunk_c() &&
-        (s.W % 4 == 2 || s.W < 13) && resolve_tap(s, variant, tile_pix, chunk_c, x_cap, w_cap, p, a, c_splits, CONV_LOADER_DIRECT_WAVES))
+        (s.W % 4 == 2 || s.W < 13) && resolve_tap(s, variant, tile_pix, chunk_c, x_cap, w_cap, p, a, c_splits, CONV_LOADER_DIRECT_WAVES, order))
         return true;
     const int RS = s.R * s.S, TK = tv.tile_k(), BLOCK = tv.block();
     const int64_t total64 = (int64_t)s.N * s.P * s.Q;
@@ -175,6 +201,10 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     const bool loader_waves = loader == CONV_LOADER_DIRECT_WAVES;
     if (loader_waves && (tv.loader_waves() == 0 || w_vec != 4)) return false;
     if (loader_waves && x_vec == 2) x_vec = 1;
+    // The deep direct loader: the same loads, into a ring of tv.deep_copies() staging copies.
+    const bool deep = loader == CONV_LOADER_DIRECT_DEEP;
+    if (deep && (tv.deep_copies() == 0 || w_vec != 4)) return false;
+    if (deep && x_vec == 2) x_vec = 1;
 
     const int col_shift = (x_vec - s.pad_w % x_vec) % x_vec;
     // Sizes of the halo tile in 64 bits first: a padded row, R of them, or a plane that cannot fit LDS ends the attempt
@@ -192,14 +222,14 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     const bool direct_fits = w_vec == 4 && (x_vec == 4 || x_vec == 1) &&
                              (int64_t)tv.chunk_c() * plane / x_vec <= (int64_t)tv.xs_direct(x_vec) * BLOCK &&
                              (int64_t)tv.chunk_c() * s.H * s.W * 4 < ((int64_t)1 << 32);  // a slot's step from chunk to chunk, in bytes
-    if ((loader == CONV_LOADER_DIRECT || loader_waves) && !direct_fits) return false;
+    if ((loader == CONV_LOADER_DIRECT || loader_waves || deep) && !direct_fits) return false;
     // Rule, from timings of every tile shape with both loaders on the shape grid and on random layers off it: direct
     // loads win 2-16 % wherever rows move as dwordx4 (a few layers of 10 us and less lose up to 7 %); with single dwords
     // (maps of odd width) they win 5-20 % on layers of 0.6 GFLOP and more on maps 13 wide and wider, while shorter
     // layers lose up to 17 % (one chunk of look-ahead instead of two) and 7x7 maps never gain (their LDS tile holds
     // almost as much padding as data).
     const double flops = 2.0 * s.N * s.K * s.P * s.Q * s.C * RS;
-    const bool direct = loader == CONV_LOADER_DIRECT || loader_waves ||
+    const bool direct = loader == CONV_LOADER_DIRECT || loader_waves || deep ||
                         (loader == 0 && direct_fits && (x_vec == 4 || (s.W >= 13 && flops >= 6e8)));
 
     // The chunk is a property of the tile shape; a caller may only name that size.
@@ -210,8 +240,15 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     const int64_t x_floats = (int64_t)cc * rows * s.W;
     if (!direct && x_floats > (int64_t)tv.xs(x_vec) * x_vec * BLOCK) return false;
     const int64_t copy_floats = direct ? tv.staging_floats_direct(RS, plane) : tv.staging_floats(RS, plane);
-    const int64_t lds = 4 * std::max<int64_t>(2 * copy_floats, tv.reduce_floats());
-    if (lds > tv.lds_limit() || lds > kLdsMax || copy_floats >= (1 << 16)) return false;
+    const int64_t lds = 4 * std::max<int64_t>((deep ? tv.deep_copies() : 2) * copy_floats, tv.reduce_floats());
+    // (the deep ring is for launches of about one work-group per CU: it may take the whole LDS)
+    if (lds > (deep ? kLdsMax : tv.lds_limit()) || lds > kLdsMax || copy_floats >= (1 << 16)) return false;
+    if (deep) {
+        // loads that stay in flight across the wait at the end of a chunk: the counter that orders them holds 63
+        const int div = tap_x_slot_divisor(tv, x_vec, w_vec, cc * plane / x_vec, true);
+        const int slots = (tv.xs_direct(x_vec) + div - 1) / div + tv.wslots_direct(RS);
+        if ((tv.deep_copies() - 2) * slots > 63) return false;
+    }
 
     base_args(s, a);
     a->tile_pix = tile_pix;
@@ -226,8 +263,10 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     if (splits > 1) a->split_c = chunks_share * cc;
     a->lds_rows = rows; a->lds_pitch = pitch; a->lds_plane = plane; a->col_shift = col_shift;
     a->x_items = direct ? cc * plane / x_vec : cc * rows * row_vecs;
-    a->direct = loader_waves ? 2 : direct ? 1 : 0;
+    a->direct = deep ? 3 : loader_waves ? 2 : direct ? 1 : 0;
     a->div_ktiles = make_fastdiv(a->ktiles); a->div_ptiles = make_fastdiv(a->ptiles);
+    a->pt_all = a->ptiles * splits; a->div_pt_all = make_fastdiv(a->pt_all);
+    a->pixel_fast = order ? order == CONV_ORDER_PIXEL_FAST : pixel_fast_fetches_less(s, a->ktiles, a->ptiles, splits);
     a->div_PQ = make_fastdiv(a->PQ); a->div_Q = make_fastdiv(s.Q); a->div_Hp = make_fastdiv(a->Hp);
     a->div_row_vecs = make_fastdiv(direct ? pitch / x_vec : row_vecs);
     a->div_slot_c = make_fastdiv(direct ? plane / x_vec : rows * row_vecs);
@@ -245,7 +284,8 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     p->lds_bytes = (int)lds;
     fill_common(s, p);
     p->c_splits = splits;
-    p->loader = loader_waves ? CONV_LOADER_DIRECT_WAVES : direct ? CONV_LOADER_DIRECT : CONV_LOADER_REGISTERS;
+    p->loader = deep ? CONV_LOADER_DIRECT_DEEP : loader_waves ? CONV_LOADER_DIRECT_WAVES : direct ? CONV_LOADER_DIRECT : CONV_LOADER_REGISTERS;
+    p->order = a->pixel_fast ? CONV_ORDER_PIXEL_FAST : CONV_ORDER_CHANNEL_FAST;
     if (splits > 1) p->workspace_bytes = 4LL * splits * s.K * total;
     return true;
 }
@@ -503,6 +543,29 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
     return cycles * (1.0 - 0.05 * std::max(0, tv.occ - 2));
 }
 
+// The deep direct loader (a ring of four staging copies) pays where a launch is one round of work-groups whose chunks
+// are shorter than a load takes: every mapping of the 3x3 / 5x5 layers of the shape grid with batch <= 16 was timed with
+// each loader, and against the model's choice two substitutions never lost there:
+//  - the 16 x 64 shapes (2 and its four-wave twin 24), at most 400 work-groups, four chunks or more: shape 2 with the
+//    deep ring, 0.5-15 % faster (1 x 64 x 56 x 56 -> 64: 8.9 -> 7.7 us; 8 x 256 x 14 x 14 -> 256: 35.4 -> 30.9 us);
+//  - the 16 x 32 shapes with channel shares (18 and 20), at most 256 work-groups, 256 channels or more, rows that do not
+//    move as dwordx4: shape 18 with the deep ring, 3-10 % faster (1 x 512 x 14 x 14 -> 512: 23.4 -> 20.8 us; with
+//    dwordx4 rows the plain direct loader is already the choice and the ring lost 4 % on 1 x 320 x 20 x 20 -> 256).
+// Elsewhere (more work-groups than one round, the four-share shapes 10, 11 and 13, short reductions) it lost as often as it
+// won, by up to 2x where the ring's LDS keeps a second work-group off the CU.
+void prefer_deep_ring(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a)
+{
+    int variant = -1;
+    if ((p->variant == 2 || p->variant == 24) && p->grid <= 400 && s.C >= 4 * kTapVariants[2].chunk_c()) variant = 2;
+    if ((p->variant == 18 || p->variant == 20) && p->grid <= 256 && s.C >= 256 && s.W % 4 != 0) variant = 18;
+    if (variant < 0 || p->c_splits > 1) return;
+    conv_plan_t dp;
+    KernelArgs da;
+    if (resolve_tap(s, variant, p->tile_pix, 0, x_cap, w_cap, &dp, &da, 1, CONV_LOADER_DIRECT_DEEP) && dp.grid == p->grid) {
+        *p = dp; *a = da;
+    }
+}
+
 // Measured best mappings of known layer shapes (sweeps over tile shape x pixel tile on an MI355X);
 // shapes not listed go through the cost model.
 struct TunedEntry {
@@ -622,7 +685,10 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_pl
                 }
             }
         }
-        if (found) return CONV_OK;
+        if (found) {
+            prefer_deep_ring(s, x_cap, w_cap, p, a);
+            return CONV_OK;
+        }
     }
     resolve_generic(s, p, a);
     return CONV_OK;
@@ -778,7 +844,7 @@ extern "C" int conv_fwd(const float* x, const float* w, float* y, int N, int C, 
 struct RequestEntry {
     Shape s;
     int x_cap, w_cap, y_cap;
-    int kernel, variant, tile_pix, chunk_c, c_splits, loader;
+    int kernel, variant, tile_pix, chunk_c, c_splits, loader, order;
     conv_plan_t p;
     KernelArgs a;
 };
@@ -794,7 +860,7 @@ static int resolve_request(const Shape& s, int x_cap, int w_cap, int y_cap, cons
         for (const RequestEntry& e : g_request_cache)
             if (same_shape(e.s, s) && e.x_cap == x_cap && e.w_cap == w_cap && e.y_cap == y_cap && e.kernel == req.kernel &&
                 e.variant == req.variant && e.tile_pix == req.tile_pix && e.chunk_c == req.chunk_c && e.c_splits == req.c_splits &&
-                e.loader == req.loader) {
+                e.loader == req.loader && e.order == req.order) {
                 *p = e.p; *a = e.a;
                 return CONV_OK;
             }
@@ -807,7 +873,7 @@ static int resolve_request(const Shape& s, int x_cap, int w_cap, int y_cap, cons
         resolve_generic(s, p, a);
     } else if (req.kernel == CONV_KERNEL_TAP) {
         if (req.tile_pix < 0 || req.chunk_c < 0 || req.c_splits < 0) return CONV_E_PLAN;
-        if (!resolve_tap(s, req.variant, req.tile_pix, req.chunk_c, x_cap, w_cap, p, a, std::max(1, req.c_splits), req.loader))
+        if (!resolve_tap(s, req.variant, req.tile_pix, req.chunk_c, x_cap, w_cap, p, a, std::max(1, req.c_splits), req.loader, req.order))
             return CONV_E_PLAN;
     } else {
         return CONV_E_PLAN;
@@ -815,7 +881,7 @@ static int resolve_request(const Shape& s, int x_cap, int w_cap, int y_cap, cons
     std::lock_guard<std::mutex> lock(g_cache_mutex);
     if (g_request_cache.size() >= kCacheEntries) g_request_cache.erase(g_request_cache.begin());
     g_request_cache.push_back(RequestEntry{s, x_cap, w_cap, y_cap, req.kernel, req.variant, req.tile_pix, req.chunk_c,
-                                           req.c_splits, req.loader, *p, *a});
+                                           req.c_splits, req.loader, req.order, *p, *a});
     return CONV_OK;
 }
 
@@ -948,7 +1014,7 @@ static void enumerate_candidates(const Shape& s, int x_cap, int w_cap, int y_cap
                 bool seen = false;
                 for (int k = 0; k < i; ++k) seen = seen || cands[k] == cands[i];
                 if (seen || cands[i] < 1) continue;
-                for (int loader = CONV_LOADER_REGISTERS; loader <= CONV_LOADER_DIRECT_WAVES; ++loader) {  // each one that can run
+                for (int loader = CONV_LOADER_REGISTERS; loader <= CONV_LOADER_DIRECT_DEEP; ++loader) {  // each one that can run
                     if (!resolve_tap(s, v, cands[i], 0, x_cap, w_cap, &c.p, &c.a, 1, loader)) continue;
                     c.model = tap_cost(c.p, c.a, tv, s.R * s.S);
                     if (taps.empty() || c.model < best) best = c.model;

@@ -103,9 +103,15 @@ template <int N_MFMA> __device__ __forceinline__ void interleave_with_mfma()
 // LW > 0: the work-group has LW more waves, the loader waves, which do nothing but the direct loads of the staging copies
 // (all slots are theirs, XS and WS count slots per loader thread); the other waves then contain no memory instruction
 // between the prologue and the stores. OCC counts all waves of a SIMD.
-template <int R, int S, int MT, int NT, int WK, int WP, int WC, int GPC, int OCC, int XS, int WS, int VX, int VW, bool DMA = false, int LW = 0>
+// DEPTH: staging copies in LDS. Two everywhere but in the deep direct loader (DMA, LW == 0), which keeps DEPTH - 1 chunks
+// on their way while one is multiplied: a chunk's loads then have DEPTH - 1 chunk times to arrive instead of one, for
+// layers whose chunk is shorter than the ~0.5-1 us a load takes from the L2 or beyond.
+template <int R, int S, int MT, int NT, int WK, int WP, int WC, int GPC, int OCC, int XS, int WS, int VX, int VW, bool DMA = false, int LW = 0,
+          int DEPTH = 2>
 __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(const KernelArgs a)
 {
+    static_assert(DEPTH == 2 || (DMA && LW == 0 && DEPTH > 2 && DEPTH <= 8), "only the direct loader of the multiplying waves runs deeper");
+    static_assert((DEPTH - 2) * (XS + WS) <= 63, "the in-order load counter holds 63");
     static_assert(WC >= 1 && WC <= 16 && (WC & (WC - 1)) == 0, "the cross-wave reduction is a binary tree");
     static_assert(LW == 0 || DMA, "loader waves move data with direct loads");
     constexpr int BLOCK = 64 * WK * WP * WC;  // threads of the waves that multiply
@@ -149,15 +155,22 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     const int lwave = LW > 0 ? wave - NWC : wave;       // position among the waves that own staging slots
 
     // Work-groups are dealt round-robin to the 8 XCDs; renumber them so that each XCD (one L2)
-    // gets a contiguous run of tiles: neighbours share the pixel tile and walk the K tiles.
+    // gets a contiguous run of tiles: neighbours share the pixel tile and walk the K tiles, or - a.pixel_fast, layers
+    // whose filters outweigh their inputs - share the K tile and walk the pixel tiles.
     int L;
     {
         const int nb = gridDim.x, b = blockIdx.x;
         const int per = nb >> 3, rem = nb & 7, xcd = b & 7;
         L = xcd * per + (xcd < rem ? xcd : rem) + (b >> 3);
     }
-    const int pt_all = a.div_ktiles.div(L);
-    const int ktile = L - pt_all * a.ktiles;
+    int pt_all, ktile;
+    if (a.pixel_fast) {
+        ktile = a.div_pt_all.div(L);
+        pt_all = L - ktile * a.pt_all;
+    } else {
+        pt_all = a.div_ktiles.div(L);
+        ktile = L - pt_all * a.ktiles;
+    }
     // Channel splitting across work-groups: share `split` reduces channels cb .. cb+C_l-1 and writes a whole
     // partial output tensor of its own (a.y then points at the workspace; a second kernel adds the shares).
     // Without splitting there is one share, all of C.
@@ -378,7 +391,24 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
             for (int i = 0; i < XS; ++i) xp[i] = a.zeros;
 #pragma unroll
             for (int i = 0; i < WS; ++i) wq[i] = a.zeros;
+            if constexpr (STEPS && DEPTH > 2) {  // (more than one round follows: the parked pointers must stay put)
+#pragma unroll
+                for (int i = 0; i < XS; ++i) xstep[i] = 0;
+#pragma unroll
+                for (int i = 0; i < WS; ++i) wstep[i] = 0;
+            }
         }
+    };
+    // Direct loads, before the fetch of chunk f (the pointers stand there): the last chunk of a ragged share takes its
+    // missing channels from the zeros, and past the last chunk every slot does.
+    auto before_fetch = [&](int f) {
+        if (ragged && f == nchunks - 1) zero_past_share();
+        if (f == nchunks) park_slots();
+    };
+    // s_waitcnt vmcnt(n), n a constant below 64: bits 3:0 and 15:14 hold the count, the other counters are left alone
+    auto wait_loads = [](auto nc) {
+        constexpr int n = decltype(nc)::value;
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (n & 15) | ((n >> 4) << 14));
     };
     auto for_each_slot = [&](auto&& f) {
         [&]<int... Ks>(std::integer_sequence<int, Ks...>) { (f(IntC<Ks>{}), ...); }
@@ -432,10 +462,12 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     if constexpr (LW > 0) {
         // (the loader waves fetch)
     } else if constexpr (DMA) {
-        if (ragged && nchunks == 1) zero_past_share();
-        for_each_slot([&](auto kc) { slot_fetch(kc, 0); });
-        if (ragged && nchunks == 2) zero_past_share();
-        if (nchunks == 1) park_slots();
+        before_fetch(0);
+#pragma unroll
+        for (int d = 0; d < DEPTH - 1; ++d) {  // chunk d into copy d
+            for_each_slot([&](auto kc) { slot_fetch(kc, d * buf_floats); });
+            before_fetch(d + 1);
+        }
     } else {
         if (ragged && nchunks == 1) retarget_last_chunk();
         for_each_slot([&](auto kc) { slot_load(kc, 0); });
@@ -466,14 +498,21 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
 
     if constexpr (LW > 0) {
     } else if constexpr (DMA) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's part of chunk 0 is in LDS
+        wait_loads(IntC<(DEPTH - 2) * TS>{});  // this wave's part of chunk 0 is in LDS (later chunks may still be on their way)
     } else {
         __syncthreads();  // zero fill complete before any data lands
         for_each_slot([&](auto kc) { slot_store(kc, 0, 0); });
         if (ragged && nchunks == 2) retarget_last_chunk();
         for_each_slot([&](auto kc) { slot_load(kc, min(CC, last_c0)); });
     }
-    __syncthreads();
+    // The barrier between chunks. __syncthreads() carries a fence, and before a fence the compiler waits for every direct
+    // load still in flight (they write LDS): the deep ring, whose later chunks must stay in flight across the barrier,
+    // waits for its own loads by count (above and in the loop) and for its LDS reads here, and then takes the bare barrier.
+    auto chunk_barrier = [] {
+        if constexpr (DEPTH > 2) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        else __syncthreads();
+    };
+    chunk_barrier();
 
     struct Operands {
         float a[UT][MT];
@@ -484,9 +523,10 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     // Where work-groups share a CU, waves in the chunk loop go ahead of waves in a prologue, reduction or epilogue
     // (measured: +0.4-0.8 % on layers of 60 us and more, nothing elsewhere).
     __builtin_amdgcn_s_setprio(1);
+    int cur_copy = 0, fill_copy = DEPTH - 1;  // ch % DEPTH and (ch + DEPTH - 1) % DEPTH
     for (int ch = 0; ch < nchunks; ++ch) {
-        const int cur_bytes = (ch & 1) * buf_floats * 4;
-        const int nxt_floats = ((ch + 1) & 1) * buf_floats;
+        const int cur_bytes = cur_copy * buf_floats * 4;
+        const int nxt_floats = fill_copy * buf_floats;  // the copy the staging slots fill: chunk ch + DEPTH - 1
         const int c0_regs = min((ch + 1) * CC, last_c0);  // chunk whose data the staging registers hold
         const int c0_load = min((ch + 2) * CC, last_c0);  // chunk to fetch next (the last one again at the end)
         if constexpr (!DMA) {
@@ -539,7 +579,7 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
             if constexpr (LW == 0) for_each_slot([&](auto kc) {
                 if constexpr (decltype(kc)::value * UI / TS == ui) {
                     if constexpr (DMA) {
-                        slot_fetch(kc, nxt_floats);  // chunk ch+1 (in the last round: zeros, unused)
+                        slot_fetch(kc, nxt_floats);  // chunk ch + DEPTH - 1 (past the last chunk: zeros, unused)
                     } else {
                         slot_store(kc, c0_regs, nxt_floats);
                         slot_load(kc, c0_load);
@@ -555,11 +595,15 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
         (std::make_integer_sequence<int, U>{});
 
         if constexpr (DMA && LW == 0) {
-            if (ragged && ch + 3 == nchunks) zero_past_share();  // the pointers now stand at chunk ch+2, the last
-            if (ch + 2 == nchunks) park_slots();                 // chunk ch+1 was the last one to fetch
-            __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this wave's part of chunk ch+1 is in LDS
+            before_fetch(ch + DEPTH);
+            // this wave's part of chunk ch+1 is in LDS; after the last chunk nothing may still be on its way (the reduction
+            // reuses the copies, and LDS that a load still writes must not be handed to another work-group)
+            if (DEPTH == 2 || ch + 1 == nchunks) wait_loads(IntC<0>{});
+            else wait_loads(IntC<(DEPTH - 2) * TS>{});
         }
-        __syncthreads();  // every wave is done reading this copy and writing the other
+        chunk_barrier();  // every wave is done reading this copy and writing the next one to fill
+        fill_copy = cur_copy;
+        cur_copy = cur_copy + 1 == DEPTH ? 0 : cur_copy + 1;
     }
 
     __builtin_amdgcn_s_setprio(0);
@@ -644,11 +688,18 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
 
 using KernFn = void (*)(const KernelArgs);
 
-template <int VX, int VW, int DIV = 1, bool DMA = false, bool LOADER_WAVES = false> static KernFn instance()
+template <int VX, int VW, int DIV = 1, bool DMA = false, bool LOADER_WAVES = false, bool DEEP = false> static KernFn instance()
 {
     constexpr TapVariant tv = kTapVariants[TAP_VARIANT];
     if constexpr (!tv.supports(TAP_R * TAP_S) || (VW == 1 && !tv.supports_scalar(TAP_R * TAP_S, VX))) {
         return nullptr;  // the filter block of this filter size does not fit the variant's registers
+    } else if constexpr (DEEP) {
+        constexpr int XS = (tv.xs_direct(VX) + DIV - 1) / DIV, WS = tv.wslots_direct(TAP_R * TAP_S);
+        if constexpr (tv.deep_copies() == 0 || (tv.deep_copies() - 2) * (XS + WS) > 63) {
+            return nullptr;
+        } else {
+            return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, tv.occ, XS, WS, VX, VW, true, 0, tv.deep_copies()>;
+        }
     } else if constexpr (LOADER_WAVES) {
         constexpr int LW = tv.loader_waves();
         if constexpr (LW == 0) {
@@ -680,7 +731,17 @@ hipError_t TAP_CAT(TAP_R, TAP_S, TAP_VARIANT)(int x_vec, int w_vec, int grid, in
     KernFn fn = nullptr;
     int mode = -1;
     int block = tv.block();
-    if (a.direct == 2 && w_vec == 4 && x_vec == 4) {
+    if (a.direct == 3 && w_vec == 4 && x_vec == 4) {
+        fn = div == 2 ? instance<4, 4, 2, true, false, true>() : instance<4, 4, 1, true, false, true>();
+        mode = div == 2 ? 20 : 19;
+    } else if (a.direct == 3 && w_vec == 4 && x_vec == 1) {
+        fn = div == 4   ? instance<1, 4, 4, true, false, true>()
+             : div == 2 ? instance<1, 4, 2, true, false, true>()
+                        : instance<1, 4, 1, true, false, true>();
+        mode = div == 4 ? 23 : div == 2 ? 22 : 21;
+    } else if (a.direct == 3) {
+        return hipErrorInvalidValue;
+    } else if (a.direct == 2 && w_vec == 4 && x_vec == 4) {
         fn = div == 2 ? instance<4, 4, 2, true, true>() : instance<4, 4, 1, true, true>();
         mode = div == 2 ? 15 : 14;
         block += 64 * tv.loader_waves();
@@ -716,7 +777,7 @@ hipError_t TAP_CAT(TAP_R, TAP_S, TAP_VARIANT)(int x_vec, int w_vec, int grid, in
     }
     if (!fn) return hipErrorInvalidValue;
     // Kernels may use all 160 KB of a CU's LDS; the runtime wants to be told once per kernel (and device).
-    static std::atomic<int> lds_allowed[19][kMaxDevices] = {};
+    static std::atomic<int> lds_allowed[24][kMaxDevices] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
     if (lds_bytes > 48 * 1024 && lds_allowed[mode][dev].load(std::memory_order_acquire) < lds_bytes) {

@@ -140,7 +140,7 @@ def traffic(directory: str):
         body.append((tag, name, fe["FETCH_SIZE"], fb, alg_r, wr["WRITE_SIZE"], wb, alg_w, us, scale_f, scale_w, plan))
         table["layers"][",".join(str(d) for d in dims)] = {
             "layer": name, "fetch_bytes": int(fb), "write_bytes": int(wb), "algorithmic_bytes": alg_bytes,
-            "plan": [plan["kernel"], plan["variant"], plan["tile_pix"], plan["loader"]]}
+            "plan": [plan["kernel"], plan["variant"], plan["tile_pix"], plan["loader"], plan.get("order", 0)]}
     lines += ["", "calibration: the plain 64 MiB device-to-device copy bench.py makes at start-up (the runtime's copyBuffer kernel: 65536 KiB",
               "read + 65536 KiB written), found in the same counter files: scale = 65536 / reading (FETCH_SIZE reads about half the copied",
               "bytes on this GPU, hence ~2; WRITE_SIZE ~1). Scaled bytes = reading x 1024 x scale.", ""]
@@ -276,9 +276,9 @@ def stats(directory: str):
 
 
 FAMILY = {0: "generic", 1: "tap", 2: "pointwise", 3: "panel"}
-LOADER = {1: " R", 2: " D", 3: " W"}
+LOADER = {1: " R", 2: " D", 3: " W", 4: " D4"}
 PLAN_NOTE = ("plan: family, variant, tile_pix (panel: work-groups per channel tile), grid, block, loader of the tap family (R: through the\n"
-             "registers, D: direct to LDS, W: direct by loader waves).")
+             "registers, D: direct to LDS, W: direct by loader waves, D4: direct into a ring of four staging copies).")
 
 
 def _plan(p):

@@ -200,13 +200,17 @@ def test_plan_requests_resolve_on_the_host_and_the_planner_minimises_the_model()
     checked = 0
     for s in inputs.sweep_shapes()[5::9]:
         base = binding.conv_fwd_plan(*s.dims)
-        same, cost = binding.conv_fwd_plan_request(*s.dims, base.kernel, base.variant, base.tile_pix)
+        deep = base.loader == binding.CONV_LOADER_DIRECT_DEEP    # a measured substitution made after the model's choice
+        same, cost = binding.conv_fwd_plan_request(*s.dims, base.kernel, base.variant, base.tile_pix,
+                                                   loader=base.loader if deep else 0)
         assert (same.kernel, same.variant, same.tile_pix, same.grid, same.block, same.lds_bytes) == \
                (base.kernel, base.variant, base.tile_pix, base.grid, base.block, base.lds_bytes)
         if base.kernel != tap:
             assert cost == 0.0
             continue
         assert cost > 0.0
+        if deep:
+            continue
         if s.dims in [tuple(c.dims) for c in (inputs.config(i) for i in range(1, 6))]:
             continue                                             # the five benchmark layers use measured mappings
         for variant in range(binding.conv_variant_count(tap)):
@@ -240,11 +244,13 @@ def test_tap_plans_name_their_loader():
     tap, registers, direct = binding.CONV_KERNEL_TAP, binding.CONV_LOADER_REGISTERS, binding.CONV_LOADER_DIRECT
     for dims, want in [((8, 64, 56, 56, 64, 3, 3, 1, 1), direct),        # rows of whole dwordx4
                        ((1, 48, 28, 28, 128, 5, 5, 2, 2), direct),
-                       ((1, 256, 13, 13, 384, 3, 3, 1, 1), registers),   # odd width, 0.3 GFLOP
+                       ((1, 256, 13, 13, 384, 3, 3, 1, 1), binding.CONV_LOADER_DIRECT_DEEP),  # one round of work-groups, 8 chunks
+                       ((1, 128, 13, 13, 384, 3, 3, 1, 1), registers),   # odd width, 0.15 GFLOP
                        ((8, 256, 13, 13, 384, 3, 3, 1, 1), direct),      # odd width, 2.4 GFLOP
                        ((32, 192, 7, 7, 384, 3, 3, 1, 1), registers),    # 7x7 maps: more padding than data in LDS
                        ((32, 512, 14, 14, 512, 3, 3, 1, 1), binding.CONV_LOADER_DIRECT_WAVES),  # rows of dwordx2, deep: loader waves
-                       ((32, 64, 14, 14, 64, 3, 3, 1, 1), registers),    # rows of dwordx2, four chunks
+                       ((32, 64, 14, 14, 64, 3, 3, 1, 1), binding.CONV_LOADER_DIRECT_DEEP),   # 392 work-groups of 16 x 64, 8 chunks
+                       ((64, 32, 14, 14, 64, 3, 3, 1, 1), registers),    # rows of dwordx2, four chunks, 784 work-groups
                        ((8, 3, 224, 224, 64, 3, 3, 1, 1), registers)]:   # 3 input channels
         plan = binding.conv_fwd_plan(*dims)
         assert plan.kernel == tap and plan.loader == want, (dims, plan.as_dict())
@@ -257,9 +263,18 @@ def test_tap_plans_name_their_loader():
             assert other.loader == loader and other.grid == plan.grid
             assert other.block == plan.block - (256 if plan.loader == 3 else 0)
             assert other.lds_bytes <= 160 * 1024
+            if plan.loader == binding.CONV_LOADER_DIRECT_DEEP and loader == direct:
+                assert plan.lds_bytes == 2 * other.lds_bytes       # four staging copies instead of two
     assert binding.conv_fwd_plan(32, 256, 56, 56, 64, 1, 1, 0, 0).loader == 0      # panel kernel: not a tap plan
     with pytest.raises(binding.ConvError):
-        binding.conv_fwd_plan_request(8, 64, 56, 56, 64, 3, 3, 1, 1, tap, 7, 0, loader=4)
+        binding.conv_fwd_plan_request(8, 64, 56, 56, 64, 3, 3, 1, 1, tap, 7, 0, loader=5)
+    # the deep ring: a build of the tile shapes whose waves hold one or two MFMA tiles; dwordx2 rows move as dwords
+    ring, _ = binding.conv_fwd_plan_request(1, 512, 14, 14, 512, 3, 3, 1, 1, tap, 18, 28, loader=binding.CONV_LOADER_DIRECT_DEEP)
+    assert ring.loader == 4 and ring.block == 512 and ring.x_vec == 1 and ring.lds_bytes <= 160 * 1024
+    with pytest.raises(binding.ConvError):
+        binding.conv_fwd_plan_request(8, 64, 56, 56, 64, 3, 3, 1, 1, tap, 7, 0, loader=binding.CONV_LOADER_DIRECT_DEEP)  # 7 tiles per wave
+    with pytest.raises(binding.ConvError):
+        binding.conv_fwd_plan_request(8, 6, 14, 14, 64, 3, 3, 1, 1, tap, 2, 64, loader=binding.CONV_LOADER_DIRECT_DEEP)  # dword filter rows
     # loader waves: a build of the eight-wave tile shapes only; four more waves in the work-group, rows of dwordx2 as dwords
     waves, _ = binding.conv_fwd_plan_request(32, 512, 14, 14, 512, 3, 3, 1, 1, tap, 6, 196, loader=binding.CONV_LOADER_DIRECT_WAVES)
     assert waves.loader == 3 and waves.block == 768 and waves.x_vec == 1 and waves.grid == 256

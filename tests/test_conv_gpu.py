@@ -107,10 +107,10 @@ DIRECT = [
     S("d3x3_w4_c68", 3, 68, 5, 4, 70, 3, 3, 1, 1),
     S("d1x1_w20", 2, 52, 3, 20, 35, 1, 1, 0, 0),
 ]
-REGISTERS, DIRECT_LOADS, LOADER_WAVES = 1, 2, 3
+REGISTERS, DIRECT_LOADS, LOADER_WAVES, DEEP_RING = 1, 2, 3, 4
 
 
-@pytest.mark.parametrize("loader", [REGISTERS, DIRECT_LOADS, LOADER_WAVES])
+@pytest.mark.parametrize("loader", [REGISTERS, DIRECT_LOADS, LOADER_WAVES, DEEP_RING])
 @pytest.mark.parametrize("variant", range(30))
 @pytest.mark.parametrize("shape", SMALL + DIRECT, ids=lambda s: s.name)
 def test_every_tap_variant_matches_oracle(shape, variant, loader):
@@ -140,10 +140,12 @@ def test_direct_loader_runs_where_it_should():
     assert ran >= 30
     # the default: direct wherever rows move as dwordx4, on odd widths only for layers with enough work
     assert binding.conv_fwd_plan(8, 64, 56, 56, 64, 3, 3, 1, 1).loader == DIRECT_LOADS
-    assert binding.conv_fwd_plan(1, 256, 13, 13, 384, 3, 3, 1, 1).loader == REGISTERS
+    assert binding.conv_fwd_plan(1, 128, 13, 13, 384, 3, 3, 1, 1).loader == REGISTERS
+    assert binding.conv_fwd_plan(1, 256, 13, 13, 384, 3, 3, 1, 1).loader == DEEP_RING      # one round of work-groups, 8 chunks
     assert binding.conv_fwd_plan(32, 256, 13, 13, 384, 3, 3, 1, 1).loader == DIRECT_LOADS
     assert binding.conv_fwd_plan(32, 512, 14, 14, 512, 3, 3, 1, 1).loader == LOADER_WAVES   # deep, rows of dwordx2
-    assert binding.conv_fwd_plan(32, 64, 14, 14, 64, 3, 3, 1, 1).loader == REGISTERS
+    assert binding.conv_fwd_plan(64, 32, 14, 14, 64, 3, 3, 1, 1).loader == REGISTERS
+    assert binding.conv_fwd_plan(32, 64, 14, 14, 64, 3, 3, 1, 1).loader == DEEP_RING        # 392 work-groups of 16 x 64
     assert binding.conv_fwd_plan(8, 3, 224, 224, 64, 3, 3, 1, 1).loader == REGISTERS   # C = 3: dword filter rows
 
 
@@ -348,7 +350,7 @@ def _run_split(shape, variant, c_splits, tile_pix=0, bias=False, relu=False, exa
     return plan, yd
 
 
-@pytest.mark.parametrize("loader", [REGISTERS, DIRECT_LOADS, LOADER_WAVES])
+@pytest.mark.parametrize("loader", [REGISTERS, DIRECT_LOADS, LOADER_WAVES, DEEP_RING])
 @pytest.mark.parametrize("c_splits", [2, 3, 5, 16])
 @pytest.mark.parametrize("variant", [2, 5, 13, 17, 20, 7])
 @pytest.mark.parametrize("shape", SPLIT_SHAPES, ids=lambda s: s.name)
@@ -753,7 +755,7 @@ def test_both_loaders_on_random_small_layers(shape):
     for variant in rng.sample(range(binding.conv_variant_count(TAP)), 6):
         cap = binding.conv_variant_info(TAP, variant)[1]
         tile_pix = rng.choice([0, rng.randint(1, cap)])
-        for loader in (REGISTERS, DIRECT_LOADS, LOADER_WAVES):
+        for loader in (REGISTERS, DIRECT_LOADS, LOADER_WAVES, DEEP_RING):
             try:
                 _run(shape, kernel=TAP, variant=variant, tile_pix=tile_pix, loader=loader)
                 _run_split(shape, variant, rng.choice([2, 3, 4]), tile_pix=tile_pix, loader=loader)
@@ -866,6 +868,26 @@ def test_every_built_tap_instance_runs_on_some_layer():
                 waves_ran.add((R, S_, v))
                 break
     assert waves_ran >= {(R, S_, v) for (R, S_) in ((1, 1), (3, 3)) for v in (6, 7, 12, 19, 21)} | {(5, 5, 12)}, sorted(waves_ran)
+    # the builds with the deep ring of staging copies: the tile shapes whose waves hold one or two MFMA tiles
+    ring_ran = set()
+    for (R, S_), variants in sorted(BUILT_TAP_INSTANCES.items()):
+        for v in sorted(variants & {2, 4, 10, 11, 13, 17, 18, 20, 24, 25}):
+            for N, C, H, W, tile in probes:
+                dims = (N, C, H, W, 20, R, S_, R // 2, S_ // 2)
+                try:
+                    direct, _ = binding.conv_fwd_plan_request(*dims, TAP, v, tile, loader=DIRECT_LOADS)
+                    binding.conv_fwd_plan_request(*dims, TAP, v, tile, loader=DEEP_RING)
+                except binding.ConvError as e:
+                    assert e.code == -6
+                    continue
+                plan, _ = _run(S(f"inst_{R}x{S_}_v{v}_l4_h{H}", *dims), kernel=TAP, variant=v, tile_pix=tile, loader=DEEP_RING)
+                assert plan.loader == DEEP_RING and plan.block == direct.block and plan.lds_bytes >= 2 * direct.lds_bytes - 4096
+                ring_ran.add((R, S_, v))
+                break
+    assert ring_ran >= {(R, S_, v) for (R, S_) in ((1, 1), (3, 3)) for v in (2, 4, 10, 11, 13, 18, 20, 24, 25)}, sorted(ring_ran)
+    for v in (0, 5, 7, 22):
+        with pytest.raises(binding.ConvError):
+            binding.conv_fwd_plan_request(2, 8, 8, 8, 20, 3, 3, 1, 1, TAP, v, 16, loader=DEEP_RING)
     for v in (0, 2, 5, 13, 22):                                     # other tile shapes have no such build
         with pytest.raises(binding.ConvError):
             binding.conv_fwd_plan_request(2, 8, 8, 8, 20, 3, 3, 1, 1, TAP, v, 16, loader=LOADER_WAVES)
