@@ -225,11 +225,35 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     constexpr int WPV = WPITCH / 4;  // vectors per output channel of the LDS filter block, the last one padding
     auto x_position = [&](int i) { return min(i * LB + lwave * 64, xs_floats / VX - 64); };  // wave-uniform
     auto w_position = [&](int i) { return min(i * LB + lwave * 64, WREG / 4 - 64); };
+    // Direct loads: fetch the slot's vectors into the staging copy at dst_floats, then step to the next chunk. (The
+    // step past the last chunk leaves a pointer that is never used: the slots are parked right after.)
+    auto slot_fetch = [&](auto kc, int dst_floats) {
+        constexpr int k = decltype(kc)::value;
+        if constexpr (k < XS) {
+            float* const dst = lds + dst_floats + x_position(k) * VX;  // (uniform)
+            if constexpr (VX == 4) __builtin_amdgcn_global_load_lds(GLOBAL_PTR(xp[k]), LDS_PTR(dst), 16, 0, 0);
+            else __builtin_amdgcn_global_load_lds(GLOBAL_PTR(xp[k]), LDS_PTR(dst), 4, 0, 0);
+            unsigned step;
+            if constexpr (STEPS) step = xstep[k];
+            else step = xp[k] == a.zeros ? 0u : 4u * CC * a.HW;
+            xp[k] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(xp[k]) + step);
+        } else {
+            float* const dst = lds + dst_floats + xs_floats + w_position(k - XS) * 4;
+            __builtin_amdgcn_global_load_lds(GLOBAL_PTR(wq[k - XS]), LDS_PTR(dst), 16, 0, 0);
+            unsigned step;
+            if constexpr (STEPS) step = wstep[k - XS];
+            else step = wq[k - XS] == a.zeros ? 0u : static_cast<unsigned>(CC * RS * 4);
+            wq[k - XS] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(wq[k - XS]) + step);
+        }
+    };
+    // Builds the slot tables and, as soon as a slot's pointer stands, fetches its part of chunk 0 into copy 0: the index
+    // arithmetic of the later slots then runs under the first loads' flight instead of ahead of it. (A slot whose
+    // channel lies past a share of less than one chunk takes zeros from the start.)
     auto build_direct_slots = [&]() {
         static_assert(!DMA || VW == 4, "filters move as dwordx4");
         const int plane_v = a.lds_plane / VX, pitch_v = a.lds_pitch / VX;
-#pragma unroll
-        for (int i = 0; i < XS; ++i) {
+        auto build_x = [&](auto ic) {
+            constexpr int i = decltype(ic)::value;
             const int start = x_position(i);
             const int e = start + lane;
             xp[i] = a.zeros;
@@ -241,29 +265,33 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
                 const int col = (rem - __mul24(row, pitch_v)) * VX - a.col_shift - a.pad_w;
                 int n, h;
                 image_row(row, n, h);
-                if (row < a.lds_rows && col >= 0 && col < a.W && n < a.N && h >= 0 && h < a.H) {
+                if (row < a.lds_rows && col >= 0 && col < a.W && n < a.N && h >= 0 && h < a.H && c_l < C_l) {
                     // (x holds fewer than 2^31 elements: the offset of a valid cell fits 32 bits)
                     xp[i] = x_share + ((static_cast<unsigned>(n * a.C + c_l) * a.H + h) * a.W + col);
                     if constexpr (STEPS) xstep[i] = 4u * CC * a.HW;
                 }
             }
-        }
-#pragma unroll
-        for (int i = 0; i < WS; ++i) {
+            slot_fetch(IntC<i>{}, 0);
+        };
+        auto build_w = [&](auto ic) {
+            constexpr int i = decltype(ic)::value;
             const int start = w_position(i);
             const int e = start + lane;
             wq[i] = a.zeros;
             if constexpr (STEPS) wstep[i] = 0;
             const int kl = e / WPV;
             const int ev = e - kl * WPV;
-            if (kl < TK && ev < WPV - 1 && k0 + kl < a.K) {
+            if (kl < TK && ev < WPV - 1 && k0 + kl < a.K && ev * 4 < C_l * RS) {
                 wq[i] = w_share + static_cast<size_t>(k0 + kl) * a.CRS + ev * 4;
                 if constexpr (STEPS) wstep[i] = CC * RS * 4;
             }
-        }
+            slot_fetch(IntC<XS + i>{}, 0);
+        };
+        [&]<int... Is>(std::integer_sequence<int, Is...>) { (build_x(IntC<Is>{}), ...); }(std::make_integer_sequence<int, DMA ? XS : 0>{});
+        [&]<int... Is>(std::integer_sequence<int, Is...>) { (build_w(IntC<Is>{}), ...); }(std::make_integer_sequence<int, DMA ? WS : 0>{});
     };
     if constexpr (DMA) {
-        if constexpr (LW == 0) build_direct_slots();  // (with loader waves: theirs, built where their role starts)
+        if constexpr (LW == 0) build_direct_slots();  // chunk 0 goes out here too (with loader waves: theirs, where their role starts)
     } else {
         const int XV = a.W / VX;
         const int per_c = a.lds_rows * XV;
@@ -346,27 +374,6 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
             t.store16(lds + dst_floats + (wl[k - XS] & 0xffff));
         }
     };
-    // Direct loads: fetch the slot's vectors into the staging copy at dst_floats, then step to the next chunk. (The
-    // step past the last chunk leaves a pointer that is never used: the slots are parked right after.)
-    auto slot_fetch = [&](auto kc, int dst_floats) {
-        constexpr int k = decltype(kc)::value;
-        if constexpr (k < XS) {
-            float* const dst = lds + dst_floats + x_position(k) * VX;  // (uniform)
-            if constexpr (VX == 4) __builtin_amdgcn_global_load_lds(GLOBAL_PTR(xp[k]), LDS_PTR(dst), 16, 0, 0);
-            else __builtin_amdgcn_global_load_lds(GLOBAL_PTR(xp[k]), LDS_PTR(dst), 4, 0, 0);
-            unsigned step;
-            if constexpr (STEPS) step = xstep[k];
-            else step = xp[k] == a.zeros ? 0u : 4u * CC * a.HW;
-            xp[k] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(xp[k]) + step);
-        } else {
-            float* const dst = lds + dst_floats + xs_floats + w_position(k - XS) * 4;
-            __builtin_amdgcn_global_load_lds(GLOBAL_PTR(wq[k - XS]), LDS_PTR(dst), 16, 0, 0);
-            unsigned step;
-            if constexpr (STEPS) step = wstep[k - XS];
-            else step = wq[k - XS] == a.zeros ? 0u : static_cast<unsigned>(CC * RS * 4);
-            wq[k - XS] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(wq[k - XS]) + step);
-        }
-    };
     // The pointers have just reached the last chunk of a share that is not a multiple of the chunk: vectors of
     // channels past the share come from the zeros instead.
     auto zero_past_share = [&]() {
@@ -422,9 +429,7 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     if constexpr (LW > 0) {
         if (is_loader) {
             __builtin_amdgcn_s_setprio(3);  // their few instructions go ahead of the matrix work that shares the SIMD
-            build_direct_slots();
-            if (ragged && nchunks == 1) zero_past_share();
-            for_each_slot([&](auto kc) { slot_fetch(kc, 0); });
+            build_direct_slots();  // (and chunk 0 is on its way)
             if (ragged && nchunks == 2) zero_past_share();
             __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
             __syncthreads();
@@ -462,9 +467,9 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     if constexpr (LW > 0) {
         // (the loader waves fetch)
     } else if constexpr (DMA) {
-        before_fetch(0);
+        before_fetch(1);  // (chunk 0 went out with the slot tables)
 #pragma unroll
-        for (int d = 0; d < DEPTH - 1; ++d) {  // chunk d into copy d
+        for (int d = 1; d < DEPTH - 1; ++d) {  // chunk d into copy d
             for_each_slot([&](auto kc) { slot_fetch(kc, d * buf_floats); });
             before_fetch(d + 1);
         }
@@ -523,8 +528,10 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     // Where work-groups share a CU, waves in the chunk loop go ahead of waves in a prologue, reduction or epilogue
     // (measured: +0.4-0.8 % on layers of 60 us and more, nothing elsewhere).
     __builtin_amdgcn_s_setprio(1);
-    int cur_copy = 0, fill_copy = DEPTH - 1;  // ch % DEPTH and (ch + DEPTH - 1) % DEPTH
+    int ring_cur = 0, ring_fill = DEPTH - 1;  // ch % DEPTH and (ch + DEPTH - 1) % DEPTH
     for (int ch = 0; ch < nchunks; ++ch) {
+        const int cur_copy = DEPTH == 2 ? (ch & 1) : ring_cur;
+        const int fill_copy = DEPTH == 2 ? ((ch + 1) & 1) : ring_fill;
         const int cur_bytes = cur_copy * buf_floats * 4;
         const int nxt_floats = fill_copy * buf_floats;  // the copy the staging slots fill: chunk ch + DEPTH - 1
         const int c0_regs = min((ch + 1) * CC, last_c0);  // chunk whose data the staging registers hold
@@ -602,8 +609,8 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
             else wait_loads(IntC<(DEPTH - 2) * TS>{});
         }
         chunk_barrier();  // every wave is done reading this copy and writing the next one to fill
-        fill_copy = cur_copy;
-        cur_copy = cur_copy + 1 == DEPTH ? 0 : cur_copy + 1;
+        ring_fill = ring_cur;
+        ring_cur = ring_cur + 1 == DEPTH ? 0 : ring_cur + 1;
     }
 
     __builtin_amdgcn_s_setprio(0);
