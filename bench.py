@@ -99,6 +99,7 @@ class Layer:
         from paper_2103_16234_amd import binding
         req = binding.ConvPlan()
         req.kernel, req.variant, req.tile_pix, req.loader = plan.kernel, plan.variant, plan.tile_pix, plan.loader
+        req.order = plan.order
         self.request = req
 
     def measure(self, steps, warmup):
@@ -338,6 +339,15 @@ def sweep(torch, binding, inputs, oracle, only=None, find=False):
             _, fp, _ = binding.conv_fwd_find(layer.x[0], layer.w[0], shape.pad_h, shape.pad_w, y=layer.y[0], flush=flush)
             _, f_ms = layer.measure(k, 3)
             fpar = layer.parity_sample(oracle, 128)
+            # once more each, the default now by request: whichever mapping is timed right after the search's burst of
+            # launches finds the clocks up, which is worth up to 20 % on layers of a few microseconds
+            layer.use_plan(p)
+            e_ms = min(e_ms, layer.measure(k, 3)[1])
+            layer.use_plan(None)
+            f_ms = min(f_ms, layer.measure(k, 3)[1])
+            roof = layer.roofline(e_ms)
+            rec.update({"kernel_us": e_ms * 1e3, "tflops": shape.flops / e_ms / 1e9, "gbs": shape.algorithmic_bytes / e_ms / 1e6,
+                        "frac": roof["frac"]})
             rec.update({"found_us": f_ms * 1e3, "found_plan": [fp.kernel, fp.variant, fp.tile_pix, fp.grid, fp.block, fp.loader],
                         "found_frac": layer.roofline(f_ms)["frac"], "found_parity_ok": fpar["ok"]})
         rows.append(rec)
@@ -377,6 +387,11 @@ def holdout(torch, binding, inputs, oracle, seed, count=40):
         _, f_ms = layer.measure(k, 3)
         par = layer.parity_sample(oracle, 64)
         p = layer.plan
+        # once more each, the default now by request (see sweep): the faster of a mapping's two runs counts
+        layer.use_plan(p)
+        d_ms = min(d_ms, layer.measure(k, 3)[1])
+        layer.use_plan(None)
+        f_ms = min(f_ms, layer.measure(k, 3)[1])
         rows.append({"shape": shape.name, "default_us": d_ms * 1e3, "found_us": f_ms * 1e3, "frac": layer.roofline(d_ms)["frac"],
                      "default_plan": [p.kernel, p.variant, p.tile_pix, p.grid, p.block, p.loader],
                      "found_plan": [fp.kernel, fp.variant, fp.tile_pix, fp.grid, fp.block, fp.loader], "found_parity_ok": par["ok"]})

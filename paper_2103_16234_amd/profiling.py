@@ -307,8 +307,10 @@ def sweep(paths):
              "paper_2103_16234_amd.inputs.sweep_shapes, tensors of at most 2^25 elements), HIP-event time per launch over rotating buffer",
              "sets on one MI355X, each layer spot-checked against the oracle on 128 outputs."
              + (" Two mappings per layer: the planner's default," if found else ""),
-             ("and the one conv_fwd_find measures to be fastest (cold-cache timing with a 512 MiB flush buffer)." if found else
-              "The planner's default mapping."),
+             ("and the one conv_fwd_find measures to be fastest (cold-cache timing with a 512 MiB flush buffer); each of the two is timed"
+              if found else "The planner's default mapping."),
+             ("twice in turn (default, found, default, found) and its faster run counts: whichever runs right after the search's burst of\n"
+              "launches finds the clocks up, worth up to 20 % on layers of a few microseconds." if found else ""),
              "Command (from the repository root):",
              "  python3 bench.py --no-layers --no-cpu --sweep" + (" --find" if found else "") + " > gpurun_out/prof/sweep.json"
              + ("      (run as three: --sweep sweep_1x1, sweep_3x3, sweep_5x5)" if len(paths) > 1 else ""),
@@ -344,7 +346,9 @@ def holdout(paths):
     lines = ["Planner check on layers it was not fitted on: 40 random layers per seed inside the paper's ranges but off the synthetic",
              "sweep grid (batch 1, 2, 4, 16, 64; 16...640 channels; maps 7...112; 24...768 filters; 1x1 / 3x3 / 5x5), each timed on one",
              "MI355X with the default mapping (conv_fwd) and with the mapping conv_fwd_find measures to be fastest (cold-cache timing),",
-             "HIP events over rotating buffer sets, the found mapping spot-checked against the oracle on 64 outputs.",
+             "HIP events over rotating buffer sets, the found mapping spot-checked against the oracle on 64 outputs. Each of the two",
+             "mappings is timed twice in turn (default, found, default, found) and its faster run counts (a run right after the search's",
+             "burst of launches finds the clocks up, worth up to 20 % on layers of a few microseconds).",
              "Commands (from the repository root), one per seed:",
              "  python3 bench.py --no-cpu --no-layers --holdout SEED > gpurun_out/prof/holdout_SEED.json      (SEED = "
              + ", ".join(str(h["seed"]) for h in runs) + ")",
