@@ -543,27 +543,38 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
     return cycles * (1.0 - 0.05 * std::max(0, tv.occ - 2));
 }
 
-// The deep direct loader (a ring of four staging copies) pays where a launch is one round of work-groups whose chunks
-// are shorter than a load takes: every mapping of the 3x3 / 5x5 layers of the shape grid with batch <= 16 was timed with
-// each loader, and against the model's choice two substitutions never lost there:
-//  - the 16 x 64 shapes (2 and its four-wave twin 24), at most 400 work-groups, four chunks or more: shape 2 with the
-//    deep ring, 0.5-15 % faster (1 x 64 x 56 x 56 -> 64: 8.9 -> 7.7 us; 8 x 256 x 14 x 14 -> 256: 35.4 -> 30.9 us);
-//  - the 16 x 32 shapes with channel shares (18 and 20), at most 256 work-groups, 256 channels or more, rows that do not
-//    move as dwordx4: shape 18 with the deep ring, 3-10 % faster (1 x 512 x 14 x 14 -> 512: 23.4 -> 20.8 us; with
-//    dwordx4 rows the plain direct loader is already the choice and the ring lost 4 % on 1 x 320 x 20 x 20 -> 256).
-// Elsewhere (more work-groups than one round, the four-share shapes 10, 11 and 13, short reductions) it lost as often as it
-// won, by up to 2x where the ring's LDS keeps a second work-group off the CU.
+// The deep direct loader (a ring of four staging copies) pays where a launch is one or two rounds of work-groups whose
+// chunks are shorter than a load takes: every mapping of the 3x3 / 5x5 layers of the shape grid with batch <= 16 and of
+// 18 layers off it was timed with each loader, and against the model's choice these substitutions did not lose:
+//  - the 16 x 64 shapes (2 and its four-wave twin 24), four chunks or more, at most 400 work-groups (256 where rows move
+//    as dwordx4: two layers of 300 work-groups lost 8 %; 512 with 256 channels or more): shape 2 with the deep ring,
+//    0.5-22 % faster (1 x 64 x 56 x 56 -> 64: 8.9 -> 7.7 us; 8 x 256 x 14 x 14 -> 256: 35.4 -> 30.9 us; 2 x 320 x 17 x 17
+//    -> 768: 45.3 -> 37.1 us);
+//  - the 16 x 32 shapes with eight channel shares (18 and 20), at most 256 work-groups, 256 channels or more, rows that
+//    do not move as dwordx4: shape 18 with the deep ring, 3-10 % faster (1 x 512 x 14 x 14 -> 512: 23.4 -> 20.8 us; with
+//    dwordx4 rows the plain direct loader is already the choice and the ring lost 4 % on 1 x 320 x 20 x 20 -> 256);
+//    where four copies of its 32-channel chunks do not fit LDS (maps wider than ~30), shape 13 (16-channel chunks) with
+//    the ring instead (1 x 448 x 35 x 35 -> 48: 29.2 -> 25.1 us).
+// Elsewhere (more rounds of work-groups, short reductions, the four-share shapes as the model's own choice) it lost as
+// often as it won, by up to 2x where the ring's LDS keeps a second work-group off the CU.
 void prefer_deep_ring(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a)
 {
-    int variant = -1;
-    if ((p->variant == 2 || p->variant == 24) && p->grid <= 400 && s.C >= 4 * kTapVariants[2].chunk_c()) variant = 2;
-    if ((p->variant == 18 || p->variant == 20) && p->grid <= 256 && s.C >= 256 && s.W % 4 != 0) variant = 18;
+    int variant = -1, fallback = -1;
+    const bool wide_rows = s.W % 4 == 0;
+    if ((p->variant == 2 || p->variant == 24) && s.C >= 4 * kTapVariants[2].chunk_c() &&
+        p->grid <= (wide_rows ? 256 : s.C >= 256 ? 512 : 400))
+        variant = 2;
+    if ((p->variant == 18 || p->variant == 20) && p->grid <= 256 && s.C >= 256 && !wide_rows) {
+        variant = 18; fallback = 13;
+    }
     if (variant < 0 || p->c_splits > 1) return;
     conv_plan_t dp;
     KernelArgs da;
-    if (resolve_tap(s, variant, p->tile_pix, 0, x_cap, w_cap, &dp, &da, 1, CONV_LOADER_DIRECT_DEEP) && dp.grid == p->grid) {
-        *p = dp; *a = da;
-    }
+    for (int v : {variant, fallback})
+        if (v >= 0 && resolve_tap(s, v, p->tile_pix, 0, x_cap, w_cap, &dp, &da, 1, CONV_LOADER_DIRECT_DEEP) && dp.grid == p->grid) {
+            *p = dp; *a = da;
+            return;
+        }
 }
 
 // Measured best mappings of known layer shapes (sweeps over tile shape x pixel tile on an MI355X);
