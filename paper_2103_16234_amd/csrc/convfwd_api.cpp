@@ -554,7 +554,8 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
 //    do not move as dwordx4: shape 18 with the deep ring, 3-10 % faster (1 x 512 x 14 x 14 -> 512: 23.4 -> 20.8 us; with
 //    dwordx4 rows the plain direct loader is already the choice and the ring lost 4 % on 1 x 320 x 20 x 20 -> 256);
 //    where four copies of its 32-channel chunks do not fit LDS (maps wider than ~30), shape 13 (16-channel chunks) with
-//    the ring instead (1 x 448 x 35 x 35 -> 48: 29.2 -> 25.1 us).
+//    the ring instead (1 x 448 x 35 x 35 -> 48: 29.2 -> 25.1 us). Batch 1 and 2 only: every such layer timed had one of
+//    them but 16 x 320 x 7 x 7 -> 160, which lost 10 %.
 // Elsewhere (more rounds of work-groups, short reductions, the four-share shapes as the model's own choice) it lost as
 // often as it won, by up to 2x where the ring's LDS keeps a second work-group off the CU.
 void prefer_deep_ring(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a)
@@ -564,7 +565,7 @@ void prefer_deep_ring(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, Kern
     if ((p->variant == 2 || p->variant == 24) && s.C >= 4 * kTapVariants[2].chunk_c() &&
         p->grid <= (wide_rows ? 256 : s.C >= 256 ? 512 : 400))
         variant = 2;
-    if ((p->variant == 18 || p->variant == 20) && p->grid <= 256 && s.C >= 256 && !wide_rows) {
+    if ((p->variant == 18 || p->variant == 20) && p->grid <= 256 && s.C >= 256 && !wide_rows && s.N <= 2) {
         variant = 18; fallback = 13;
     }
     if (variant < 0 || p->c_splits > 1) return;
@@ -734,7 +735,11 @@ int plan_split_shape(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_
             }
     }
     if (int rc = plan_shape(s, x_cap, w_cap, y_cap, p, a)) return rc;
-    if (p->kernel == CONV_KERNEL_TAP) search_split_plans(s, x_cap, w_cap, p, a);
+    // Where the single-kernel default already runs the deep ring on rows that move as dwordx2 or dwordx4, shares stopped
+    // paying once it existed (8 x 256 x 14 x 14 -> 256: 1.14x before, 0.99x after; 1 x 512 x 14 x 14 -> 512: 1.08x -> 0.96x);
+    // on odd widths, where the single kernel's dword loads are bound by the address path, they still gain 12-18 %.
+    const bool ring_suffices = p->kernel == CONV_KERNEL_TAP && p->loader == CONV_LOADER_DIRECT_DEEP && s.W % 2 == 0;
+    if (p->kernel == CONV_KERNEL_TAP && !ring_suffices) search_split_plans(s, x_cap, w_cap, p, a);
     std::lock_guard<std::mutex> lock(g_cache_mutex);
     if (g_split_cache.size() >= kCacheEntries) g_split_cache.erase(g_split_cache.begin());
     g_split_cache.push_back(CacheEntry{s, x_cap, w_cap, y_cap, *p, *a});
