@@ -474,9 +474,12 @@ int pick_panel(const Shape& s, int x_cap, int y_cap)
     const bool dwords = panel_pixel_mode(s, x_cap, y_cap) == 1;
     const int c64 = round_up(s.C, 32);
     if (dwords && s.K >= 64 && tiles * ceil_div(s.K, 64) >= 704 && 64 * (c64 + 4) * 4 <= kLdsMax) return 6;  // {4, 4, 2}
-    // 64 channels per panel also win 8-10 % on layers with 256 or more filters whose panel still lets two work-groups
-    // share a CU (C <= 256)
-    if (s.K >= 256 && tiles * ceil_div(s.K, 64) >= 704 && 64 * (c64 + 4) * 4 <= kLdsMax / 2) return 6;
+    // 64 channels per panel also win on layers with 256 or more filters whose panel still lets two work-groups share a CU
+    // (C <= 256) - on maps whose tiles are cut per image (27 x 27): 7-20 % there. Where pixels move as aligned dwordx4 the
+    // same rule once applied too; timings of every panel shape on the 27 such layers of the grid and off it put the
+    // 32-channel panel ahead on all of them (8.5 % in the geometric mean, up to 32 %), and it was dropped for those.
+    if (panel_pixel_mode(s, x_cap, y_cap) == 2 && s.K >= 256 && tiles * ceil_div(s.K, 64) >= 704 && 64 * (c64 + 4) * 4 <= kLdsMax / 2)
+        return 6;
     // a 32-channel panel of more than half the LDS leaves one work-group per CU: eight waves then (two per SIMD)
     // when every CU still gets a work-group whose waves all have a tile
     if (32 * (c64 + 4) * 4 > kLdsMax / 2 && 32 * (c64 + 4) * 4 <= kLdsMax &&
