@@ -107,6 +107,10 @@ struct TapVariant {
     int occ;     // waves per SIMD the kernel is compiled for (bounds its registers)
     int xslots;  // dwordx4 halo-tile loads a thread keeps in flight (x2 as many when rows force dwordx2)
     int xslots1; // the same for rows that force single dwords (maps of odd width are small: fewer than 4 * xslots do)
+    // Nonzero: the wave's last pixel tile holds at most four pixels and is multiplied by the 4x4x1 matrix instruction (16
+    // blocks of 4 channels x 4 pixels, a quarter of the cycles of a 16 x 16 tile) instead of a 16 x 16 x 4 one that would
+    // be three quarters padding: a 14 x 14 map (196 = 12 * 16 + 4 pixels) then costs 12.25 tiles instead of 13.
+    int tail = 0;
     constexpr int xs(int x_vec) const { return x_vec == 1 ? xslots1 : xslots * 4 / x_vec; }
     // Direct loads (global memory -> LDS without passing the registers) also fetch the padding cells of the halo tile,
     // and a slot costs half the registers: half as many slots again.
@@ -118,7 +122,9 @@ struct TapVariant {
         return (chunk_c() * plane + 255) / 256 * 256 + (tile_k() * (chunk_c() * RS + 4) + 255) / 256 * 256;
     }
     constexpr int tile_k() const { return 16 * MT * WK; }
-    constexpr int max_pix() const { return 16 * NT * WP; }
+    constexpr int max_pix() const { return 16 * NT * WP - (tail ? 12 : 0); }
+    // matrix-pipeline cycles of one tap of one 4-channel group of a wave
+    constexpr int tap_cycles() const { return MT * (32 * (NT - (tail ? 1 : 0)) + (tail ? 8 : 0)); }
     constexpr int block() const { return 64 * WK * WP * WC; }
     constexpr int chunk_c() const { return 4 * WC * GPC; }
     // filter-block loads per thread and chunk, and whether that many registers are reasonable
@@ -179,6 +185,8 @@ constexpr TapVariant kTapVariants[] = {
     {1, 7, 2, 2, 1, 1, 3, 4, 8},    // 23: 32 ch x 224 px, 4-channel chunks, three waves per SIMD
     {1, 1, 1, 4, 1, 2, 4, 4, 8},    // 24: as 2 with four waves per SIMD
     {1, 2, 2, 2, 1, 2, 4, 4, 8},    // 25: as 4 with four waves per SIMD
+    {1, 13, 4, 1, 2, 2, 2, 2, 8, 1},  // 26: as 6 for tiles of 196 pixels (a 14x14 image, four 7x7 images): the 13th tile is a four-pixel tail
+    {1, 7, 4, 1, 2, 2, 2, 3, 8, 1},   // 27: as 7 for tiles of up to 100 pixels (six tiles and a tail): 98 pixels put 8 x 56 x 56 outputs on 256 work-groups
 };
 constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
 
@@ -195,7 +203,7 @@ constexpr int tap_x_slot_divisor(const TapVariant& tv, int x_vec, int w_vec, int
     if (x_vec == 1 && (full + 3) / 4 >= need) return 4;
     return (full + 1) / 2 >= need ? 2 : 1;
 }
-#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18) X(19) X(20) X(21) X(22) X(23) X(24) X(25)
+#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18) X(19) X(20) X(21) X(22) X(23) X(24) X(25) X(26) X(27)
 
 // Filter sizes the tap kernel is instantiated for. The three the paper evaluates (Section 4: 1x1, 3x3, 5x5) get every
 // tile shape; the others (filter rows and columns, even and 7x7 filters, as the factorised layers of later CNNs use)

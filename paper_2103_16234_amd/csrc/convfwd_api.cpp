@@ -533,7 +533,7 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
     const int slots = x_slots + (a.direct ? tv.wslots_direct(RS) : ceil_div(tv.tile_k() * tv.chunk_c() * RS / p.w_vec, tv.block()));
     // (with loader waves the slots are not the multiplying waves' business, but their traffic into LDS still is: measured
     // 2-4 % under the register loader on deep layers)
-    const double work = waves_per_simd * (tv.MT * tv.NT * tv.GPC * RS * 32.0 + (a.direct == 2 ? 80.0 : a.direct ? 50.0 : 110.0) * slots);  // per SIMD, chunk, work-group
+    const double work = waves_per_simd * ((double)tv.tap_cycles() * tv.GPC * RS + (a.direct == 2 ? 80.0 : a.direct ? 50.0 : 110.0) * slots);  // per SIMD, chunk, work-group
     const double staged = 4.0 * ((double)tv.chunk_c() * a.lds_rows * a.W + (double)tv.tile_k() * tv.chunk_c() * RS);
     const double chunk = std::max(std::max(cu * work / eff, batches * ((a.direct ? 1500.0 : 750.0) + work)), cu * staged / 16.0);
     // cross-wave reduction: per round of the tree every tile goes through LDS once each way (~8 cycles per 64 B with
@@ -589,9 +589,9 @@ struct TunedEntry {
 constexpr TunedEntry kTuned[] = {
     {1, 16, 14, 14, 16, 3, 1, CONV_KERNEL_TAP, 2, 16},
     {1, 256, 56, 56, 64, 1, 0, CONV_KERNEL_POINTWISE, 1, 64},
-    {8, 64, 56, 56, 64, 3, 1, CONV_KERNEL_TAP, 7, 112},
+    {8, 64, 56, 56, 64, 3, 1, CONV_KERNEL_TAP, 27, 98},
     {1, 48, 28, 28, 128, 5, 2, CONV_KERNEL_TAP, 11, 28},
-    {32, 512, 14, 14, 512, 3, 1, CONV_KERNEL_TAP, 6, 196},
+    {32, 512, 14, 14, 512, 3, 1, CONV_KERNEL_TAP, 26, 196},
 };
 const TunedEntry* find_tuned(const Shape& s)
 {

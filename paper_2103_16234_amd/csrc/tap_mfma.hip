@@ -76,6 +76,14 @@ template <> struct Vec<1> {
 };
 
 template <int N> using IntC = std::integral_constant<int, N>;
+// f(IntC<Lo>{}), ..., f(IntC<Hi - 1>{})
+template <int Lo, int Hi, class F> __device__ __forceinline__ void for_range(F&& f)
+{
+    if constexpr (Lo < Hi) {
+        f(IntC<Lo>{});
+        for_range<Lo + 1, Hi>(f);
+    }
+}
 
 // x / d for a small non-negative x (below 2^22) and a launch-time divisor d whose correctly rounded float reciprocal
 // the host supplies: (x + 1/2) / d is at least 1/(2d) away from every integer, and the two roundings (the reciprocal, the
@@ -106,14 +114,20 @@ template <int N_MFMA> __device__ __forceinline__ void interleave_with_mfma()
 // DEPTH: staging copies in LDS. Two everywhere but in the deep direct loader (DMA, LW == 0), which keeps DEPTH - 1 chunks
 // on their way while one is multiplied: a chunk's loads then have DEPTH - 1 chunk times to arrive instead of one, for
 // layers whose chunk is shorter than the ~0.5-1 us a load takes from the L2 or beyond.
+// TAIL: the wave's last pixel tile (index NT - 1) covers at most four pixels and is multiplied with v_mfma_f32_4x4x1 (16 blocks,
+// 8 cycles instead of 32). Block b of that instruction takes lanes 4b .. 4b+3: with block = (channel lane >> 4, output-channel
+// quad (lane >> 2) & 3) the A operand is the very register the 16 x 16 x 4 tiles use (lane holds w[k = lane & 15][c = lane >> 4]),
+// and the B operand is read like any other tile's, only with pixel lane & 3 instead of lane & 15. Each block sums one channel:
+// the four channels of a quad are added across lanes once, before the stores.
 template <int R, int S, int MT, int NT, int WK, int WP, int WC, int GPC, int OCC, int XS, int WS, int VX, int VW, bool DMA = false, int LW = 0,
-          int DEPTH = 2>
+          int DEPTH = 2, bool TAIL = false>
 __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(const KernelArgs a)
 {
     static_assert(DEPTH == 2 || (DMA && LW == 0 && DEPTH > 2 && DEPTH <= 8), "only the direct loader of the multiplying waves runs deeper");
     static_assert((DEPTH - 2) * (XS + WS) <= 63, "the in-order load counter holds 63");
     static_assert(WC >= 1 && WC <= 16 && (WC & (WC - 1)) == 0, "the cross-wave reduction is a binary tree");
     static_assert(LW == 0 || DMA, "loader waves move data with direct loads");
+    static_assert(!TAIL || (WP == 1 && NT >= 2), "the four-pixel tail is the last tile of the work-group's pixel range");
     constexpr int BLOCK = 64 * WK * WP * WC;  // threads of the waves that multiply
     constexpr int NWC = WK * WP * WC;
     constexpr int LB = LW > 0 ? 64 * LW : BLOCK;  // threads that own staging slots
@@ -253,46 +267,63 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     // Builds the slot tables and, as soon as a slot's pointer stands, fetches its part of chunk 0 into copy 0: the index
     // arithmetic of the later slots then runs under the first loads' flight instead of ahead of it. (A slot whose
     // channel lies past a share of less than one chunk takes zeros from the start.)
+    // The slot tables are a launch's fixed cost and pure vector arithmetic (one loader wave per SIMD builds some thirty slots
+    // before the first byte moves), so what all channels of a chunk share is worked out once: a table in LDS - in the last
+    // staging copy, which nothing fills before the chunk loop - maps a vector position of the halo plane to the offset of
+    // its cell in channel 0 of the share (all ones: padding, a row outside the images, the plane's spare cells). A
+    // slot then takes a division, a table look-up and a multiply-add per lane instead of decoding row, column and image
+    // again for every channel (the 512-channel benchmark layer: 6.1 us until the last slot's load went out).
+    constexpr unsigned kNoCell = 0xffffffffu;
+    [[maybe_unused]] unsigned* const cell_table = reinterpret_cast<unsigned*>(lds + (DEPTH - 1) * buf_floats);
+    if constexpr (DMA) {
+        const int plane_v = a.lds_plane / VX, pitch_v = a.lds_pitch / VX;
+        for (int v = tid; v < plane_v; v += 64 * (NWC + LW)) {
+            const int row = small_div(v, a.inv_row_vecs);
+            const int col = (v - __mul24(row, pitch_v)) * VX - a.col_shift - a.pad_w;
+            int n, h;
+            image_row(row, n, h);
+            const bool cell = row < a.lds_rows && col >= 0 && col < a.W && n < a.N && h >= 0 && h < a.H;
+            // (x holds fewer than 2^31 elements: the offset of a valid cell fits 32 bits)
+            cell_table[v] = cell ? (static_cast<unsigned>(n) * a.C * a.H + h) * a.W + col : kNoCell;
+        }
+        __syncthreads();
+    }
+    // A direct load writes LDS, so no table look-up may move across one, and a wave that builds and fetches slot by slot
+    // runs one short dependent chain after the other (measured: ~400 cycles per slot either way). Hence groups of eight:
+    // eight pointers are worked out side by side, branch-free, then their eight loads go out.
     auto build_direct_slots = [&]() {
         static_assert(!DMA || VW == 4, "filters move as dwordx4");
-        const int plane_v = a.lds_plane / VX, pitch_v = a.lds_pitch / VX;
-        auto build_x = [&](auto ic) {
+        const int plane_v = a.lds_plane / VX;
+        auto point_x = [&](auto ic) {
             constexpr int i = decltype(ic)::value;
-            const int start = x_position(i);
-            const int e = start + lane;
-            xp[i] = a.zeros;
-            if constexpr (XSTEPS) xstep[i] = 0;
-            if (e < a.x_items) {
-                const int c_l = small_div(e, a.inv_slot_c);
-                const int rem = e - __mul24(c_l, plane_v);
-                const int row = small_div(rem, a.inv_row_vecs);
-                const int col = (rem - __mul24(row, pitch_v)) * VX - a.col_shift - a.pad_w;
-                int n, h;
-                image_row(row, n, h);
-                if (row < a.lds_rows && col >= 0 && col < a.W && n < a.N && h >= 0 && h < a.H && c_l < C_l) {
-                    // (x holds fewer than 2^31 elements: the offset of a valid cell fits 32 bits)
-                    xp[i] = x_share + ((static_cast<unsigned>(n * a.C + c_l) * a.H + h) * a.W + col);
-                    if constexpr (XSTEPS) xstep[i] = 4u * CC * a.HW;
-                }
-            }
-            slot_fetch(IntC<i>{}, 0);
+            const int e = x_position(i) + lane;
+            const int c_l = small_div(e, a.inv_slot_c);
+            const unsigned off = cell_table[e - __mul24(c_l, plane_v)];  // (e stays inside the CC planes and their round-up: the index is below plane_v)
+            const bool cell = e < a.x_items && off != kNoCell && c_l < C_l;
+            xp[i] = cell ? x_share + (off + static_cast<unsigned>(c_l) * a.HW) : a.zeros;
+            if constexpr (XSTEPS) xstep[i] = cell ? 4u * CC * a.HW : 0u;
         };
-        auto build_w = [&](auto ic) {
+        auto point_w = [&](auto ic) {
             constexpr int i = decltype(ic)::value;
-            const int start = w_position(i);
-            const int e = start + lane;
-            wq[i] = a.zeros;
-            if constexpr (STEPS) wstep[i] = 0;
-            const int kl = e / WPV;
+            const int e = w_position(i) + lane;  // (below 2^16: small_div is exact)
+            const int kl = small_div(e, 1.0f / WPV);
             const int ev = e - kl * WPV;
-            if (kl < TK && ev < WPV - 1 && k0 + kl < a.K && ev * 4 < C_l * RS) {
-                wq[i] = w_share + static_cast<size_t>(k0 + kl) * a.CRS + ev * 4;
-                if constexpr (STEPS) wstep[i] = CC * RS * 4;
-            }
-            slot_fetch(IntC<XS + i>{}, 0);
+            const bool cell = kl < TK && ev < WPV - 1 && k0 + kl < a.K && ev * 4 < C_l * RS;
+            // (w holds fewer than 2^31 elements)
+            wq[i] = cell ? w_share + (static_cast<unsigned>(k0 + kl) * a.CRS + ev * 4) : a.zeros;
+            if constexpr (STEPS) wstep[i] = cell ? CC * RS * 4 : 0;
         };
-        [&]<int... Is>(std::integer_sequence<int, Is...>) { (build_x(IntC<Is>{}), ...); }(std::make_integer_sequence<int, DMA ? XS : 0>{});
-        [&]<int... Is>(std::integer_sequence<int, Is...>) { (build_w(IntC<Is>{}), ...); }(std::make_integer_sequence<int, DMA ? WS : 0>{});
+        constexpr int G = 8;
+        for_range<0, (XS + G - 1) / G>([&](auto gc) {
+            constexpr int lo = decltype(gc)::value * G, hi = lo + G < XS ? lo + G : XS;
+            for_range<lo, hi>(point_x);
+            for_range<lo, hi>([&](auto ic) { slot_fetch(ic, 0); });
+        });
+        for_range<0, (WS + G - 1) / G>([&](auto gc) {
+            constexpr int lo = decltype(gc)::value * G, hi = lo + G < WS ? lo + G : WS;
+            for_range<lo, hi>(point_w);
+            for_range<lo, hi>([&](auto ic) { slot_fetch(IntC<XS + decltype(ic)::value>{}, 0); });
+        });
     };
     if constexpr (DMA) {
         if constexpr (LW == 0) build_direct_slots();  // chunk 0 goes out here too (with loader waves: theirs, where their role starts)
@@ -489,7 +520,7 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     int xb[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        const int d = min((wp * NT + t) * 16 + j, g_end - 1 - g0);  // pixel g0 + d
+        const int d = min((wp * NT + t) * 16 + ((TAIL && t == NT - 1) ? (j & 3) : j), g_end - 1 - g0);  // pixel g0 + d
         int q = q0 + d;  // below Q + the tile: small
         const int dp = small_div(q, a.inv_Q);
         q -= __mul24(dp, a.Q);
@@ -578,7 +609,8 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
                 for (int m = 0; m < MT; ++m)
 #pragma unroll
                     for (int t = 0; t < NT; ++t)
-                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(o.a[i][m], o.b[i][t], acc[m][t], 0, 0, 0);
+                        if (TAIL && t == NT - 1) acc[m][t] = __builtin_amdgcn_mfma_f32_4x4x1f32(o.a[i][m], o.b[i][t], acc[m][t], 0, 0, 0);
+                        else acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(o.a[i][m], o.b[i][t], acc[m][t], 0, 0, 0);
         };
         // Unit ui: read the operands of unit ui+1, move this unit's share of the staging slots
         // (write chunk ch+1 to the other copy, refill with chunk ch+2), multiply.
@@ -654,6 +686,23 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
 #pragma unroll
         for (int v = 0; v < 4; ++v)
             bk[m][v] = a.bias ? a.bias[min(k0 + (wk * MT + m) * 16 + 4 * kq + v, a.K - 1)] : 0.f;
+    // Four-pixel tail: lane (c, quad, pixel) holds the sum over its one channel c of every 4-channel group, for output
+    // channels 4*quad .. 4*quad+3 and the tail's pixel lane & 3. Adding the lanes 16 and 32 apart completes the sums (in
+    // every lane; the c = 0 lanes store them).
+    const int quad = (lane >> 2) & 3;
+    float bt[TAIL ? MT : 1][4];
+    if constexpr (TAIL) {
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float s = acc[m][NT - 1][v];
+                s += __shfl_xor(s, 16, 64);
+                s += __shfl_xor(s, 32, 64);
+                acc[m][NT - 1][v] = s;
+                bt[m][v] = a.bias ? a.bias[min(k0 + (wk * MT + m) * 16 + 4 * quad + v, a.K - 1)] : 0.f;
+            }
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     // Offsets in y of the lane's pixels (image n0 + dn, pixel pq of it); lanes past the end of the tile get -1.
     const int kpq = a.K * a.PQ;
@@ -661,7 +710,8 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     int yb[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        const int d = (wp * NT + t) * 16 + j;
+        const bool tail = TAIL && t == NT - 1;
+        const int d = (wp * NT + t) * 16 + (tail ? (j & 3) : j);
         int pq = pq0 + d, dn = 0;
         const int r = pq - a.PQ;
         if (r >= 0) {
@@ -669,25 +719,27 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
             dn = 1 + m;
             pq = r - __mul24(m, a.PQ);  // (m > 0 only on maps smaller than the tile)
         }
-        yb[t] = g0 + d < g_end ? dn * kpq + pq : -1;
+        yb[t] = g0 + d < g_end && !(tail && lane >= 16) ? dn * kpq + pq : -1;
     }
     // Work-groups whose channel tile lies inside K (all but the last one along K) store without a test per channel.
     const bool whole_k = k0 + TK <= a.K;
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
-        const int kbase = k0 + (wk * MT + m) * 16 + 4 * kq;
-        float* const y_row = y_tile + static_cast<size_t>(kbase) * a.PQ;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             if (yb[t] < 0) continue;
-            float* const yp = y_row + yb[t];
+            const bool tail = TAIL && t == NT - 1;
+            const int kbase = k0 + (wk * MT + m) * 16 + 4 * (tail ? quad : kq);
+            float* const yp = y_tile + static_cast<size_t>(kbase) * a.PQ + yb[t];
             if (whole_k) {
 #pragma unroll
-                for (int v = 0; v < 4; ++v) yp[static_cast<size_t>(v) * a.PQ] = finish_output(acc[m][t][v], bk[m][v], a.relu);
+                for (int v = 0; v < 4; ++v)
+                    yp[static_cast<size_t>(v) * a.PQ] = finish_output(acc[m][t][v], tail ? bt[TAIL ? m : 0][v] : bk[m][v], a.relu);
             } else {
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    if (kbase + v < a.K) yp[static_cast<size_t>(v) * a.PQ] = finish_output(acc[m][t][v], bk[m][v], a.relu);
+                    if (kbase + v < a.K)
+                        yp[static_cast<size_t>(v) * a.PQ] = finish_output(acc[m][t][v], tail ? bt[TAIL ? m : 0][v] : bk[m][v], a.relu);
             }
         }
     }
@@ -709,7 +761,7 @@ template <int VX, int VW, int DIV = 1, bool DMA = false, bool LOADER_WAVES = fal
         if constexpr (tv.deep_copies() == 0 || (tv.deep_copies() - 2) * (XS + WS) > 63) {
             return nullptr;
         } else {
-            return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, tv.occ, XS, WS, VX, VW, true, 0, tv.deep_copies()>;
+            return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, tv.occ, XS, WS, VX, VW, true, 0, tv.deep_copies(), tv.tail != 0>;
         }
     } else if constexpr (LOADER_WAVES) {
         constexpr int LW = tv.loader_waves();
@@ -720,14 +772,14 @@ template <int VX, int VW, int DIV = 1, bool DMA = false, bool LOADER_WAVES = fal
             constexpr int XS_ALL = (tv.xs_direct(VX) + DIV - 1) / DIV * tv.block();
             constexpr int WS_ALL = tv.wslots_direct(TAP_R * TAP_S) * tv.block();
             return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, (tv.block() / 64 + LW + 3) / 4,
-                                 (XS_ALL + 64 * LW - 1) / (64 * LW), (WS_ALL + 64 * LW - 1) / (64 * LW), VX, VW, true, LW>;
+                                 (XS_ALL + 64 * LW - 1) / (64 * LW), (WS_ALL + 64 * LW - 1) / (64 * LW), VX, VW, true, LW, 2, tv.tail != 0>;
         }
     } else if constexpr (DMA) {
         return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, tv.occ, (tv.xs_direct(VX) + DIV - 1) / DIV,
-                             tv.wslots_direct(TAP_R * TAP_S), VX, VW, true>;
+                             tv.wslots_direct(TAP_R * TAP_S), VX, VW, true, 0, 2, tv.tail != 0>;
     } else {
         return conv_tap_mfma<TAP_R, TAP_S, tv.MT, tv.NT, tv.WK, tv.WP, tv.WC, tv.GPC, tv.occ, (tv.xs(VX) + DIV - 1) / DIV,
-                             tv.wslots(TAP_R * TAP_S, VW), VX, VW>;
+                             tv.wslots(TAP_R * TAP_S, VW), VX, VW, false, 0, 2, tv.tail != 0>;
     }
 }
 

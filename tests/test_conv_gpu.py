@@ -125,6 +125,69 @@ def test_every_tap_variant_matches_oracle(shape, variant, loader):
         assert e.code == -6
 
 
+# Tile shapes whose last pixel tile is a four-pixel tail, multiplied by the 4x4x1 matrix instruction: every count of
+# valid tail pixels (cut 0..3) and tiles that end before the tail (cut 5, 20), tiles that start mid-row and run across
+# images, ragged K and C, every loader.
+TAIL_VARIANTS = {26: 196, 27: 100}
+TAIL_LAYERS = [
+    S("t14", 3, 20, 14, 14, 70, 3, 3, 1, 1),
+    S("t7", 9, 12, 7, 7, 33, 3, 3, 1, 1),
+    S("t1x1_14", 2, 24, 14, 14, 64, 1, 1, 0, 0),
+    S("t_w12", 2, 16, 9, 12, 40, 3, 3, 1, 1),
+    S("t_w13_c6", 2, 6, 13, 13, 17, 3, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("loader", [REGISTERS, DIRECT_LOADS, LOADER_WAVES])
+@pytest.mark.parametrize("cut", [0, 1, 2, 3, 5, 20])
+@pytest.mark.parametrize("variant", sorted(TAIL_VARIANTS))
+@pytest.mark.parametrize("shape", TAIL_LAYERS, ids=lambda s: s.name)
+def test_four_pixel_tail_tiles_match_oracle(shape, variant, cut, loader):
+    tile = TAIL_VARIANTS[variant] - cut
+    try:
+        plan, _ = _run(shape, kernel=TAP, variant=variant, tile_pix=tile, loader=loader)
+    except binding.ConvError as e:
+        # a tile that is not a whole image touches more rows than the staging slots of some loader hold, and the direct
+        # loaders need filter rows of whole dwordx4: the library must refuse, not run (the test below names cases that
+        # may not be refused)
+        assert e.code == -6
+        return
+    assert plan.variant == variant and plan.tile_pix == tile
+    with pytest.raises(binding.ConvError):
+        binding.conv_fwd_plan_request(*shape.dims, TAP, variant, TAIL_VARIANTS[variant] + 1)      # a fifth tail pixel
+
+
+def test_every_count_of_tail_pixels_runs():
+    """(No refusal may hide a tail of one, two or three pixels: these two layers take every cut.)"""
+    for variant, cap in TAIL_VARIANTS.items():
+        for cut in (0, 1, 2, 3):
+            for shape, loader in ((TAIL_LAYERS[1], LOADER_WAVES), (TAIL_LAYERS[2], REGISTERS)):
+                plan, _ = _run(shape, kernel=TAP, variant=variant, tile_pix=cap - cut, loader=loader)
+                assert plan.tile_pix == cap - cut
+
+
+def test_four_pixel_tail_tiles_are_exact_on_integers_and_take_the_epilogue():
+    shape = inputs.ConvShape("ints_tail", 3, 20, 14, 14, 70, 3, 3, 1, 1, "int", "int", 41, 42)
+    for variant, tile in TAIL_VARIANTS.items():
+        _run(shape, kernel=TAP, variant=variant, tile_pix=tile, exact=True)
+        _run(shape, kernel=TAP, variant=variant, tile_pix=tile, exact=True, loader=LOADER_WAVES)
+    shape = TAIL_LAYERS[0]
+    x, w = inputs.make_inputs(shape)
+    b = inputs.uniform_pm1(977, shape.K) * np.float32(0.5)
+    y_ref, ya_ref = oracle.conv_bias_relu_ref(x, w, b, shape.pad_h, shape.pad_w, True)
+    for variant, tile in TAIL_VARIANTS.items():
+        yd = torch.full(shape.y_shape, float("nan"), device="cuda")
+        _say(f"[case] tail bias_relu {shape.name} variant={variant}")
+        _, plan = binding.conv_fwd_bias_relu(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(b).cuda(),
+                                             shape.pad_h, shape.pad_w, True, TAP, variant, tile, y=yd)
+        torch.cuda.synchronize()
+        assert plan.variant == variant
+        y = yd.cpu().numpy().astype(np.float64)
+        assert not np.isnan(y).any()
+        ok, worst = oracle.within_tolerance(y, y_ref, ya_ref)
+        assert ok, worst
+
+
 def test_direct_loader_runs_where_it_should():
     ran = 0
     for shape in SMALL + DIRECT:
@@ -852,10 +915,10 @@ def test_every_built_tap_instance_runs_on_some_layer():
                     assert plan.variant == v and plan.loader == loader
                     ran[loader].add((R, S_, v))
                     break
-    # the builds with loader waves: the five tile shapes of eight waves at two per SIMD, for every filter size they take
+    # the builds with loader waves: the seven tile shapes of eight waves at two per SIMD, for every filter size they take
     waves_ran = set()
     for (R, S_), variants in sorted(BUILT_TAP_INSTANCES.items()):
-        for v in sorted(variants & {6, 7, 12, 19, 21}):
+        for v in sorted(variants & {6, 7, 12, 19, 21, 26, 27}):
             for N, C, H, W, tile in probes:
                 dims = (N, C, H, W, 20, R, S_, R // 2, S_ // 2)
                 try:
@@ -867,7 +930,7 @@ def test_every_built_tap_instance_runs_on_some_layer():
                 assert plan.loader == LOADER_WAVES and plan.block == 768
                 waves_ran.add((R, S_, v))
                 break
-    assert waves_ran >= {(R, S_, v) for (R, S_) in ((1, 1), (3, 3)) for v in (6, 7, 12, 19, 21)} | {(5, 5, 12)}, sorted(waves_ran)
+    assert waves_ran >= {(R, S_, v) for (R, S_) in ((1, 1), (3, 3)) for v in (6, 7, 12, 19, 21, 26, 27)} | {(5, 5, 12)}, sorted(waves_ran)
     # the builds with the deep ring of staging copies: the tile shapes whose waves hold one or two MFMA tiles
     ring_ran = set()
     for (R, S_), variants in sorted(BUILT_TAP_INSTANCES.items()):
