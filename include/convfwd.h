@@ -52,8 +52,8 @@ extern "C" {
 /* Kernel families a plan can name. */
 #define CONV_KERNEL_GENERIC 0 /* one output per thread, fp32 FMA; any R, S, padding */
 #define CONV_KERNEL_TAP 1     /* LDS halo tile + filter block, fp32 MFMA over (channel, tap). Built for 1x1 and 3x3 with all
-                                 28 tile shapes; for 5x5 with the 13 whose filter block fits the staging registers (2, 4,
-                                 8-12, 14-16, 22-24); for 1x3, 3x1, 1x5, 5x1, 1x7, 7x1, 2x2, 4x4 with shapes 2, 5, 7, 14, 16,
+                                 30 tile shapes; for 5x5 with the 14 whose filter block fits the staging registers (2, 4,
+                                 8-12, 14-16, 22-24, 28); for 1x3, 3x1, 1x5, 5x1, 1x7, 7x1, 2x2, 4x4 with shapes 2, 5, 7, 14, 16,
                                  20, 22 and for 7x7 with 2, 14, 16, 22. conv_fwd_plan_request tells whether a pair exists */
 #define CONV_KERNEL_POINTWISE 2 /* 1x1, pad 0: inputs and filters streamed HBM -> registers -> fp32 MFMA, waves split C */
 #define CONV_KERNEL_PANEL 3   /* 1x1, pad 0, batched: filters of a channel tile resident in LDS, waves stream pixel tiles */

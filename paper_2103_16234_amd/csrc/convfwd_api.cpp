@@ -183,8 +183,12 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     // loader - rows of dwordx2 on 14-wide maps, 7 x 7 maps - the shapes with two channel shares run 1-4 % faster with
     // four loader waves (32 x 256 x 14 x 14 -> 256: 76.7 -> 73.7 us; 128 x 512 x 7 x 7 -> 512: 258 -> 248 us); the shapes
     // with four shares, short layers and layers whose rows already move as direct dwordx4 lose 1-10 %.
-    if (loader == 0 && tv.loader_waves() > 0 && tv.WC == 2 && s.C % 4 == 0 && w_cap >= 4 && s.C >= 12 * tv.chunk_c() &&
-        (s.W % 4 == 2 || s.W < 13) && resolve_tap(s, variant, tile_pix, chunk_c, x_cap, w_cap, p, a, c_splits, CONV_LOADER_DIRECT_WAVES, order))
+    // (Four shares on rows of dwordx2, eight chunks or more: timed on 8 x 512 x 14 x 14 -> 512 and 16 x 256 x 14 x 14 -> 256, where
+    // the 32 x 112 shapes and their tail twins run 11-13 % faster with loader waves than with the register loader.)
+    if (loader == 0 && tv.loader_waves() > 0 && s.C % 4 == 0 && w_cap >= 4 &&
+        ((tv.WC == 2 && s.C >= 12 * tv.chunk_c() && (s.W % 4 == 2 || s.W < 13)) ||
+         (tv.WC == 4 && s.C >= 8 * tv.chunk_c() && s.W % 4 == 2)) &&
+        resolve_tap(s, variant, tile_pix, chunk_c, x_cap, w_cap, p, a, c_splits, CONV_LOADER_DIRECT_WAVES, order))
         return true;
     const int RS = s.R * s.S, TK = tv.tile_k(), BLOCK = tv.block();
     const int64_t total64 = (int64_t)s.N * s.P * s.Q;
@@ -543,7 +547,10 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
                           8.0 * p.grid;
     // Tile shapes compiled for three or four waves per SIMD measure 3-5 % faster per step of occupancy than their
     // two-wave twins even where the model sees no difference (all work-groups co-resident either way).
-    return cycles * (1.0 - 0.05 * std::max(0, tv.occ - 2));
+    // (between pixel tiles that cost the same otherwise, the one whose halo tile has fewer rows: a tile of 98 pixels of a
+    // 14 x 14 map against one of 100 - 8 x 512 x 14 x 14 -> 512 runs 5 % faster on it)
+    const double tie_break = 1.0 + 1e-3 * a.lds_rows / std::max(1, p.tile_pix);
+    return cycles * (1.0 - 0.05 * std::max(0, tv.occ - 2)) * tie_break;
 }
 
 // The deep direct loader (a ring of four staging copies) pays where a launch is one or two rounds of work-groups whose

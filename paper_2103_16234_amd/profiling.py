@@ -191,7 +191,7 @@ def counters(directory: str):
         waves = max(c["SQ_WAVES"], 1.0)
         busy = c["SQ_VALU_MFMA_BUSY_CYCLES"] / (cyc * 1024)
         at_bench = c["SQ_VALU_MFMA_BUSY_CYCLES"] / (us * 1e-6 * 2.4e9 * 1024) if us else float("nan")
-        useful = flops / (c["SQ_INSTS_MFMA"] * 2048) if c.get("SQ_INSTS_MFMA") else float("nan")
+        useful = flops / (c["SQ_VALU_MFMA_BUSY_CYCLES"] * 64) if c.get("SQ_VALU_MFMA_BUSY_CYCLES") else float("nan")
         lines.append(f"{name[:28]:<28} {waves:>7.0f} {cyc:>9.0f} {c['SQ_INSTS_MFMA']:>10.0f} {busy:>9.3f} {at_bench:>10.3f} {useful:>7.3f} "
                      f"{c['SQ_INSTS_VALU'] / waves:>9.0f} {c['SQ_INSTS_LDS'] / waves:>9.0f} {c['SQ_INSTS_MFMA'] / waves:>9.0f} "
                      f"{c['SQ_LDS_BANK_CONFLICT']:>21.0f} {us if us else float('nan'):>9.2f}")
@@ -199,8 +199,8 @@ def counters(directory: str):
     for name, c, flops, plan, us in body:
         lines.append(f"  {name[:28]:<28} kernel {plan['kernel']} variant {plan['variant']} tile_pix {plan['tile_pix']} loader {plan['loader']} "
                      f"grid {plan['grid']} block {plan['block']} lds {plan['lds_bytes']}")
-    lines += ["", "useful = the layer's 2*N*K*P*Q*C*R*S over 2048 flops per issued MFMA (16-pixel tiles that hang over the end of a pixel tile and",
-              "channel groups past C are the rest). SQ_BUSY_CYCLES and SQ_WAVE_CYCLES (per layer, in the order above):"]
+    lines += ["", "useful = the layer's 2*N*K*P*Q*C*R*S over 64 flops per busy cycle of a matrix unit (2048 per v_mfma_f32_16x16x4_f32 = 32 cycles, 512 per",
+              "v_mfma_f32_4x4x1_16B_f32 = 8 cycles; 16-pixel tiles that hang over the end of a pixel tile and channel groups past C are the rest). SQ_BUSY_CYCLES and SQ_WAVE_CYCLES (per layer, in the order above):"]
     for name, c, *_ in body:
         lines.append(f"  {name[:28]:<28} SQ_BUSY_CYCLES {c['SQ_BUSY_CYCLES']:.0f}  SQ_WAVE_CYCLES {c['SQ_WAVE_CYCLES']:.0f}")
     os.makedirs(PROFILES, exist_ok=True)
@@ -210,10 +210,10 @@ def counters(directory: str):
 
 
 # The same two figures as measured with the kernels of commit 9ec1455 (registers-or-direct loaders only, per-lane integer division in the
-# prologue): layer -> (mapping, MFMA busy under the profiler, MFMA busy at the benchmark duration, benchmark us).
+# prologue): layer -> (mapping, MFMA busy under the profiler, MFMA busy at the benchmark duration, benchmark us, useful fraction).
 EARLIER_MFMA = {
-    "cfg3_3x3_c64_56": ("variant 7 tile_pix 112 loader 2", 0.375, 0.495, 23.75),
-    "cfg5_3x3_c512_14": ("variant 6 tile_pix 196 loader 1", 0.760, 0.781, 255.58),
+    "cfg3_3x3_c64_56": ("variant 7 tile_pix 112 loader 2", 0.375, 0.495, 23.75, 1.000),
+    "cfg5_3x3_c512_14": ("variant 6 tile_pix 196 loader 1", 0.760, 0.781, 255.58, 0.942),
 }
 
 
@@ -222,14 +222,15 @@ def _mfma_utilisation(body, commands):
              "commands:"] + ["  " + c for c in commands]
     lines += ["", "MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE / 8 x 1024 SIMDs); a v_mfma_f32_16x16x4_f32 holds its SIMD's matrix unit for",
               "32 cycles. 'at bench' divides the same busy cycles by the kernel's duration in the unprofiled run (HIP events, 2.4 GHz); counter",
-              "collection slows the short kernel down. useful = the layer's flops over 2048 per issued MFMA.", "",
+              "collection slows the short kernel down. useful = the layer's flops over 64 per busy cycle (the four-pixel tail tiles of the",
+              "current kernels run v_mfma_f32_4x4x1_16B_f32: 8 cycles, 512 flops).", "",
               f"{'layer':<20} {'kernels':<10} {'mapping':<34} {'busy':>6} {'at bench':>9} {'useful':>7} {'bench us':>9}"]
     for name, c, flops, plan, us in body:
         if name not in EARLIER_MFMA:
             continue
-        m, busy0, bench0, us0 = EARLIER_MFMA[name]
-        useful = flops / (c["SQ_INSTS_MFMA"] * 2048)
-        lines.append(f"{name:<20} {'9ec1455':<10} {m:<34} {busy0:>6.3f} {bench0:>9.3f} {useful:>7.3f} {us0:>9.2f}")
+        m, busy0, bench0, us0, useful0 = EARLIER_MFMA[name]
+        useful = flops / (c["SQ_VALU_MFMA_BUSY_CYCLES"] * 64)
+        lines.append(f"{name:<20} {'9ec1455':<10} {m:<34} {busy0:>6.3f} {bench0:>9.3f} {useful0:>7.3f} {us0:>9.2f}")
         cyc = c["GRBM_GUI_ACTIVE"] / 8
         now = f"variant {plan['variant']} tile_pix {plan['tile_pix']} loader {plan['loader']}"
         lines.append(f"{name:<20} {'this tree':<10} {now:<34} {c['SQ_VALU_MFMA_BUSY_CYCLES'] / (cyc * 1024):>6.3f} "

@@ -128,7 +128,7 @@ def test_every_tap_variant_matches_oracle(shape, variant, loader):
 # Tile shapes whose last pixel tile is a four-pixel tail, multiplied by the 4x4x1 matrix instruction: every count of
 # valid tail pixels (cut 0..3) and tiles that end before the tail (cut 5, 20), tiles that start mid-row and run across
 # images, ragged K and C, every loader.
-TAIL_VARIANTS = {26: 196, 27: 100}
+TAIL_VARIANTS = {26: 196, 27: 100, 28: 100, 29: 100}
 TAIL_LAYERS = [
     S("t14", 3, 20, 14, 14, 70, 3, 3, 1, 1),
     S("t7", 9, 12, 7, 7, 33, 3, 3, 1, 1),
@@ -915,10 +915,10 @@ def test_every_built_tap_instance_runs_on_some_layer():
                     assert plan.variant == v and plan.loader == loader
                     ran[loader].add((R, S_, v))
                     break
-    # the builds with loader waves: the seven tile shapes of eight waves at two per SIMD, for every filter size they take
+    # the builds with loader waves: the nine tile shapes of eight waves at two per SIMD, for every filter size they take
     waves_ran = set()
     for (R, S_), variants in sorted(BUILT_TAP_INSTANCES.items()):
-        for v in sorted(variants & {6, 7, 12, 19, 21, 26, 27}):
+        for v in sorted(variants & {6, 7, 12, 19, 21, 26, 27, 28, 29}):
             for N, C, H, W, tile in probes:
                 dims = (N, C, H, W, 20, R, S_, R // 2, S_ // 2)
                 try:
@@ -930,7 +930,7 @@ def test_every_built_tap_instance_runs_on_some_layer():
                 assert plan.loader == LOADER_WAVES and plan.block == 768
                 waves_ran.add((R, S_, v))
                 break
-    assert waves_ran >= {(R, S_, v) for (R, S_) in ((1, 1), (3, 3)) for v in (6, 7, 12, 19, 21, 26, 27)} | {(5, 5, 12)}, sorted(waves_ran)
+    assert waves_ran >= {(R, S_, v) for (R, S_) in ((1, 1), (3, 3)) for v in (6, 7, 12, 19, 21, 26, 27, 28, 29)} | {(5, 5, 12), (5, 5, 28)}, sorted(waves_ran)
     # the builds with the deep ring of staging copies: the tile shapes whose waves hold one or two MFMA tiles
     ring_ran = set()
     for (R, S_), variants in sorted(BUILT_TAP_INSTANCES.items()):
