@@ -225,7 +225,10 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     // The direct loader moves dwordx4 or single dwords; its slots also cover the padding cells of the halo tile.
     const bool direct_fits = w_vec == 4 && (x_vec == 4 || x_vec == 1) &&
                              (int64_t)tv.chunk_c() * plane / x_vec <= (int64_t)tv.xs_direct(x_vec) * BLOCK &&
-                             (int64_t)tv.chunk_c() * s.H * s.W * 4 < ((int64_t)1 << 32);  // a slot's step from chunk to chunk, in bytes
+                             // a slot's byte offset from the first channel of its chunk in the tile's first image (x), from the
+                             // chunk's first element of the tile's first output channel (w), is kept in 32 bits
+                             ((int64_t)(rows / (s.H + 2 * s.pad_h) + 2) * s.C + tv.chunk_c()) * s.H * s.W * 4 < ((int64_t)1 << 32) - 64 &&
+                             (int64_t)TK * s.C * RS * 4 < ((int64_t)1 << 32) - 64;
     if ((loader == CONV_LOADER_DIRECT || loader_waves || deep) && !direct_fits) return false;
     // Rule, from timings of every tile shape with both loaders on the shape grid and on random layers off it: direct
     // loads win 2-16 % wherever rows move as dwordx4 (a few layers of 10 us and less lose up to 7 %); with single dwords

@@ -123,6 +123,7 @@ template <int R, int S, int MT, int NT, int WK, int WP, int WC, int GPC, int OCC
           int DEPTH = 2, bool TAIL = false>
 __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(const KernelArgs a)
 {
+#if defined(__HIP_DEVICE_COMPILE__)  // (the buffer-descriptor type below exists for the GPU only; the host needs just the kernel's symbol)
     static_assert(DEPTH == 2 || (DMA && LW == 0 && DEPTH > 2 && DEPTH <= 8), "only the direct loader of the multiplying waves runs deeper");
     static_assert((DEPTH - 2) * (XS + WS) <= 63, "the in-order load counter holds 63");
     static_assert(WC >= 1 && WC <= 16 && (WC & (WC - 1)) == 0, "the cross-wave reduction is a binary tree");
@@ -205,7 +206,7 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     const int pq0 = g0 - n0 * a.PQ;
     const int p0 = a.div_Q.div(pq0);
     const int q0 = pq0 - p0 * a.Q;
-    const int V0 = n0 * a.Hp + p0;  // first stacked padded row held in LDS
+    // (the first stacked padded row held in LDS is V0 = n0 * Hp + p0)
     // row `row` of the LDS halo tile (stacked padded row V0 + row) -> image and input row of that image
     auto image_row = [&](int row, int& n, int& h) {
         int t = p0 + row;  // padded row counted from the top of image n0; runs on into the following images
@@ -226,47 +227,39 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     constexpr int XR = DMA ? 1 : XS, WR = DMA ? 1 : WS;
     unsigned xg[XR], xl[XR], wg[WR], wl[WR];
     // Direct loads: slot i of a wave fills the vectors start .. start+63 of a region (start = x_position(i) /
-    // w_position(i), wave-uniform), lane l the l-th of them, from xp / wq; after each load the pointer moves on by
-    // xstep / wstep bytes (one chunk). Vectors that hold padding, rows outside the images, output channels past K or
-    // nothing at all are fetched from a 16-byte block of zeros, with step 0. Runs that would reach past the region
-    // start earlier and repeat part of the previous run.
-    const float* xp[DMA ? XS : 1];
-    const float* wq[DMA ? WS : 1];
-    // (Loader waves hold many more slots per thread and keep no step: a pointer that still equals the zeros' address does
-    // not move, any other moves by the chunk.)
-    constexpr bool STEPS = DMA && LW == 0;
-    // Loader waves keep the steps of their halo-tile slots too where the registers allow (up to 24 slots): the compare and
-    // select per slot and chunk that replaces a stored step is issued ahead of the matrix work of the SIMD's other waves
-    // (the 512-channel benchmark layer: 250.0 -> 247.1 us).
-    constexpr bool XSTEPS = STEPS || (DMA && LW > 0 && XS <= 24);
-    unsigned xstep[XSTEPS ? XS : 1], wstep[STEPS ? WS : 1];
+    // w_position(i), wave-uniform), lane l the l-th of them. They are buffer loads: the address is a base held in scalar
+    // registers - the first channel of the chunk being fetched, in the tile's first image (x) or first output channel (w) -
+    // plus the slot's byte offset xo / wo, which never changes; moving on to the next chunk is scalar arithmetic on the two
+    // bases, no vector instruction per slot (a 64-bit add per slot and chunk cost the 5x5 benchmark layer 4 % and the
+    // others 1-2 %). Vectors that hold padding, rows outside the images, output channels past K, channels past a ragged
+    // last chunk or nothing at all carry an offset beyond the buffer's size, for which the hardware returns zeros without
+    // touching memory; past the last chunk the size is zero and every lane gets them. Runs that would reach past the
+    // region start earlier and repeat part of the previous run.
+    constexpr unsigned kNoData = 0xfffffff0u;  // (also the buffers' size: the host keeps real offsets 64 bytes below)
+    unsigned xo[DMA ? XS : 1], wo[DMA ? WS : 1];
+    const float* const x_tile = x_share + static_cast<size_t>(n0) * a.C * a.HW;
+    const float* const w_tile = w_share + static_cast<size_t>(k0) * a.CRS;
+    auto chunk_buffer = [&](const float* base, bool live) {
+        // (stride 0: a raw buffer, offsets in bytes; the fourth word is the data format field every gfx9 descriptor carries)
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base), static_cast<short>(0), live ? kNoData : 0u, 0x00020000);
+    };
+    __amdgpu_buffer_rsrc_t x_buffer = chunk_buffer(x_tile, true), w_buffer = chunk_buffer(w_tile, true);
     constexpr int WPV = WPITCH / 4;  // vectors per output channel of the LDS filter block, the last one padding
     auto x_position = [&](int i) { return min(i * LB + lwave * 64, xs_floats / VX - 64); };  // wave-uniform
     auto w_position = [&](int i) { return min(i * LB + lwave * 64, WREG / 4 - 64); };
-    // Direct loads: fetch the slot's vectors into the staging copy at dst_floats, then step to the next chunk. (The
-    // step past the last chunk leaves a pointer that is never used: the slots are parked right after.)
+    // Direct loads: fetch the slot's vectors of the chunk the buffers stand at into the staging copy at dst_floats.
     auto slot_fetch = [&](auto kc, int dst_floats) {
         constexpr int k = decltype(kc)::value;
         if constexpr (k < XS) {
             float* const dst = lds + dst_floats + x_position(k) * VX;  // (uniform)
-            if constexpr (VX == 4) __builtin_amdgcn_global_load_lds(GLOBAL_PTR(xp[k]), LDS_PTR(dst), 16, 0, 0);
-            else __builtin_amdgcn_global_load_lds(GLOBAL_PTR(xp[k]), LDS_PTR(dst), 4, 0, 0);
-            unsigned step;
-            if constexpr (XSTEPS) step = xstep[k];
-            else step = xp[k] == a.zeros ? 0u : 4u * CC * a.HW;
-            xp[k] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(xp[k]) + step);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(x_buffer, LDS_PTR(dst), VX == 4 ? 16 : 4, xo[k], 0, 0, 0);
         } else {
             float* const dst = lds + dst_floats + xs_floats + w_position(k - XS) * 4;
-            __builtin_amdgcn_global_load_lds(GLOBAL_PTR(wq[k - XS]), LDS_PTR(dst), 16, 0, 0);
-            unsigned step;
-            if constexpr (STEPS) step = wstep[k - XS];
-            else step = wq[k - XS] == a.zeros ? 0u : static_cast<unsigned>(CC * RS * 4);
-            wq[k - XS] = reinterpret_cast<const float*>(reinterpret_cast<const char*>(wq[k - XS]) + step);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(w_buffer, LDS_PTR(dst), 16, wo[k - XS], 0, 0, 0);
         }
     };
-    // Builds the slot tables and, as soon as a slot's pointer stands, fetches its part of chunk 0 into copy 0: the index
-    // arithmetic of the later slots then runs under the first loads' flight instead of ahead of it. (A slot whose
-    // channel lies past a share of less than one chunk takes zeros from the start.)
+    // Building the slot offsets (and fetching chunk 0 into copy 0 with them; a slot whose channel lies past a share of less
+    // than one chunk gets no data from the start).
     // The slot tables are a launch's fixed cost and pure vector arithmetic (one loader wave per SIMD builds some thirty slots
     // before the first byte moves), so what all channels of a chunk share is worked out once: a table in LDS - in the last
     // staging copy, which nothing fills before the chunk loop - maps a vector position of the halo plane to the offset of
@@ -283,8 +276,8 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
             int n, h;
             image_row(row, n, h);
             const bool cell = row < a.lds_rows && col >= 0 && col < a.W && n < a.N && h >= 0 && h < a.H;
-            // (x holds fewer than 2^31 elements: the offset of a valid cell fits 32 bits)
-            cell_table[v] = cell ? (static_cast<unsigned>(n) * a.C * a.H + h) * a.W + col : kNoCell;
+            // (the host checked that the images a tile touches span less than 2^32 bytes)
+            cell_table[v] = cell ? (static_cast<unsigned>(n - n0) * a.C * a.H + h) * a.W + col : kNoCell;  // (from x_tile)
         }
         __syncthreads();
     }
@@ -300,8 +293,7 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
             const int c_l = small_div(e, a.inv_slot_c);
             const unsigned off = cell_table[e - __mul24(c_l, plane_v)];  // (e stays inside the CC planes and their round-up: the index is below plane_v)
             const bool cell = e < a.x_items && off != kNoCell && c_l < C_l;
-            xp[i] = cell ? x_share + (off + static_cast<unsigned>(c_l) * a.HW) : a.zeros;
-            if constexpr (XSTEPS) xstep[i] = cell ? 4u * CC * a.HW : 0u;
+            xo[i] = cell ? 4u * (off + static_cast<unsigned>(c_l) * a.HW) : kNoData;
         };
         auto point_w = [&](auto ic) {
             constexpr int i = decltype(ic)::value;
@@ -309,18 +301,17 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
             const int kl = small_div(e, 1.0f / WPV);
             const int ev = e - kl * WPV;
             const bool cell = kl < TK && ev < WPV - 1 && k0 + kl < a.K && ev * 4 < C_l * RS;
-            // (w holds fewer than 2^31 elements)
-            wq[i] = cell ? w_share + (static_cast<unsigned>(k0 + kl) * a.CRS + ev * 4) : a.zeros;
-            if constexpr (STEPS) wstep[i] = cell ? CC * RS * 4 : 0;
+            // (the host checked that the filters of a channel tile span less than 2^32 bytes)
+            wo[i] = cell ? 4u * (static_cast<unsigned>(kl) * a.CRS + ev * 4) : kNoData;
         };
-        constexpr int G = 8;
-        for_range<0, (XS + G - 1) / G>([&](auto gc) {
-            constexpr int lo = decltype(gc)::value * G, hi = lo + G < XS ? lo + G : XS;
+        constexpr int G = 8, XN = DMA ? XS : 0, WN = DMA ? WS : 0;
+        for_range<0, (XN + G - 1) / G>([&](auto gc) {
+            constexpr int lo = decltype(gc)::value * G, hi = lo + G < XN ? lo + G : XN;
             for_range<lo, hi>(point_x);
             for_range<lo, hi>([&](auto ic) { slot_fetch(ic, 0); });
         });
-        for_range<0, (WS + G - 1) / G>([&](auto gc) {
-            constexpr int lo = decltype(gc)::value * G, hi = lo + G < WS ? lo + G : WS;
+        for_range<0, (WN + G - 1) / G>([&](auto gc) {
+            constexpr int lo = decltype(gc)::value * G, hi = lo + G < WN ? lo + G : WN;
             for_range<lo, hi>(point_w);
             for_range<lo, hi>([&](auto ic) { slot_fetch(IntC<XS + decltype(ic)::value>{}, 0); });
         });
@@ -409,43 +400,31 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
             t.store16(lds + dst_floats + (wl[k - XS] & 0xffff));
         }
     };
-    // The pointers have just reached the last chunk of a share that is not a multiple of the chunk: vectors of
-    // channels past the share come from the zeros instead.
+    // The buffers are about to stand at the last chunk of a share that is not a multiple of the chunk: vectors of
+    // channels past the share get no data from here on.
     auto zero_past_share = [&]() {
         if constexpr (DMA) {
 #pragma unroll
             for (int i = 0; i < XS; ++i) {
                 const int e = x_position(i) + lane;
-                if (e < a.x_items && last_c0 + small_div(e, a.inv_slot_c) >= C_l) xp[i] = a.zeros;
+                if (e < a.x_items && last_c0 + small_div(e, a.inv_slot_c) >= C_l) xo[i] = kNoData;
             }
 #pragma unroll
             for (int i = 0; i < WS; ++i) {
                 const int ev = (w_position(i) + lane) % WPV;
-                if (ev * 4 >= (C_l - last_c0) * RS) wq[i] = a.zeros;
+                if (ev * 4 >= (C_l - last_c0) * RS) wo[i] = kNoData;
             }
         }
     };
-    // After the loads of the last chunk have been issued, the slots still run once (the loop is branch-free): point
-    // them at the zeros, one cache line for the whole wave, instead of fetching the last chunk a second time.
-    auto park_slots = [&]() {
-        if constexpr (DMA) {
-#pragma unroll
-            for (int i = 0; i < XS; ++i) xp[i] = a.zeros;
-#pragma unroll
-            for (int i = 0; i < WS; ++i) wq[i] = a.zeros;
-            if constexpr (STEPS && DEPTH > 2) {  // (more than one round follows: the parked pointers must stay put)
-#pragma unroll
-                for (int i = 0; i < XS; ++i) xstep[i] = 0;
-#pragma unroll
-                for (int i = 0; i < WS; ++i) wstep[i] = 0;
-            }
-        }
-    };
-    // Direct loads, before the fetch of chunk f (the pointers stand there): the last chunk of a ragged share takes its
-    // missing channels from the zeros, and past the last chunk every slot does.
+    // Direct loads: the next fetches are those of chunk f. Past the last chunk the slots still run once (the loop is
+    // branch-free): the buffers then have size zero, and nothing is read.
     auto before_fetch = [&](int f) {
-        if (ragged && f == nchunks - 1) zero_past_share();
-        if (f == nchunks) park_slots();
+        if constexpr (DMA) {
+            if (ragged && f == nchunks - 1) zero_past_share();
+            const int fc = min(f, nchunks - 1);
+            x_buffer = chunk_buffer(x_tile + static_cast<size_t>(fc) * CC * a.HW, f < nchunks);
+            w_buffer = chunk_buffer(w_tile + fc * (CC * RS), f < nchunks);
+        }
     };
     // s_waitcnt vmcnt(n), n a constant below 64: bits 3:0 and 15:14 hold the count, the other counters are left alone
     auto wait_loads = [](auto nc) {
@@ -465,14 +444,14 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
         if (is_loader) {
             __builtin_amdgcn_s_setprio(3);  // their few instructions go ahead of the matrix work that shares the SIMD
             build_direct_slots();  // (and chunk 0 is on its way)
-            if (ragged && nchunks == 2) zero_past_share();
+            before_fetch(1);
             __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
             __syncthreads();
             for (int ch = 0; ch < nchunks; ++ch) {
                 if (ch + 1 < nchunks) {
                     const int nxt_floats = ((ch + 1) & 1) * buf_floats;
                     for_each_slot([&](auto kc) { slot_fetch(kc, nxt_floats); });
-                    if (ragged && ch + 3 == nchunks) zero_past_share();  // the pointers now stand at chunk ch+2, the last
+                    before_fetch(ch + 2);
                     __builtin_amdgcn_s_waitcnt(0x0F70);
                 }
                 __syncthreads();
@@ -743,6 +722,7 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
             }
         }
     }
+#endif
 }
 
 #ifndef TAP_R
