@@ -67,7 +67,6 @@ struct KernelArgs {
                      // of their own; 3: with deep_copies() staging copies instead of two). Then x_items counts the
                      // vectors of the LDS halo tile of a chunk, padding included (chunk_c * lds_plane / x_vec), and
                      // div_slot_c / div_row_vecs divide by lds_plane / x_vec and lds_pitch / x_vec
-    const float* zeros;  // 16 bytes of zeros in device memory (source of the padding cells for the direct loader)
     // dividers for the index arithmetic of the prologue
     FastDiv div_ktiles, div_ptiles, div_pt_all, div_PQ, div_Q, div_Hp, div_row_vecs, div_slot_c;
     // tap family: correctly rounded float reciprocals of the divisors of the per-lane index arithmetic (the divisors of
@@ -273,8 +272,6 @@ bool tap_is_built(int rs_index, int variant);
 hipError_t launch_tap(int rs_index, int variant, int x_vec, int w_vec, int grid, int lds_bytes,
                       hipStream_t stream, const KernelArgs& a);
 hipError_t launch_generic(int grid, int block, hipStream_t stream, const KernelArgs& a);
-// *zeros = 16 bytes of zeros in the current device's memory (a static device array, looked up once per device)
-hipError_t zero_block(const float** zeros);
 // *ptr = the current device's copy of the library's static scratch array (kStaticScratchBytes bytes, 256-byte aligned),
 // looked up once per device
 constexpr long long kStaticScratchBytes = 16ll << 20;

@@ -190,6 +190,10 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
          (tv.WC == 4 && s.C >= 8 * tv.chunk_c() && s.W % 4 == 2)) &&
         resolve_tap(s, variant, tile_pix, chunk_c, x_cap, w_cap, p, a, c_splits, CONV_LOADER_DIRECT_WAVES, order))
         return true;
+    // (rows of dwordx2 are not for the direct loader: by rule it takes them as dwords where that fits)
+    if (loader == 0 && s.C % 4 == 0 && w_cap >= 4 && std::min(s.W % 4 == 0 ? 4 : s.W % 2 == 0 ? 2 : 1, x_cap) == 2 &&
+        resolve_tap(s, variant, tile_pix, chunk_c, x_cap, w_cap, p, a, c_splits, CONV_LOADER_DIRECT, order))
+        return true;
     const int RS = s.R * s.S, TK = tv.tile_k(), BLOCK = tv.block();
     const int64_t total64 = (int64_t)s.N * s.P * s.Q;
     if (tile_pix == 0) tile_pix = (int)std::min<int64_t>(tv.max_pix(), total64);
@@ -205,6 +209,7 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     const bool loader_waves = loader == CONV_LOADER_DIRECT_WAVES;
     if (loader_waves && (tv.loader_waves() == 0 || w_vec != 4)) return false;
     if (loader_waves && x_vec == 2) x_vec = 1;
+    if (loader == CONV_LOADER_DIRECT && x_vec == 2) x_vec = 1;  // (on request only: the rule below never picks it)
     // The deep direct loader: the same loads, into a ring of tv.deep_copies() staging copies.
     const bool deep = loader == CONV_LOADER_DIRECT_DEEP;
     if (deep && (tv.deep_copies() == 0 || w_vec != 4)) return false;
@@ -230,14 +235,13 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
                              ((int64_t)(rows / (s.H + 2 * s.pad_h) + 2) * s.C + tv.chunk_c()) * s.H * s.W * 4 < ((int64_t)1 << 32) - 64 &&
                              (int64_t)TK * s.C * RS * 4 < ((int64_t)1 << 32) - 64;
     if ((loader == CONV_LOADER_DIRECT || loader_waves || deep) && !direct_fits) return false;
-    // Rule, from timings of every tile shape with both loaders on the shape grid and on random layers off it: direct
-    // loads win 2-16 % wherever rows move as dwordx4 (a few layers of 10 us and less lose up to 7 %); with single dwords
-    // (maps of odd width) they win 5-20 % on layers of 0.6 GFLOP and more on maps 13 wide and wider, while shorter
-    // layers lose up to 17 % (one chunk of look-ahead instead of two) and 7x7 maps never gain (their LDS tile holds
-    // almost as much padding as data).
-    const double flops = 2.0 * s.N * s.K * s.P * s.Q * s.C * RS;
-    const bool direct = loader == CONV_LOADER_DIRECT || loader_waves || deep ||
-                        (loader == 0 && direct_fits && (x_vec == 4 || (s.W >= 13 && flops >= 6e8)));
+    // Rule: direct loads wherever they fit. (With a pointer and a 64-bit add per slot and chunk they lost to the register
+    // loader on short layers with rows of single dwords and on 7x7 maps; as buffer loads with a constant offset per slot
+    // they win almost everywhere - the cost model's best mapping under each loader, timed on the 188 3x3 / 5x5 layers of
+    // the shape grid and 113 random layers off it: where the old rule chose the register loader (84 layers) the direct
+    // loader is 11.5 % faster in the geometric mean, 10 % slower at worst (1 x 512 x 7 x 7 -> 512); rows of dwordx2 go dword
+    // by dword.)
+    const bool direct = loader == CONV_LOADER_DIRECT || loader_waves || deep || (loader == 0 && direct_fits);
 
     // The chunk is a property of the tile shape; a caller may only name that size.
     const int cc = tv.chunk_c();
@@ -540,13 +544,13 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
     const int slots = x_slots + (a.direct ? tv.wslots_direct(RS) : ceil_div(tv.tile_k() * tv.chunk_c() * RS / p.w_vec, tv.block()));
     // (with loader waves the slots are not the multiplying waves' business, but their traffic into LDS still is: measured
     // 2-4 % under the register loader on deep layers)
-    const double work = waves_per_simd * ((double)tv.tap_cycles() * tv.GPC * RS + (a.direct == 2 ? 80.0 : a.direct ? 50.0 : 110.0) * slots);  // per SIMD, chunk, work-group
+    const double work = waves_per_simd * ((double)tv.tap_cycles() * tv.GPC * RS + (a.direct == 2 ? 40.0 : a.direct ? 25.0 : 110.0) * slots);  // per SIMD, chunk, work-group
     const double staged = 4.0 * ((double)tv.chunk_c() * a.lds_rows * a.W + (double)tv.tile_k() * tv.chunk_c() * RS);
     const double chunk = std::max(std::max(cu * work / eff, batches * ((a.direct ? 1500.0 : 750.0) + work)), cu * staged / 16.0);
     // cross-wave reduction: per round of the tree every tile goes through LDS once each way (~8 cycles per 64 B with
     // the waves of a round writing at once, then reading), plus ~1000 cycles of barriers
     const double tree = tv.WC > 1 ? tv.MT * tv.NT * 128.0 * tv.WK * tv.WP * std::log2((double)tv.WC) + 1000.0 : 0.0;
-    const double cycles = a.nchunks * chunk + batches * (a.direct ? 20000.0 : 12000.0) + cu * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree) + 5000.0 +
+    const double cycles = a.nchunks * chunk + batches * (a.direct ? 13000.0 : 12000.0) + cu * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree) + 5000.0 +
                           8.0 * p.grid;
     // Tile shapes compiled for three or four waves per SIMD measure 3-5 % faster per step of occupancy than their
     // two-wave twins even where the model sees no difference (all work-groups co-resident either way).
@@ -724,7 +728,7 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_pl
 // a dependent launch (~10000 cycles), ~500 per share and the traffic of the partial outputs (fitted to timings of
 // every tile shape x pixel tile x share count on the batch-1 layers of the shape grid; shares that would put more
 // than two work-groups on a CU never won there and are not considered).
-constexpr double kSplitPassCycles = 10000.0;
+constexpr double kSplitPassCycles = 6000.0;
 constexpr double kSplitShareCycles = 500.0;
 constexpr int kSplitCandidates[] = {1, 2, 3, 4, 6, 8, 12, 16};
 void search_split_plans(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, KernelArgs* a);
@@ -809,10 +813,6 @@ int launch(const conv_plan_t& p, KernelArgs& a, const Shape& s, const float* x, 
 {
     a.x = x; a.w = w; a.y = y; a.bias = bias; a.relu = relu;
     hipStream_t stream = g_stream;
-    if (p.kernel == CONV_KERNEL_TAP && a.direct) {
-        const hipError_t e = zero_block(&a.zeros);
-        if (e != hipSuccess) return record_hip(e);
-    }
     if (p.kernel == CONV_KERNEL_TAP)
         return record_hip(launch_tap(tap_rs_index(s), p.variant, p.x_vec, p.w_vec, p.grid, p.lds_bytes, stream, a));
     if (p.kernel == CONV_KERNEL_POINTWISE) return record_hip(launch_pointwise(p.variant, p.x_vec, p.grid, p.lds_bytes, stream, a));

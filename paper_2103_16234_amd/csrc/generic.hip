@@ -47,27 +47,6 @@ __global__ void __launch_bounds__(256) scratch_fill(float4* p, long long n16)
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) p[i] = float4{0.f, 0.f, 0.f, 0.f};
 }
 
-__device__ __attribute__((aligned(16))) float g_zero_block[4];  // static storage: zeros, never written
-
-hipError_t zero_block(const float** zeros)
-{
-    static std::atomic<const float*> known[kMaxDevices] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
-    const float* p = known[dev].load(std::memory_order_acquire);
-    if (!p) {
-        void* q = nullptr;
-        e = hipGetSymbolAddress(&q, HIP_SYMBOL(g_zero_block));
-        if (e != hipSuccess) return e;
-        p = static_cast<const float*>(q);
-        known[dev].store(p, std::memory_order_release);
-    }
-    *zeros = p;
-    return hipSuccess;
-}
-
 // Scratch of conv_fwd_split_c_static, the entry point for callers that cannot allocate: the partial output tensors
 // of the channel shares live here instead of in a caller's workspace. Every GPU the library runs on holds its own copy
 // until the process ends. The name stands for the array in host code only as a symbol: its device address is looked up

@@ -28,12 +28,13 @@
 //   * waves can split the channels of a chunk (WC) and each own a larger tile, which cuts the LDS
 //     reads per MFMA; their partial tiles are added through LDS in a fixed order at the end.
 //
-//   * the second loader (template flag DMA) skips the registers: global_load_lds moves 64 consecutive dwordx4 (or
-//     dwords) per wave instruction from 64 arbitrary addresses straight into LDS. A slot is then a run of 64
-//     vectors of a staging copy, padding cells included (those lanes read a block of zeros, so nothing is ever
-//     zero-filled or masked), one pointer and one step per slot instead of a table entry and a data register,
-//     no LDS store instructions, and chunk ch+1 is fetched while chunk ch is multiplied (one chunk of look-ahead:
-//     long layers gain, short latency-bound ones prefer the register loader's two).
+//   * the second loader (template flag DMA) skips the registers: a buffer load with the lds modifier moves 64
+//     consecutive dwordx4 (or dwords) per wave instruction from 64 arbitrary offsets straight into LDS. A slot is then
+//     a run of 64 vectors of a staging copy, padding cells included (those lanes carry an offset past the buffer's end
+//     and receive zeros, so nothing is ever zero-filled or masked), one constant offset per slot instead of a table
+//     entry and a data register, no LDS store instructions, no address arithmetic per chunk, and chunk ch+1 is fetched
+//     while chunk ch is multiplied (one chunk of look-ahead: long layers gain, short latency-bound ones prefer the
+//     register loader's two).
 //
 // Compiled once per (filter size, tile shape): TAP_R, TAP_S, TAP_VARIANT come from the build.
 #include "conv_internal.h"
@@ -45,7 +46,6 @@ namespace convfwd {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 template <int V> struct Vec;

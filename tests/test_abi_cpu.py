@@ -245,20 +245,20 @@ def test_tap_plans_name_their_loader():
     for dims, want in [((8, 64, 56, 56, 64, 3, 3, 1, 1), direct),        # rows of whole dwordx4
                        ((1, 48, 28, 28, 128, 5, 5, 2, 2), direct),
                        ((1, 256, 13, 13, 384, 3, 3, 1, 1), binding.CONV_LOADER_DIRECT_DEEP),  # one round of work-groups, 8 chunks
-                       ((1, 128, 13, 13, 384, 3, 3, 1, 1), registers),   # odd width, 0.15 GFLOP
-                       ((8, 256, 13, 13, 384, 3, 3, 1, 1), direct),      # odd width, 2.4 GFLOP
-                       ((32, 192, 7, 7, 384, 3, 3, 1, 1), registers),    # 7x7 maps: more padding than data in LDS
+                       ((1, 128, 13, 13, 384, 3, 3, 1, 1), direct),      # odd width: rows of single dwords
+                       ((8, 256, 13, 13, 384, 3, 3, 1, 1), direct),
+                       ((32, 192, 7, 7, 384, 3, 3, 1, 1), direct),       # 7x7 maps
                        ((32, 512, 14, 14, 512, 3, 3, 1, 1), binding.CONV_LOADER_DIRECT_WAVES),  # rows of dwordx2, deep: loader waves
                        ((32, 64, 14, 14, 64, 3, 3, 1, 1), binding.CONV_LOADER_DIRECT_DEEP),   # 392 work-groups of 16 x 64, 8 chunks
-                       ((64, 32, 14, 14, 64, 3, 3, 1, 1), registers),    # rows of dwordx2, four chunks, 784 work-groups
-                       ((8, 3, 224, 224, 64, 3, 3, 1, 1), registers)]:   # 3 input channels
+                       ((64, 32, 14, 14, 64, 3, 3, 1, 1), direct),       # rows of dwordx2 go dword by dword
+                       ((8, 3, 224, 224, 64, 3, 3, 1, 1), registers)]:   # 3 input channels: dword filter rows
         plan = binding.conv_fwd_plan(*dims)
         assert plan.kernel == tap and plan.loader == want, (dims, plan.as_dict())
         for loader in (registers, direct):
             try:
                 other, _ = binding.conv_fwd_plan_request(*dims, tap, plan.variant, plan.tile_pix, loader=loader)
             except binding.ConvError as e:
-                assert e.code == -6 and loader == direct and (dims[1] % 4 != 0 or dims[3] % 4 == 2), (dims, loader)
+                assert e.code == -6 and loader == direct and dims[1] % 4 != 0, (dims, loader)
                 continue
             assert other.loader == loader and other.grid == plan.grid
             assert other.block == plan.block - (256 if plan.loader == 3 else 0)

@@ -191,7 +191,7 @@ def test_four_pixel_tail_tiles_are_exact_on_integers_and_take_the_epilogue():
 def test_direct_loader_runs_where_it_should():
     ran = 0
     for shape in SMALL + DIRECT:
-        can = shape.C % 4 == 0 and (shape.W % 4 == 0 or shape.W % 2 == 1)
+        can = shape.C % 4 == 0                 # (rows of dwordx2 go dword by dword when the direct loader is asked for by name)
         for variant in (2, 4, 7, 23):
             try:
                 plan, _ = binding.conv_fwd_plan_request(*shape.dims, TAP, variant, 0, 0, DIRECT_LOADS)
@@ -201,13 +201,13 @@ def test_direct_loader_runs_where_it_should():
             assert can and plan.loader == DIRECT_LOADS and plan.x_vec in (1, 4) and plan.w_vec == 4
             ran += 1
     assert ran >= 30
-    # the default: direct wherever rows move as dwordx4, on odd widths only for layers with enough work
+    # the default: direct wherever filter rows are whole dwordx4 (rows of the maps as dwordx4 or as single dwords)
     assert binding.conv_fwd_plan(8, 64, 56, 56, 64, 3, 3, 1, 1).loader == DIRECT_LOADS
-    assert binding.conv_fwd_plan(1, 128, 13, 13, 384, 3, 3, 1, 1).loader == REGISTERS
+    assert binding.conv_fwd_plan(1, 128, 13, 13, 384, 3, 3, 1, 1).loader == DIRECT_LOADS
     assert binding.conv_fwd_plan(1, 256, 13, 13, 384, 3, 3, 1, 1).loader == DEEP_RING      # one round of work-groups, 8 chunks
     assert binding.conv_fwd_plan(32, 256, 13, 13, 384, 3, 3, 1, 1).loader == DIRECT_LOADS
     assert binding.conv_fwd_plan(32, 512, 14, 14, 512, 3, 3, 1, 1).loader == LOADER_WAVES   # deep, rows of dwordx2
-    assert binding.conv_fwd_plan(64, 32, 14, 14, 64, 3, 3, 1, 1).loader == REGISTERS
+    assert binding.conv_fwd_plan(64, 32, 14, 14, 64, 3, 3, 1, 1).loader == DIRECT_LOADS
     assert binding.conv_fwd_plan(32, 64, 14, 14, 64, 3, 3, 1, 1).loader == DEEP_RING        # 392 work-groups of 16 x 64
     assert binding.conv_fwd_plan(8, 3, 224, 224, 64, 3, 3, 1, 1).loader == REGISTERS   # C = 3: dword filter rows
 
