@@ -519,17 +519,21 @@ void resolve_generic(const Shape& s, conv_plan_t* p, KernelArgs* a)
 // longest of
 //   all its matrix work          (cu x per-SIMD cycles: 32 per MFMA plus ~110 per staging slot of a thread - the
 //                                 load, the LDS store and their address arithmetic take issue slots from the
-//                                 matrix instructions - or ~50 per slot of the direct loader, which has no LDS
-//                                 store and no masking; issue efficiency 0.88 with two or more waves per SIMD,
-//                                 0.64 with one),
+//                                 matrix instructions - or ~25 per slot of the direct loader, which has no LDS
+//                                 store, no masking and no address arithmetic (40 with loader waves: their traffic
+//                                 into LDS is still the multiplying waves' business); issue efficiency 0.88 with
+//                                 two or more waves per SIMD, 0.64 with one),
 //   its latency chains           (one per batch of co-resident work-groups: ~750 cycles from a staging load's
 //                                 issue to its data sitting in LDS behind the barrier - 1500 for the direct loader,
 //                                 whose loads run one chunk ahead instead of two - plus the chunk's own work), and
 //   its staging traffic          (halo rows + filter block into LDS, ~16 B/clk per CU);
-// every batch of co-resident work-groups adds ~12000 cycles of prologue and epilogue (first loads, LDS fill; 20000
+// every batch of co-resident work-groups adds ~12000 cycles of prologue and epilogue (first loads, LDS fill; 17000
 // with the direct loader, which cannot start chunk 1 before chunk 0 has landed), every work-group its reduction tree
 // and stores (~32 B/clk), the launch ~5000 and the dispatcher ~8 per work-group. Constants fitted to timings of every
-// tile shape x candidate pixel tile x loader on the 3x3 / 5x5 layers of the shape grid and on 84 random layers off it.
+// tile shape x candidate pixel tile x loader on the 3x3 / 5x5 layers of the shape grid and on 84 random layers off it;
+// the direct loader's (once 50 and 80 per slot, 20000 per batch) were lowered by hand when its loads became buffer loads
+// with constant offsets, and checked against the mappings conv_fwd_find measures on the same layers (default / found
+// 1.03 in the geometric mean before and after).
 double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv, int RS)
 {
     const int by_regs = std::max(1, tv.occ * 256 / tv.block());
@@ -550,7 +554,7 @@ double tap_cost(const conv_plan_t& p, const KernelArgs& a, const TapVariant& tv,
     // cross-wave reduction: per round of the tree every tile goes through LDS once each way (~8 cycles per 64 B with
     // the waves of a round writing at once, then reading), plus ~1000 cycles of barriers
     const double tree = tv.WC > 1 ? tv.MT * tv.NT * 128.0 * tv.WK * tv.WP * std::log2((double)tv.WC) + 1000.0 : 0.0;
-    const double cycles = a.nchunks * chunk + batches * (a.direct ? 13000.0 : 12000.0) + cu * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree) + 5000.0 +
+    const double cycles = a.nchunks * chunk + batches * (a.direct ? 17000.0 : 12000.0) + cu * (4.0 * tv.tile_k() * p.tile_pix / 32.0 + tree) + 5000.0 +
                           8.0 * p.grid;
     // Tile shapes compiled for three or four waves per SIMD measure 3-5 % faster per step of occupancy than their
     // two-wave twins even where the model sees no difference (all work-groups co-resident either way).
@@ -725,7 +729,8 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_pl
 
 // Channel-splitting mode: as the tap branch of plan_shape_uncached, with the number of channel shares as a third
 // search dimension. The model sees a share as a layer with fewer chunks and more work-groups; the second pass costs
-// a dependent launch (~10000 cycles), ~500 per share and the traffic of the partial outputs (fitted to timings of
+// a dependent launch (~6000 cycles; 10000 until the direct loader's buffer loads made the unsplit kernels faster than
+// the model's picture of a split one), ~500 per share and the traffic of the partial outputs (fitted to timings of
 // every tile shape x pixel tile x share count on the batch-1 layers of the shape grid; shares that would put more
 // than two work-groups on a CU never won there and are not considered).
 constexpr double kSplitPassCycles = 6000.0;

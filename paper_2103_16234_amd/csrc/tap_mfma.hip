@@ -266,9 +266,48 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     // its cell in channel 0 of the share (all ones: padding, a row outside the images, the plane's spare cells). A
     // slot then takes a division, a table look-up and a multiply-add per lane instead of decoding row, column and image
     // again for every channel (the 512-channel benchmark layer: 6.1 us until the last slot's load went out).
+    // A direct load writes LDS, so no table look-up may move across one, and a wave that builds and fetches slot by slot
+    // runs one short dependent chain after the other (measured: ~400 cycles per slot either way). Hence groups of eight:
+    // eight pointers are worked out side by side, branch-free, then their eight loads go out.
     constexpr unsigned kNoCell = 0xffffffffu;
     [[maybe_unused]] unsigned* const cell_table = reinterpret_cast<unsigned*>(lds + (DEPTH - 1) * buf_floats);
+    static_assert(!DMA || VW == 4, "filters move as dwordx4");
+    constexpr int G = 8, XN = DMA ? XS : 0, WN = DMA ? WS : 0;
+    auto build_x_slots = [&]() {
+        const int plane_v = a.lds_plane / VX;
+        auto point_x = [&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            const int e = x_position(i) + lane;
+            const int c_l = small_div(e, a.inv_slot_c);
+            const unsigned off = cell_table[e - __mul24(c_l, plane_v)];  // (e stays inside the CC planes and their round-up: the index is below plane_v)
+            const bool cell = e < a.x_items && off != kNoCell && c_l < C_l;
+            xo[i] = cell ? 4u * (off + static_cast<unsigned>(c_l) * a.HW) : kNoData;
+        };
+        for_range<0, (XN + G - 1) / G>([&](auto gc) {
+            constexpr int lo = decltype(gc)::value * G, hi = lo + G < XN ? lo + G : XN;
+            for_range<lo, hi>(point_x);
+            for_range<lo, hi>([&](auto ic) { slot_fetch(ic, 0); });
+        });
+    };
+    // (The filter slots need no table: their part of chunk 0 goes out first, before the table's barrier.)
+    auto build_w_slots = [&]() {
+        auto point_w = [&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            const int e = w_position(i) + lane;  // (below 2^16: small_div is exact)
+            const int kl = small_div(e, 1.0f / WPV);
+            const int ev = e - kl * WPV;
+            const bool cell = kl < TK && ev < WPV - 1 && k0 + kl < a.K && ev * 4 < C_l * RS;
+            // (the host checked that the filters of a channel tile span less than 2^32 bytes)
+            wo[i] = cell ? 4u * (static_cast<unsigned>(kl) * a.CRS + ev * 4) : kNoData;
+        };
+        for_range<0, (WN + G - 1) / G>([&](auto gc) {
+            constexpr int lo = decltype(gc)::value * G, hi = lo + G < WN ? lo + G : WN;
+            for_range<lo, hi>(point_w);
+            for_range<lo, hi>([&](auto ic) { slot_fetch(IntC<XS + decltype(ic)::value>{}, 0); });
+        });
+    };
     if constexpr (DMA) {
+        if (LW == 0 || is_loader) build_w_slots();
         const int plane_v = a.lds_plane / VX, pitch_v = a.lds_pitch / VX;
         for (int v = tid; v < plane_v; v += 64 * (NWC + LW)) {
             const int row = small_div(v, a.inv_row_vecs);
@@ -279,45 +318,11 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
             // (the host checked that the images a tile touches span less than 2^32 bytes)
             cell_table[v] = cell ? (static_cast<unsigned>(n - n0) * a.C * a.H + h) * a.W + col : kNoCell;  // (from x_tile)
         }
-        __syncthreads();
+        // (a bare barrier: __syncthreads() carries a fence, before which the compiler would wait for the filter loads just issued)
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     }
-    // A direct load writes LDS, so no table look-up may move across one, and a wave that builds and fetches slot by slot
-    // runs one short dependent chain after the other (measured: ~400 cycles per slot either way). Hence groups of eight:
-    // eight pointers are worked out side by side, branch-free, then their eight loads go out.
-    auto build_direct_slots = [&]() {
-        static_assert(!DMA || VW == 4, "filters move as dwordx4");
-        const int plane_v = a.lds_plane / VX;
-        auto point_x = [&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            const int e = x_position(i) + lane;
-            const int c_l = small_div(e, a.inv_slot_c);
-            const unsigned off = cell_table[e - __mul24(c_l, plane_v)];  // (e stays inside the CC planes and their round-up: the index is below plane_v)
-            const bool cell = e < a.x_items && off != kNoCell && c_l < C_l;
-            xo[i] = cell ? 4u * (off + static_cast<unsigned>(c_l) * a.HW) : kNoData;
-        };
-        auto point_w = [&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            const int e = w_position(i) + lane;  // (below 2^16: small_div is exact)
-            const int kl = small_div(e, 1.0f / WPV);
-            const int ev = e - kl * WPV;
-            const bool cell = kl < TK && ev < WPV - 1 && k0 + kl < a.K && ev * 4 < C_l * RS;
-            // (the host checked that the filters of a channel tile span less than 2^32 bytes)
-            wo[i] = cell ? 4u * (static_cast<unsigned>(kl) * a.CRS + ev * 4) : kNoData;
-        };
-        constexpr int G = 8, XN = DMA ? XS : 0, WN = DMA ? WS : 0;
-        for_range<0, (XN + G - 1) / G>([&](auto gc) {
-            constexpr int lo = decltype(gc)::value * G, hi = lo + G < XN ? lo + G : XN;
-            for_range<lo, hi>(point_x);
-            for_range<lo, hi>([&](auto ic) { slot_fetch(ic, 0); });
-        });
-        for_range<0, (WN + G - 1) / G>([&](auto gc) {
-            constexpr int lo = decltype(gc)::value * G, hi = lo + G < WN ? lo + G : WN;
-            for_range<lo, hi>(point_w);
-            for_range<lo, hi>([&](auto ic) { slot_fetch(IntC<XS + decltype(ic)::value>{}, 0); });
-        });
-    };
     if constexpr (DMA) {
-        if constexpr (LW == 0) build_direct_slots();  // chunk 0 goes out here too (with loader waves: theirs, where their role starts)
+        if constexpr (LW == 0) build_x_slots();  // chunk 0 goes out here too (with loader waves: theirs, where their role starts)
     } else {
         const int XV = a.W / VX;
         const int per_c = a.lds_rows * XV;
@@ -443,7 +448,7 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     if constexpr (LW > 0) {
         if (is_loader) {
             __builtin_amdgcn_s_setprio(3);  // their few instructions go ahead of the matrix work that shares the SIMD
-            build_direct_slots();  // (and chunk 0 is on its way)
+            build_x_slots();  // (and chunk 0 is on its way)
             before_fetch(1);
             __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
             __syncthreads();
