@@ -706,6 +706,10 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_pl
         double best = 0;
         for (int v = 0; v < kNumTapVariants; ++v) {
             const TapVariant tv = kTapVariants[v];
+            // The shapes with eight and sixteen channel shares are for deep layers: on layers of less than two of their
+            // chunks (24..80 channels on the 64-channel chunks of shape 17) most of their waves multiply padding, which the
+            // model does not see - five of the six largest misses on random layers off the grid (1.20-1.36x).
+            if (tv.WC >= 8 && s.C < 2 * tv.chunk_c()) continue;
             int cands[8];
             const int nc = tap_tile_candidates(s, tv, cands);
             for (int i = 0; i < nc; ++i) {

@@ -323,6 +323,28 @@ def test_the_set_of_built_tap_instances_is_pinned():
             binding.conv_fwd_plan_request(2, 8, 16, 16, 16, R, S, 0, 0, binding.CONV_KERNEL_TAP, 2, 16)
 
 
+def test_direct_loaders_keep_their_byte_offsets_inside_32_bits():
+    """The direct loaders address a tile's cells as a scalar base plus a 32-bit byte offset per slot: a layer whose images
+    (x) or whose channel tile of filters (w) span 4 GiB or more must not get them (host-only; nothing is launched)."""
+    tap, direct = binding.CONV_KERNEL_TAP, binding.CONV_LOADER_DIRECT
+    big_images = (2, 1 << 17, 80, 80, 16, 3, 3, 1, 1)          # one image: 2^17 * 6400 * 4 B = 3.1 GiB, and a tile may touch two
+    plan = binding.conv_fwd_plan(*big_images)
+    assert plan.loader in (0, binding.CONV_LOADER_REGISTERS), plan.as_dict()
+    for v in range(binding.conv_variant_count(tap)):
+        for loader in (direct, binding.CONV_LOADER_DIRECT_WAVES, binding.CONV_LOADER_DIRECT_DEEP):
+            with pytest.raises(binding.ConvError):
+                binding.conv_fwd_plan_request(*big_images, tap, v, 0, loader=loader)
+    big_filters = (1, 1 << 21, 4, 4, 64, 3, 3, 1, 1)            # 64 output channels of 2^21 * 9 floats: 4.5 GiB per channel tile
+    with pytest.raises(binding.ConvError):
+        binding.conv_fwd_plan_request(*big_filters, tap, 7, 16, loader=direct)       # 64-channel tile
+    narrow, _ = binding.conv_fwd_plan_request(*big_filters, tap, 2, 16, loader=direct)   # 16-channel tile: 1.1 GiB
+    assert narrow.loader == direct
+    plan = binding.conv_fwd_plan(*big_filters)
+    assert plan.loader == binding.CONV_LOADER_REGISTERS or plan.tile_k * (1 << 21) * 9 * 4 < (1 << 32) - 64, plan.as_dict()
+    small = binding.conv_fwd_plan(2, 1 << 10, 80, 80, 16, 3, 3, 1, 1)
+    assert small.kernel == tap and small.loader != binding.CONV_LOADER_REGISTERS
+
+
 def test_halo_tiles_that_cannot_fit_lds_never_reach_the_tap_kernel():
     """Padded rows of millions of floats: every size of the halo tile is computed in 64 bits, and what cannot fit LDS goes
     to the generic kernel instead of a tap launch with wrapped-around sizes (host-only; nothing is launched)."""
