@@ -99,7 +99,7 @@ class Layer:
         from paper_2103_16234_amd import binding
         req = binding.ConvPlan()
         req.kernel, req.variant, req.tile_pix, req.loader = plan.kernel, plan.variant, plan.tile_pix, plan.loader
-        req.order = plan.order
+        req.order, req.k_group = plan.order, plan.k_group
         self.request = req
 
     def measure(self, steps, warmup):

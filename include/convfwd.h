@@ -73,6 +73,9 @@ extern "C" {
 /* Work-group numbering of the tap family (conv_plan_t.order). */
 #define CONV_ORDER_CHANNEL_FAST 1
 #define CONV_ORDER_PIXEL_FAST 2
+#define CONV_ORDER_CHANNEL_GROUPS 3 /* in between: the channel tiles in groups of conv_plan_t.k_group, the pixel tiles of a group
+                                       next, then the groups - an XCD's work-groups then share some channel tiles and some pixel
+                                       tiles, and the eight L2s fetch fewer bytes in all than under either plain order */
 
 /*
  * How one layer is mapped onto the GPU. Filled by conv_fwd_plan; plain data.
@@ -103,8 +106,11 @@ typedef struct conv_plan {
     int order;           /* CONV_KERNEL_TAP: which tile index runs fastest in the work-group numbering, and so what the
                             work-groups of one XCD (one L2) share: CONV_ORDER_CHANNEL_FAST (a few pixel tiles, every
                             channel tile: the inputs are fetched once, the filters by every L2) or CONV_ORDER_PIXEL_FAST
-                            (the reverse, for layers whose filters outweigh their inputs); as a request: 0 = the
-                            planner's rule; 0 for the other families */
+                            (the reverse, for layers whose filters outweigh their inputs) or CONV_ORDER_CHANNEL_GROUPS;
+                            as a request: 0 = the planner's rule; 0 for the other families */
+    int k_group;         /* CONV_KERNEL_TAP: channel tiles that are neighbours in the work-group numbering: all of them
+                            (CHANNEL_FAST), 1 (PIXEL_FAST) or a divisor of their number in between (CHANNEL_GROUPS; as a
+                            request with that order: 0 = the group that fetches least); 0 for the other families */
     long long workspace_bytes; /* 0 unless c_splits > 1: then 4 * c_splits * N*K*P*Q */
     long long flops;     /* 2*N*K*P*Q*C*R*S */
     long long bytes;     /* 4*(N*C*H*W + K*C*R*S + N*K*P*Q): compulsory HBM traffic */

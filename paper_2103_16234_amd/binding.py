@@ -23,6 +23,7 @@ CONV_LOADER_DIRECT_WAVES = 3
 CONV_LOADER_DIRECT_DEEP = 4
 CONV_ORDER_CHANNEL_FAST = 1
 CONV_ORDER_PIXEL_FAST = 2
+CONV_ORDER_CHANNEL_GROUPS = 3
 
 EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_plan_untuned", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_fwd_find", "conv_two_stage_workspace_bytes",
            "conv_fwd_two_stage", "conv_fwd_plan_split_c", "conv_fwd_split_c", "conv_fwd_split_c_static", "conv_fwd_plan_request", "conv_probe_mfma", "conv_probe_copy",
@@ -33,7 +34,7 @@ class ConvPlan(ctypes.Structure):
     """Mirror of conv_plan_t in include/convfwd.h."""
     _fields_ = [(n, ctypes.c_int) for n in (
         "kernel", "variant", "tile_k", "tile_pix", "chunk_c", "x_vec", "w_vec", "lds_rows", "lds_pitch",
-        "lds_plane", "grid", "block", "lds_bytes", "P", "Q", "c_splits", "loader", "order")] + [
+        "lds_plane", "grid", "block", "lds_bytes", "P", "Q", "c_splits", "loader", "order", "k_group")] + [
         ("workspace_bytes", ctypes.c_longlong), ("flops", ctypes.c_longlong), ("bytes", ctypes.c_longlong)]
 
     def as_dict(self):
@@ -166,7 +167,7 @@ def conv_fwd(x, w, pad_h: int, pad_w: int, y=None, use_current_stream: bool = Tr
 
 
 def conv_fwd_planned(x, w, pad_h: int, pad_w: int, kernel: int, variant: int = 0, tile_pix: int = 0,
-                     chunk_c: int = 0, y=None, use_current_stream: bool = True, loader: int = 0):
+                     chunk_c: int = 0, y=None, use_current_stream: bool = True, loader: int = 0, order: int = 0, k_group: int = 0):
     """As conv_fwd with a requested kernel family / tile shape; returns (y, resolved ConvPlan)."""
     import torch
     y, dims = _device_args(x, w, y, pad_h, pad_w)
@@ -175,6 +176,7 @@ def conv_fwd_planned(x, w, pad_h: int, pad_w: int, kernel: int, variant: int = 0
         conv_set_stream(torch.cuda.current_stream(x.device))
     req, res = ConvPlan(), ConvPlan()
     req.kernel, req.variant, req.tile_pix, req.chunk_c, req.loader = kernel, variant, tile_pix, chunk_c, loader
+    req.order, req.k_group = order, k_group
     _check(lib.conv_fwd_planned(x.data_ptr(), w.data_ptr(), y.data_ptr(), *dims, ctypes.byref(req), ctypes.byref(res)))
     return y, res
 
@@ -202,10 +204,11 @@ def conv_fwd_bias_relu(x, w, bias, pad_h: int, pad_w: int, relu: bool, kernel=No
 
 
 def conv_fwd_plan_request(N, C, H, W, K, R, S, pad_h, pad_w, kernel: int, variant: int = 0, tile_pix: int = 0,
-                          c_splits: int = 0, loader: int = 0):
+                          c_splits: int = 0, loader: int = 0, order: int = 0, k_group: int = 0):
     """Host-only: resolve a requested mapping without launching it; returns (plan, modelled cycles - tap family only)."""
     req, res, cycles = ConvPlan(), ConvPlan(), ctypes.c_double(0)
     req.kernel, req.variant, req.tile_pix, req.c_splits, req.loader = kernel, variant, tile_pix, c_splits, loader
+    req.order, req.k_group = order, k_group
     _check(load_library().conv_fwd_plan_request(N, C, H, W, K, R, S, pad_h, pad_w, ctypes.byref(req), ctypes.byref(res),
                                                 ctypes.byref(cycles)))
     return res, float(cycles.value)

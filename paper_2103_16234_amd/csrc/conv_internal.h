@@ -55,7 +55,9 @@ struct KernelArgs {
     int nchunks;     // channel chunks (the chunk size is a property of the tile shape) of one work-group
     int split_c;     // tap family: channels one work-group reduces (a multiple of the chunk, or >= C: no splitting);
                      // work-group index = ((share * ptiles) + pixel tile) * ktiles + channel tile
-    int pixel_fast;  // tap family: nonzero = work-group index = channel tile * pt_all + (share * ptiles + pixel tile) instead,
+    int k_group;     // tap family: channel tiles per group in the work-group numbering,
+                     // index = ((group * pt_all) + (share * ptiles + pixel tile)) * k_group + channel tile within the group:
+                     // ktiles = the channel tile is the fast index, 1 = work-group index = channel tile * pt_all + (share * ptiles + pixel tile),
                      // so that the run of work-groups one XCD receives shares few channel tiles (filters) and many pixel
                      // tiles; the host picks the order that makes the eight L2s fetch fewer bytes in total
     int pt_all;      // ptiles * shares
@@ -68,7 +70,7 @@ struct KernelArgs {
                      // vectors of the LDS halo tile of a chunk, padding included (chunk_c * lds_plane / x_vec), and
                      // div_slot_c / div_row_vecs divide by lds_plane / x_vec and lds_pitch / x_vec
     // dividers for the index arithmetic of the prologue
-    FastDiv div_ktiles, div_ptiles, div_pt_all, div_PQ, div_Q, div_Hp, div_row_vecs, div_slot_c;
+    FastDiv div_ktiles, div_ptiles, div_pt_all, div_k_group, div_PQ, div_Q, div_Hp, div_row_vecs, div_slot_c;
     // tap family: correctly rounded float reciprocals of the divisors of the per-lane index arithmetic (the divisors of
     // div_slot_c and div_row_vecs, Hp, Q, P, P*Q); the dividends there are small, see small_div in the kernel
     float inv_slot_c, inv_row_vecs, inv_Hp, inv_Q, inv_P, inv_PQ;

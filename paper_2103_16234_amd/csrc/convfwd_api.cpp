@@ -143,38 +143,47 @@ int max_halo_rows(const Shape& s, int tile_pix)
 
 // Resolve a tap-family mapping. tile_pix / chunk_c of 0 mean "choose". c_splits > 1 asks for that many channel
 // shares, each reduced by work-groups of its own into a partial output tensor (fewer if C has fewer chunks).
-// The eight XCDs (one L2 each) receive contiguous runs of the work-group numbering. With the output-channel tile as
-// the fast index a run holds every channel tile of a few pixel tiles, so each L2 fetches all the filters and an eighth of
-// the inputs; with the pixel tile fast it is the other way round. Bytes all eight L2s fetch, for either order: a run of
-// `per` work-groups touches min(fast, per) indices of the fast dimension and ceil(per / fast) (+1 where runs straddle) of
-// the slow one; with channel shares (splits) a pixel index is a (share, pixel tile) pair and reads 1/splits of the
-// channels. True if the pixel-fast order fetches at least a fifth less.
-bool pixel_fast_fetches_less(const Shape& s, int ktiles, int ptiles, int splits)
+// The eight XCDs (one L2 each) receive contiguous runs of the work-group numbering, which walks a group of g channel tiles,
+// then the pixel tiles, then the groups. With g = all channel tiles a run holds every channel tile of a few pixel tiles,
+// so each L2 fetches all the filters and an eighth of the inputs; with g = 1 it is the other way round; a divisor of the
+// channel tiles in between shares both. Bytes all eight L2s fetch under a group size: a run of `per` work-groups touches
+// ceil(per / g) (+1 where runs straddle) (group, pixel tile) pairs, so that many pixel indices (at most all) of
+// ceil(pairs / pixel indices) groups; with channel shares (splits) a pixel index is a (share, pixel tile) pair and reads
+// 1/splits of the channels.
+double fetched_bytes(const Shape& s, int ktiles, int ptiles, int splits, int g)
 {
     const double pt_all = (double)ptiles * splits;
     const double per = std::max(1.0, std::ceil(ktiles * pt_all / 8.0));
     const double w_unit = 4.0 * s.K * s.C * s.R * s.S / ((double)ktiles * splits);  // one channel tile, one share
     const double x_unit = 4.0 * s.N * s.C * s.H * s.W / pt_all;                      // one pixel tile, one share
-    auto slow_cover = [&](double fast, double slow) {
-        const double whole = std::ceil(per / fast);
-        return std::min(slow, whole + ((per > fast && std::fmod(per, fast) != 0.0) ? 1.0 : 0.0));
-    };
-    // channel tile fast
-    const double p0 = slow_cover(ktiles, pt_all), k0 = std::min<double>(ktiles, per);
-    const double bytes0 = p0 * x_unit + k0 * std::min<double>(splits, std::ceil(p0 / ptiles)) * w_unit;
-    // pixel tile fast
-    const double k1 = slow_cover(pt_all, ktiles), p1 = std::min(pt_all, per);
-    const double bytes1 = p1 * x_unit + k1 * std::min<double>(splits, std::ceil(p1 / ptiles)) * w_unit;
-    return bytes1 < 0.8 * bytes0;
+    const double groups = (double)ktiles / g;
+    const double pairs = std::min(groups * pt_all, std::ceil(per / g) + ((per > g && std::fmod(per, (double)g) != 0.0) ? 1.0 : 0.0));
+    const double pix = std::min(pt_all, pairs);
+    const double grp = std::min(groups, std::ceil(pairs / pt_all) + ((pairs > pt_all && std::fmod(pairs, pt_all) != 0.0) ? 1.0 : 0.0));
+    const double kt = std::min<double>(std::min<double>(ktiles, per), grp * g);
+    return 8.0 * (pix * x_unit + kt * std::min<double>(splits, std::ceil(pix / ptiles)) * w_unit);
+}
+// Group size of the work-group numbering: all channel tiles (the channel tile is the fast index) unless another divisor
+// of their number fetches at least a fifth less; then the one that fetches least (ties: the larger group).
+int pick_k_group(const Shape& s, int ktiles, int ptiles, int splits, bool groups_only = false)
+{
+    int best = groups_only ? 0 : ktiles;
+    double best_bytes = groups_only ? 0.0 : 0.8 * fetched_bytes(s, ktiles, ptiles, splits, ktiles);
+    for (int g = ktiles - 1; g >= 1; --g) {
+        if (ktiles % g != 0 || (groups_only && g == 1)) continue;
+        const double b = fetched_bytes(s, ktiles, ptiles, splits, g);
+        if (best == 0 || b < best_bytes) { best = g; best_bytes = b; }
+    }
+    return best;
 }
 
 // Returns false if it cannot run.
 // loader: 0 = by rule, else CONV_LOADER_REGISTERS / CONV_LOADER_DIRECT. order: 0 = by rule, else CONV_ORDER_*.
 bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_cap, int w_cap,
-                 conv_plan_t* p, KernelArgs* a, int c_splits = 1, int loader = 0, int order = 0)
+                 conv_plan_t* p, KernelArgs* a, int c_splits = 1, int loader = 0, int order = 0, int k_group = 0)
 {
     if (loader < 0 || loader > CONV_LOADER_DIRECT_DEEP) return false;
-    if (order < 0 || order > CONV_ORDER_PIXEL_FAST) return false;
+    if (order < 0 || order > CONV_ORDER_CHANNEL_GROUPS || k_group < 0) return false;
     const int rs_index = tap_rs_index(s);
     if (!tap_is_built(rs_index, variant)) return false;
     const TapVariant tv = kTapVariants[variant];
@@ -188,11 +197,11 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     if (loader == 0 && tv.loader_waves() > 0 && s.C % 4 == 0 && w_cap >= 4 &&
         ((tv.WC == 2 && s.C >= 12 * tv.chunk_c() && (s.W % 4 == 2 || s.W < 13)) ||
          (tv.WC == 4 && s.C >= 8 * tv.chunk_c() && s.W % 4 == 2)) &&
-        resolve_tap(s, variant, tile_pix, chunk_c, x_cap, w_cap, p, a, c_splits, CONV_LOADER_DIRECT_WAVES, order))
+        resolve_tap(s, variant, tile_pix, chunk_c, x_cap, w_cap, p, a, c_splits, CONV_LOADER_DIRECT_WAVES, order, k_group))
         return true;
     // (rows of dwordx2 are not for the direct loader: by rule it takes them as dwords where that fits)
     if (loader == 0 && s.C % 4 == 0 && w_cap >= 4 && std::min(s.W % 4 == 0 ? 4 : s.W % 2 == 0 ? 2 : 1, x_cap) == 2 &&
-        resolve_tap(s, variant, tile_pix, chunk_c, x_cap, w_cap, p, a, c_splits, CONV_LOADER_DIRECT, order))
+        resolve_tap(s, variant, tile_pix, chunk_c, x_cap, w_cap, p, a, c_splits, CONV_LOADER_DIRECT, order, k_group))
         return true;
     const int RS = s.R * s.S, TK = tv.tile_k(), BLOCK = tv.block();
     const int64_t total64 = (int64_t)s.N * s.P * s.Q;
@@ -277,7 +286,13 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     a->direct = deep ? 3 : loader_waves ? 2 : direct ? 1 : 0;
     a->div_ktiles = make_fastdiv(a->ktiles); a->div_ptiles = make_fastdiv(a->ptiles);
     a->pt_all = a->ptiles * splits; a->div_pt_all = make_fastdiv(a->pt_all);
-    a->pixel_fast = order ? order == CONV_ORDER_PIXEL_FAST : pixel_fast_fetches_less(s, a->ktiles, a->ptiles, splits);
+    if (order == CONV_ORDER_CHANNEL_FAST) a->k_group = a->ktiles;
+    else if (order == CONV_ORDER_PIXEL_FAST) a->k_group = 1;
+    else if (order == CONV_ORDER_CHANNEL_GROUPS && k_group > 0) a->k_group = k_group;
+    else a->k_group = pick_k_group(s, a->ktiles, a->ptiles, splits, order == CONV_ORDER_CHANNEL_GROUPS);
+    // (a group must divide the channel tiles and lie strictly between the two plain orders)
+    if (order == CONV_ORDER_CHANNEL_GROUPS && (a->k_group <= 1 || a->k_group >= a->ktiles || a->ktiles % a->k_group != 0)) return false;
+    a->div_k_group = make_fastdiv(a->k_group);
     a->div_PQ = make_fastdiv(a->PQ); a->div_Q = make_fastdiv(s.Q); a->div_Hp = make_fastdiv(a->Hp);
     a->div_row_vecs = make_fastdiv(direct ? pitch / x_vec : row_vecs);
     a->div_slot_c = make_fastdiv(direct ? plane / x_vec : rows * row_vecs);
@@ -296,7 +311,8 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     fill_common(s, p);
     p->c_splits = splits;
     p->loader = deep ? CONV_LOADER_DIRECT_DEEP : loader_waves ? CONV_LOADER_DIRECT_WAVES : direct ? CONV_LOADER_DIRECT : CONV_LOADER_REGISTERS;
-    p->order = a->pixel_fast ? CONV_ORDER_PIXEL_FAST : CONV_ORDER_CHANNEL_FAST;
+    p->order = a->k_group == a->ktiles ? CONV_ORDER_CHANNEL_FAST : a->k_group == 1 ? CONV_ORDER_PIXEL_FAST : CONV_ORDER_CHANNEL_GROUPS;
+    p->k_group = a->k_group;
     if (splits > 1) p->workspace_bytes = 4LL * splits * s.K * total;
     return true;
 }
@@ -882,7 +898,7 @@ extern "C" int conv_fwd(const float* x, const float* w, float* y, int N, int C, 
 struct RequestEntry {
     Shape s;
     int x_cap, w_cap, y_cap;
-    int kernel, variant, tile_pix, chunk_c, c_splits, loader, order;
+    int kernel, variant, tile_pix, chunk_c, c_splits, loader, order, k_group;
     conv_plan_t p;
     KernelArgs a;
 };
@@ -898,7 +914,7 @@ static int resolve_request(const Shape& s, int x_cap, int w_cap, int y_cap, cons
         for (const RequestEntry& e : g_request_cache)
             if (same_shape(e.s, s) && e.x_cap == x_cap && e.w_cap == w_cap && e.y_cap == y_cap && e.kernel == req.kernel &&
                 e.variant == req.variant && e.tile_pix == req.tile_pix && e.chunk_c == req.chunk_c && e.c_splits == req.c_splits &&
-                e.loader == req.loader && e.order == req.order) {
+                e.loader == req.loader && e.order == req.order && e.k_group == req.k_group) {
                 *p = e.p; *a = e.a;
                 return CONV_OK;
             }
@@ -911,7 +927,7 @@ static int resolve_request(const Shape& s, int x_cap, int w_cap, int y_cap, cons
         resolve_generic(s, p, a);
     } else if (req.kernel == CONV_KERNEL_TAP) {
         if (req.tile_pix < 0 || req.chunk_c < 0 || req.c_splits < 0) return CONV_E_PLAN;
-        if (!resolve_tap(s, req.variant, req.tile_pix, req.chunk_c, x_cap, w_cap, p, a, std::max(1, req.c_splits), req.loader, req.order))
+        if (!resolve_tap(s, req.variant, req.tile_pix, req.chunk_c, x_cap, w_cap, p, a, std::max(1, req.c_splits), req.loader, req.order, req.k_group))
             return CONV_E_PLAN;
     } else {
         return CONV_E_PLAN;
@@ -919,7 +935,7 @@ static int resolve_request(const Shape& s, int x_cap, int w_cap, int y_cap, cons
     std::lock_guard<std::mutex> lock(g_cache_mutex);
     if (g_request_cache.size() >= kCacheEntries) g_request_cache.erase(g_request_cache.begin());
     g_request_cache.push_back(RequestEntry{s, x_cap, w_cap, y_cap, req.kernel, req.variant, req.tile_pix, req.chunk_c,
-                                           req.c_splits, req.loader, req.order, *p, *a});
+                                           req.c_splits, req.loader, req.order, req.k_group, *p, *a});
     return CONV_OK;
 }
 

@@ -170,22 +170,19 @@ __global__ void __launch_bounds__(64 * (WK * WP * WC + LW), OCC) conv_tap_mfma(c
     const int lwave = LW > 0 ? wave - NWC : wave;       // position among the waves that own staging slots
 
     // Work-groups are dealt round-robin to the 8 XCDs; renumber them so that each XCD (one L2)
-    // gets a contiguous run of tiles: neighbours share the pixel tile and walk the K tiles, or - a.pixel_fast, layers
-    // whose filters outweigh their inputs - share the K tile and walk the pixel tiles.
+    // gets a contiguous run of tiles: neighbours share the pixel tile and walk a group of a.k_group channel tiles, then
+    // the next pixel tile, and after the last one the next group (all channel tiles in one group: each L2 fetches few
+    // inputs and every filter; groups of one: the reverse, for layers whose filters outweigh their inputs).
     int L;
     {
         const int nb = gridDim.x, b = blockIdx.x;
         const int per = nb >> 3, rem = nb & 7, xcd = b & 7;
         L = xcd * per + (xcd < rem ? xcd : rem) + (b >> 3);
     }
-    int pt_all, ktile;
-    if (a.pixel_fast) {
-        ktile = a.div_pt_all.div(L);
-        pt_all = L - ktile * a.pt_all;
-    } else {
-        pt_all = a.div_ktiles.div(L);
-        ktile = L - pt_all * a.ktiles;
-    }
+    const int pair = a.div_k_group.div(L);          // (group, pixel tile)
+    const int group = a.div_pt_all.div(pair);
+    const int pt_all = pair - group * a.pt_all;
+    const int ktile = group * a.k_group + (L - pair * a.k_group);
     // Channel splitting across work-groups: share `split` reduces channels cb .. cb+C_l-1 and writes a whole
     // partial output tensor of its own (a.y then points at the workspace; a second kernel adds the shares).
     // Without splitting there is one share, all of C.

@@ -188,6 +188,29 @@ def test_four_pixel_tail_tiles_are_exact_on_integers_and_take_the_epilogue():
         assert ok, worst
 
 
+def test_every_work_group_numbering_matches_oracle():
+    """Channel tile fast, pixel tile fast and every group size in between (the numbering only decides which work-group
+    computes which tile): 6 channel tiles of 16, with and without channel shares in the grid."""
+    shape = S("order_k96", 3, 24, 9, 10, 96, 3, 3, 1, 1)
+    x, w, y_ref, ya_ref = _reference(shape)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    for order, k_group, want in ((1, 0, 6), (2, 0, 1), (3, 2, 2), (3, 3, 3), (3, 0, None), (0, 0, None)):
+        yd = torch.full(shape.y_shape, float("nan"), device="cuda")
+        _say(f"[case] {shape.name} order={order} k_group={k_group}")
+        _, plan = binding.conv_fwd_planned(xd, wd, 1, 1, TAP, 2, 32, y=yd, order=order, k_group=k_group)
+        torch.cuda.synchronize()
+        assert plan.tile_k == 16 and (want is None or plan.k_group == want) and 6 % plan.k_group == 0
+        assert plan.order == (1 if plan.k_group == 6 else 2 if plan.k_group == 1 else 3)
+        y = yd.cpu().numpy().astype(np.float64)
+        assert not np.isnan(y).any()
+        assert oracle.within_tolerance(y, y_ref, ya_ref)[0]
+    for order, k_group in ((3, 4), (3, 6), (3, 1), (4, 0)):             # not a divisor / not in between / no such order
+        with pytest.raises(binding.ConvError):
+            binding.conv_fwd_plan_request(*shape.dims, TAP, 2, 32, order=order, k_group=k_group)
+    with pytest.raises(binding.ConvError):                              # five channel tiles: no group in between
+        binding.conv_fwd_plan_request(3, 24, 9, 10, 80, 3, 3, 1, 1, TAP, 2, 32, order=3)
+
+
 def test_direct_loader_runs_where_it_should():
     ran = 0
     for shape in SMALL + DIRECT:
