@@ -193,10 +193,11 @@ bool resolve_tap(const Shape& s, int variant, int tile_pix, int chunk_c, int x_c
     // four loader waves (32 x 256 x 14 x 14 -> 256: 76.7 -> 73.7 us; 128 x 512 x 7 x 7 -> 512: 258 -> 248 us); the shapes
     // with four shares, short layers and layers whose rows already move as direct dwordx4 lose 1-10 %.
     // (Four shares on rows of dwordx2, eight chunks or more: timed on 8 x 512 x 14 x 14 -> 512 and 16 x 256 x 14 x 14 -> 256, where
-    // the 32 x 112 shapes and their tail twins run 11-13 % faster with loader waves than with the register loader.)
+    // the 32 x 112 shapes and their tail twins run 11-13 % faster with loader waves than with the register loader; against
+    // the direct loader of the multiplying waves they keep 3-5 % on these and on 7 x 7 maps: 8 x 512 x 7 x 7 -> 2048 70.9 -> 67.3 us.)
     if (loader == 0 && tv.loader_waves() > 0 && s.C % 4 == 0 && w_cap >= 4 &&
         ((tv.WC == 2 && s.C >= 12 * tv.chunk_c() && (s.W % 4 == 2 || s.W < 13)) ||
-         (tv.WC == 4 && s.C >= 8 * tv.chunk_c() && s.W % 4 == 2)) &&
+         (tv.WC == 4 && s.C >= 8 * tv.chunk_c() && (s.W % 4 == 2 || s.W < 13))) &&
         resolve_tap(s, variant, tile_pix, chunk_c, x_cap, w_cap, p, a, c_splits, CONV_LOADER_DIRECT_WAVES, order, k_group))
         return true;
     // (rows of dwordx2 are not for the direct loader: by rule it takes them as dwords where that fits)
