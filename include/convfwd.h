@@ -50,10 +50,12 @@ extern "C" {
 #define CONV_E_WORKSPACE (-7) /* the workspace given to conv_fwd_two_stage / conv_fwd_split_c is too small */
 
 /* Kernel families a plan can name. */
-#define CONV_KERNEL_GENERIC 0 /* one output per thread, fp32 FMA; any R, S, padding */
+#define CONV_KERNEL_GENERIC 0 /* one output per thread, fp32 FMA; any R, S, padding (also what maps too wide for a halo tile of
+                                 whole padded rows run: wider than ~1500 pixels for 3x3 filters on rows of whole dwordx4,
+                                 about half of that for odd widths or 5x5 filters) */
 #define CONV_KERNEL_TAP 1     /* LDS halo tile + filter block, fp32 MFMA over (channel, tap). Built for 1x1 and 3x3 with all
-                                 30 tile shapes; for 5x5 with the 14 whose filter block fits the staging registers (2, 4,
-                                 8-12, 14-16, 22-24, 28); for 1x3, 3x1, 1x5, 5x1, 1x7, 7x1, 2x2, 4x4 with shapes 2, 5, 7, 14, 16,
+                                 31 tile shapes; for 5x5 with the 15 whose filter block fits the staging registers (2, 4,
+                                 8-12, 14-16, 22-24, 28, 30); for 1x3, 3x1, 1x5, 5x1, 1x7, 7x1, 2x2, 4x4 with shapes 2, 5, 7, 14, 16,
                                  20, 22 and for 7x7 with 2, 14, 16, 22. conv_fwd_plan_request tells whether a pair exists */
 #define CONV_KERNEL_POINTWISE 2 /* 1x1, pad 0: inputs and filters streamed HBM -> registers -> fp32 MFMA, waves split C */
 #define CONV_KERNEL_PANEL 3   /* 1x1, pad 0, batched: filters of a channel tile resident in LDS, waves stream pixel tiles */

@@ -190,6 +190,7 @@ constexpr TapVariant kTapVariants[] = {
     {1, 7, 4, 1, 2, 2, 2, 3, 8, 1},   // 27: as 7 for tiles of up to 100 pixels (six tiles and a tail): 98 pixels put 8 x 56 x 56 outputs on 256 work-groups
     {1, 7, 2, 1, 4, 1, 2, 8, 12, 1},  // 28: as 12 with a tail: 32 ch x 100 px, half a 14x14 image per tile
     {1, 7, 2, 1, 4, 2, 2, 8, 12, 1},  // 29: as 19 with a tail
+    {1, 7, 1, 4, 1, 1, 1, 16, 32},    // 30: as 16 with twice the staging slots and the whole LDS (one work-group per CU): maps 600 to ~1200 pixels wide, which no other shape's halo tile takes
 };
 constexpr int kNumTapVariants = sizeof(kTapVariants) / sizeof(kTapVariants[0]);
 
@@ -206,7 +207,7 @@ constexpr int tap_x_slot_divisor(const TapVariant& tv, int x_vec, int w_vec, int
     if (x_vec == 1 && (full + 3) / 4 >= need) return 4;
     return (full + 1) / 2 >= need ? 2 : 1;
 }
-#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18) X(19) X(20) X(21) X(22) X(23) X(24) X(25) X(26) X(27) X(28) X(29)
+#define TAP_VARIANT_LIST(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18) X(19) X(20) X(21) X(22) X(23) X(24) X(25) X(26) X(27) X(28) X(29) X(30)
 
 // Filter sizes the tap kernel is instantiated for. The three the paper evaluates (Section 4: 1x1, 3x3, 5x5) get every
 // tile shape; the others (filter rows and columns, even and 7x7 filters, as the factorised layers of later CNNs use)

@@ -671,8 +671,9 @@ int plan_shape(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, 
     return rc;
 }
 
-// Candidate pixel tiles of a tap tile shape: full capacity, an even split, whole images, whole rows, halves, quarters.
-int tap_tile_candidates(const Shape& s, const TapVariant& tv, int (&cands)[8])
+// Candidate pixel tiles of a tap tile shape: full capacity, an even split, whole images, whole rows (or the largest part that
+// divides a row longer than the tile), halves, quarters.
+int tap_tile_candidates(const Shape& s, const TapVariant& tv, int (&cands)[10])
 {
     const int PQ = s.P * s.Q;
     const int64_t total = (int64_t)s.N * PQ;
@@ -688,6 +689,13 @@ int tap_tile_candidates(const Shape& s, const TapVariant& tv, int (&cands)[8])
             if (PQ % d == 0) { cands[nc++] = PQ / d; break; }
     }
     if (s.Q <= cap) cands[nc++] = cap / s.Q * s.Q;
+    else {
+        // rows longer than a tile: the largest part of a row that divides it (tiles then never straddle two rows, which would
+        // cost a fourth halo row - on maps a thousand pixels wide the difference between fitting LDS and not)
+        const int parts = ceil_div(s.Q, cap);
+        for (int d = parts; d <= std::min(s.Q, parts + 16); ++d)
+            if (s.Q % d == 0) { cands[nc++] = s.Q / d; break; }
+    }
     if (cap >= 32) cands[nc++] = cap / 2;
     if (cap >= 64) cands[nc++] = cap / 4;
     return nc;
@@ -727,7 +735,7 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_pl
             // chunks (24..80 channels on the 64-channel chunks of shape 17) most of their waves multiply padding, which the
             // model does not see - five of the six largest misses on random layers off the grid (1.20-1.36x).
             if (tv.WC >= 8 && s.C < 2 * tv.chunk_c()) continue;
-            int cands[8];
+            int cands[10];
             const int nc = tap_tile_candidates(s, tv, cands);
             for (int i = 0; i < nc; ++i) {
                 conv_plan_t cp;
@@ -798,7 +806,7 @@ void search_split_plans(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, Ke
     KernelArgs sa;
     for (int v = 0; v < kNumTapVariants; ++v) {
         const TapVariant tv = kTapVariants[v];
-        int cands[8];
+        int cands[10];
         const int nc = tap_tile_candidates(s, tv, cands);
         for (int i = 0; i < nc; ++i) {
             for (int splits : kSplitCandidates) {
@@ -1063,7 +1071,7 @@ static void enumerate_candidates(const Shape& s, int x_cap, int w_cap, int y_cap
         double best = 0;
         for (int v = 0; v < kNumTapVariants; ++v) {
             const TapVariant tv = kTapVariants[v];
-            int cands[8];
+            int cands[10];
             const int nc = tap_tile_candidates(s, tv, cands);
             for (int i = 0; i < nc; ++i) {
                 bool seen = false;

@@ -287,10 +287,10 @@ def test_tap_plans_name_their_loader():
 # Which (filter size, tile shape) pairs of the tap family are built. Written out by hand from the rule in the
 # kernels' header (a shape takes a filter size if its filter block per chunk fits the staging registers); a change
 # of the build that drops or adds an instance must change this table too.
-_ALL = set(range(30))
+_ALL = set(range(31))
 _EXTRA = {2, 5, 7, 14, 16, 20, 22}
 BUILT_TAP_INSTANCES = {
-    (1, 1): _ALL, (3, 3): _ALL, (5, 5): {2, 4, 8, 9, 10, 11, 12, 14, 15, 16, 22, 23, 24, 28},
+    (1, 1): _ALL, (3, 3): _ALL, (5, 5): {2, 4, 8, 9, 10, 11, 12, 14, 15, 16, 22, 23, 24, 28, 30},
     (1, 3): _EXTRA, (3, 1): _EXTRA, (1, 5): _EXTRA, (5, 1): _EXTRA, (1, 7): _EXTRA, (7, 1): _EXTRA,
     (2, 2): _EXTRA, (4, 4): _EXTRA, (7, 7): {2, 14, 16, 22},
 }
@@ -315,7 +315,7 @@ def built_tap_instances():
 
 
 def test_the_set_of_built_tap_instances_is_pinned():
-    assert binding.conv_variant_count(binding.CONV_KERNEL_TAP) == 30
+    assert binding.conv_variant_count(binding.CONV_KERNEL_TAP) == 31
     assert built_tap_instances() == BUILT_TAP_INSTANCES
     # sizes outside the table have no tap kernel at all
     for R, S in [(2, 3), (6, 6), (3, 5), (9, 9), (1, 2), (11, 11)]:
@@ -343,6 +343,19 @@ def test_direct_loaders_keep_their_byte_offsets_inside_32_bits():
     assert plan.loader == binding.CONV_LOADER_REGISTERS or plan.tile_k * (1 << 21) * 9 * 4 < (1 << 32) - 64, plan.as_dict()
     small = binding.conv_fwd_plan(2, 1 << 10, 80, 80, 16, 3, 3, 1, 1)
     assert small.kernel == tap and small.loader != binding.CONV_LOADER_REGISTERS
+
+
+def test_wide_maps_stay_in_the_tap_family():
+    """Halo tiles hold whole padded rows: up to ~580 pixels every layer finds a tile shape whose staging slots take them, and
+    beyond that the wide shape (twice the slots of the 16 x 448 one, the whole LDS) does: up to ~1500 pixels for 3x3 filters
+    on rows of dwordx4 (pixel tiles that divide a row keep the halo tile at three rows), about half of that on rows of single dwords or with 5x5 filters."""
+    tap = binding.CONV_KERNEL_TAP
+    for W in (224, 512, 580):
+        assert binding.conv_fwd_plan(1, 16, 32, W, 16, 3, 3, 1, 1).kernel == tap
+    for dims in ((1, 16, 32, 1000, 16, 3, 3, 1, 1), (2, 32, 128, 1200, 64, 3, 3, 1, 1), (1, 16, 32, 1400, 16, 3, 3, 1, 1), (1, 16, 32, 701, 16, 3, 3, 1, 1), (1, 8, 32, 800, 32, 5, 5, 2, 2)):
+        p = binding.conv_fwd_plan(*dims)
+        assert p.kernel == tap and p.variant == 30 and p.lds_bytes <= 160 * 1024, (dims, p.as_dict())
+    assert binding.conv_fwd_plan(1, 16, 32, 4000, 16, 3, 3, 1, 1).kernel == binding.CONV_KERNEL_GENERIC
 
 
 def test_halo_tiles_that_cannot_fit_lds_never_reach_the_tap_kernel():

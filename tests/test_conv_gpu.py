@@ -84,6 +84,8 @@ SMALL = [
     S("s3x3_wide", 1, 4, 4, 70, 8, 3, 3, 1, 1),             # rows longer than a pixel tile
     S("s3x3_single", 1, 1, 5, 5, 1, 3, 3, 1, 1),
     S("s3x3_c3_w8", 2, 3, 6, 8, 20, 3, 3, 1, 1),            # first-layer like: dwordx4 input rows, dword filter rows
+    S("s3x3_w900", 1, 8, 5, 900, 20, 3, 3, 1, 1),           # a map wider than every shape's halo tile but the wide one's
+    S("s5x5_w501", 1, 4, 6, 501, 9, 5, 5, 2, 2),            # ... with rows of single dwords
     S("s5x5_c6_w12", 1, 6, 9, 12, 18, 5, 5, 2, 2),
 ]
 
@@ -111,7 +113,7 @@ REGISTERS, DIRECT_LOADS, LOADER_WAVES, DEEP_RING = 1, 2, 3, 4
 
 
 @pytest.mark.parametrize("loader", [REGISTERS, DIRECT_LOADS, LOADER_WAVES, DEEP_RING])
-@pytest.mark.parametrize("variant", range(30))
+@pytest.mark.parametrize("variant", range(32))
 @pytest.mark.parametrize("shape", SMALL + DIRECT, ids=lambda s: s.name)
 def test_every_tap_variant_matches_oracle(shape, variant, loader):
     if variant >= binding.conv_variant_count(TAP):
