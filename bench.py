@@ -445,8 +445,8 @@ def split_c_layers(torch, binding, inputs, oracle):
 
 
 def layer_record(layer, torch, binding, oracle, measured, warmup, auto_steps):
-    """One entry of `layers`: the default mapping (a measured one for the five benchmark layers), then the cost model's
-    own pick for the same layer timed the same way, so that the table of measured mappings hides nothing."""
+    """One entry of `layers`: the planner's mapping of the layer (the benchmark layers go through the same cost model and
+    rules as every other shape: the library keeps no table of measured mappings)."""
     k = auto_steps(layer)
     w_ms, e_ms = layer.measure(k, warmup)
     rec = layer.report(w_ms, e_ms, k)
@@ -455,20 +455,6 @@ def layer_record(layer, torch, binding, oracle, measured, warmup, auto_steps):
     rec["frac_of_measured_mfma"] = rec["gflops"] / 1e3 / measured["mfma_fp32_tflops"]
     rec["frac_of_measured_copy_bw"] = rec["gbs"] / measured["copy_read_plus_write_gbs"]
     rec["roofline"] = layer.roofline(e_ms)
-    model = binding.conv_fwd_plan_untuned(*layer.dims)
-    same = all(getattr(model, f) == getattr(layer.plan, f) for f in ("kernel", "variant", "tile_pix", "loader"))
-    pick = {"plan": {f: getattr(model, f) for f in ("kernel", "variant", "tile_pix", "grid", "block", "loader")},
-            "same_as_default": same}
-    if same:
-        pick["kernel_us"] = rec["kernel_us"]
-    else:
-        layer.use_plan(model)
-        _, m_ms = layer.measure(k, warmup)
-        pick["kernel_us"] = m_ms * 1e3
-        pick["parity"] = layer.parity_sample(oracle, 256)
-        layer.use_plan(None)
-    pick["over_default"] = pick["kernel_us"] / rec["kernel_us"]
-    rec["cost_model_pick"] = pick
     return rec
 
 

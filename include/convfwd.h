@@ -137,15 +137,6 @@ int conv_fwd_plan(int N, int C, int H, int W, int K, int R, int S, int pad_h, in
                   conv_plan_t* out);
 
 /*
- * Host-only: conv_fwd_plan's choice without the short table of measured mappings the library keeps for a few
- * known layer shapes - the planner's cost model alone (for the tap family; Section 5 of the paper: the best work
- * distribution depends on all five layer parameters). Lets a benchmark report how far the model's pick is from
- * the measured one. Arguments and errors as conv_fwd_plan.
- */
-int conv_fwd_plan_untuned(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w,
-                          conv_plan_t* out);
-
-/*
  * As conv_fwd, with the mapping requested by the caller. Only plan->kernel,
  * plan->variant, plan->tile_pix and plan->chunk_c are read as requests (0 in
  * tile_pix means "the variant's capacity"; chunk_c is fixed by the variant and

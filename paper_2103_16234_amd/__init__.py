@@ -6,7 +6,7 @@ compiled library is missing.
 """
 from . import inputs  # noqa: F401
 
-_BINDING_NAMES = ("conv_fwd", "conv_fwd_plan", "conv_fwd_plan_untuned", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_fwd_find", "conv_fwd_two_stage",
+_BINDING_NAMES = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_fwd_find", "conv_fwd_two_stage",
                   "conv_two_stage_workspace_bytes", "conv_fwd_plan_split_c", "conv_fwd_split_c", "conv_fwd_split_c_static", "conv_fwd_plan_request", "conv_set_stream", "conv_strerror",
                   "ConvPlan", "ConvError", "load_library", "library_path", "build_library")
 

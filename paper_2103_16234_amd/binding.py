@@ -25,7 +25,7 @@ CONV_ORDER_CHANNEL_FAST = 1
 CONV_ORDER_PIXEL_FAST = 2
 CONV_ORDER_CHANNEL_GROUPS = 3
 
-EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_plan_untuned", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_fwd_find", "conv_two_stage_workspace_bytes",
+EXPORTS = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_fwd_bias_relu", "conv_fwd_find", "conv_two_stage_workspace_bytes",
            "conv_fwd_two_stage", "conv_fwd_plan_split_c", "conv_fwd_split_c", "conv_fwd_split_c_static", "conv_fwd_plan_request", "conv_probe_mfma", "conv_probe_copy",
            "conv_variant_count", "conv_variant_info", "conv_set_stream", "conv_strerror")
 
@@ -69,7 +69,6 @@ def load_library():
     dims = [ci] * 9
     lib.conv_fwd.argtypes = [vp, vp, vp] + dims
     lib.conv_fwd_plan.argtypes = dims + [ctypes.POINTER(ConvPlan)]
-    lib.conv_fwd_plan_untuned.argtypes = dims + [ctypes.POINTER(ConvPlan)]
     lib.conv_fwd_planned.argtypes = [vp, vp, vp] + dims + [ctypes.POINTER(ConvPlan), ctypes.POINTER(ConvPlan)]
     lib.conv_fwd_bias_relu.argtypes = [vp, vp, vp, vp] + dims + [ci, ctypes.POINTER(ConvPlan), ctypes.POINTER(ConvPlan)]
     lib.conv_fwd_find.argtypes = [vp, vp, vp] + dims + [vp, ctypes.c_longlong, ctypes.POINTER(ConvPlan),
@@ -109,13 +108,6 @@ def _check(code: int):
 def conv_fwd_plan(N, C, H, W, K, R, S, pad_h, pad_w) -> ConvPlan:
     plan = ConvPlan()
     _check(load_library().conv_fwd_plan(N, C, H, W, K, R, S, pad_h, pad_w, ctypes.byref(plan)))
-    return plan
-
-
-def conv_fwd_plan_untuned(N, C, H, W, K, R, S, pad_h, pad_w) -> ConvPlan:
-    """The planner's own choice, without the table of measured mappings of known layers."""
-    plan = ConvPlan()
-    _check(load_library().conv_fwd_plan_untuned(N, C, H, W, K, R, S, pad_h, pad_w, ctypes.byref(plan)))
     return plan
 
 

@@ -616,27 +616,6 @@ void prefer_deep_ring(const Shape& s, int x_cap, int w_cap, conv_plan_t* p, Kern
         }
 }
 
-// Measured best mappings of known layer shapes (sweeps over tile shape x pixel tile on an MI355X);
-// shapes not listed go through the cost model.
-struct TunedEntry {
-    int N, C, H, W, K, R, pad, kernel, variant, tile_pix;
-};
-constexpr TunedEntry kTuned[] = {
-    {1, 16, 14, 14, 16, 3, 1, CONV_KERNEL_TAP, 2, 16},
-    {1, 256, 56, 56, 64, 1, 0, CONV_KERNEL_POINTWISE, 1, 64},
-    {8, 64, 56, 56, 64, 3, 1, CONV_KERNEL_TAP, 27, 98},
-    {1, 48, 28, 28, 128, 5, 2, CONV_KERNEL_TAP, 11, 28},
-    {32, 512, 14, 14, 512, 3, 1, CONV_KERNEL_TAP, 26, 196},
-};
-const TunedEntry* find_tuned(const Shape& s)
-{
-    for (const TunedEntry& t : kTuned)
-        if (t.N == s.N && t.C == s.C && t.H == s.H && t.W == s.W && t.K == s.K && t.R == s.R && t.R == s.S &&
-            t.pad == s.pad_h && t.pad == s.pad_w)
-            return &t;
-    return nullptr;
-}
-
 // conv_fwd plans on every call; remember recent shapes so a launch costs a table lookup.
 struct CacheEntry {
     Shape s;
@@ -650,7 +629,7 @@ constexpr size_t kCacheEntries = 64;
 
 bool same_shape(const Shape& a, const Shape& b) { return std::memcmp(&a, &b, sizeof(Shape)) == 0; }
 
-int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a, bool use_tuned = true);
+int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a);
 
 int plan_shape(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
 {
@@ -701,12 +680,8 @@ int tap_tile_candidates(const Shape& s, const TapVariant& tv, int (&cands)[10])
     return nc;
 }
 
-int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a, bool use_tuned)
+int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
 {
-    const TunedEntry* const tuned = use_tuned ? find_tuned(s) : nullptr;
-    if (tuned && tuned->kernel == CONV_KERNEL_POINTWISE &&
-        resolve_pointwise(s, tuned->variant, x_cap, w_cap, y_cap, p, a))
-        return CONV_OK;
     if (pointwise_ok(s, x_cap, w_cap, y_cap)) {
         const int pv = pick_panel(s, x_cap, y_cap);
         // Small layers with few input channels (under ~150 MFLOP, C <= 80, pixels that move as dwordx4) have nothing
@@ -724,9 +699,6 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_pl
         if (resolve_pointwise(s, pick_pointwise(s), x_cap, w_cap, y_cap, p, a)) return CONV_OK;
     }
     if (tap_rs_index(s) >= 0) {
-        if (tuned && tuned->kernel == CONV_KERNEL_TAP &&
-            resolve_tap(s, tuned->variant, tuned->tile_pix, 0, x_cap, w_cap, p, a))
-            return CONV_OK;
         bool found = false;
         double best = 0;
         for (int v = 0; v < kNumTapVariants; ++v) {
@@ -875,15 +847,6 @@ extern "C" int conv_fwd_plan(int N, int C, int H, int W, int K, int R, int S, in
     if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
     KernelArgs a;
     return plan_shape(s, 4, 4, 4, out, &a);
-}
-
-extern "C" int conv_fwd_plan_untuned(int N, int C, int H, int W, int K, int R, int S, int pad_h, int pad_w, conv_plan_t* out)
-{
-    if (!out) return CONV_E_NULL;
-    Shape s;
-    if (int rc = validate(N, C, H, W, K, R, S, pad_h, pad_w, &s)) return rc;
-    KernelArgs a;
-    return plan_shape_uncached(s, 4, 4, 4, out, &a, false);
 }
 
 extern "C" int conv_fwd(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,

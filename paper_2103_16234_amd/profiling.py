@@ -261,13 +261,11 @@ def stats(directory: str):
               f"  kernel {b['roofline']['kernel']}: {b['roofline']['kernel_us']:.2f} us per launch over {b['steps']} launches -> "
               f"{b['roofline']['achieved']:.2f} {b['roofline']['unit']} = {b['roofline']['frac']:.3f} of {b['roofline']['peak']} "
               f"({b['roofline']['bound']} roofline)", "",
-              "layers of the same untraced run (default mapping | the cost model's own pick):"]
+              "layers of the same untraced run (the planner's mapping; the library keeps no table of measured mappings):"]
     for l in b.get("layers", []):
-        m = l["cost_model_pick"]
         lines.append(f"  {l['layer']:<18} {l['kernel_us'] * 1000:>9.0f} ns ({l['gflops'] / 1e3:>7.2f} TFLOP/s, {l['gbs']:>6.0f} GB/s, "
                      f"{l['roofline']['frac']:.3f} of the {l['roofline']['bound']} roofline) variant {l['plan']['variant']} tile_pix "
-                     f"{l['plan']['tile_pix']} loader {l['plan']['loader']} grid {l['plan']['grid']} | model: variant {m['plan']['variant']} tile_pix "
-                     f"{m['plan']['tile_pix']} loader {m['plan']['loader']} {m['kernel_us'] * 1000:.0f} ns ({m['over_default']:.3f}x)")
+                     f"{l['plan']['tile_pix']} loader {l['plan']['loader']} grid {l['plan']['grid']}")
     for r in b.get("batch_scaled_1x1", []):
         lines.append(f"  {r['layer']:<36} {r['kernel_us'] * 1000:>9.0f} ns ({r['tflops']:.2f} TFLOP/s, {r['gbs']:.0f} GB/s, "
                      f"{100 * r['frac_hbm_peak']:.1f} % of HBM peak)")
