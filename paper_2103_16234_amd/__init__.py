@@ -12,7 +12,7 @@ _BINDING_NAMES = ("conv_fwd", "conv_fwd_plan", "conv_fwd_planned", "conv_fwd_bia
 
 
 def __getattr__(name):
-    if name in _BINDING_NAMES or name == "binding":
+    if name in _BINDING_NAMES or name == "binding" or name.startswith("CONV_"):
         import importlib
         mod = importlib.import_module(".binding", __name__)
         return mod if name == "binding" else getattr(mod, name)
