@@ -140,6 +140,9 @@ def test_plans_of_the_sweep_grid_are_well_formed():
         if p.kernel == tap:
             assert 1 <= p.tile_pix <= cap
             assert p.grid == -(-s.K // p.tile_k) * -(-total // p.tile_pix)
+            ktiles = -(-s.K // p.tile_k)           # the work-group numbering walks whole groups of channel tiles
+            assert 1 <= p.k_group <= ktiles and ktiles % p.k_group == 0
+            assert p.order == (1 if p.k_group == ktiles else 2 if p.k_group == 1 else 3)
             assert p.chunk_c % 4 == 0 and p.x_vec in (1, 2, 4) and p.w_vec in (1, 4)
             assert s.W % p.x_vec == 0 and (p.w_vec == 1 or s.C % 4 == 0)
         elif p.kernel == pw:
