@@ -364,7 +364,9 @@ int panel_pixel_mode(const Shape& s, int x_cap, int y_cap)
 
 // Panel kernel of the pointwise family: the filters of a channel tile must fit LDS whole. tile_pix > 0
 // requests that many work-groups per channel tile (0 = choose).
-bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
+// With groups chosen here, *modelled (if given) receives the chosen grid's cost in cycles of the busiest SIMD.
+bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a,
+                   double* modelled = nullptr)
 {
     if (!pointwise_ok(s, x_cap, w_cap, y_cap) || variant < 0 || variant >= kNumPanelVariants) return false;
     const PanelVariant pv = kPanelVariants[variant];
@@ -429,6 +431,7 @@ bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w
             consider(g);
         }
         consider(most);
+        if (modelled) *modelled = best * tile_cycles;
     }
     groups = std::min(groups, most);
     if ((int64_t)groups * a->ktiles >= ((int64_t)1 << 31)) return false;
@@ -486,29 +489,48 @@ int pick_pointwise(const Shape& s)
 // Panel kernel or not, from sweeps over batched 1x1 layers: it wins once there are about 700 units of
 // (64-pixel tile) x (32 output channels) - roughly one per SIMD with some to spare - and loses below, where
 // splitting the channels over the waves of a work-group fills the chip better. 32 channels per panel and two
-// steps in flight is the best or within 3 % of it almost everywhere; maps whose pixels move as single dwords
-// do better with 64 channels per panel (half as many input load instructions per output).
-int pick_panel(const Shape& s, int x_cap, int y_cap)
+// steps in flight is the best or within 3 % of it almost everywhere on maps whose pixels move as aligned dwordx4;
+// on the others the four shapes are ranked by the grid each would get.
+int pick_panel(const Shape& s, int x_cap, int w_cap, int y_cap)
 {
     const int64_t tiles = ((int64_t)s.N * s.H * s.W + 63) / 64;
+    const int pix = panel_pixel_mode(s, x_cap, y_cap);
+    // Maps whose pixels do not move as aligned dwordx4 (7 x 7, 13 x 13, 27 x 27, ...): the grid model of resolve_panel
+    // ranks the four shapes once each is weighted for what that model leaves out - a wave's input loads per output fall
+    // with the channels of its panel, and eight waves hide more of a work-group's start than four. Weights fitted on
+    // timings of the four shapes over 63 layers (batch 16..128, 256..512 channels, 64..384 filters): the pick is
+    // 0.9 % (single dwords) and 1.5 % (tiles cut per image) behind the measured best in the geometric mean, 6 % and 13 %
+    // at worst, where fixed thresholds on the work were 7 % and 3 % behind, 35 % and 26 % at worst (a grid of
+    // 64-channel panels two work-groups over a multiple of the CU count runs a whole extra round).
+    auto ranked = [&]() {
+        static constexpr int kShapes[4] = {5, 7, 6, 8};
+        static constexpr double kWeight[2][4] = {{1.2, 1.0, 0.8, 0.9}, {1.5, 1.0, 0.92, 1.08}};
+        int pick = -1;
+        double least = 0;
+        for (int i = 0; i < 4; ++i) {
+            conv_plan_t tp;
+            KernelArgs ta;
+            double cycles = 0;
+            if (!resolve_panel(s, kShapes[i], 0, x_cap, w_cap, y_cap, &tp, &ta, &cycles)) continue;
+            cycles *= kWeight[pix - 1][i];
+            if (pick < 0 || cycles < least) { pick = kShapes[i]; least = cycles; }
+        }
+        return pick;
+    };
     if (tiles * ceil_div(s.K, 32) < 704) {
         // fewer 32-channel units than that, but 512 or more 16-channel ones: 16 channels per panel still beat the
         // channel-splitting kernel by 5-25 % in the sweeps (deep layers on 7..14-pixel maps at batch 8..32)
         // (at batch 1 only with 256 or more input channels: with fewer the resident filters save too little to pay for
         // the panel's start-up)
-        if ((s.N > 1 || s.C >= 256) && tiles * ceil_div(s.K, 16) >= 512 && 16 * (round_up(s.C, 64) + 4) * 4 <= kLdsMax) return 5;  // {1, 4, 4}
+        if ((s.N > 1 || s.C >= 256) && tiles * ceil_div(s.K, 16) >= 512 && 16 * (round_up(s.C, 64) + 4) * 4 <= kLdsMax)
+            return pix != 0 ? ranked() : 5;  // {1, 4, 4}
         return -1;
     }
-    const bool dwords = panel_pixel_mode(s, x_cap, y_cap) == 1;
+    if (pix != 0) return ranked();
     const int c64 = round_up(s.C, 32);
-    if (dwords && s.K >= 64 && tiles * ceil_div(s.K, 64) >= 704 && 64 * (c64 + 4) * 4 <= kLdsMax) return 6;  // {4, 4, 2}
-    // 64 channels per panel also win on layers with 256 or more filters whose panel still lets two work-groups share a CU
-    // (C <= 256) - on maps whose tiles are cut per image (27 x 27): 7-20 % there. Where pixels move as aligned dwordx4 the
-    // same rule once applied too; timings of every panel shape on the 27 such layers of the grid and off it put the
-    // 32-channel panel ahead on all of them (8.5 % in the geometric mean, up to 32 %), and it was dropped for those.
-    if (panel_pixel_mode(s, x_cap, y_cap) == 2 && s.K >= 256 && tiles * ceil_div(s.K, 64) >= 704 && 64 * (c64 + 4) * 4 <= kLdsMax / 2)
-        return 6;
-    // a 32-channel panel of more than half the LDS leaves one work-group per CU: eight waves then (two per SIMD)
+    // Aligned dwordx4 pixels: timings of every panel shape on 27 such layers with 256 or more filters put the 32-channel
+    // panel ahead of the 64-channel one on all of them (8.5 % in the geometric mean, up to 32 %).
+    // A 32-channel panel of more than half the LDS leaves one work-group per CU: eight waves then (two per SIMD)
     // when every CU still gets a work-group whose waves all have a tile
     if (32 * (c64 + 4) * 4 > kLdsMax / 2 && 32 * (c64 + 4) * 4 <= kLdsMax &&
         static_cast<long long>(ceil_div(s.K, 32)) * ceil_div(tiles, 8) >= kNumCU) return 8;                    // {2, 8, 2}
@@ -683,7 +705,7 @@ int tap_tile_candidates(const Shape& s, const TapVariant& tv, int (&cands)[10])
 int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_plan_t* p, KernelArgs* a)
 {
     if (pointwise_ok(s, x_cap, w_cap, y_cap)) {
-        const int pv = pick_panel(s, x_cap, y_cap);
+        const int pv = pick_panel(s, x_cap, w_cap, y_cap);
         // Small layers with few input channels (under ~150 MFLOP, C <= 80, pixels that move as dwordx4) have nothing
         // to share between waves: the register-streaming shape whose four waves each take 64 pixels and all channels
         // beats the panel kernel by 10-20 % there (measured on 64 x 48 x 14 x 14 -> 64, 4 x 16 x 80 x 80 -> 48,

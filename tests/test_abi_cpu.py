@@ -241,6 +241,26 @@ def test_panel_plans_follow_the_batch():
     assert deep.kernel != binding.CONV_KERNEL_PANEL
 
 
+def test_panel_shapes_on_unaligned_maps_follow_the_grid_they_would_get():
+    """13 x 13 and 27 x 27 maps: the panel shape is the one whose grid fills the chip, not a threshold on the work.
+    64 x 384 x 13 x 13 -> 384 has 169 tiles: 64-channel panels would make 258 work-groups of one tile per wave on 256 CUs
+    (two rounds); twice the batch makes 510 of them, which is two clean rounds and the fastest shape measured."""
+    panel = binding.CONV_KERNEL_PANEL
+    awkward = binding.conv_fwd_plan(64, 384, 13, 13, 384, 1, 1, 0, 0)
+    assert awkward.kernel == panel and awkward.variant != 6
+    clean = binding.conv_fwd_plan(128, 384, 13, 13, 384, 1, 1, 0, 0)
+    assert (clean.kernel, clean.variant, clean.grid) == (panel, 6, 510)
+    few_filters = binding.conv_fwd_plan(128, 256, 13, 13, 64, 1, 1, 0, 0)   # one round of 32-channel panels, not two of 16
+    assert (few_filters.kernel, few_filters.variant) == (panel, 7)
+    thin = binding.conv_fwd_plan(48, 320, 27, 27, 48, 1, 1, 0, 0)           # three 16-channel tiles, none padded
+    assert (thin.kernel, thin.variant) == (panel, 5)
+    # every pick is a shape the kernel is built for and whose panel fits LDS
+    for n, c, hw, k in [(16, 256, 7, 384), (256, 1024, 7, 256), (8, 640, 15, 512), (192, 128, 27, 768), (32, 2048, 13, 64)]:
+        plan = binding.conv_fwd_plan(n, c, hw, hw, k, 1, 1, 0, 0)
+        if plan.kernel == panel:
+            assert plan.variant in (5, 6, 7, 8) and plan.lds_bytes <= 160 * 1024 and plan.grid >= 1
+
+
 def test_tap_plans_name_their_loader():
     """Tap-family plans report how chunks reach LDS; a request may name the loader, and the direct one is refused
     where it cannot run (dword filter rows, input rows that move as dwordx2)."""
