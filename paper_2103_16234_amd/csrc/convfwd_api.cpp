@@ -399,8 +399,12 @@ bool resolve_panel(const Shape& s, int variant, int groups_req, int x_cap, int w
         // 11.6 against 14.4), a second wave per SIMD buys nothing and every further work-group per CU costs ~8 %.
         // That holds for long layers only (six or more tiles per wave at one work-group per CU); short ones gain more
         // from the extra waves that hide their start-up latencies.
-        const bool streaming = 2.0 * s.C * s.K / (4.0 * (s.C + s.K)) < 32.0 &&
-                               (int64_t)tiles * a->ktiles >= (int64_t)6 * kNumCU * pv.NW;
+        // On maps whose pixels do not move as aligned dwordx4 the same holds further out: up to ~55 flop per byte and
+        // from 2.5 tiles per wave, grids of two work-groups per CU ran 10-20 % behind grids of one on 13 x 13 and
+        // 35 x 35 maps (128 x 64 x 13 x 13 -> 256: 20.3 us against 17.2; 64 x 192 x 35 x 35 -> 256: 79.4 against 69.9).
+        const double flop_per_byte = 2.0 * s.C * s.K / (4.0 * (s.C + s.K));
+        const bool streaming = pix != 0 ? flop_per_byte < 60.0 && 2 * (int64_t)tiles * a->ktiles >= (int64_t)5 * kNumCU * pv.NW
+                                        : flop_per_byte < 32.0 && (int64_t)tiles * a->ktiles >= (int64_t)6 * kNumCU * pv.NW;
         double best = 0;
         auto consider = [&](int g) {
             g = std::max(1, std::min(g, most));
