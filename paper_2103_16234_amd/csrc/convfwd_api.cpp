@@ -508,7 +508,7 @@ int pick_panel(const Shape& s, int x_cap, int w_cap, int y_cap)
     // 64-channel panels two work-groups over a multiple of the CU count runs a whole extra round).
     auto ranked = [&]() {
         static constexpr int kShapes[4] = {5, 7, 6, 8};
-        static constexpr double kWeight[2][4] = {{1.2, 1.0, 0.8, 0.9}, {1.5, 1.0, 0.92, 1.08}};
+        static constexpr double kWeight[2][4] = {{1.2, 1.0, 0.75, 0.9}, {1.5, 1.0, 0.92, 1.08}};
         int pick = -1;
         double least = 0;
         for (int i = 0; i < 4; ++i) {
