@@ -473,7 +473,8 @@ int pick_pointwise(const Shape& s)
     // about one 32-channel work-group per CU and 256 or more channels: eight shares of them (measured 4-18 % over the
     // 16-channel shapes on 32 x 832 x 7 x 7 -> 256, 4 x 512 x 14 x 14 -> 512, 16 x 320 x 7 x 7 -> 512)
     const int64_t groups32 = pix_tiles * ceil_div(s.K, 32);
-    if (groups32 >= 224 && groups32 <= 288 && steps >= 16) return 3;  // {MT 2, WC 8}
+    // (and about two per CU: 4-25 % over the other shapes on 1 x 256 x 56 x 56 -> 320, 2 x 512 x 40 x 40 -> 320)
+    if (((groups32 >= 224 && groups32 <= 288) || (groups32 >= 448 && groups32 <= 576)) && steps >= 16) return 3;  // {MT 2, WC 8}
     // {1, 4} or {1, 8} shares (16 shares, 1024 threads, measured 25 % slower even on 512..832 channels); with three or
     // more steps per wave the twin that keeps four steps of loads in flight (3-7 % on 512..1024-channel N=1 layers)
     const int pick = (groups * 4 >= 1024 || steps <= 8) ? (steps >= 12 ? 15 : 0) : (steps >= 24 ? 14 : 1);
@@ -526,8 +527,14 @@ int pick_panel(const Shape& s, int x_cap, int w_cap, int y_cap)
         // channel-splitting kernel by 5-25 % in the sweeps (deep layers on 7..14-pixel maps at batch 8..32)
         // (at batch 1 only with 256 or more input channels: with fewer the resident filters save too little to pay for
         // the panel's start-up)
-        if ((s.N > 1 || s.C >= 256) && tiles * ceil_div(s.K, 16) >= 512 && 16 * (round_up(s.C, 64) + 4) * 4 <= kLdsMax)
+        if ((s.N > 1 || s.C >= 256) && tiles * ceil_div(s.K, 16) >= 512 && 16 * (round_up(s.C, 64) + 4) * 4 <= kLdsMax) {
+            // ... unless one tile per wave makes a few work-groups more than the chip has CUs: the CUs that get two of them
+            // take twice as long (260 work-groups on 1 x 256 x 56 x 56 -> 320 and 2 x 512 x 40 x 40 -> 320: 12.4 and 20.4 us,
+            // where eight channel shares of the pointwise kernel take 9.1 and 14.8)
+            const int64_t one_tile_each = (int64_t)ceil_div(s.K, 16) * ((tiles + 3) / 4);
+            if (pix == 0 && one_tile_each > kNumCU && one_tile_each <= kNumCU + kNumCU / 8) return -1;
             return pix != 0 ? ranked() : 5;  // {1, 4, 4}
+        }
         return -1;
     }
     if (pix != 0) return ranked();

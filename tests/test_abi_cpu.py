@@ -241,6 +241,15 @@ def test_panel_plans_follow_the_batch():
     assert deep.kernel != binding.CONV_KERNEL_PANEL
 
 
+def test_sixteen_channel_panels_stay_off_grids_just_over_the_cu_count():
+    """1 x 256 x 56 x 56 -> 320 would make 260 work-groups of one tile per wave on 256 CUs: the pointwise kernel takes it with
+    eight channel shares; with 768 filters the grid is 336 and the panel kernel keeps the layer."""
+    over = binding.conv_fwd_plan(1, 256, 56, 56, 320, 1, 1, 0, 0)
+    assert (over.kernel, over.variant) == (binding.CONV_KERNEL_POINTWISE, 3)
+    fine = binding.conv_fwd_plan(1, 256, 40, 40, 768, 1, 1, 0, 0)
+    assert (fine.kernel, fine.variant) == (binding.CONV_KERNEL_PANEL, 5)
+
+
 def test_panel_shapes_on_unaligned_maps_follow_the_grid_they_would_get():
     """13 x 13 and 27 x 27 maps: the panel shape is the one whose grid fills the chip, not a threshold on the work.
     64 x 384 x 13 x 13 -> 384 has 169 tiles: 64-channel panels would make 258 work-groups of one tile per wave on 256 CUs
