@@ -725,8 +725,12 @@ int plan_shape_uncached(const Shape& s, int x_cap, int w_cap, int y_cap, conv_pl
         // 256-pixel tiles waste less than 30 % of an image: 64 x 24 x 35 x 35 -> 48: 12.7 -> 9.6 us)
         const int64_t hw = (int64_t)s.H * s.W;
         const double pw_flops = 2.0 * s.N * s.H * s.W * s.C * s.K;
+        // (and up to ~120 MFLOP whatever its tiles waste: on 7 x 7 ... 17 x 17 maps at batch 1..8 it matches the other shapes
+        // where all of them sit at the launch floor and is 10-25 % faster from ~300 work-groups of theirs on,
+        // 8 x 16 x 13 x 13 -> 768: 6.2 -> 4.8 us, 2 x 32 x 17 x 17 -> 768: 5.1 -> 3.7 us)
         const bool small_thin = (s.C <= 80 && hw % 4 == 0 && pw_flops <= 1.5e8) ||
-                                (s.C <= 32 && pw_flops <= 3e8 && (hw + 255) / 256 * 256 * 10 <= hw * 13);
+                                (s.C <= 32 && pw_flops <= 3e8 && (hw + 255) / 256 * 256 * 10 <= hw * 13) ||
+                                (s.C <= 32 && pw_flops <= 1.2e8);
         if (small_thin && resolve_pointwise(s, 8, x_cap, w_cap, y_cap, p, a)) return CONV_OK;
         if (pv >= 0 && resolve_panel(s, pv, 0, x_cap, w_cap, y_cap, p, a)) return CONV_OK;
         if (resolve_pointwise(s, pick_pointwise(s), x_cap, w_cap, y_cap, p, a)) return CONV_OK;

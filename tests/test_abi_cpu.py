@@ -241,6 +241,14 @@ def test_panel_plans_follow_the_batch():
     assert deep.kernel != binding.CONV_KERNEL_PANEL
 
 
+def test_thin_small_pointwise_layers_stream_on_any_map():
+    """Up to 32 channels and ~120 MFLOP the register-streaming shape takes a 1x1 layer whatever its 256-pixel tiles waste."""
+    odd = binding.conv_fwd_plan(2, 16, 17, 17, 768, 1, 1, 0, 0)
+    assert (odd.kernel, odd.variant) == (binding.CONV_KERNEL_POINTWISE, 8)
+    big = binding.conv_fwd_plan(8, 32, 35, 35, 768, 1, 1, 0, 0)        # 480 MFLOP: the panel kernel keeps it
+    assert big.kernel == binding.CONV_KERNEL_PANEL
+
+
 def test_sixteen_channel_panels_stay_off_grids_just_over_the_cu_count():
     """1 x 256 x 56 x 56 -> 320 would make 260 work-groups of one tile per wave on 256 CUs: the pointwise kernel takes it with
     eight channel shares; with 768 filters the grid is 336 and the panel kernel keeps the layer."""
